@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the RaZeR W4A16 / W4A4 linear path on one MI355X.
+
+Headline (the benchmark spec): HBM GB/s of the fused-decode GEMV at M=1 over a
+Llama-7B-shaped decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; down
+4096x11008), weights resident in HBM in RaZeR form.  One timed "step" is one
+pass over the seven projections at M=1; enough distinct copies of the packed
+layer are rotated through that every pass streams its weights from HBM rather
+than from the last-level cache.  The other legs of the path (small-M GEMV,
+MFMA GEMM at M=512/2048, encoder, decoder, W4A4) are timed in the same run and
+reported in "legs".  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+LLC_BYTES = 256 << 20          # Infinity Cache
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=20)
+    p.add_argument("--legs", default="all", help="all | gemv (headline only)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    return p.parse_args()
+
+
+def student_t_weight(n, k, gen, outlier_frac=0.001, gain=20.0):
+    """fp32 [n][k] on the GPU: Student-t(nu=4) scaled to std 0.02, 0.1% of input channels x20."""
+    import torch
+    z = torch.randn((n, k), generator=gen, device="cuda", dtype=torch.float32)
+    chi = torch.zeros((n, k), device="cuda", dtype=torch.float32)
+    for _ in range(4):
+        chi += torch.randn((n, k), generator=gen, device="cuda", dtype=torch.float32) ** 2
+    w = z / torch.sqrt(chi / 4.0) * (0.02 / 2.0 ** 0.5)
+    n_out = int(round(outlier_frac * k))
+    if n_out:
+        cols = torch.randperm(k, generator=gen, device="cuda")[:n_out]
+        w[:, cols] *= gain
+    return w
+
+
+def time_region(fn, steps, warmup):
+    """Run fn(step) warmup+steps times on the current stream; returns ms per step (HIP events)."""
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        fn(warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2501_04052_amd as razer
+    from paper_2501_04052_amd import synth
+
+    razer.load_library()            # raises if the HIP library is not built: no fallback
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(2000)
+    layers = synth.LLAMA_7B_LAYER
+    sv = (5.0, 8.0)
+
+    # ---- encode the layer once (also the encoder leg) --------------------------------
+    legs = {}
+    packed = []
+    enc_bytes = enc_ms = 0.0
+    for name, n, k in layers:
+        w = student_t_weight(n, k, gen)
+        t = razer.razer_quantize(w, razer.WEIGHT, sv)                      # warm-up + result
+        torch.cuda.synchronize()
+        ms = time_region(lambda i: razer.razer_quantize(w, razer.WEIGHT, sv, out=t), 3, 1)
+        enc_ms += ms
+        enc_bytes += n * k * (4 + 0.5625)
+        packed.append(t)
+        del w
+    legs["encode_weights_fp32"] = {"GB/s": enc_bytes / enc_ms / 1e6, "ms_per_layer_set": enc_ms,
+                                   "bytes": "4 B in + 0.5625 B out per element; the absmax pre-pass re-reads the input"}
+
+    layer_bytes = sum(n * k * 9 // 16 for _, n, k in layers)
+    n_copies = max(2, -(-2 * LLC_BYTES // layer_bytes))                     # working set >= 2x the LLC
+    copies = [packed]
+    for _ in range(n_copies - 1):
+        copies.append([razer.RazerTensor(t.codes.clone(), t.scales.clone(), t.tensor_scale.clone(),
+                                         t.rows, t.cols, t.fmt, t.sv) for t in packed])
+
+    def make_act(m, k, seed):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(seed)
+        return torch.randn((m, k), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+
+    def linear_leg(m, steps, warmup, rotate=True):
+        acts = {k: make_act(m, k, 2100 + m) for k in {k for _, _, k in layers}}
+        outs = [torch.empty((m, n), dtype=torch.bfloat16, device="cuda") for _, n, _ in layers]
+
+        def step(i):
+            cp = copies[i % n_copies] if rotate else copies[0]
+            for j, t in enumerate(cp):
+                razer.razer_linear(t, acts[t.cols], out=outs[j])
+        ms = time_region(step, steps, warmup)
+        byts = sum(n * k * 9 // 16 + 2 * m * k + 2 * m * n + 4 for _, n, k in layers)
+        flops = sum(2.0 * m * n * k for _, n, k in layers)
+        return ms, byts, flops
+
+    # ---- headline: GEMV at M=1 ----------------------------------------------------------
+    ms1, bytes1, _ = linear_leg(1, args.steps, args.warmup)
+    gbs = bytes1 / ms1 / 1e6
+    ms1c, _, _ = linear_leg(1, max(10, args.steps // 4), 5, rotate=False)
+    legs["gemv_m1_cache_resident"] = {"GB/s": bytes1 / ms1c / 1e6, "note": "same 113.8 MB copy every step: served by the last-level cache, not HBM"}
+
+    gemm_roof = None
+    if args.legs == "all":
+        for m in (4, 16):
+            ms, b, _ = linear_leg(m, max(10, args.steps // 4), 5)
+            legs["linear_m%d" % m] = {"GB/s": b / ms / 1e6, "frac_hbm": b / ms / 1e6 / HBM_PEAK_GBS, "ms_per_step": ms}
+        for m in (512, 2048):
+            ms, _, fl = linear_leg(m, 5, 2)
+            legs["gemm_m%d" % m] = {"TFLOP/s": fl / ms / 1e9, "frac_mfma_bf16": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                                    "ms_per_step": ms}
+            if m == 2048:
+                gemm_roof = {"bound": "mfma", "achieved": fl / ms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
+                             "unit": "TFLOP/s", "frac": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                             "kernel": "gemm_kernel (M=2048, Llama-7B layer set, flops = 2MNK)"}
+        # decoder leg: packed -> bf16
+        t = packed[4]
+        out = torch.empty((t.rows, t.cols), dtype=torch.bfloat16, device="cuda")
+        ms = time_region(lambda i: razer.razer_dequant(t, out=out), 10, 2)
+        legs["dequant_bf16_11008x4096"] = {"GB/s": t.rows * t.cols * (0.5625 + 2) / ms / 1e6}
+        del out
+        # W4A4 leg: on-the-fly activation encode + linear against the gate projection
+        a = make_act(4096, 4096, 5000)
+        cols = torch.randperm(4096, generator=gen, device="cuda")[:20]
+        a[:, cols] *= 50.0
+        aq = razer.razer_quantize(a, razer.ACT, (5.0, 0.0))
+        ms_e = time_region(lambda i: razer.razer_quantize(a, razer.ACT, (5.0, 0.0), out=aq), 10, 2)
+        y = torch.empty((4096, 11008), dtype=torch.bfloat16, device="cuda")
+        ms_l = time_region(lambda i: razer.razer_linear(packed[4], aq, out=y), 5, 2)
+        legs["w4a4_act_encode_4096x4096"] = {"GB/s": 4096 * 4096 * (2 + 0.5625) / ms_e / 1e6, "ms": ms_e}
+        legs["w4a4_linear_4096x11008x4096"] = {"TFLOP/s": 2.0 * 4096 * 11008 * 4096 / ms_l / 1e9, "ms": ms_l,
+                                               "end_to_end_TFLOP/s": 2.0 * 4096 * 11008 * 4096 / (ms_l + ms_e) / 1e9}
+
+    # ---- CPU baseline: the oracle, as it stands, on the host cores ------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        name, n, k = layers[0]
+        rows = 1024                                                     # bounded sample: 1024 output rows of q
+        t = packed[0]
+        wq = (t.codes[:rows].cpu().numpy(), t.scales[:rows].cpu().numpy(),
+              np.float32(t.tensor_scale.cpu().numpy()[0]))
+        a_bits = make_act(1, k, 2101).view(torch.int16).cpu().numpy().view(np.uint16)
+        oracle.linear(wq, a_bf16=a_bits, rows=None, cols=np.arange(8, dtype=np.int64))   # page in
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            oracle.linear(wq, a_bf16=a_bits)
+            reps += 1
+        dt = (time.perf_counter() - t0) / reps
+        cpu = {"value": (rows * k * 9 // 16 + 2 * k + 2 * rows) / dt / 1e9, "unit": "GB/s",
+               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())), "kind": "oracle",
+               "sample": "oracle_linear, M=1, first %d of %d output rows of the %dx%d q projection, %d repeats in ~10 s"
+                         % (rows, n, n, k, reps)}
+
+    out = {
+        "metric": "RaZeR W4A16 GEMV HBM GB/s at M=1 (Llama-7B-shaped layer set)",
+        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp4 codes x bf16 activations, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": "configs[1]: Llama-7B-shaped decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; "
+                               "down 4096x11008), RaZeR weights (block 16, E3M3 scale + 2 meta bits, sv {5,8}), M=1; "
+                               "one step = the 7 projections once; %d packed copies rotated (%.0f MB > 2x LLC)"
+                               % (n_copies, n_copies * layer_bytes / 1e6),
+                   "m": 1, "bytes_per_step": bytes1},
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "gemv_kernel<M=1> (7 launches per step; achieved = algorithmic bytes of the step / step time)"},
+        "cpu_baseline": cpu,
+        "legs": legs,
+    }
+    if gemm_roof:
+        out["roofline_gemm"] = gemm_roof
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

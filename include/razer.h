@@ -1,0 +1,132 @@
+/*
+ * razer.h -- C ABI of the MI355X (gfx950) RaZeR library.
+ *
+ * RaZeR (Redundant Zero Remapping, arxiv 2501.04052) is NVFP4 with the
+ * redundant FP4 zero code turned into a per-block "special value":
+ *
+ *   element   FP4-E2M1 code S|EE|M (Sec. 4.1, FP4 equation): +-{0,.5,1,1.5,2,3,4,6};
+ *             code 0x8 (negative zero) is the remapped one (Sec. 4.2).
+ *   block     16 consecutive elements along the last (contraction) axis share one
+ *             scale byte (Sec. 3; Sec. 5.1 "block size of 16 with 8-bit block scale"):
+ *               weights      bit7 = special-value sign, bit6 = special-value selector,
+ *                            bits5:0 = E3M3 scale EEE|MMM, value 2^(E-3)(1+M/8), E=0: M/32
+ *                            (Sec. 4.1 adopts E3M3 for weights; 2 freed bits, Sec. 4.2)
+ *               activations  bit7 = special-value sign, bits6:0 = FP8-E4M3 scale
+ *                            EEEE|MMM, value 2^(E-7)(1+M/8), E=0: M/512 (Sec. 4.1, FP8
+ *                            equation; 1 freed bit, Sec. 4.2); code 0x7F is never written.
+ *   tensor    one FP32 scale = absmax / (Qmax_scale * 6)  (Eq. 1).
+ *   special   weights: {+sv[0], +sv[1], -sv[0], -sv[1]} indexed by (sign<<1 | selector);
+ *             activations: {+sv[0], -sv[0]} (Sec. 4.2, Sec. 4.4 decoder, App. B.2).
+ *   value     x^ = tensor_scale * block_scale * (code == 0x8 ? special : FP4[code]).
+ *
+ * Storage (dense, row-major, all DEVICE memory, caller-owned):
+ *   codes  [rows][cols/2]   uint8, element k even in the LOW nibble, k odd in the high
+ *   scales [rows][cols/16]  uint8 as above
+ *   tensor_scale            one float
+ * i.e. 4.5 bits per element plus 4 bytes, the NVFP4 footprint (Sec. 4.2).
+ *
+ * Every entry point only enqueues kernels on the HIP stream passed in
+ * (hipStream_t cast to void*, NULL = default stream); nothing allocates,
+ * synchronizes or keeps state.  Errors are returned as status codes; no
+ * exceptions, no aborts.  Non-finite inputs give unspecified values, no faults.
+ */
+#ifndef RAZER_H
+#define RAZER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RAZER_OK = 0,
+    RAZER_ERR_NULL = 1,        /* a required pointer is NULL                        */
+    RAZER_ERR_SHAPE = 2,       /* negative size, cols % 32 != 0, ld too small       */
+    RAZER_ERR_ALIGN = 3,       /* a pointer or leading dimension is not 16-byte aligned */
+    RAZER_ERR_CONFIG = 4,      /* bad format id, dtype or special value             */
+    RAZER_ERR_WORKSPACE = 5,   /* workspace missing, misaligned or too small        */
+    RAZER_ERR_HIP = 6          /* a kernel launch failed                            */
+} razer_status;
+
+typedef enum {
+    RAZER_FMT_WEIGHT = 0,      /* E3M3 scale + 2 metadata bits, 4 special values    */
+    RAZER_FMT_ACT = 1          /* E4M3 scale + 1 metadata bit, 2 special values     */
+} razer_format;
+
+typedef enum { RAZER_F32 = 0, RAZER_BF16 = 1 } razer_dtype;
+
+/* Special-value configuration.  Each magnitude must be 6 + an offset that the
+ * decoder's 4-bit offset register can hold (multiple of 0.5 in [-3.5, 3.5],
+ * Sec. 4.4) and must not be an FP4 value: {2.5,3.5,4.5,5,5.5,6.5,...,9.5}.
+ * The paper uses sv = {5, 8} for most models' weights ({5,7}, {5,9} for two)
+ * and {5} for activations (App. B.2).  sv[1] is ignored for RAZER_FMT_ACT. */
+typedef struct {
+    int32_t format;            /* razer_format */
+    float sv[2];
+} razer_config;
+
+/* A quantized tensor: device pointers + shape + configuration. */
+typedef struct {
+    const uint8_t *codes;        /* [rows][cols/2]  */
+    const uint8_t *scales;       /* [rows][cols/16] */
+    const float *tensor_scale;   /* device float    */
+    int64_t rows, cols;
+    razer_config cfg;
+} razer_tensor;
+
+enum { RAZER_OP_QUANTIZE = 0, RAZER_OP_DEQUANT = 1, RAZER_OP_LINEAR = 2 };
+
+/* razer_quantize flag: *tensor_scale is an input (a calibrated / static scale)
+ * instead of being computed from the tensor's absmax by Eq. 1. */
+#define RAZER_GIVEN_TENSOR_SCALE 1u
+
+/* Bytes of device workspace the given operation needs for these sizes
+ * (rows x cols operand; m = activation rows for RAZER_OP_LINEAR, else 0).
+ * Never more than a few MiB; 0 means the workspace may be NULL.            */
+size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m);
+
+/* Encoder: Eq. 1 (tensor scale), Eq. 2 (block scale, round-to-nearest-even on
+ * the format's scale grid, saturating), Eq. 4 (per block, the special value
+ * with the smallest squared error in the scaled domain, fp64 sum over the 16
+ * elements in index order, ties to the smallest metadata index) and Eq. 5
+ * (round-to-nearest on Q_FP4 U {special}; ties between FP4 values go to the
+ * even code, an FP4 value beats the special value on a tie, zero is always
+ * code 0).  A block whose scale rounds to 0 is written as all-zero codes.
+ *   x       device, [rows][ld] elements of dtype (fp32 or bf16), cols used per row
+ *   codes, scales, tensor_scale   device outputs (tensor_scale input with the flag)
+ *   workspace  device, >= razer_workspace_bytes(RAZER_OP_QUANTIZE, ...) bytes, 16-aligned
+ * Requirements: cols % 32 == 0, ld >= cols, x/codes/scales 16-byte aligned,
+ * ld * sizeof(elt) % 16 == 0.                                               */
+razer_status razer_quantize(const razer_config *cfg, const void *x, int32_t dtype,
+                            int64_t rows, int64_t cols, int64_t ld,
+                            uint8_t *codes, uint8_t *scales, float *tensor_scale,
+                            uint32_t flags, void *workspace, size_t workspace_bytes,
+                            void *hip_stream);
+
+/* Decoder (Sec. 3 dequantization identity, Sec. 4.4 decoder): out[r][k] =
+ * fp32(tensor_scale * (block_scale * element)), the inner product exact, one
+ * fp32 rounding; bf16 output is that fp32 rounded to nearest even.
+ *   out   device, [rows][ld] elements of dtype.  ld >= cols, 16-byte aligned rows. */
+razer_status razer_dequant(const razer_tensor *t, void *out, int32_t dtype, int64_t ld,
+                           void *hip_stream);
+
+/* Quantized linear layer Y = A W^T (Sec. 4.3 weight-only kernels; App. D.3
+ * weight-activation).  w is [N][K] in RAZER_FMT_WEIGHT.  Exactly one of
+ *   a_bf16  device bf16 [m][K] dense                      (W4A16), or
+ *   a_q     RAZER_FMT_ACT tensor [m][K]                   (W4A4)
+ * is non-NULL.  Products are accumulated in fp32 (bf16 matrix cores for large
+ * m, wavefront dot products for m <= 4), scaled by the tensor scale(s) and
+ * rounded to bf16:  y_bf16 device [m][ld_y], ld_y >= N.
+ * workspace: >= razer_workspace_bytes(RAZER_OP_LINEAR, N, K, m) bytes (may be 0). */
+razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer_tensor *a_q,
+                          int64_t m, void *y_bf16, int64_t ld_y,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+const char *razer_status_string(razer_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAZER_H */

@@ -1,0 +1,10 @@
+"""MI355X-native RaZeR (arxiv 2501.04052) weight-only / weight-activation linear layer.
+
+The product is the HIP shared library behind ``include/razer.h``; this package
+is its thin Python binding (argument marshalling only) plus seeded synthetic
+inputs.  There is no CPU fallback: without the built library every call raises.
+"""
+from .binding import (  # noqa: F401
+    ACT, BF16, F32, WEIGHT, RazerError, RazerTensor, lib_path, load_library, razer_dequant,
+    razer_linear, razer_quantize, razer_status_string, razer_workspace_bytes,
+)

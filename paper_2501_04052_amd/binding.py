@@ -1,0 +1,195 @@
+"""ctypes binding of the C ABI in include/razer.h.
+
+Same names, same arguments; torch supplies device memory and the current
+stream, nothing else.  Every step of the path runs in the library's kernels.
+"""
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "librazer_hip.so")
+
+WEIGHT, ACT = 0, 1
+F32, BF16 = 0, 1
+OP_QUANTIZE, OP_DEQUANT, OP_LINEAR = 0, 1, 2
+GIVEN_TENSOR_SCALE = 1
+
+EXPORTS = ["razer_workspace_bytes", "razer_quantize", "razer_dequant", "razer_linear",
+           "razer_status_string"]
+
+
+class RazerError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: status %d (%s)" % (where, status, razer_status_string(status)))
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [("format", ctypes.c_int32), ("sv", ctypes.c_float * 2)]
+
+
+class _Tensor(ctypes.Structure):
+    _fields_ = [("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("tensor_scale", ctypes.c_void_p), ("rows", ctypes.c_int64),
+                ("cols", ctypes.c_int64), ("cfg", _Config)]
+
+
+_lib = None
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the built library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError("librazer_hip.so is not built: run `python -m paper_2501_04052_amd.build` "
+                           "(or __graft_entry__.build()) first; there is no CPU fallback")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, u32, sz = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
+                             ctypes.c_size_t)
+    L.razer_workspace_bytes.restype = sz
+    L.razer_workspace_bytes.argtypes = [ctypes.c_int, i64, i64, i64]
+    L.razer_quantize.restype = ctypes.c_int
+    L.razer_quantize.argtypes = [ctypes.POINTER(_Config), vp, i32, i64, i64, i64, vp, vp, vp, u32,
+                                 vp, sz, vp]
+    L.razer_dequant.restype = ctypes.c_int
+    L.razer_dequant.argtypes = [ctypes.POINTER(_Tensor), vp, i32, i64, vp]
+    L.razer_linear.restype = ctypes.c_int
+    L.razer_linear.argtypes = [ctypes.POINTER(_Tensor), vp, ctypes.POINTER(_Tensor), i64, vp, i64,
+                               vp, sz, vp]
+    L.razer_status_string.restype = ctypes.c_char_p
+    L.razer_status_string.argtypes = [ctypes.c_int]
+    _lib = L
+    return L
+
+
+def razer_status_string(status):
+    return load_library().razer_status_string(int(status)).decode()
+
+
+def razer_workspace_bytes(op, rows, cols, m=0):
+    return int(load_library().razer_workspace_bytes(int(op), int(rows), int(cols), int(m)))
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _cfg(fmt, sv):
+    c = _Config()
+    c.format = fmt
+    c.sv[0] = float(sv[0])
+    c.sv[1] = float(sv[1]) if len(sv) > 1 else 0.0
+    return c
+
+
+class RazerTensor:
+    """A quantized tensor: device buffers + shape + configuration (razer_tensor in the ABI)."""
+
+    def __init__(self, codes, scales, tensor_scale, rows, cols, fmt, sv):
+        self.codes, self.scales, self.tensor_scale = codes, scales, tensor_scale
+        self.rows, self.cols, self.fmt, self.sv = int(rows), int(cols), fmt, tuple(sv)
+
+    def c_struct(self):
+        t = _Tensor()
+        t.codes = self.codes.data_ptr()
+        t.scales = self.scales.data_ptr()
+        t.tensor_scale = self.tensor_scale.data_ptr()
+        t.rows, t.cols = self.rows, self.cols
+        t.cfg = _cfg(self.fmt, self.sv)
+        return t
+
+    @staticmethod
+    def from_host(codes, scales, tensor_scale, fmt, sv, device="cuda"):
+        """Upload numpy codes [rows][cols/2], scales [rows][cols/16] and a scalar tensor scale."""
+        import numpy as np
+        rows, cols = codes.shape[0], codes.shape[1] * 2
+        return RazerTensor(torch.from_numpy(np.ascontiguousarray(codes)).to(device),
+                           torch.from_numpy(np.ascontiguousarray(scales)).to(device),
+                           torch.tensor([float(tensor_scale)], dtype=torch.float32, device=device),
+                           rows, cols, fmt, sv)
+
+
+def razer_quantize(x, fmt=WEIGHT, sv=(5.0, 8.0), tensor_scale=None, out=None, workspace=None, cols=None):
+    """Encode a 2-D device tensor x (float32 or bfloat16); blocks of 16 run along the last axis.
+
+    tensor_scale: optional 1-element float32 device tensor used as a given (static) scale.
+    cols: number of leading columns to encode when x's rows are longer (x.stride(0) is the ld).
+    Returns a RazerTensor whose buffers live on x's device."""
+    L = load_library()
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1
+    rows = x.shape[0]
+    cols = x.shape[1] if cols is None else cols
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[x.dtype]
+    dev = x.device
+    if out is None:
+        codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=dev)
+        scales = torch.empty((rows, cols // 16), dtype=torch.uint8, device=dev)
+        ts = torch.empty(1, dtype=torch.float32, device=dev) if tensor_scale is None else tensor_scale
+    else:
+        codes, scales, ts = out.codes, out.scales, out.tensor_scale
+    flags = 0 if tensor_scale is None else GIVEN_TENSOR_SCALE
+    if tensor_scale is not None and ts is not tensor_scale:
+        ts.copy_(tensor_scale)
+    need = razer_workspace_bytes(OP_QUANTIZE, rows, cols)
+    if workspace is None and not flags:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    cfg = _cfg(fmt, sv)
+    ld = x.stride(0) if rows > 1 else max(x.stride(0), cols)
+    st = L.razer_quantize(ctypes.byref(cfg), _ptr(x), dtype, rows, cols, ld, _ptr(codes), _ptr(scales),
+                          _ptr(ts), flags, _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                          _stream())
+    if st != 0:
+        raise RazerError(st, "razer_quantize")
+    return RazerTensor(codes, scales, ts, rows, cols, fmt, sv)
+
+
+def razer_dequant(t, dtype=torch.float32, out=None):
+    """Decode a RazerTensor to float32 or bfloat16 [rows][cols]."""
+    L = load_library()
+    if out is None:
+        out = torch.empty((t.rows, t.cols), dtype=dtype, device=t.codes.device)
+    code = {torch.float32: F32, torch.bfloat16: BF16}[out.dtype]
+    cs = t.c_struct()
+    ld = out.stride(0) if t.rows > 1 else max(out.stride(0), t.cols)
+    st = L.razer_dequant(ctypes.byref(cs), _ptr(out), code, ld, _stream())
+    if st != 0:
+        raise RazerError(st, "razer_dequant")
+    return out
+
+
+def razer_linear(w, a, out=None, workspace=None):
+    """Y = A W^T.  w: RazerTensor [N][K] (weight format).  a: bfloat16 [M][K] device tensor
+    (W4A16) or a RazerTensor [M][K] in the activation format (W4A4).  Returns bfloat16 [M][N]."""
+    L = load_library()
+    if isinstance(a, RazerTensor):
+        m = a.rows
+        a_struct = a.c_struct()
+        a_ptr, aq_ptr = None, ctypes.byref(a_struct)
+        dev = a.codes.device
+    else:
+        assert a.is_cuda and a.dtype == torch.bfloat16 and a.dim() == 2 and a.is_contiguous()
+        assert a.shape[1] == w.cols
+        m = a.shape[0]
+        a_ptr, aq_ptr = _ptr(a), None
+        dev = a.device
+    if out is None:
+        out = torch.empty((m, w.rows), dtype=torch.bfloat16, device=dev)
+    ws = w.c_struct()
+    ld_y = out.stride(0) if m > 1 else max(out.stride(0), w.rows)
+    st = L.razer_linear(ctypes.byref(ws), a_ptr, aq_ptr, m, _ptr(out), ld_y, _ptr(workspace),
+                        0 if workspace is None else workspace.numel(), _stream())
+    if st != 0:
+        raise RazerError(st, "razer_linear")
+    return out

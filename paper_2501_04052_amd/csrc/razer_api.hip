@@ -1,0 +1,163 @@
+// C ABI of the gfx950 RaZeR library: argument validation and kernel dispatch.
+// Every entry point enqueues on the caller's stream and returns; nothing here
+// allocates, synchronizes or keeps per-call state.
+#include "../../include/razer.h"
+#include "razer_kernels.hpp"
+
+using namespace razer;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// A special-value magnitude must be what the decoder's offset register can form:
+// 6 + (multiple of 0.5 in [-3.5, 3.5]) (Sec. 4.4), and not an FP4 value itself.
+bool sv_ok(float v)
+{
+    if (!(v >= 2.5f && v <= 9.5f)) return false;
+    float twice = v * 2.0f;
+    if (twice != (float)(int)twice) return false;
+    return v != 3.0f && v != 4.0f && v != 6.0f;
+}
+
+razer_status check_cfg(const razer_config& c, SvConfig& out)
+{
+    if (c.format != RAZER_FMT_WEIGHT && c.format != RAZER_FMT_ACT) return RAZER_ERR_CONFIG;
+    if (!sv_ok(c.sv[0])) return RAZER_ERR_CONFIG;
+    if (c.format == RAZER_FMT_WEIGHT && !sv_ok(c.sv[1])) return RAZER_ERR_CONFIG;
+    out.sv0 = c.sv[0];
+    out.sv1 = (c.format == RAZER_FMT_WEIGHT) ? c.sv[1] : c.sv[0];
+    return RAZER_OK;
+}
+
+razer_status check_tensor(const razer_tensor* t, int want_fmt, SvConfig& cfg)
+{
+    if (!t) return RAZER_ERR_NULL;
+    if (t->rows < 0 || t->cols < 0 || t->cols % 32 != 0) return RAZER_ERR_SHAPE;
+    razer_status s = check_cfg(t->cfg, cfg);
+    if (s != RAZER_OK) return s;
+    if (want_fmt >= 0 && t->cfg.format != want_fmt) return RAZER_ERR_CONFIG;
+    if (!t->tensor_scale) return RAZER_ERR_NULL;
+    if (t->rows > 0 && t->cols > 0) {
+        if (!t->codes || !t->scales) return RAZER_ERR_NULL;
+        if (!aligned16(t->codes) || !aligned16(t->scales)) return RAZER_ERR_ALIGN;
+    }
+    return RAZER_OK;
+}
+
+__global__ void fill_zero_bf16_kernel(uint16_t* y, int64_t m, int64_t n, int64_t ld)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < m * n) y[(i / n) * ld + (i % n)] = 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* razer_status_string(razer_status s)
+{
+    switch (s) {
+        case RAZER_OK: return "ok";
+        case RAZER_ERR_NULL: return "null pointer";
+        case RAZER_ERR_SHAPE: return "bad shape";
+        case RAZER_ERR_ALIGN: return "bad alignment";
+        case RAZER_ERR_CONFIG: return "bad configuration";
+        case RAZER_ERR_WORKSPACE: return "bad workspace";
+        case RAZER_ERR_HIP: return "HIP error";
+    }
+    return "unknown status";
+}
+
+size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m)
+{
+    (void)rows; (void)cols; (void)m;
+    switch (op) {
+        case RAZER_OP_QUANTIZE: return 256;    // the absmax cell of Eq. 1
+        default: return 0;
+    }
+}
+
+razer_status razer_quantize(const razer_config* cfg, const void* x, int32_t dtype, int64_t rows, int64_t cols,
+                            int64_t ld, uint8_t* codes, uint8_t* scales, float* tensor_scale, uint32_t flags,
+                            void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!cfg || !tensor_scale) return RAZER_ERR_NULL;
+    SvConfig sv;
+    razer_status s = check_cfg(*cfg, sv);
+    if (s != RAZER_OK) return s;
+    if (dtype != RAZER_F32 && dtype != RAZER_BF16) return RAZER_ERR_CONFIG;
+    if (flags & ~RAZER_GIVEN_TENSOR_SCALE) return RAZER_ERR_CONFIG;
+    if (rows < 0 || cols < 0 || cols % 32 != 0 || ld < cols) return RAZER_ERR_SHAPE;
+    const size_t esz = (dtype == RAZER_F32) ? 4 : 2;
+    if (rows > 0 && cols > 0) {
+        if (!x || !codes || !scales) return RAZER_ERR_NULL;
+        if (!aligned16(x) || !aligned16(codes) || !aligned16(scales) || ((size_t)ld * esz) % 16 != 0)
+            return RAZER_ERR_ALIGN;
+    }
+    const int given = (flags & RAZER_GIVEN_TENSOR_SCALE) ? 1 : 0;
+    if (!given) {
+        if (!workspace || workspace_bytes < razer_workspace_bytes(RAZER_OP_QUANTIZE, rows, cols, 0) ||
+            !aligned16(workspace))
+            return RAZER_ERR_WORKSPACE;
+    }
+    hipError_t e = launch_quantize(cfg->format, sv, x, dtype == RAZER_BF16, rows, cols, ld, codes, scales,
+                                   tensor_scale, given, workspace, (hipStream_t)hip_stream);
+    return e == hipSuccess ? RAZER_OK : RAZER_ERR_HIP;
+}
+
+razer_status razer_dequant(const razer_tensor* t, void* out, int32_t dtype, int64_t ld, void* hip_stream)
+{
+    SvConfig sv;
+    razer_status s = check_tensor(t, -1, sv);
+    if (s != RAZER_OK) return s;
+    if (dtype != RAZER_F32 && dtype != RAZER_BF16) return RAZER_ERR_CONFIG;
+    if (ld < t->cols) return RAZER_ERR_SHAPE;
+    const size_t esz = (dtype == RAZER_F32) ? 4 : 2;
+    if (t->rows > 0 && t->cols > 0) {
+        if (!out) return RAZER_ERR_NULL;
+        if (!aligned16(out) || ((size_t)ld * esz) % 16 != 0) return RAZER_ERR_ALIGN;
+    }
+    hipError_t e = launch_dequant(t->cfg.format, sv, t->codes, t->scales, t->tensor_scale, t->rows, t->cols, out,
+                                  dtype == RAZER_BF16, ld, (hipStream_t)hip_stream);
+    return e == hipSuccess ? RAZER_OK : RAZER_ERR_HIP;
+}
+
+razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer_tensor* a_q, int64_t m,
+                          void* y_bf16, int64_t ld_y, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    SvConfig wsv, asv = {5.0f, 5.0f};
+    razer_status s = check_tensor(w, RAZER_FMT_WEIGHT, wsv);
+    if (s != RAZER_OK) return s;
+    if (m < 0 || ld_y < w->rows) return RAZER_ERR_SHAPE;
+    if (m == 0 && !a_q) return RAZER_OK;                                  // nothing to compute, operands may be NULL
+    if ((a_bf16 == nullptr) == (a_q == nullptr)) return RAZER_ERR_NULL;   // exactly one activation operand
+    const int64_t n = w->rows, k = w->cols;
+    if (a_q) {
+        s = check_tensor(a_q, RAZER_FMT_ACT, asv);
+        if (s != RAZER_OK) return s;
+        if (a_q->rows != m || a_q->cols != k) return RAZER_ERR_SHAPE;
+    } else if (m > 0 && k > 0 && !aligned16(a_bf16)) {
+        return RAZER_ERR_ALIGN;
+    }
+    if (m > 0 && n > 0 && !y_bf16) return RAZER_ERR_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (m == 0 || n == 0) return RAZER_OK;
+    hipError_t e;
+    if (k == 0) {                                                        // empty contraction: Y = 0
+        const int64_t total = m * n;
+        fill_zero_bf16_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((uint16_t*)y_bf16, m, n, ld_y);
+        e = hipGetLastError();
+    } else if (!a_q && m <= kGemvMaxM) {
+        e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
+                        (uint16_t*)y_bf16, ld_y, st);
+    } else {
+        e = launch_gemm(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, asv,
+                        a_q ? a_q->codes : nullptr, a_q ? a_q->scales : nullptr,
+                        a_q ? a_q->tensor_scale : nullptr, m, (uint16_t*)y_bf16, ld_y, st);
+    }
+    return e == hipSuccess ? RAZER_OK : RAZER_ERR_HIP;
+}
+
+}  // extern "C"

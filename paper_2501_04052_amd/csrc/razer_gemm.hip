@@ -1,0 +1,279 @@
+// RaZeR linear layer on the gfx950 bf16 matrix cores (prefill-shaped problems,
+// Sec. 4.3 of arxiv 2501.04052; weight-activation mode of App. D.3 by decoding
+// both operands): packed codes are read from HBM, decoded to scaled bf16 in
+// registers, staged in LDS and consumed by v_mfma_f32_32x32x16_bf16 with fp32
+// accumulation.  block_scale * element needs at most 8 significant bits for the
+// paper's special values, so the bf16 tile is exact; the tensor scale(s) multiply
+// the fp32 accumulator once at the end.
+//
+// Tile: BM activation rows x BN weight rows x 64 k per stage, double-buffered.
+// LDS rows are 128 B (64 bf16); 16-byte chunks are xor-swizzled with the row so
+// that the 128-bit MFMA operand reads of 32 consecutive rows hit distinct banks.
+// The weight fragment is the MFMA "A" operand (rows = n) and the activation
+// fragment the "B" operand (columns = m), so every lane ends up holding 4
+// consecutive n of one output row and stores them as one 8-byte write.
+#include "razer_device.hpp"
+#include "razer_kernels.hpp"
+
+namespace razer {
+
+constexpr int kBK = 64;
+
+// LUT entry per scale byte: { block scale (fp32 bits), -(special * scale) as a bf16 pair }.
+template <int FMT>
+__device__ __forceinline__ void fill_scaled_lut(uint2* lut, SvConfig cfg, int tid, int nthreads)
+{
+    for (uint32_t sb = tid; sb < 256u; sb += nthreads) {
+        float s, sv;
+        decode_scale_byte<FMT>(sb, cfg, s, sv);
+        const uint32_t p = (uint32_t)f32_to_bf16_rne(-(sv * s));
+        lut[sb] = make_uint2(f2u(s), p | (p << 16));
+    }
+}
+
+template <int BYTE>
+__device__ __forceinline__ uint32_t cvt_scaled_pair(uint32_t xflip, float s, uint32_t patch)
+{
+    v2f p = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(xflip, 1.0f, BYTE);   // -element, exact
+    p.x *= s;                                                              // exact (<= 6 significant bits)
+    p.y *= s;
+    v2bf b = __builtin_convertvector(p, v2bf);                             // exact
+    return patch_zero_halves(__builtin_bit_cast(uint32_t, b), patch);
+}
+// 8 codes of one block -> 8 scaled, negated bf16 values (one 16-byte LDS chunk).
+__device__ __forceinline__ uint4 decode_dword(uint32_t x, uint2 lut_entry)
+{
+    const uint32_t xf = x ^ kRemapXor;
+    const float s = u2f(lut_entry.x);
+    return make_uint4(cvt_scaled_pair<0>(xf, s, lut_entry.y), cvt_scaled_pair<1>(xf, s, lut_entry.y),
+                      cvt_scaled_pair<2>(xf, s, lut_entry.y), cvt_scaled_pair<3>(xf, s, lut_entry.y));
+}
+
+__device__ __forceinline__ uint32_t lds_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+
+template <int BM, int BN, int WGM, int WGN, bool AQ>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
+    const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
+    SvConfig wcfg, int64_t n, int64_t k, const uint16_t* __restrict__ a, const uint8_t* __restrict__ a_codes,
+    const uint8_t* __restrict__ a_scales, const float* __restrict__ a_ts, SvConfig acfg, int64_t m,
+    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m)
+{
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
+    constexpr int NU_A = AQ ? (BM * 2 + NT - 1) / NT : (BM * 8) / NT;   // units per thread: 16 B of global data each
+    constexpr int NU_B = (BN * 2 + NT - 1) / NT;
+    static_assert(AQ || (BM * 8) % NT == 0, "A tile must divide over the threads");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
+
+    extern __shared__ __align__(16) uint8_t smem[];
+    uint8_t* As = smem;                              // 2 stages x BM x 128 B
+    uint8_t* Bs = smem + 2 * BM * 128;               // 2 stages x BN x 128 B
+    uint2* wlut = reinterpret_cast<uint2*>(smem + 2 * (BM + BN) * 128);
+    uint2* alut = wlut + 256;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+    const int KT = (int)((k + kBK - 1) / kBK);
+
+    fill_scaled_lut<0>(wlut, wcfg, tid, NT);
+    if (AQ) fill_scaled_lut<1>(alut, acfg, tid, NT);
+
+    v16f acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    uint4 ra[NU_A];
+    uint32_t rsa[NU_A];
+    uint4 rb[NU_B];
+    uint32_t rsb[NU_B];
+
+    auto load_tiles = [&](int kt) {
+        const int64_t kbase = (int64_t)kt * kBK;
+        if (AQ) {
+#pragma unroll
+            for (int i = 0; i < NU_A; ++i) {
+                const int u = tid + i * NT, row = u >> 1, half = u & 1;
+                const int64_t gr = m0 + row, kk = kbase + half * 32;
+                ra[i] = make_uint4(0, 0, 0, 0);
+                rsa[i] = 0;
+                if (u < BM * 2 && gr < m && kk < k) {
+                    ra[i] = *reinterpret_cast<const uint4*>(a_codes + gr * (k / 2) + kk / 2);
+                    rsa[i] = *reinterpret_cast<const uint16_t*>(a_scales + gr * (k / 16) + kk / 16);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NU_A; ++i) {
+                const int u = tid + i * NT, row = u >> 3, chunk = u & 7;
+                const int64_t gr = m0 + row, kk = kbase + chunk * 8;
+                ra[i] = make_uint4(0, 0, 0, 0);
+                if (gr < m && kk < k) ra[i] = *reinterpret_cast<const uint4*>(a + gr * k + kk);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NU_B; ++i) {
+            const int u = tid + i * NT, row = u >> 1, half = u & 1;
+            const int64_t gr = n0 + row, kk = kbase + half * 32;
+            rb[i] = make_uint4(0, 0, 0, 0);
+            rsb[i] = 0;
+            if (u < BN * 2 && gr < n && kk < k) {
+                rb[i] = *reinterpret_cast<const uint4*>(w_codes + gr * (k / 2) + kk / 2);
+                rsb[i] = *reinterpret_cast<const uint16_t*>(w_scales + gr * (k / 16) + kk / 16);
+            }
+        }
+    };
+    // part q (0..3) of the register-held tiles -> LDS stage st
+    auto store_part = [&](int st, int q) {
+        uint8_t* as = As + st * BM * 128;
+        uint8_t* bs = Bs + st * BN * 128;
+        if (AQ) {
+#pragma unroll
+            for (int i = 0; i < NU_A; ++i) {
+                const int u = tid + i * NT, row = u >> 1, half = u & 1;
+                if (u < BM * 2) {
+                    const uint32_t x = (q == 0) ? ra[i].x : (q == 1) ? ra[i].y : (q == 2) ? ra[i].z : ra[i].w;
+                    const uint2 le = alut[(rsa[i] >> (8 * (q >> 1))) & 255u];
+                    *reinterpret_cast<uint4*>(as + lds_off(row, half * 4 + q)) = decode_dword(x, le);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NU_A; ++i) {
+                if ((i & 3) == q) {
+                    const int u = tid + i * NT, row = u >> 3, chunk = u & 7;
+                    *reinterpret_cast<uint4*>(as + lds_off(row, chunk)) = ra[i];
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NU_B; ++i) {
+            const int u = tid + i * NT, row = u >> 1, half = u & 1;
+            if (u < BN * 2) {
+                const uint32_t x = (q == 0) ? rb[i].x : (q == 1) ? rb[i].y : (q == 2) ? rb[i].z : rb[i].w;
+                const uint2 le = wlut[(rsb[i] >> (8 * (q >> 1))) & 255u];
+                *reinterpret_cast<uint4*>(bs + lds_off(row, half * 4 + q)) = decode_dword(x, le);
+            }
+        }
+    };
+
+    load_tiles(0);
+    __syncthreads();                                   // LUTs ready
+#pragma unroll
+    for (int q = 0; q < 4; ++q) store_part(0, q);
+    __syncthreads();
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const int st = kt & 1;
+        const bool more = kt + 1 < KT;
+        if (more) load_tiles(kt + 1);
+        const uint8_t* as = As + st * BM * 128;
+        const uint8_t* bs = Bs + st * BN * 128;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            v8bf fw[TN], fa[TM];
+            const int chunk = ks * 2 + (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+                fw[i] = *reinterpret_cast<const v8bf*>(bs + lds_off(wn * WTN + i * 32 + (lane & 31), chunk));
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+                fa[j] = *reinterpret_cast<const v8bf*>(as + lds_off(wm * WTM + j * 32 + (lane & 31), chunk));
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+            if (more) store_part(st ^ 1, ks);
+        }
+        __syncthreads();
+    }
+
+    // epilogue: undo the sign flip of the weight decode (and of the activation decode
+    // in W4A4, where the two flips cancel), apply the tensor scales, round to bf16.
+    float scale = AQ ? (*w_ts) * (*a_ts) : -(*w_ts);
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int64_t gm = m0 + wm * WTM + j * 32 + (lane & 31);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int64_t gn = n0 + wn * WTN + i * 32 + 8 * g + 4 * (lane >> 5);
+                if (gm < m && gn < n) {
+                    uint16_t o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_rne(acc[i][j][4 * g + e] * scale);
+                    uint16_t* dst = y + gm * ld_y + gn;
+                    if (gn + 3 < n && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {
+                        *reinterpret_cast<uint2*>(dst) =
+                            make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (gn + e < n) dst[e] = o[e];
+                    }
+                }
+            }
+        }
+}
+
+template <int BM, int BN, int WGM, int WGN, bool AQ>
+static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
+                             int64_t n, int64_t k, const uint16_t* a, const uint8_t* a_codes,
+                             const uint8_t* a_scales, const float* a_ts, SvConfig acfg, int64_t m, uint16_t* y,
+                             int64_t ld_y, hipStream_t st)
+{
+    constexpr size_t smem = 2 * (BM + BN) * 128 + 2 * 256 * sizeof(uint2);
+    auto kern = gemm_kernel<BM, BN, WGM, WGN, AQ>;
+    static bool attr_set = false;                      // one GPU per process
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
+    kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WGM * WGN), smem, st>>>(
+        w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, tiles_m);
+    return hipGetLastError();
+}
+
+template <bool AQ>
+static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
+                                int64_t n, int64_t k, const uint16_t* a, const uint8_t* a_codes,
+                                const uint8_t* a_scales, const float* a_ts, SvConfig acfg, int64_t m, uint16_t* y,
+                                int64_t ld_y, hipStream_t st)
+{
+#define RAZER_GEMM(BM, BN, WGM, WGN) \
+    launch_cfg<BM, BN, WGM, WGN, AQ>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st)
+    if (m <= 32) return RAZER_GEMM(32, 256, 1, 4);
+    if (m <= 64) return RAZER_GEMM(64, 256, 1, 4);
+    if (m <= 128) return RAZER_GEMM(128, 128, 2, 2);
+    // Large m: 256-row activation tiles so every weight is decoded once per 256 rows.  Pick the
+    // weight-tile width that wastes fewer of the 256 compute units in the last round of workgroups.
+    const int64_t tm = (m + 255) / 256;
+    const int64_t t256 = tm * ((n + 255) / 256), t128 = tm * ((n + 127) / 128);
+    auto eff = [](int64_t tiles) { return (double)tiles / (double)(((tiles + 255) / 256) * 256); };
+    if (eff(t256) >= eff(t128)) return RAZER_GEMM(256, 256, 2, 4);
+    return RAZER_GEMM(256, 128, 4, 2);
+#undef RAZER_GEMM
+}
+
+hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
+                       int64_t n, int64_t k, const uint16_t* a, SvConfig acfg, const uint8_t* a_codes,
+                       const uint8_t* a_scales, const float* a_ts, int64_t m, uint16_t* y, int64_t ld_y,
+                       hipStream_t st)
+{
+    if (n == 0 || m == 0) return hipSuccess;
+    if (a_codes)
+        return launch_gemm_t<true>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st);
+    return launch_gemm_t<false>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st);
+}
+
+}  // namespace razer

@@ -1,0 +1,168 @@
+// Weight-only RaZeR linear layer for 1..4 activation rows on gfx950 (the decode
+// regime of Sec. 4.3 / App. D.2 of arxiv 2501.04052): fused decode + dot product,
+// bound by the HBM read of the packed weights (0.5625 B per weight).
+//
+// Mapping.  A workgroup owns R consecutive weight rows; its waves split K into
+// slices of 2048 elements.  In a slice lane l owns the 16-byte code chunk
+// [32 l, 32 l + 32) of every row -- so a wave reads 1 KiB of consecutive codes
+// and 128 B of consecutive scale bytes per row -- and keeps the matching 32
+// activations of each activation row in registers across the R rows.
+//
+// Decode.  The 8 codes of a dword are sign-flipped with one xor, converted to
+// packed bf16 pairs by the hardware FP4 conversion, and the (now all-zero)
+// remapped slots are patched with the block's special value by two packed
+// 16-bit integer ops.  Pairs go straight into v_dot2_f32_bf16 against the
+// activation pairs; the block scale (negated, undoing the sign flip) multiplies
+// the 16-element partial sum once per block.
+#include "razer_device.hpp"
+#include "razer_kernels.hpp"
+
+namespace razer {
+
+constexpr int kSliceK = 2048;          // K elements one wave covers per pass: 64 lanes x 32 codes
+constexpr int kMaxWaves = 16;
+
+// Per scale byte: { -block_scale (fp32 bits), negated special value as a bf16 pair }.
+__device__ __forceinline__ void fill_weight_lut(uint2* lut, SvConfig cfg)
+{
+    for (uint32_t sb = threadIdx.x; sb < 256u; sb += blockDim.x) {
+        float s, sv;
+        decode_scale_byte<0>(sb, cfg, s, sv);
+        const uint32_t nsv = (uint32_t)f32_to_bf16_rne(-sv);              // exact: multiples of 0.5 below 16
+        lut[sb] = make_uint2(f2u(-s), nsv | (nsv << 16));
+    }
+}
+
+template <int BYTE>
+__device__ __forceinline__ uint32_t cvt_pair(uint32_t x)
+{
+    v2bf p = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(x, 1.0f, BYTE);
+    return __builtin_bit_cast(uint32_t, p);
+}
+__device__ __forceinline__ float dot2(uint32_t w, uint32_t a, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, w), __builtin_bit_cast(v2bf, a), acc, false);
+}
+
+template <int M, int R>
+__global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __restrict__ codes,
+                                                              const uint8_t* __restrict__ scales,
+                                                              const float* __restrict__ w_ts, SvConfig cfg,
+                                                              int64_t n, int64_t k,
+                                                              const uint16_t* __restrict__ a,
+                                                              uint16_t* __restrict__ y, int64_t ld_y)
+{
+    __shared__ uint2 lut[256];
+    __shared__ float part[kMaxWaves][R][M];
+    fill_weight_lut(lut, cfg);
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int64_t row0 = (int64_t)blockIdx.x * R;
+    const int64_t chunks = k / 32;                                        // 16-byte code chunks per row
+    const int64_t nslices = (k + kSliceK - 1) / kSliceK;
+
+    float acc[R][M];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int m = 0; m < M; ++m) acc[r][m] = 0.0f;
+
+    for (int64_t sl = wave; sl < nslices; sl += nwaves) {
+        const int64_t c = sl * 64 + lane;
+        if (c < chunks) {
+            // activations of this lane's 32 k's, all M rows
+            uint4 av[M][4];
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const uint4* ap = reinterpret_cast<const uint4*>(a + (int64_t)m * k + c * 32);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) av[m][j] = ap[j];
+            }
+            uint4 cw[R];
+            uint32_t sw[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int64_t row = (row0 + r < n) ? row0 + r : n - 1;   // clamp: tail rows recompute the last row
+                cw[r] = *reinterpret_cast<const uint4*>(codes + row * (k / 2) + c * 16);
+                sw[r] = *reinterpret_cast<const uint16_t*>(scales + row * (k / 16) + c * 2);
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const uint32_t xw[4] = {cw[r].x, cw[r].y, cw[r].z, cw[r].w};
+#pragma unroll
+                for (int blk = 0; blk < 2; ++blk) {
+                    const uint2 le = lut[(sw[r] >> (8 * blk)) & 255u];
+                    const float ns = u2f(le.x);
+                    float p[M];
+#pragma unroll
+                    for (int m = 0; m < M; ++m) p[m] = 0.0f;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t x = xw[2 * blk + h] ^ kRemapXor;
+                        const uint32_t w0 = patch_zero_halves(cvt_pair<0>(x), le.y);
+                        const uint32_t w1 = patch_zero_halves(cvt_pair<1>(x), le.y);
+                        const uint32_t w2 = patch_zero_halves(cvt_pair<2>(x), le.y);
+                        const uint32_t w3 = patch_zero_halves(cvt_pair<3>(x), le.y);
+#pragma unroll
+                        for (int m = 0; m < M; ++m) {
+                            const uint4 aq = av[m][2 * blk + h];
+                            p[m] = dot2(w0, aq.x, p[m]);
+                            p[m] = dot2(w1, aq.y, p[m]);
+                            p[m] = dot2(w2, aq.z, p[m]);
+                            p[m] = dot2(w3, aq.w, p[m]);
+                        }
+                    }
+#pragma unroll
+                    for (int m = 0; m < M; ++m) acc[r][m] = __builtin_fmaf(ns, p[m], acc[r][m]);
+                }
+            }
+        }
+    }
+
+    // lanes -> wave total (lane 63), waves -> workgroup total through LDS
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            const float t = wave_sum_to_lane63(acc[r][m]);
+            if (lane == 63) part[wave][r][m] = t;
+        }
+    __syncthreads();
+    if (threadIdx.x < R * M) {
+        const int r = threadIdx.x / M, m = threadIdx.x % M;
+        if (row0 + r < n) {
+            float t = 0.0f;
+            for (int w = 0; w < nwaves; ++w) t += part[w][r][m];
+            y[(int64_t)m * ld_y + row0 + r] = f32_to_bf16_rne(t * (*w_ts));
+        }
+    }
+}
+
+template <int M>
+static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,
+                                int64_t n, int64_t k, const uint16_t* a, uint16_t* y, int64_t ld_y, hipStream_t st)
+{
+    constexpr int R = 4;
+    int64_t nslices = (k + kSliceK - 1) / kSliceK;
+    int nwaves = (int)(nslices < kMaxWaves ? nslices : kMaxWaves);
+    unsigned grid = (unsigned)((n + R - 1) / R);
+    gemv_kernel<M, R><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg, n, k, a, y, ld_y);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
+                       int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
+                       hipStream_t st)
+{
+    if (n == 0 || m == 0) return hipSuccess;
+    switch (m) {
+        case 1: return launch_gemv_m<1>(wcfg, w_codes, w_scales, w_ts, n, k, a, y, ld_y, st);
+        case 2: return launch_gemv_m<2>(wcfg, w_codes, w_scales, w_ts, n, k, a, y, ld_y, st);
+        case 3: return launch_gemv_m<3>(wcfg, w_codes, w_scales, w_ts, n, k, a, y, ld_y, st);
+        case 4: return launch_gemv_m<4>(wcfg, w_codes, w_scales, w_ts, n, k, a, y, ld_y, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace razer

@@ -1,0 +1,32 @@
+// Host-side launchers of the gfx950 RaZeR kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "razer_device.hpp"
+
+namespace razer {
+
+// Encoder (absmax pass + block encoder).  ws: >= 16 bytes of device scratch.
+hipError_t launch_quantize(int fmt, SvConfig cfg, const void* x, int dtype_bf16, int64_t rows, int64_t cols,
+                           int64_t ld, uint8_t* codes, uint8_t* scales, float* tensor_scale, int given,
+                           void* ws, hipStream_t st);
+
+// Decoder to fp32 or bf16.
+hipError_t launch_dequant(int fmt, SvConfig cfg, const uint8_t* codes, const uint8_t* scales,
+                          const float* tensor_scale, int64_t rows, int64_t cols, void* out, int dtype_bf16,
+                          int64_t ld, hipStream_t st);
+
+// Y[m][n] = A[m][:] . W[n][:], m <= kGemvMaxM: wavefront dot products, HBM-bound.
+constexpr int kGemvMaxM = 4;
+hipError_t launch_gemv(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
+                       int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
+                       hipStream_t st);
+
+// Same contraction on bf16 matrix cores with LDS-staged decoded tiles.  Activations are
+// bf16 (a != nullptr) or RaZeR activation-format (a_codes != nullptr).
+hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
+                       int64_t n, int64_t k, const uint16_t* a, SvConfig acfg, const uint8_t* a_codes,
+                       const uint8_t* a_scales, const float* a_ts, int64_t m, uint16_t* y, int64_t ld_y,
+                       hipStream_t st);
+
+}  // namespace razer

@@ -1,0 +1,216 @@
+// RaZeR block encoder for gfx950: Eq. 1 (tensor scale), Eq. 2 (block scale),
+// Eq. 4 (special-value search) and Eq. 5 (final rounding) of arxiv 2501.04052.
+//
+// Bit-exactness contract: every fp32 operation below is a single IEEE operation
+// (true division, no reciprocal, no contraction), squared errors are summed in
+// fp64 over the 16 elements in index order, and ties are broken as documented
+// in razer.h.  Compile without fast-math.
+#include "razer_device.hpp"
+#include "razer_kernels.hpp"
+
+namespace razer {
+
+// ---------------------------------------------------------------- absmax (Eq. 1)
+__global__ void absmax_init_kernel(uint32_t* ws) { ws[0] = 0u; }
+
+template <typename T>
+__global__ __launch_bounds__(256) void absmax_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
+                                                     int64_t ld, uint32_t* __restrict__ ws)
+{
+    // 16-byte vectors: 4 floats or 8 bf16.  |x| of finite non-negative floats orders like uint32.
+    constexpr int VEC = 16 / sizeof(T);
+    const int64_t vec_per_row = cols / VEC;
+    const int64_t total = rows * vec_per_row;
+    uint32_t m = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        int64_t r = i / vec_per_row, c = i - r * vec_per_row;
+        uint4 v = *reinterpret_cast<const uint4*>(x + r * ld + c * VEC);
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (sizeof(T) == 4) {
+                m = max(m, w[j] & 0x7FFFFFFFu);
+            } else {
+                m = max(m, (w[j] << 16) & 0x7FFFFFFFu);
+                m = max(m, w[j] & 0x7FFF0000u);
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+    if ((threadIdx.x & 63) == 0) atomicMax(ws, m);
+}
+
+// ---------------------------------------------------------------- scale rounding (Eq. 2)
+// Nearest value of the scale grid, ties to the even code, saturating at the top.
+template <int FMT>
+__device__ __forceinline__ uint32_t round_scale(float t)
+{
+    constexpr float kMinNormal = (FMT == 0) ? 0.25f : 0.015625f;          // 2^-2 / 2^-6
+    constexpr float kSubScale = (FMT == 0) ? 32.0f : 512.0f;              // 1 / subnormal step
+    constexpr uint32_t kBiasAdj = (FMT == 0) ? (124u << 3) : (120u << 3);
+    constexpr uint32_t kMaxCode = (FMT == 0) ? 63u : 126u;
+    uint32_t code;
+    if (t < kMinNormal) {
+        code = (uint32_t)__builtin_rintf(t * kSubScale);                  // exact product, RNE
+    } else {
+        uint32_t b = f2u(t);
+        b += 0x7FFFFu + ((b >> 20) & 1u);                                 // RNE to 3 mantissa bits
+        code = (b >> 20) - kBiasAdj;
+    }
+    return code > kMaxCode ? kMaxCode : code;
+}
+
+// ---------------------------------------------------------------- block encoder
+// One thread encodes one block of 16 elements.
+template <typename T, int FMT>
+__global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
+                                                     int64_t ld, SvConfig cfg,
+                                                     const uint32_t* __restrict__ absmax_ws,
+                                                     float* __restrict__ tensor_scale, int given_scale,
+                                                     uint8_t* __restrict__ codes, uint8_t* __restrict__ scales)
+{
+    constexpr int NC = (FMT == 0) ? 4 : 2;
+    const int64_t nb = cols / kBlock;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+
+    float delta32;
+    if (given_scale) {
+        delta32 = *tensor_scale;
+    } else {
+        float amax = u2f(*absmax_ws);
+        constexpr float kDenom = (FMT == 0) ? 180.0f : 2688.0f;           // Qmax_scale * 6
+        delta32 = (amax == 0.0f) ? 1.0f : amax / kDenom;
+        if (gid == 0) *tensor_scale = delta32;
+    }
+    if (gid >= rows * nb) return;
+    const int64_t r = gid / nb, b = gid - r * nb;
+
+    float xv[kBlock];
+    if (sizeof(T) == 4) {
+        const uint4* p = reinterpret_cast<const uint4*>(x + r * ld + b * kBlock);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint4 v = p[j];
+            xv[4 * j + 0] = u2f(v.x); xv[4 * j + 1] = u2f(v.y);
+            xv[4 * j + 2] = u2f(v.z); xv[4 * j + 3] = u2f(v.w);
+        }
+    } else {
+        const uint4* p = reinterpret_cast<const uint4*>(x + r * ld + b * kBlock);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            uint4 v = p[j];
+            uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                xv[8 * j + 2 * i + 0] = u2f(w[i] << 16);
+                xv[8 * j + 2 * i + 1] = u2f(w[i] & 0xFFFF0000u);
+            }
+        }
+    }
+
+    float bmax = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kBlock; ++k) bmax = fmaxf(bmax, fabsf(xv[k]));
+
+    // Eq. 2
+    const float d = delta32 * 6.0f;
+    const float t = bmax / d;
+    const uint32_t sc = round_scale<FMT>(t);
+    const float s = (FMT == 0) ? e3m3_value(sc) : e4m3_value(sc);
+
+    uint32_t lo = 0, hi = 0, meta = 0;                                    // 16 nibbles, low dword = k 0..7
+    if (s != 0.0f) {
+        const float den = delta32 * s;
+        double cand[NC];
+        if (FMT == 0) { cand[0] = cfg.sv0; cand[1] = cfg.sv1; cand[2] = -cfg.sv0; cand[3] = -cfg.sv1; }
+        else { cand[0] = cfg.sv0; cand[1] = -cfg.sv0; }
+        double sse[NC];
+        uint32_t take[NC];                                                // bit k: element k takes the special value
+#pragma unroll
+        for (int m = 0; m < NC; ++m) { sse[m] = 0.0; take[m] = 0u; }
+#pragma unroll
+        for (int k = 0; k < kBlock; ++k) {
+            const float xs = xv[k] / den;                                 // X^Scaled
+            const float a = fabsf(xs);
+            // nearest FP4 magnitude, ties to the even code
+            uint32_t c = (uint32_t)(a > 0.25f) + (uint32_t)(a >= 0.75f) + (uint32_t)(a > 1.25f) +
+                         (uint32_t)(a >= 1.75f) + (uint32_t)(a > 2.5f) + (uint32_t)(a >= 3.5f) +
+                         (uint32_t)(a > 5.0f);
+            const float qmag = (c < 4u) ? 0.5f * (float)c : ((c & 1u) ? 1.5f : 1.0f) * (float)(1u << ((c >> 1) - 1u));
+            const float q = (xs < 0.0f) ? -qmag : qmag;
+            if (c != 0u && xs < 0.0f) c |= 8u;
+            if (k < 8) lo |= c << (4 * k); else hi |= c << (4 * (k - 8));
+            const double eb = (double)xs - (double)q;
+#pragma unroll
+            for (int m = 0; m < NC; ++m) {
+                const double ev = (double)xs - cand[m];
+                const bool sp = fabs(ev) < fabs(eb);
+                const double e = sp ? ev : eb;
+                sse[m] += e * e;                                          // e*e is exact in fp64
+                take[m] |= (uint32_t)sp << k;
+            }
+        }
+        // Eq. 4: smallest error, ties to the smallest metadata index
+        double best = sse[0];
+#pragma unroll
+        for (int m = 1; m < NC; ++m)
+            if (sse[m] < best) { best = sse[m]; meta = m; }
+        uint32_t tk = take[0];
+#pragma unroll
+        for (int m = 1; m < NC; ++m) tk = (meta == (uint32_t)m) ? take[m] : tk;
+        // Eq. 5: taken elements get the remapped code 0x8
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if (tk & (1u << k)) lo = (lo & ~(0xFu << (4 * k))) | (0x8u << (4 * k));
+            if (tk & (1u << (k + 8))) hi = (hi & ~(0xFu << (4 * k))) | (0x8u << (4 * k));
+        }
+    }
+    *reinterpret_cast<uint2*>(codes + r * (cols / 2) + b * 8) = make_uint2(lo, hi);
+    scales[r * nb + b] = (uint8_t)((meta << (FMT == 0 ? 6 : 7)) | sc);
+}
+
+// ---------------------------------------------------------------- host launchers
+template <typename T>
+static hipError_t launch_quantize_t(int fmt, SvConfig cfg, const T* x, int64_t rows, int64_t cols, int64_t ld,
+                                    uint8_t* codes, uint8_t* scales, float* tensor_scale, int given,
+                                    uint32_t* ws, hipStream_t st)
+{
+    if (rows == 0 || cols == 0) {
+        if (!given) {                       // an empty tensor gets the all-zero tensor's scale of 1
+            absmax_init_kernel<<<1, 1, 0, st>>>(ws);
+            if (fmt == 0) encode_kernel<T, 0><<<1, 64, 0, st>>>(x, 0, 16, 16, cfg, ws, tensor_scale, 0, codes, scales);
+            else encode_kernel<T, 1><<<1, 64, 0, st>>>(x, 0, 16, 16, cfg, ws, tensor_scale, 0, codes, scales);
+        }
+        return hipGetLastError();
+    }
+    if (!given) {
+        absmax_init_kernel<<<1, 1, 0, st>>>(ws);
+        constexpr int VEC = 16 / sizeof(T);
+        int64_t total = rows * (cols / VEC);
+        int64_t blocks = (total + 255) / 256;
+        if (blocks > 256 * 16) blocks = 256 * 16;
+        absmax_kernel<T><<<(unsigned)blocks, 256, 0, st>>>(x, rows, cols, ld, ws);
+    }
+    int64_t nblk = rows * (cols / kBlock);
+    unsigned grid = (unsigned)((nblk + 255) / 256);
+    if (fmt == 0)
+        encode_kernel<T, 0><<<grid, 256, 0, st>>>(x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
+    else
+        encode_kernel<T, 1><<<grid, 256, 0, st>>>(x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize(int fmt, SvConfig cfg, const void* x, int dtype_bf16, int64_t rows, int64_t cols,
+                           int64_t ld, uint8_t* codes, uint8_t* scales, float* tensor_scale, int given,
+                           void* ws, hipStream_t st)
+{
+    if (dtype_bf16)
+        return launch_quantize_t<uint16_t>(fmt, cfg, (const uint16_t*)x, rows, cols, ld, codes, scales,
+                                           tensor_scale, given, (uint32_t*)ws, st);
+    return launch_quantize_t<float>(fmt, cfg, (const float*)x, rows, cols, ld, codes, scales, tensor_scale,
+                                    given, (uint32_t*)ws, st);
+}
+
+}  // namespace razer

@@ -1,0 +1,90 @@
+"""The C-ABI library loads, exports every symbol the header declares, and turns
+bad arguments into status codes before any GPU work (runs without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def razer():
+    import paper_2501_04052_amd as r
+    if not os.path.exists(r.lib_path()):
+        from paper_2501_04052_amd import build
+        build.build()
+    r.load_library()
+    return r
+
+
+def test_header_symbols_are_exported(razer):
+    header = open(os.path.join(ROOT, "include", "razer.h")).read()
+    names = set(re.findall(r"\b(razer_[a-z_]+)\s*\(", header))
+    assert {"razer_quantize", "razer_dequant", "razer_linear", "razer_workspace_bytes",
+            "razer_status_string"} <= names
+    lib = ctypes.CDLL(razer.lib_path())
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2501_04052_amd import binding
+    assert set(binding.EXPORTS) == names
+
+
+def test_status_strings(razer):
+    seen = {razer.razer_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert razer.razer_status_string(99) == "unknown status"
+
+
+def test_workspace_sizes(razer):
+    assert razer.razer_workspace_bytes(0, 4096, 4096) >= 4
+    assert razer.razer_workspace_bytes(1, 4096, 4096) == 0
+
+
+def test_bad_arguments_return_status_codes_without_gpu(razer):
+    from paper_2501_04052_amd.binding import _Config, _Tensor, load_library
+    L = load_library()
+    cfg = _Config(); cfg.format = 0; cfg.sv[0] = 5.0; cfg.sv[1] = 8.0
+    fake = ctypes.c_void_p(0x1000)          # aligned, never dereferenced: every call fails validation first
+    odd = ctypes.c_void_p(0x1004)
+    q = lambda **kw: L.razer_quantize(kw.get("cfg", ctypes.byref(cfg)), kw.get("x", fake), kw.get("dtype", 0),
+                                      kw.get("rows", 4), kw.get("cols", 64), kw.get("ld", 64),
+                                      kw.get("codes", fake), kw.get("scales", fake), kw.get("ts", fake),
+                                      kw.get("flags", 0), kw.get("ws", fake), kw.get("wsb", 256), None)
+    assert q(cfg=None) == 1 and q(x=None) == 1 and q(ts=None) == 1
+    assert q(cols=48) == 2 and q(cols=-32) == 2 and q(ld=32) == 2 and q(rows=-1) == 2
+    assert q(x=odd) == 3 and q(ld=66) == 3
+    assert q(dtype=7) == 4 and q(flags=8) == 4
+    assert q(ws=None) == 5 and q(wsb=1) == 5
+    for bad in (6.0, 4.0, 5.25, 10.0, 2.0, float("nan")):
+        c2 = _Config(); c2.format = 0; c2.sv[0] = bad; c2.sv[1] = 8.0
+        assert q(cfg=ctypes.byref(c2)) == 4
+    c3 = _Config(); c3.format = 3; c3.sv[0] = 5.0; c3.sv[1] = 8.0
+    assert q(cfg=ctypes.byref(c3)) == 4
+
+    t = _Tensor(); t.codes = 0x1000; t.scales = 0x2000; t.tensor_scale = 0x3000
+    t.rows = 8; t.cols = 64; t.cfg = cfg
+    assert L.razer_dequant(None, fake, 0, 64, None) == 1
+    assert L.razer_dequant(ctypes.byref(t), None, 0, 64, None) == 1
+    assert L.razer_dequant(ctypes.byref(t), fake, 0, 32, None) == 2
+    assert L.razer_dequant(ctypes.byref(t), odd, 0, 64, None) == 3
+    assert L.razer_dequant(ctypes.byref(t), fake, 5, 64, None) == 4
+    # linear: both or neither activation operand, wrong formats, shape mismatches
+    assert L.razer_linear(ctypes.byref(t), None, None, 1, fake, 8, None, 0, None) == 1
+    assert L.razer_linear(ctypes.byref(t), None, None, 0, None, 8, None, 0, None) == 0
+    assert L.razer_linear(ctypes.byref(t), fake, ctypes.byref(t), 1, fake, 8, None, 0, None) == 1
+    assert L.razer_linear(ctypes.byref(t), fake, None, 1, fake, 4, None, 0, None) == 2
+    assert L.razer_linear(ctypes.byref(t), fake, None, -1, fake, 8, None, 0, None) == 2
+    assert L.razer_linear(ctypes.byref(t), odd, None, 1, fake, 8, None, 0, None) == 3
+    ta = _Tensor(); ta.codes = 0x1000; ta.scales = 0x2000; ta.tensor_scale = 0x3000
+    ta.rows = 2; ta.cols = 64; ta.cfg = cfg                      # weight format used as activation
+    assert L.razer_linear(ctypes.byref(t), None, ctypes.byref(ta), 2, fake, 8, None, 0, None) == 4
+    ca = _Config(); ca.format = 1; ca.sv[0] = 5.0
+    ta.cfg = ca; ta.cols = 32
+    assert L.razer_linear(ctypes.byref(t), None, ctypes.byref(ta), 2, fake, 8, None, 0, None) == 2
+    tw = _Tensor(); tw.codes = 0x1000; tw.scales = 0x2000; tw.tensor_scale = 0x3000
+    tw.rows = 8; tw.cols = 64; tw.cfg = ca                      # activation format used as weight
+    assert L.razer_linear(ctypes.byref(tw), fake, None, 1, fake, 8, None, 0, None) == 4
+    # empty problems are fine and launch nothing
+    assert L.razer_linear(ctypes.byref(t), fake, None, 0, None, 8, None, 0, None) == 0

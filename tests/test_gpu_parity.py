@@ -1,0 +1,232 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle.
+Codes, scale bytes, tensor scales and decoded values must match bit for bit;
+bf16 linear outputs within 8e-3 max relative error."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2501_04052_amd as razer
+from paper_2501_04052_amd import synth
+from gpu_util import TOL, bf16_bits_to_dev, dev_to_bf16_bits, max_rel_err, tensor_to_host
+
+pytestmark = pytest.mark.gpu
+W, A = 0, 1
+
+
+def _rand_tensor(rng, fmt, rows, cols):
+    codes = rng.integers(0, 256, size=(rows, cols // 2), dtype=np.uint8)
+    scales = rng.integers(0, 256, size=(rows, cols // 16), dtype=np.uint8)
+    if fmt == A:
+        scales[(scales & 127) == 127] = 126                       # the NaN code is never written
+    return codes, scales, np.float32(rng.uniform(1e-4, 1e-2))
+
+
+# ------------------------------------------------------------------ dequant
+@pytest.mark.parametrize("fmt,sv", [(W, (5.0, 8.0)), (W, (4.5, 9.0)), (A, (5.0, 0.0))])
+@pytest.mark.parametrize("rows,cols", [(1, 32), (37, 1056), (256, 4096)])
+def test_dequant_bit_exact(oracle, fmt, sv, rows, cols):
+    print("dequant", fmt, sv, rows, cols, flush=True)
+    rng = np.random.default_rng(100 + rows)
+    codes, scales, ts = _rand_tensor(rng, fmt, rows, cols)
+    ref = oracle.dequant(fmt, codes, scales, ts, sv=sv, want=("f32", "bf16"))
+    t = razer.RazerTensor.from_host(codes, scales, ts, fmt, sv)
+    out32 = razer.razer_dequant(t, torch.float32).cpu().numpy()
+    assert np.array_equal(out32.view(np.uint32), ref["f32"].view(np.uint32))
+    out16 = dev_to_bf16_bits(razer.razer_dequant(t, torch.bfloat16))
+    assert np.array_equal(out16, ref["bf16"])
+
+
+def test_dequant_strided_output_and_empty(oracle):
+    rng = np.random.default_rng(7)
+    codes, scales, ts = _rand_tensor(rng, W, 9, 64)
+    t = razer.RazerTensor.from_host(codes, scales, ts, W, (5.0, 8.0))
+    buf = torch.full((9, 96), 7.0, dtype=torch.float32, device="cuda")
+    razer.razer_dequant(t, out=buf[:, :64])
+    ref = oracle.dequant(W, codes, scales, ts)["f32"]
+    assert np.array_equal(buf[:, :64].cpu().numpy(), ref)
+    assert torch.all(buf[:, 64:] == 7.0)
+    empty = razer.RazerTensor.from_host(codes[:0], scales[:0], ts, W, (5.0, 8.0))
+    assert razer.razer_dequant(empty).shape == (0, 64)
+
+
+# ------------------------------------------------------------------ quantize
+def _check_quantize(oracle, x_host, fmt, sv, x_dev=None, given=None):
+    if x_dev is None:
+        x_dev = bf16_bits_to_dev(x_host) if x_host.dtype == np.uint16 else torch.from_numpy(x_host).cuda()
+    ts_dev = None if given is None else torch.tensor([given], dtype=torch.float32, device="cuda")
+    t = razer.razer_quantize(x_dev, fmt, sv, tensor_scale=ts_dev)
+    torch.cuda.synchronize()
+    codes, scales, ts = tensor_to_host(t)
+    rc, rs, rts = oracle.quantize(fmt, x_host, sv=sv, given_tensor_scale=given)
+    assert np.float32(ts).view(np.uint32) == np.float32(rts).view(np.uint32)
+    bad = np.argwhere(scales != rs)
+    assert bad.size == 0, ("scale bytes differ", bad[:5], scales[tuple(bad[0])], rs[tuple(bad[0])])
+    bad = np.argwhere(codes != rc)
+    assert bad.size == 0, ("codes differ", bad[:5])
+    return t, (rc, rs, rts)
+
+
+@pytest.mark.parametrize("rows,cols", [(1, 32), (3, 96), (67, 1056), (128, 4096)])
+def test_quantize_weights_bit_exact(oracle, rows, cols):
+    print("quantize W", rows, cols, flush=True)
+    w = synth.weight(rows, cols, seed=200 + rows, outlier_frac=0.002 if cols >= 1024 else 0.0)
+    _check_quantize(oracle, w, W, (5.0, 8.0))
+    _check_quantize(oracle, w, W, (5.0, 7.0))
+
+
+@pytest.mark.parametrize("rows,cols", [(1, 32), (5, 160), (130, 2048)])
+def test_quantize_activations_bit_exact(oracle, rows, cols):
+    print("quantize A", rows, cols, flush=True)
+    a = synth.activation(rows, cols, seed=300 + rows, outlier_frac=0.005 if cols >= 1024 else 0.0)
+    _check_quantize(oracle, a, A, (5.0, 0.0))
+    # fp32 input in the activation format and bf16 input in the weight format
+    _check_quantize(oracle, synth.bf16_bits_to_f32(a) * np.float32(1.37), A, (5.0, 0.0))
+    _check_quantize(oracle, a, W, (5.0, 8.0))
+
+
+def test_quantize_wide_dynamic_range_hits_subnormal_and_zero_scales(oracle):
+    """A few huge outliers push most blocks onto the smallest scales, where the second
+    special-value pair becomes reachable and some blocks decode to zero."""
+    w = synth.weight(64, 2048, seed=17)
+    w[3, 100] = 40.0
+    w[10, 7] = -55.0
+    rng = np.random.default_rng(4)
+    w *= np.exp(rng.uniform(-4, 2, size=(64, 1))).astype(np.float32)     # per-row magnitude spread
+    t, (rc, rs, _) = _check_quantize(oracle, w, W, (5.0, 8.0))
+    assert (rs & 63 == 0).any() and ((rs & 63) < 8).any()
+    assert ((rs >> 6) & 1).any()                                          # +-8 chosen somewhere
+    a = synth.bf16_bits_to_f32(synth.activation(32, 1024, seed=18)) * np.float32(1e-3)
+    a[0, 0] = 3000.0
+    _check_quantize(oracle, a.astype(np.float32), A, (5.0, 0.0))
+
+
+def test_quantize_edge_cases(oracle):
+    z = np.zeros((4, 64), np.float32)
+    t, _ = _check_quantize(oracle, z, W, (5.0, 8.0))
+    assert float(t.tensor_scale.cpu()[0]) == 1.0
+    w = synth.weight(16, 256, seed=5)
+    _check_quantize(oracle, w, W, (5.0, 8.0), given=float(np.float32(2.0 ** -12)))
+    _check_quantize(oracle, w, W, (5.0, 8.0), given=1e-5)                 # saturating block scales
+    # exact ties of the element rounding and of the special-value choice
+    ties = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, 4.5, 5.5, -4.5, -5.5, -5.0, 6.0, -0.25, 0.0, -0.0],
+                    np.float32)
+    x = np.tile(ties, (2, 2)).astype(np.float32)
+    _check_quantize(oracle, x, W, (5.0, 8.0), given=1.0)
+    _check_quantize(oracle, x, A, (5.0, 0.0), given=1.0)
+    # leading dimension larger than cols
+    big = torch.from_numpy(synth.weight(8, 192, seed=6)).cuda()
+    t = razer.razer_quantize(big, W, (5.0, 8.0), cols=128)
+    rc, rs, rts = oracle.quantize(W, np.ascontiguousarray(big.cpu().numpy()[:, :128]))
+    codes, scales, ts = tensor_to_host(t)
+    assert np.array_equal(codes, rc) and np.array_equal(scales, rs) and ts == rts
+    # empty tensor
+    e = razer.razer_quantize(torch.empty((0, 64), dtype=torch.float32, device="cuda"))
+    assert e.codes.numel() == 0 and float(e.tensor_scale.cpu()[0]) == 1.0
+
+
+def test_quantize_then_dequant_round_trip_on_device(oracle):
+    w = synth.weight(40, 512, seed=8)
+    t, (rc, rs, rts) = _check_quantize(oracle, w, W, (5.0, 8.0))
+    out = razer.razer_dequant(t).cpu().numpy()
+    assert np.array_equal(out, oracle.dequant(W, rc, rs, rts)["f32"])
+
+
+# ------------------------------------------------------------------ linear
+def _linear_case(oracle, m, n, k, seed, w_out=0.002):
+    w = synth.weight(n, k, seed=seed, outlier_frac=w_out if k >= 1024 else 0.0)
+    a = synth.activation(m, k, seed=seed + 1)
+    wq = oracle.quantize(W, w)
+    y64, _ = oracle.linear(wq, a_bf16=a)
+    wt = razer.RazerTensor.from_host(*wq, W, (5.0, 8.0))
+    y = razer.razer_linear(wt, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    return max_rel_err(dev_to_bf16_bits(y), y64)
+
+
+@pytest.mark.parametrize("m", [1, 2, 3, 4])
+@pytest.mark.parametrize("n,k", [(1, 32), (7, 96), (130, 2048), (66, 4096 + 160), (33, 11008), (20, 28672),
+                                 (12, 2048 * 17 + 64)])
+def test_linear_gemv_matches_oracle(oracle, m, n, k):
+    print("gemv", m, n, k, flush=True)
+    err = _linear_case(oracle, m, n, k, seed=400 + m + n)
+    assert err <= TOL, err
+
+
+@pytest.mark.parametrize("m,n,k", [(5, 40, 64), (8, 300, 1056), (16, 256, 2048), (33, 100, 96), (64, 513, 1024),
+                                   (100, 130, 4096), (129, 384, 512), (300, 260, 1120), (512, 512, 1024),
+                                   (257, 257, 224)])
+def test_linear_gemm_matches_oracle(oracle, m, n, k):
+    print("gemm", m, n, k, flush=True)
+    err = _linear_case(oracle, m, n, k, seed=500 + m)
+    assert err <= TOL, err
+
+
+def test_linear_special_values_matter(oracle):
+    """Decoding the remapped code as a plain zero must show up as an error: guards
+    against a kernel that silently drops the special values."""
+    n, k, m = 64, 1024, 3
+    w = synth.weight(n, k, seed=31)
+    a = synth.activation(m, k, seed=32)
+    wq = oracle.quantize(W, w)
+    y64, _ = oracle.linear(wq, a_bf16=a)
+    codes = wq[0]
+    frac = np.mean(((codes & 15) == 8) | ((codes >> 4) == 8))
+    assert frac > 0.01
+    y_plain, _ = oracle.linear((wq[0], wq[1] & 63, wq[2]), a_bf16=a, w_sv=(5.0, 8.0))
+    wt = razer.RazerTensor.from_host(*wq, W, (5.0, 8.0))
+    yg = dev_to_bf16_bits(razer.razer_linear(wt, bf16_bits_to_dev(a)))
+    assert max_rel_err(yg, y64) <= TOL
+    assert max_rel_err(yg, y_plain) > 10 * TOL
+    # other special-value sets, both kernels
+    for sv in ((5.0, 7.0), (4.5, 9.0), (2.5, 9.5)):
+        for mm in (2, 40):
+            aa = synth.activation(mm, k, seed=33 + mm)
+            wq2 = oracle.quantize(W, w, sv=sv)
+            y2, _ = oracle.linear(wq2, a_bf16=aa, w_sv=sv)
+            wt2 = razer.RazerTensor.from_host(*wq2, W, sv)
+            assert max_rel_err(dev_to_bf16_bits(razer.razer_linear(wt2, bf16_bits_to_dev(aa))), y2) <= TOL
+
+
+def test_linear_random_codes_all_scale_bytes(oracle):
+    """Arbitrary code / scale bytes (not produced by the encoder) decode identically in the
+    fused kernels: every scale code, every metadata value, every nibble."""
+    rng = np.random.default_rng(77)
+    n, k = 96, 1024
+    codes, scales, ts = _rand_tensor(rng, W, n, k)
+    for m in (1, 4, 24):
+        a = synth.activation(m, k, seed=60 + m)
+        y64, _ = oracle.linear((codes, scales, ts), a_bf16=a)
+        wt = razer.RazerTensor.from_host(codes, scales, ts, W, (5.0, 8.0))
+        assert max_rel_err(dev_to_bf16_bits(razer.razer_linear(wt, bf16_bits_to_dev(a))), y64) <= TOL
+
+
+@pytest.mark.parametrize("m,n,k", [(4, 64, 256), (130, 260, 512), (257, 128, 1056)])
+def test_linear_w4a4_matches_oracle(oracle, m, n, k):
+    print("w4a4", m, n, k, flush=True)
+    w = synth.weight(n, k, seed=600 + m, outlier_frac=0.002 if k >= 1024 else 0.0)
+    a = synth.activation(m, k, seed=601 + m, outlier_frac=0.005)
+    wq = oracle.quantize(W, w)
+    aq = oracle.quantize(A, a, sv=(5.0, 0.0))
+    y64, _ = oracle.linear(wq, a_q=aq)
+    wt = razer.RazerTensor.from_host(*wq, W, (5.0, 8.0))
+    at = razer.razer_quantize(bf16_bits_to_dev(a), A, (5.0, 0.0))       # on-the-fly activation encode
+    ac, asc, ats = tensor_to_host(at)
+    assert np.array_equal(ac, aq[0]) and np.array_equal(asc, aq[1]) and ats == aq[2]
+    y = razer.razer_linear(wt, at)
+    assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
+
+
+def test_linear_strided_output_and_empty(oracle):
+    n, k = 40, 256
+    w = synth.weight(n, k, seed=70)
+    wq = oracle.quantize(W, w)
+    wt = razer.RazerTensor.from_host(*wq, W, (5.0, 8.0))
+    for m in (2, 20):
+        a = synth.activation(m, k, seed=71 + m)
+        y64, _ = oracle.linear(wq, a_bf16=a)
+        buf = torch.full((m, 64), 3.0, dtype=torch.bfloat16, device="cuda")
+        razer.razer_linear(wt, bf16_bits_to_dev(a), out=buf[:, :n])
+        assert max_rel_err(dev_to_bf16_bits(buf[:, :n]), y64) <= TOL
+        assert torch.all(buf[:, n:] == 3.0)
+    y = razer.razer_linear(wt, torch.empty((0, k), dtype=torch.bfloat16, device="cuda"))
+    assert y.shape == (0, n)
