@@ -21,7 +21,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict_
     const float ts = *tensor_scale;
     const uint2 cw = *reinterpret_cast<const uint2*>(codes + r * (cols / 2) + b * 8);
     float s, sv;
-    decode_scale_byte<FMT>(scales[r * nb + b], cfg, s, sv);
+    decode_scale_byte<FMT>(scales[r * nb + b], cfg.sv0, cfg.sv1, s, sv);
     const float ssv = s * sv;                                   // exact: <= 9 significant bits
     float w[kBlock];
 #pragma unroll

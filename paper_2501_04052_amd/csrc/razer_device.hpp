@@ -43,16 +43,19 @@ __device__ __forceinline__ float e4m3_value(uint32_t c7)
     return E ? u2f(bits) : u2f(bits) - 0.015625f;
 }
 // Scale and signed special value selected by a scale byte.
+// sv0 / sv1 are passed as scalars on purpose: selecting between two fields of a by-value
+// kernel-argument struct makes the compiler index the struct in memory, and the private
+// copy it then needs costs every workgroup a read of the dispatch packet.
 template <int FMT>
-__device__ __forceinline__ void decode_scale_byte(uint32_t sb, const SvConfig& cfg, float& s, float& sv)
+__device__ __forceinline__ void decode_scale_byte(uint32_t sb, float sv0, float sv1, float& s, float& sv)
 {
     if (FMT == 0) {
         s = e3m3_value(sb & 63u);
-        float mag = (sb & 0x40u) ? cfg.sv1 : cfg.sv0;
-        sv = (sb & 0x80u) ? -mag : mag;
+        const uint32_t mag = (sb & 0x40u) ? f2u(sv1) : f2u(sv0);
+        sv = u2f(mag | ((sb & 0x80u) << 24));
     } else {
         s = e4m3_value(sb & 127u);
-        sv = (sb & 0x80u) ? -cfg.sv0 : cfg.sv0;
+        sv = u2f(f2u(sv0) | ((sb & 0x80u) << 24));
     }
 }
 

@@ -21,11 +21,11 @@ constexpr int kBK = 64;
 
 // LUT entry per scale byte: { block scale (fp32 bits), -(special * scale) as a bf16 pair }.
 template <int FMT>
-__device__ __forceinline__ void fill_scaled_lut(uint2* lut, SvConfig cfg, int tid, int nthreads)
+__device__ __forceinline__ void fill_scaled_lut(uint2* lut, float sv0, float sv1, int tid, int nthreads)
 {
     for (uint32_t sb = tid; sb < 256u; sb += nthreads) {
         float s, sv;
-        decode_scale_byte<FMT>(sb, cfg, s, sv);
+        decode_scale_byte<FMT>(sb, sv0, sv1, s, sv);
         const uint32_t p = (uint32_t)f32_to_bf16_rne(-(sv * s));
         lut[sb] = make_uint2(f2u(s), p | (p << 16));
     }
@@ -77,8 +77,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int KT = (int)((k + kBK - 1) / kBK);
 
-    fill_scaled_lut<0>(wlut, wcfg, tid, NT);
-    if (AQ) fill_scaled_lut<1>(alut, acfg, tid, NT);
+    fill_scaled_lut<0>(wlut, wcfg.sv0, wcfg.sv1, tid, NT);
+    if (AQ) fill_scaled_lut<1>(alut, acfg.sv0, acfg.sv1, tid, NT);
 
     v16f acc[TN][TM];
 #pragma unroll

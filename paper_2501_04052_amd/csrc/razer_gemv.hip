@@ -23,11 +23,11 @@ constexpr int kSliceK = 2048;          // K elements one wave covers per pass: 6
 constexpr int kMaxWaves = 16;
 
 // Per scale byte: { -block_scale (fp32 bits), negated special value as a bf16 pair }.
-__device__ __forceinline__ void fill_weight_lut(uint2* lut, SvConfig cfg)
+__device__ __forceinline__ void fill_weight_lut(uint2* lut, float sv0, float sv1)
 {
     for (uint32_t sb = threadIdx.x; sb < 256u; sb += blockDim.x) {
         float s, sv;
-        decode_scale_byte<0>(sb, cfg, s, sv);
+        decode_scale_byte<0>(sb, sv0, sv1, s, sv);
         const uint32_t nsv = (uint32_t)f32_to_bf16_rne(-sv);              // exact: multiples of 0.5 below 16
         lut[sb] = make_uint2(f2u(-s), nsv | (nsv << 16));
     }
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __r
 {
     __shared__ uint2 lut[256];
     __shared__ float part[kMaxWaves][R][M];
-    fill_weight_lut(lut, cfg);
+    fill_weight_lut(lut, cfg.sv0, cfg.sv1);
     __syncthreads();
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
@@ -143,9 +143,9 @@ template <int M>
 static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,
                                 int64_t n, int64_t k, const uint16_t* a, uint16_t* y, int64_t ld_y, hipStream_t st)
 {
-    constexpr int R = 4;
     int64_t nslices = (k + kSliceK - 1) / kSliceK;
     int nwaves = (int)(nslices < kMaxWaves ? nslices : kMaxWaves);
+    constexpr int R = 4;
     unsigned grid = (unsigned)((n + R - 1) / R);
     gemv_kernel<M, R><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg, n, k, a, y, ld_y);
     return hipGetLastError();
