@@ -31,6 +31,7 @@ def parse():
     p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--legs", default="all", help="all | gemv (headline only)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying HIP graphs")
     return p.parse_args()
 
 
@@ -49,9 +50,28 @@ def student_t_weight(n, k, gen, outlier_frac=0.001, gain=20.0):
     return w
 
 
-def time_region(fn, steps, warmup):
-    """Run fn(step) warmup+steps times on the current stream; returns ms per step (HIP events)."""
+def time_region(fn, steps, warmup, graph_period=0):
+    """Run fn(step) warmup+steps times on the current stream; returns ms per step (HIP events).
+
+    graph_period > 0: fn(i) only depends on i % graph_period; each of those variants is captured
+    once into a HIP graph (the launches go to the capturing stream through the C ABI) and the
+    timed region replays the graphs, so the host cost of the Python binding is off the clock."""
     import torch
+    if graph_period:
+        graphs = []
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            for i in range(graph_period):
+                fn(i)                                   # warm up outside capture
+            torch.cuda.synchronize()
+            for i in range(graph_period):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    fn(i)
+                graphs.append(g)
+        torch.cuda.synchronize()
+        eager = fn
+        fn = lambda i: graphs[i % graph_period].replay()
     for i in range(warmup):
         fn(i)
     torch.cuda.synchronize()
@@ -111,7 +131,7 @@ def main():
         g.manual_seed(seed)
         return torch.randn((m, k), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
 
-    def linear_leg(m, steps, warmup, rotate=True):
+    def linear_leg(m, steps, warmup, rotate=True, graph=False):
         acts = {k: make_act(m, k, 2100 + m) for k in {k for _, _, k in layers}}
         outs = [torch.empty((m, n), dtype=torch.bfloat16, device="cuda") for _, n, _ in layers]
 
@@ -119,21 +139,26 @@ def main():
             cp = copies[i % n_copies] if rotate else copies[0]
             for j, t in enumerate(cp):
                 razer.razer_linear(t, acts[t.cols], out=outs[j])
-        ms = time_region(step, steps, warmup)
+        ms = time_region(step, steps, warmup, graph_period=(n_copies if rotate else 1) if graph else 0)
         byts = sum(n * k * 9 // 16 + 2 * m * k + 2 * m * n + 4 for _, n, k in layers)
         flops = sum(2.0 * m * n * k for _, n, k in layers)
         return ms, byts, flops
 
     # ---- headline: GEMV at M=1 ----------------------------------------------------------
-    ms1, bytes1, _ = linear_leg(1, args.steps, args.warmup)
+    use_graph = not args.no_graph
+    ms1, bytes1, _ = linear_leg(1, args.steps, args.warmup, graph=use_graph)
     gbs = bytes1 / ms1 / 1e6
-    ms1c, _, _ = linear_leg(1, max(10, args.steps // 4), 5, rotate=False)
+    ms1c, _, _ = linear_leg(1, max(10, args.steps // 4), 5, rotate=False, graph=use_graph)
+    if use_graph:
+        ms1e, _, _ = linear_leg(1, max(10, args.steps // 4), 5)
+        legs["gemv_m1_eager_launches"] = {"GB/s": bytes1 / ms1e / 1e6, "ms_per_step": ms1e,
+                                          "note": "same step launched call by call through the Python binding (host-bound)"}
     legs["gemv_m1_cache_resident"] = {"GB/s": bytes1 / ms1c / 1e6, "note": "same 113.8 MB copy every step: served by the last-level cache, not HBM"}
 
     gemm_roof = None
     if args.legs == "all":
         for m in (4, 16):
-            ms, b, _ = linear_leg(m, max(10, args.steps // 4), 5)
+            ms, b, _ = linear_leg(m, max(10, args.steps // 4), 5, graph=use_graph)
             legs["linear_m%d" % m] = {"GB/s": b / ms / 1e6, "frac_hbm": b / ms / 1e6 / HBM_PEAK_GBS, "ms_per_step": ms}
         for m in (512, 2048):
             ms, _, fl = linear_leg(m, 5, 2)
@@ -190,8 +215,8 @@ def main():
         "dtype": "fp4 codes x bf16 activations, fp32 accumulate", "data": "synthetic",
         "config": {"workload": "configs[1]: Llama-7B-shaped decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; "
                                "down 4096x11008), RaZeR weights (block 16, E3M3 scale + 2 meta bits, sv {5,8}), M=1; "
-                               "one step = the 7 projections once; %d packed copies rotated (%.0f MB > 2x LLC)"
-                               % (n_copies, n_copies * layer_bytes / 1e6),
+                               "one step = the 7 projections once%s; %d packed copies rotated (%.0f MB > 2x LLC)"
+                               % (" (replayed as a HIP graph)" if use_graph else "", n_copies, n_copies * layer_bytes / 1e6),
                    "m": 1, "bytes_per_step": bytes1},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": None,

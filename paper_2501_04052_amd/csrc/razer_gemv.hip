@@ -6,7 +6,9 @@
 // slices of 2048 elements.  In a slice lane l owns the 16-byte code chunk
 // [32 l, 32 l + 32) of every row -- so a wave reads 1 KiB of consecutive codes
 // and 128 B of consecutive scale bytes per row -- and keeps the matching 32
-// activations of each activation row in registers across the R rows.
+// activations of each activation row in registers across the R rows.  Kernels
+// this short are latency-bound: every load is issued before anything else
+// happens, and nothing in the kernel may touch the dispatch packet or scratch.
 //
 // Decode.  The 8 codes of a dword are sign-flipped with one xor, converted to
 // packed bf16 pairs by the hardware FP4 conversion, and the (now all-zero)
@@ -44,6 +46,70 @@ __device__ __forceinline__ float dot2(uint32_t w, uint32_t a, float acc)
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2bf, w), __builtin_bit_cast(v2bf, a), acc, false);
 }
 
+// Registers one lane holds for one group of R rows: 16 bytes of codes and 2 scale bytes per row.
+template <int R>
+struct RowGroup {
+    uint4 cw[R];
+    uint32_t sw[R];
+};
+
+template <int R>
+__device__ __forceinline__ void load_group(RowGroup<R>& g, const uint8_t* __restrict__ codes,
+                                           const uint8_t* __restrict__ scales, int64_t row0, int64_t n,
+                                           int64_t k, int64_t c)
+{
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int64_t row = (row0 + r < n) ? row0 + r : n - 1;           // clamp: tail rows re-read the last row
+        g.cw[r] = *reinterpret_cast<const uint4*>(codes + row * (k / 2) + c * 16);
+        g.sw[r] = *reinterpret_cast<const uint16_t*>(scales + row * (k / 16) + c * 2);
+    }
+}
+
+// sum_k a[m][k] * (scale * element) over this lane's 32 k's, for the R rows of a group.
+template <int M, int R>
+__device__ __forceinline__ void dot_group(const RowGroup<R>& g, const uint4 (&av)[M][4], const uint2* lut,
+                                          float (&acc)[R][M])
+{
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t xw[4] = {g.cw[r].x, g.cw[r].y, g.cw[r].z, g.cw[r].w};
+#pragma unroll
+        for (int m = 0; m < M; ++m) acc[r][m] = 0.0f;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            const uint2 le = lut[(g.sw[r] >> (8 * blk)) & 255u];
+            const float ns = u2f(le.x);
+            float p[M];
+#pragma unroll
+            for (int m = 0; m < M; ++m) p[m] = 0.0f;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t x = xw[2 * blk + h] ^ kRemapXor;
+                const uint32_t w0 = patch_zero_halves(cvt_pair<0>(x), le.y);
+                const uint32_t w1 = patch_zero_halves(cvt_pair<1>(x), le.y);
+                const uint32_t w2 = patch_zero_halves(cvt_pair<2>(x), le.y);
+                const uint32_t w3 = patch_zero_halves(cvt_pair<3>(x), le.y);
+#pragma unroll
+                for (int m = 0; m < M; ++m) {
+                    const uint4 aq = av[m][2 * blk + h];
+                    p[m] = dot2(w0, aq.x, p[m]);
+                    p[m] = dot2(w1, aq.y, p[m]);
+                    p[m] = dot2(w2, aq.z, p[m]);
+                    p[m] = dot2(w3, aq.w, p[m]);
+                }
+            }
+#pragma unroll
+            for (int m = 0; m < M; ++m) acc[r][m] = __builtin_fmaf(ns, p[m], acc[r][m]);
+        }
+    }
+}
+
+// A workgroup owns R consecutive rows; wave w owns K-slice w (and w + waves, ... when K exceeds
+// 2048 elements per wave).  All loads of a wave are issued up front, the rows are decoded, reduced
+// over the 64 lanes and the slice totals parked in LDS; after one barrier the first threads add
+// the slices and write bf16.  The grid is one workgroup per R rows: for the matrices of a decoder
+// layer the whole problem is in flight at once, which is what hides the HBM latency.
 template <int M, int R>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __restrict__ codes,
                                                               const uint8_t* __restrict__ scales,
@@ -54,101 +120,89 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __r
 {
     __shared__ uint2 lut[256];
     __shared__ float part[kMaxWaves][R][M];
-    fill_weight_lut(lut, cfg.sv0, cfg.sv1);
-    __syncthreads();
-
+    const float ts = *w_ts;                                               // issued early, used last
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int64_t row0 = (int64_t)blockIdx.x * R;
     const int64_t chunks = k / 32;                                        // 16-byte code chunks per row
-    const int64_t nslices = (k + kSliceK - 1) / kSliceK;
+    const int npass = (int)((chunks + 64 * nwaves - 1) / (64 * nwaves));  // > 1 only when K > 2048 * waves
 
-    float acc[R][M];
+    // first pass: loads go out before the LUT is built
+    int64_t c = (int64_t)wave * 64 + lane;
+    bool active = c < chunks;
+    int64_t cc = active ? c : 0;                                          // idle lanes read chunk 0, weight 0
+    uint4 av[M][4];
+    RowGroup<R> grp;
+    auto issue_loads = [&]() {
+        const uint32_t amask = active ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            const uint4* ap = reinterpret_cast<const uint4*>(a + (int64_t)m * k + cc * 32);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {                                 // unconditional load, then mask:
+                const uint4 t = ap[j];                                    // keeps the code branch-free
+                av[m][j] = make_uint4(t.x & amask, t.y & amask, t.z & amask, t.w & amask);
+            }
+        }
+        load_group<R>(grp, codes, scales, row0, n, k, cc);
+    };
+    issue_loads();
+    fill_weight_lut(lut, cfg.sv0, cfg.sv1);
+    __syncthreads();                                                      // LUT ready
+
+    float tot[R][M];
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int m = 0; m < M; ++m) acc[r][m] = 0.0f;
-
-    for (int64_t sl = wave; sl < nslices; sl += nwaves) {
-        const int64_t c = sl * 64 + lane;
-        if (c < chunks) {
-            // activations of this lane's 32 k's, all M rows
-            uint4 av[M][4];
-#pragma unroll
-            for (int m = 0; m < M; ++m) {
-                const uint4* ap = reinterpret_cast<const uint4*>(a + (int64_t)m * k + c * 32);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) av[m][j] = ap[j];
-            }
-            uint4 cw[R];
-            uint32_t sw[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int64_t row = (row0 + r < n) ? row0 + r : n - 1;   // clamp: tail rows recompute the last row
-                cw[r] = *reinterpret_cast<const uint4*>(codes + row * (k / 2) + c * 16);
-                sw[r] = *reinterpret_cast<const uint16_t*>(scales + row * (k / 16) + c * 2);
-            }
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const uint32_t xw[4] = {cw[r].x, cw[r].y, cw[r].z, cw[r].w};
-#pragma unroll
-                for (int blk = 0; blk < 2; ++blk) {
-                    const uint2 le = lut[(sw[r] >> (8 * blk)) & 255u];
-                    const float ns = u2f(le.x);
-                    float p[M];
-#pragma unroll
-                    for (int m = 0; m < M; ++m) p[m] = 0.0f;
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const uint32_t x = xw[2 * blk + h] ^ kRemapXor;
-                        const uint32_t w0 = patch_zero_halves(cvt_pair<0>(x), le.y);
-                        const uint32_t w1 = patch_zero_halves(cvt_pair<1>(x), le.y);
-                        const uint32_t w2 = patch_zero_halves(cvt_pair<2>(x), le.y);
-                        const uint32_t w3 = patch_zero_halves(cvt_pair<3>(x), le.y);
-#pragma unroll
-                        for (int m = 0; m < M; ++m) {
-                            const uint4 aq = av[m][2 * blk + h];
-                            p[m] = dot2(w0, aq.x, p[m]);
-                            p[m] = dot2(w1, aq.y, p[m]);
-                            p[m] = dot2(w2, aq.z, p[m]);
-                            p[m] = dot2(w3, aq.w, p[m]);
-                        }
-                    }
-#pragma unroll
-                    for (int m = 0; m < M; ++m) acc[r][m] = __builtin_fmaf(ns, p[m], acc[r][m]);
-                }
-            }
+        for (int m = 0; m < M; ++m) tot[r][m] = 0.0f;
+    for (int pass = 0; pass < npass; ++pass) {
+        if (pass) {
+            c = ((int64_t)pass * nwaves + wave) * 64 + lane;
+            active = c < chunks;
+            cc = active ? c : 0;
+            issue_loads();
         }
+        float acc[R][M];
+        dot_group<M, R>(grp, av, lut, acc);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int m = 0; m < M; ++m) tot[r][m] += acc[r][m];
     }
-
-    // lanes -> wave total (lane 63), waves -> workgroup total through LDS
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int m = 0; m < M; ++m) {
-            const float t = wave_sum_to_lane63(acc[r][m]);
+            const float t = wave_sum_to_lane63(tot[r][m]);
             if (lane == 63) part[wave][r][m] = t;
         }
     __syncthreads();
     if (threadIdx.x < R * M) {
-        const int r = threadIdx.x / M, m = threadIdx.x % M;
+        const int r = threadIdx.x / M, m = threadIdx.x - r * M;
         if (row0 + r < n) {
             float t = 0.0f;
             for (int w = 0; w < nwaves; ++w) t += part[w][r][m];
-            y[(int64_t)m * ld_y + row0 + r] = f32_to_bf16_rne(t * (*w_ts));
+            y[(int64_t)m * ld_y + row0 + r] = f32_to_bf16_rne(t * ts);
         }
     }
 }
 
+template <int M, int R>
+static hipError_t launch_gemv_mr(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,
+                                 int64_t n, int64_t k, const uint16_t* a, uint16_t* y, int64_t ld_y, hipStream_t st)
+{
+    // One wave per 2048-element K-slice, at most 16; longer rows take several passes.
+    const int64_t nslices = (k + kSliceK - 1) / kSliceK;
+    const int nwaves = (int)(nslices < kMaxWaves ? nslices : kMaxWaves);
+    const unsigned grid = (unsigned)((n + R - 1) / R);
+    gemv_kernel<M, R><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg, n, k, a, y, ld_y);
+    return hipGetLastError();
+}
 template <int M>
 static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,
                                 int64_t n, int64_t k, const uint16_t* a, uint16_t* y, int64_t ld_y, hipStream_t st)
 {
-    int64_t nslices = (k + kSliceK - 1) / kSliceK;
-    int nwaves = (int)(nslices < kMaxWaves ? nslices : kMaxWaves);
-    constexpr int R = 4;
-    unsigned grid = (unsigned)((n + R - 1) / R);
-    gemv_kernel<M, R><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg, n, k, a, y, ld_y);
-    return hipGetLastError();
+    // 4 rows per workgroup measured best on MI355X over 2 and 8 for every shape of the 7B / 70B layers.
+    return launch_gemv_mr<M, 4>(cfg, codes, scales, ts, n, k, a, y, ld_y, st);
 }
 
 hipError_t launch_gemv(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
