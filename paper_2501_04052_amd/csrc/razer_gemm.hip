@@ -8,7 +8,7 @@
 //
 // Tile: BM activation rows x BN weight rows x 64 k per stage, double-buffered.
 // LDS rows are 128 B (64 bf16); 16-byte chunks are xor-swizzled with the row so
-// that the 128-bit MFMA operand reads of 32 consecutive rows hit distinct banks.
+// that the 128-bit MFMA operand reads of consecutive rows hit distinct banks.
 // The weight fragment is the MFMA "A" operand (rows = n) and the activation
 // fragment the "B" operand (columns = m), so every lane ends up holding 4
 // consecutive n of one output row and stores them as one 8-byte write.
@@ -49,7 +49,45 @@ __device__ __forceinline__ uint4 decode_dword(uint32_t x, uint2 lut_entry)
                       cvt_scaled_pair<2>(xf, s, lut_entry.y), cvt_scaled_pair<3>(xf, s, lut_entry.y));
 }
 
-__device__ __forceinline__ uint32_t lds_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+// gfx950 LDS: 64 banks x 4 B; a 128-bit access is served 16 lanes per clock, so 16 consecutive rows
+// (256-byte period = 2 rows) must land on 16 distinct 16-byte slots: swizzle with bits 1..3 of the row.
+__device__ __forceinline__ uint32_t lds_off(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
+
+// Epilogue shared by the GEMM kernels: undo the sign flip of the weight decode (in W4A4 the
+// flips of the two operands cancel), apply the tensor scale(s), round to bf16 and store.  Lane l
+// of a 32x32 accumulator holds output row m = l % 32 and, per group g, the 4 consecutive columns
+// n = 8 g + 4 (l / 32) + 0..3.
+template <int TM, int TN, bool AQ>
+__device__ __forceinline__ void store_tile(const v16f (&acc)[TN][TM], const float* w_ts, const float* a_ts,
+                                           int64_t wm0, int64_t wn0, int64_t m, int64_t n, uint16_t* y,
+                                           int64_t ld_y, int lane)
+{
+    const float scale = AQ ? (*w_ts) * (*a_ts) : -(*w_ts);
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int64_t gm = wm0 + j * 32 + (lane & 31);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int64_t gn = wn0 + i * 32 + 8 * g + 4 * (lane >> 5);
+                if (gm < m && gn < n) {
+                    uint16_t o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_rne(acc[i][j][4 * g + e] * scale);
+                    uint16_t* dst = y + gm * ld_y + gn;
+                    if (gn + 3 < n && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {
+                        *reinterpret_cast<uint2*>(dst) =
+                            make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (gn + e < n) dst[e] = o[e];
+                    }
+                }
+            }
+        }
+}
 
 template <int BM, int BN, int WGM, int WGN, bool AQ>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
@@ -194,43 +232,198 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
         __syncthreads();
     }
 
-    // epilogue: undo the sign flip of the weight decode (and of the activation decode
-    // in W4A4, where the two flips cancel), apply the tensor scales, round to bf16.
-    float scale = AQ ? (*w_ts) * (*a_ts) : -(*w_ts);
+    store_tile<TM, TN, AQ>(acc, w_ts, a_ts, m0 + wm * WTM, n0 + wn * WTN, m, n, y, ld_y, lane);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Large tiles: 8 waves in two groups of 4 (one wave of each group per SIMD) that run half a step
+// out of phase.  While one group issues the MFMAs of K-tile i from LDS stage i % 2, the other
+// decodes its half of K-tile i + 1 into the other stage; then they swap.  Every SIMD therefore
+// always has one wave feeding the matrix core and one wave doing the VALU / LDS-write / global-load
+// work, instead of all waves decoding and then all waves multiplying.
+//
+//   slot 2i    : group 0  MFMA(i)                      | group 1  store its half of tile i+1
+//   slot 2i+1  : group 0  store its half of tile i+1   | group 1  MFMA(i)
+//
+// One barrier ends every slot.  Tile i+1 is complete at the end of slot 2i+1 and is first read in
+// slot 2i+2; the stage it overwrites was last read in slot 2i-1.  Global loads for a group's half of
+// tile i+2 are issued right after it stored tile i+1 and land during its next MFMA slot.
+template <int BM, int BN, int WGM, int WGN, bool AQ>
+__global__ __launch_bounds__(512) void gemm_pp_kernel(
+    const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
+    SvConfig wcfg, int64_t n, int64_t k, const uint16_t* __restrict__ a, const uint8_t* __restrict__ a_codes,
+    const uint8_t* __restrict__ a_scales, const float* __restrict__ a_ts, SvConfig acfg, int64_t m,
+    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m)
+{
+    static_assert(WGM * WGN == 8, "two groups of four waves");
+    constexpr int GT = 256;                                            // threads per group
+    constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
+    // per-thread work on one K-tile: a group handles half the rows of each operand tile
+    constexpr int A_PT = AQ ? (BM / 2 * 4) / GT : (BM / 2 * 8) / GT;   // blocks of 16 codes, or 16-byte bf16 chunks
+    constexpr int B_PT = (BN / 2 * 4) / GT;                            // blocks of 16 codes
+    static_assert(A_PT >= 1 && B_PT >= 1, "tile too small for 512 threads");
+
+    extern __shared__ __align__(16) uint8_t smem[];
+    uint8_t* As = smem;
+    uint8_t* Bs = smem + 2 * BM * 128;
+    uint2* wlut = reinterpret_cast<uint2*>(smem + 2 * (BM + BN) * 128);
+    uint2* alut = wlut + 256;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = wave >> 2, gt = tid & (GT - 1);
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+    const int KT = (int)((k + kBK - 1) / kBK);
+
+    fill_scaled_lut<0>(wlut, wcfg.sv0, wcfg.sv1, tid, 512);
+    if (AQ) fill_scaled_lut<1>(alut, acfg.sv0, acfg.sv1, tid, 512);
+
+    v16f acc[TN][TM];
 #pragma unroll
     for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int j = 0; j < TM; ++j) {
-            const int64_t gm = m0 + wm * WTM + j * 32 + (lane & 31);
+        for (int j = 0; j < TM; ++j)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int64_t gn = n0 + wn * WTN + i * 32 + 8 * g + 4 * (lane >> 5);
-                if (gm < m && gn < n) {
-                    uint16_t o[4];
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    uint4 ra[AQ ? 1 : A_PT];           // bf16 activations: 8 values per unit
+    uint2 rqa[AQ ? A_PT : 1];          // quantized activations: 16 codes per unit
+    uint32_t rsa[AQ ? A_PT : 1];
+    uint2 rb[B_PT];
+    uint32_t rsb[B_PT];
+
+    auto gload = [&](int kt) {
+        const int64_t kbase = (int64_t)kt * kBK;
+        if (AQ) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_rne(acc[i][j][4 * g + e] * scale);
-                    uint16_t* dst = y + gm * ld_y + gn;
-                    if (gn + 3 < n && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {
-                        *reinterpret_cast<uint2*>(dst) =
-                            make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (gn + e < n) dst[e] = o[e];
-                    }
+            for (int i = 0; i < A_PT; ++i) {
+                const int u = gt + i * GT, row = grp * (BM / 2) + (u >> 2), blk = u & 3;
+                const int64_t gr = m0 + row, kk = kbase + blk * 16;
+                rqa[i] = make_uint2(0, 0);
+                rsa[i] = 0;
+                if (gr < m && kk < k) {
+                    rqa[i] = *reinterpret_cast<const uint2*>(a_codes + gr * (k / 2) + kk / 2);
+                    rsa[i] = a_scales[gr * (k / 16) + kk / 16];
                 }
             }
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_PT; ++i) {
+                const int u = gt + i * GT, row = grp * (BM / 2) + (u >> 3), chunk = u & 7;
+                const int64_t gr = m0 + row, kk = kbase + chunk * 8;
+                ra[i] = make_uint4(0, 0, 0, 0);
+                if (gr < m && kk < k) ra[i] = *reinterpret_cast<const uint4*>(a + gr * k + kk);
+            }
         }
+#pragma unroll
+        for (int i = 0; i < B_PT; ++i) {
+            const int u = gt + i * GT, row = grp * (BN / 2) + (u >> 2), blk = u & 3;
+            const int64_t gr = n0 + row, kk = kbase + blk * 16;
+            rb[i] = make_uint2(0, 0);
+            rsb[i] = 0;
+            if (gr < n && kk < k) {
+                rb[i] = *reinterpret_cast<const uint2*>(w_codes + gr * (k / 2) + kk / 2);
+                rsb[i] = w_scales[gr * (k / 16) + kk / 16];
+            }
+        }
+    };
+    auto store = [&](int st) {
+        uint8_t* as = As + st * BM * 128;
+        uint8_t* bs = Bs + st * BN * 128;
+        if (AQ) {
+#pragma unroll
+            for (int i = 0; i < A_PT; ++i) {
+                const int u = gt + i * GT, row = grp * (BM / 2) + (u >> 2), blk = u & 3;
+                const uint2 le = alut[rsa[i] & 255u];
+                *reinterpret_cast<uint4*>(as + lds_off(row, 2 * blk)) = decode_dword(rqa[i].x, le);
+                *reinterpret_cast<uint4*>(as + lds_off(row, 2 * blk + 1)) = decode_dword(rqa[i].y, le);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_PT; ++i) {
+                const int u = gt + i * GT, row = grp * (BM / 2) + (u >> 3), chunk = u & 7;
+                *reinterpret_cast<uint4*>(as + lds_off(row, chunk)) = ra[i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < B_PT; ++i) {
+            const int u = gt + i * GT, row = grp * (BN / 2) + (u >> 2), blk = u & 3;
+            const uint2 le = wlut[rsb[i] & 255u];
+            *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * blk)) = decode_dword(rb[i].x, le);
+            *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * blk + 1)) = decode_dword(rb[i].y, le);
+        }
+    };
+    auto mfma_tile = [&](int st) {
+        const uint8_t* as = As + st * BM * 128;
+        const uint8_t* bs = Bs + st * BN * 128;
+        v8bf fw[2][TN], fa[2][TM];
+        auto frags = [&](int ks, int buf) {
+            const int chunk = ks * 2 + (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+                fw[buf][i] = *reinterpret_cast<const v8bf*>(bs + lds_off(wn * WTN + i * 32 + (lane & 31), chunk));
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+                fa[buf][j] = *reinterpret_cast<const v8bf*>(as + lds_off(wm * WTM + j * 32 + (lane & 31), chunk));
+        };
+        frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < 3) frags(ks + 1, (ks + 1) & 1);
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks & 1][i], fa[ks & 1][j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    gload(0);
+    __syncthreads();                                   // LUTs ready
+    store(0);
+    if (KT > 1) gload(1);
+    __syncthreads();                                   // tile 0 complete
+
+    if (grp == 0) {
+        for (int i = 0; i < KT; ++i) {
+            __builtin_amdgcn_s_setprio(1);
+            mfma_tile(i & 1);
+            __builtin_amdgcn_s_setprio(0);
+            __syncthreads();
+            if (i + 1 < KT) {
+                store((i + 1) & 1);
+                if (i + 2 < KT) gload(i + 2);
+            }
+            __syncthreads();
+        }
+    } else {
+        for (int i = 0; i < KT; ++i) {
+            if (i + 1 < KT) {
+                store((i + 1) & 1);
+                if (i + 2 < KT) gload(i + 2);
+            }
+            __syncthreads();
+            __builtin_amdgcn_s_setprio(1);
+            mfma_tile(i & 1);
+            __builtin_amdgcn_s_setprio(0);
+            __syncthreads();
+        }
+    }
+    store_tile<TM, TN, AQ>(acc, w_ts, a_ts, m0 + wm * WTM, n0 + wn * WTN, m, n, y, ld_y, lane);
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AQ>
+template <int BM, int BN, int WGM, int WGN, bool AQ, bool PP = false>
 static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                              int64_t n, int64_t k, const uint16_t* a, const uint8_t* a_codes,
                              const uint8_t* a_scales, const float* a_ts, SvConfig acfg, int64_t m, uint16_t* y,
                              int64_t ld_y, hipStream_t st)
 {
     constexpr size_t smem = 2 * (BM + BN) * 128 + 2 * 256 * sizeof(uint2);
-    auto kern = gemm_kernel<BM, BN, WGM, WGN, AQ>;
+    void (*kern)(const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, int64_t, const uint16_t*,
+                 const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, uint16_t*, int64_t, int);
+    if constexpr (PP) kern = gemm_pp_kernel<BM, BN, WGM, WGN, AQ>;
+    else kern = gemm_kernel<BM, BN, WGM, WGN, AQ>;
     static bool attr_set = false;                      // one GPU per process
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -260,8 +453,11 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
     const int64_t tm = (m + 255) / 256;
     const int64_t t256 = tm * ((n + 255) / 256), t128 = tm * ((n + 127) / 128);
     auto eff = [](int64_t tiles) { return (double)tiles / (double)(((tiles + 255) / 256) * 256); };
-    if (eff(t256) >= eff(t128)) return RAZER_GEMM(256, 256, 2, 4);
-    return RAZER_GEMM(256, 128, 4, 2);
+#define RAZER_GEMM_PP(BM, BN, WGM, WGN) \
+    launch_cfg<BM, BN, WGM, WGN, AQ, true>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st)
+    if (eff(t256) >= eff(t128)) return RAZER_GEMM_PP(256, 256, 2, 4);
+    return RAZER_GEMM_PP(256, 128, 4, 2);
+#undef RAZER_GEMM_PP
 #undef RAZER_GEMM
 }
 
