@@ -55,34 +55,49 @@ __device__ __forceinline__ uint32_t lds_off(int row, int chunk) { return row * 1
 
 // Epilogue shared by the GEMM kernels: undo the sign flip of the weight decode (in W4A4 the
 // flips of the two operands cancel), apply the tensor scale(s), round to bf16 and store.  Lane l
-// of a 32x32 accumulator holds output row m = l % 32 and, per group g, the 4 consecutive columns
-// n = 8 g + 4 (l / 32) + 0..3.
+// of a 32x32 accumulator holds output row m = l % 32 and, per group g of 4 registers, the 4
+// consecutive columns n = 8 g + 4 (l / 32) + 0..3.  Lanes l and l + 32 exchange halves
+// (v_permlane32_swap) so that each lane ends up with 8 consecutive columns -- groups 0 and 2 in the
+// lower half-wave, 1 and 3 in the upper -- and writes them as one 16-byte store.
 template <int TM, int TN, bool AQ>
 __device__ __forceinline__ void store_tile(const v16f (&acc)[TN][TM], const float* w_ts, const float* a_ts,
                                            int64_t wm0, int64_t wn0, int64_t m, int64_t n, uint16_t* y,
                                            int64_t ld_y, int lane)
 {
     const float scale = AQ ? (*w_ts) * (*a_ts) : -(*w_ts);
+    const int hi = lane >> 5;
 #pragma unroll
     for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
             const int64_t gm = wm0 + j * 32 + (lane & 31);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int64_t gn = wn0 + i * 32 + 8 * g + 4 * (lane >> 5);
-                if (gm < m && gn < n) {
-                    uint16_t o[4];
+            for (int gp = 0; gp < 2; ++gp) {                       // groups (2 gp, 2 gp + 1)
+                uint32_t pk[2][2];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_rne(acc[i][j][4 * g + e] * scale);
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int v = 4 * (2 * gp + h) + 2 * e;
+                        pk[h][e] = (uint32_t)f32_to_bf16_rne(acc[i][j][v] * scale) |
+                                   ((uint32_t)f32_to_bf16_rne(acc[i][j][v + 1] * scale) << 16);
+                    }
+                uint32_t o[4];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    auto r = __builtin_amdgcn_permlane32_swap(pk[0][e], pk[1][e], false, false);
+                    o[e] = r[0];                                    // columns +0..3 of this lane's group
+                    o[2 + e] = r[1];                                // columns +4..7
+                }
+                const int64_t gn = wn0 + i * 32 + 8 * (2 * gp + hi);
+                if (gm < m && gn < n) {
                     uint16_t* dst = y + gm * ld_y + gn;
-                    if (gn + 3 < n && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {
-                        *reinterpret_cast<uint2*>(dst) =
-                            make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
+                    if (gn + 7 < n && ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0)) {
+                        *reinterpret_cast<uint4*>(dst) = make_uint4(o[0], o[1], o[2], o[3]);
                     } else {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (gn + e < n) dst[e] = o[e];
+                        for (int e = 0; e < 8; ++e)
+                            if (gn + e < n) dst[e] = (uint16_t)(o[e >> 1] >> (16 * (e & 1)));
                     }
                 }
             }
@@ -260,7 +275,11 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
     constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
     // per-thread work on one K-tile: a group handles half the rows of each operand tile
     constexpr int A_PT = AQ ? (BM / 2 * 4) / GT : (BM / 2 * 8) / GT;   // blocks of 16 codes, or 16-byte bf16 chunks
-    constexpr int B_PT = (BN / 2 * 4) / GT;                            // blocks of 16 codes
+    // Weight share of a thread: UB consecutive blocks of one row (UB = 2: 16 bytes of codes + 2 scale
+    // bytes; UB = 1: 8 + 1), so that all 256 threads of a group have decode work.
+    constexpr int UB = (BN / 2 * 4) / GT >= 2 ? 2 : 1;
+    constexpr int B_PT = (BN / 2 * 4) / GT / UB;
+    constexpr int UPR = 4 / UB;                                        // units per 64-k row tile
     static_assert(A_PT >= 1 && B_PT >= 1, "tile too small for 512 threads");
 
     extern __shared__ __align__(16) uint8_t smem[];
@@ -287,24 +306,29 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    uint4 ra[AQ ? 1 : A_PT];           // bf16 activations: 8 values per unit
-    uint2 rqa[AQ ? A_PT : 1];          // quantized activations: 16 codes per unit
-    uint32_t rsa[AQ ? A_PT : 1];
-    uint2 rb[B_PT];
-    uint32_t rsb[B_PT];
+    // Register-held prefetch of this thread's share of one K-tile.  Two sets: tile t uses set t % 2,
+    // so a tile's global loads are issued two store-slots before they are consumed.
+    struct Prefetch {
+        uint4 ra[AQ ? 1 : A_PT];           // bf16 activations: 8 values per unit
+        uint2 rqa[AQ ? A_PT : 1];          // quantized activations: 16 codes per unit
+        uint32_t rsa[AQ ? A_PT : 1];
+        uint4 rb[B_PT];
+        uint32_t rsb[B_PT];
+    };
+    Prefetch pf0, pf1;
 
-    auto gload = [&](int kt) {
+    auto gload = [&](Prefetch& pf, int kt) {
         const int64_t kbase = (int64_t)kt * kBK;
         if (AQ) {
 #pragma unroll
             for (int i = 0; i < A_PT; ++i) {
                 const int u = gt + i * GT, row = grp * (BM / 2) + (u >> 2), blk = u & 3;
                 const int64_t gr = m0 + row, kk = kbase + blk * 16;
-                rqa[i] = make_uint2(0, 0);
-                rsa[i] = 0;
+                pf.rqa[i] = make_uint2(0, 0);
+                pf.rsa[i] = 0;
                 if (gr < m && kk < k) {
-                    rqa[i] = *reinterpret_cast<const uint2*>(a_codes + gr * (k / 2) + kk / 2);
-                    rsa[i] = a_scales[gr * (k / 16) + kk / 16];
+                    pf.rqa[i] = *reinterpret_cast<const uint2*>(a_codes + gr * (k / 2) + kk / 2);
+                    pf.rsa[i] = a_scales[gr * (k / 16) + kk / 16];
                 }
             }
         } else {
@@ -312,52 +336,66 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
             for (int i = 0; i < A_PT; ++i) {
                 const int u = gt + i * GT, row = grp * (BM / 2) + (u >> 3), chunk = u & 7;
                 const int64_t gr = m0 + row, kk = kbase + chunk * 8;
-                ra[i] = make_uint4(0, 0, 0, 0);
-                if (gr < m && kk < k) ra[i] = *reinterpret_cast<const uint4*>(a + gr * k + kk);
+                pf.ra[i] = make_uint4(0, 0, 0, 0);
+                if (gr < m && kk < k) pf.ra[i] = *reinterpret_cast<const uint4*>(a + gr * k + kk);
             }
         }
 #pragma unroll
         for (int i = 0; i < B_PT; ++i) {
-            const int u = gt + i * GT, row = grp * (BN / 2) + (u >> 2), blk = u & 3;
-            const int64_t gr = n0 + row, kk = kbase + blk * 16;
-            rb[i] = make_uint2(0, 0);
-            rsb[i] = 0;
+            const int u = gt + i * GT, row = grp * (BN / 2) + u / UPR, part = u % UPR;
+            const int64_t gr = n0 + row, kk = kbase + part * (16 * UB);
+            pf.rb[i] = make_uint4(0, 0, 0, 0);
+            pf.rsb[i] = 0;
             if (gr < n && kk < k) {
-                rb[i] = *reinterpret_cast<const uint2*>(w_codes + gr * (k / 2) + kk / 2);
-                rsb[i] = w_scales[gr * (k / 16) + kk / 16];
+                if (UB == 2) {
+                    pf.rb[i] = *reinterpret_cast<const uint4*>(w_codes + gr * (k / 2) + kk / 2);
+                    pf.rsb[i] = *reinterpret_cast<const uint16_t*>(w_scales + gr * (k / 16) + kk / 16);
+                } else {
+                    const uint2 t2 = *reinterpret_cast<const uint2*>(w_codes + gr * (k / 2) + kk / 2);
+                    pf.rb[i].x = t2.x;
+                    pf.rb[i].y = t2.y;
+                    pf.rsb[i] = w_scales[gr * (k / 16) + kk / 16];
+                }
             }
         }
     };
-    auto store = [&](int st) {
+    auto store = [&](const Prefetch& pf, int st) {
         uint8_t* as = As + st * BM * 128;
         uint8_t* bs = Bs + st * BN * 128;
         if (AQ) {
 #pragma unroll
             for (int i = 0; i < A_PT; ++i) {
                 const int u = gt + i * GT, row = grp * (BM / 2) + (u >> 2), blk = u & 3;
-                const uint2 le = alut[rsa[i] & 255u];
-                *reinterpret_cast<uint4*>(as + lds_off(row, 2 * blk)) = decode_dword(rqa[i].x, le);
-                *reinterpret_cast<uint4*>(as + lds_off(row, 2 * blk + 1)) = decode_dword(rqa[i].y, le);
+                const uint2 le = alut[pf.rsa[i] & 255u];
+                *reinterpret_cast<uint4*>(as + lds_off(row, 2 * blk)) = decode_dword(pf.rqa[i].x, le);
+                *reinterpret_cast<uint4*>(as + lds_off(row, 2 * blk + 1)) = decode_dword(pf.rqa[i].y, le);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < A_PT; ++i) {
                 const int u = gt + i * GT, row = grp * (BM / 2) + (u >> 3), chunk = u & 7;
-                *reinterpret_cast<uint4*>(as + lds_off(row, chunk)) = ra[i];
+                *reinterpret_cast<uint4*>(as + lds_off(row, chunk)) = pf.ra[i];
             }
         }
 #pragma unroll
         for (int i = 0; i < B_PT; ++i) {
-            const int u = gt + i * GT, row = grp * (BN / 2) + (u >> 2), blk = u & 3;
-            const uint2 le = wlut[rsb[i] & 255u];
-            *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * blk)) = decode_dword(rb[i].x, le);
-            *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * blk + 1)) = decode_dword(rb[i].y, le);
+            const int u = gt + i * GT, row = grp * (BN / 2) + u / UPR, part = u % UPR;
+            const uint2 le0 = wlut[pf.rsb[i] & 255u];
+            *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * UB * part + 0)) = decode_dword(pf.rb[i].x, le0);
+            *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * UB * part + 1)) = decode_dword(pf.rb[i].y, le0);
+            if (UB == 2) {
+                const uint2 le1 = wlut[(pf.rsb[i] >> 8) & 255u];
+                *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * UB * part + 2)) = decode_dword(pf.rb[i].z, le1);
+                *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * UB * part + 3)) = decode_dword(pf.rb[i].w, le1);
+            }
         }
     };
     auto mfma_tile = [&](int st) {
         const uint8_t* as = As + st * BM * 128;
         const uint8_t* bs = Bs + st * BN * 128;
-        v8bf fw[2][TN], fa[2][TM];
+        // operand fragments are fetched DEPTH k-steps ahead of the MFMAs that use them
+        constexpr int DEPTH = (TM + TN <= 4) ? 4 : 2;
+        v8bf fw[DEPTH][TN], fa[DEPTH][TM];
         auto frags = [&](int ks, int buf) {
             const int chunk = ks * 2 + (lane >> 5);
 #pragma unroll
@@ -367,46 +405,61 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
             for (int j = 0; j < TM; ++j)
                 fa[buf][j] = *reinterpret_cast<const v8bf*>(as + lds_off(wm * WTM + j * 32 + (lane & 31), chunk));
         };
-        frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < DEPTH - 1; ++ks) frags(ks, ks);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            if (ks < 3) frags(ks + 1, (ks + 1) & 1);
+            if (ks + DEPTH - 1 < 4) frags(ks + DEPTH - 1, (ks + DEPTH - 1) % DEPTH);
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks & 1][i], fa[ks & 1][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks % DEPTH][i], fa[ks % DEPTH][j], acc[i][j], 0, 0, 0);
         }
     };
 
-    gload(0);
+    gload(pf0, 0);
+    if (KT > 1) gload(pf1, 1);
     __syncthreads();                                   // LUTs ready
-    store(0);
-    if (KT > 1) gload(1);
+    store(pf0, 0);
+    if (KT > 2) gload(pf0, 2);
     __syncthreads();                                   // tile 0 complete
 
-    if (grp == 0) {
-        for (int i = 0; i < KT; ++i) {
+    // store slot for tile t (set t % 2), then refill that set with tile t + 2
+    auto store_slot = [&](Prefetch& pf, int t) {
+        if (t < KT) {
+            store(pf, t & 1);
+            if (t + 2 < KT) gload(pf, t + 2);
+        }
+    };
+    auto mfma_slot = [&](int t) {
+        if (t < KT) {
             __builtin_amdgcn_s_setprio(1);
-            mfma_tile(i & 1);
+            mfma_tile(t & 1);
             __builtin_amdgcn_s_setprio(0);
+        }
+    };
+    // two K-tiles per trip so that the prefetch sets are addressed statically
+    if (grp == 0) {
+        for (int i = 0; i < KT; i += 2) {
+            mfma_slot(i);
             __syncthreads();
-            if (i + 1 < KT) {
-                store((i + 1) & 1);
-                if (i + 2 < KT) gload(i + 2);
-            }
+            store_slot(pf1, i + 1);
+            __syncthreads();
+            mfma_slot(i + 1);
+            __syncthreads();
+            store_slot(pf0, i + 2);
             __syncthreads();
         }
     } else {
-        for (int i = 0; i < KT; ++i) {
-            if (i + 1 < KT) {
-                store((i + 1) & 1);
-                if (i + 2 < KT) gload(i + 2);
-            }
+        for (int i = 0; i < KT; i += 2) {
+            store_slot(pf1, i + 1);
             __syncthreads();
-            __builtin_amdgcn_s_setprio(1);
-            mfma_tile(i & 1);
-            __builtin_amdgcn_s_setprio(0);
+            mfma_slot(i);
+            __syncthreads();
+            store_slot(pf0, i + 2);
+            __syncthreads();
+            mfma_slot(i + 1);
             __syncthreads();
         }
     }
