@@ -117,7 +117,7 @@ razer_status razer_dequant(const razer_tensor *t, void *out, int32_t dtype, int6
  *   a_bf16  device bf16 [m][K] dense                      (W4A16), or
  *   a_q     RAZER_FMT_ACT tensor [m][K]                   (W4A4)
  * is non-NULL.  Products are accumulated in fp32 (bf16 matrix cores for large
- * m, wavefront dot products for m <= 4), scaled by the tensor scale(s) and
+ * m, wavefront dot products for m <= 16), scaled by the tensor scale(s) and
  * rounded to bf16:  y_bf16 device [m][ld_y], ld_y >= N.
  * workspace: >= razer_workspace_bytes(RAZER_OP_LINEAR, N, K, m) bytes (may be 0). */
 razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer_tensor *a_q,

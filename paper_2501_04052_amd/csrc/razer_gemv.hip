@@ -210,13 +210,22 @@ hipError_t launch_gemv(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_s
                        hipStream_t st)
 {
     if (n == 0 || m == 0) return hipSuccess;
-    switch (m) {
-        case 1: return launch_gemv_m<1>(wcfg, w_codes, w_scales, w_ts, n, k, a, y, ld_y, st);
-        case 2: return launch_gemv_m<2>(wcfg, w_codes, w_scales, w_ts, n, k, a, y, ld_y, st);
-        case 3: return launch_gemv_m<3>(wcfg, w_codes, w_scales, w_ts, n, k, a, y, ld_y, st);
-        case 4: return launch_gemv_m<4>(wcfg, w_codes, w_scales, w_ts, n, k, a, y, ld_y, st);
-        default: return hipErrorInvalidValue;
+    // Up to kGemvMaxM activation rows go through in passes of at most 4 rows; passes after the
+    // first find the packed weights in the last-level cache for the matrices of a decoder layer.
+    for (int64_t m0 = 0; m0 < m; m0 += 4) {
+        const int64_t mc = (m - m0 < 4) ? m - m0 : 4;
+        const uint16_t* ap = a + m0 * k;
+        uint16_t* yp = y + m0 * ld_y;
+        hipError_t e;
+        switch (mc) {
+            case 1: e = launch_gemv_m<1>(wcfg, w_codes, w_scales, w_ts, n, k, ap, yp, ld_y, st); break;
+            case 2: e = launch_gemv_m<2>(wcfg, w_codes, w_scales, w_ts, n, k, ap, yp, ld_y, st); break;
+            case 3: e = launch_gemv_m<3>(wcfg, w_codes, w_scales, w_ts, n, k, ap, yp, ld_y, st); break;
+            default: e = launch_gemv_m<4>(wcfg, w_codes, w_scales, w_ts, n, k, ap, yp, ld_y, st); break;
+        }
+        if (e != hipSuccess) return e;
     }
+    return hipSuccess;
 }
 
 }  // namespace razer

@@ -16,8 +16,8 @@ hipError_t launch_dequant(int fmt, SvConfig cfg, const uint8_t* codes, const uin
                           const float* tensor_scale, int64_t rows, int64_t cols, void* out, int dtype_bf16,
                           int64_t ld, hipStream_t st);
 
-// Y[m][n] = A[m][:] . W[n][:], m <= kGemvMaxM: wavefront dot products, HBM-bound.
-constexpr int kGemvMaxM = 4;
+// Y[m][n] = A[m][:] . W[n][:], m <= kGemvMaxM: wavefront dot products, HBM-bound (4 rows per pass).
+constexpr int kGemvMaxM = 16;
 hipError_t launch_gemv(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
                        int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
                        hipStream_t st);

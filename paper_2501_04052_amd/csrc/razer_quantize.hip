@@ -13,20 +13,20 @@ namespace razer {
 // ---------------------------------------------------------------- absmax (Eq. 1)
 __global__ void absmax_init_kernel(uint32_t* ws) { ws[0] = 0u; }
 
+// One atomic per workgroup and at most kAbsmaxBlocks workgroups: atomics on a single address
+// serialize at roughly 10 ns each, so thousands of them would dominate the pass.
+constexpr int kAbsmaxBlocks = 1024;
+
 template <typename T>
 __global__ __launch_bounds__(256) void absmax_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
                                                      int64_t ld, uint32_t* __restrict__ ws)
 {
     // 16-byte vectors: 4 floats or 8 bf16.  |x| of finite non-negative floats orders like uint32.
     constexpr int VEC = 16 / sizeof(T);
-    const int64_t vec_per_row = cols / VEC;
-    const int64_t total = rows * vec_per_row;
+    __shared__ uint32_t wmax[4];
     uint32_t m = 0;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        int64_t r = i / vec_per_row, c = i - r * vec_per_row;
-        uint4 v = *reinterpret_cast<const uint4*>(x + r * ld + c * VEC);
-        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    auto fold = [&](const uint4& v) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (sizeof(T) == 4) {
@@ -36,10 +36,24 @@ __global__ __launch_bounds__(256) void absmax_kernel(const T* __restrict__ x, in
                 m = max(m, w[j] & 0x7FFF0000u);
             }
         }
+    };
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    if (ld == cols) {                                   // dense: one flat array of vectors
+        const int64_t total = rows * cols / VEC;
+        const uint4* p = reinterpret_cast<const uint4*>(x);
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) fold(p[i]);
+    } else {                                            // strided rows: workgroups stride over rows
+        const int64_t vec_per_row = cols / VEC;
+        for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+            const uint4* p = reinterpret_cast<const uint4*>(x + r * ld);
+            for (int64_t c = threadIdx.x; c < vec_per_row; c += blockDim.x) fold(p[c]);
+        }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
-    if ((threadIdx.x & 63) == 0) atomicMax(ws, m);
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) atomicMax(ws, max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3])));
 }
 
 // ---------------------------------------------------------------- scale rounding (Eq. 2)
@@ -190,7 +204,7 @@ static hipError_t launch_quantize_t(int fmt, SvConfig cfg, const T* x, int64_t r
         constexpr int VEC = 16 / sizeof(T);
         int64_t total = rows * (cols / VEC);
         int64_t blocks = (total + 255) / 256;
-        if (blocks > 256 * 16) blocks = 256 * 16;
+        if (blocks > kAbsmaxBlocks) blocks = kAbsmaxBlocks;
         absmax_kernel<T><<<(unsigned)blocks, 256, 0, st>>>(x, rows, cols, ld, ws);
     }
     int64_t nblk = rows * (cols / kBlock);
