@@ -1,0 +1,128 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configurations
+bench.py times: encoders bit-exact on whole tensors, linear outputs either whole (M <= 16) or on
+sampled rows x columns (64 x 256, full K) that the oracle computes one by one."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2501_04052_amd as razer
+from paper_2501_04052_amd import synth
+from gpu_util import TOL, bf16_bits_to_dev, dev_to_bf16_bits, max_rel_err, tensor_to_host
+
+pytestmark = pytest.mark.gpu
+W, A = 0, 1
+SV = (5.0, 8.0)
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _rand_packed(n, k, seed):
+    rng = np.random.default_rng(seed)
+    codes = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
+    scales = rng.integers(0, 256, size=(n, k // 16), dtype=np.uint8)
+    scales = (scales & 0xC0) | (16 + (scales & 31))              # E3M3 codes 16..47: values 0.5..7.5
+    return codes, scales, np.float32(2.0 ** -10)
+
+
+def _check_linear(oracle, wq, wt, m, seed, sampled):
+    n, k = wq[0].shape[0], wq[0].shape[1] * 2
+    a = synth.activation(m, k, seed=seed)
+    y = razer.razer_linear(wt, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    if sampled:
+        rows = synth.sample_indices(m, 64, 9000)
+        cols = synth.sample_indices(n, 256, 9001)
+        y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=cols)
+        got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+    else:
+        y64, _ = oracle.linear(wq, a_bf16=a)
+        got = dev_to_bf16_bits(y)
+    err = max_rel_err(got, y64)
+    _say("   linear m=%d n=%d k=%d sampled=%s max rel err %.2e" % (m, n, k, sampled, err))
+    assert err <= TOL, err
+
+
+def _encode_and_check(oracle, x_host, fmt, sv):
+    x_dev = bf16_bits_to_dev(x_host) if x_host.dtype == np.uint16 else torch.from_numpy(x_host).cuda()
+    t = razer.razer_quantize(x_dev, fmt, sv)
+    torch.cuda.synchronize()
+    del x_dev
+    ref = oracle.quantize(fmt, x_host, sv=sv)
+    codes, scales, ts = tensor_to_host(t)
+    assert np.float32(ts).view(np.uint32) == np.float32(ref[2]).view(np.uint32)
+    assert np.array_equal(scales, ref[1]), "scale bytes differ"
+    assert np.array_equal(codes, ref[0]), "codes differ"
+    return t, ref
+
+
+def test_config1_single_layer_4096(oracle):
+    _say("config 1: 4096x4096 encode + M=1 linear + dequant")
+    w = synth.weight(4096, 4096, seed=1000)
+    wt, wq = _encode_and_check(oracle, w, W, SV)
+    frac8 = np.mean((wq[1] >> 6) & 1)
+    _say("   blocks choosing the second special-value pair: %.4f" % frac8)
+    _check_linear(oracle, wq, wt, 1, 1001, sampled=False)
+    ref = oracle.dequant(W, *wq, want=("bf16",))["bf16"]
+    assert np.array_equal(dev_to_bf16_bits(razer.razer_dequant(wt, torch.bfloat16)), ref)
+
+
+@pytest.mark.parametrize("name,n,k,idx", [("q", 4096, 4096, 0), ("gate", 11008, 4096, 4), ("down", 4096, 11008, 6)])
+def test_config2_3_llama7b_layer(oracle, name, n, k, idx):
+    _say("config 2/3: %s %dx%d, encode + M in {1,4,16} whole + M in {512,2048} sampled" % (name, n, k))
+    w = synth.weight(n, k, seed=2000 + idx, outlier_frac=0.001)
+    wt, wq = _encode_and_check(oracle, w, W, SV)
+    del w
+    for m in (1, 4, 16):
+        _check_linear(oracle, wq, wt, m, 2100 + m, sampled=False)
+    for m in (512, 2048):
+        _check_linear(oracle, wq, wt, m, 2100 + m, sampled=True)
+
+
+@pytest.mark.parametrize("n,k", [(8192, 8192), (1024, 8192), (28672, 8192), (8192, 28672)])
+def test_config4_llama70b_shapes(oracle, n, k):
+    _say("config 4: %dx%d random packed tensor, M in {1,8} whole-ish, M=4096 sampled" % (n, k))
+    wq = _rand_packed(n, k, seed=4000 + n // 1024 + k)
+    wt = razer.RazerTensor.from_host(*wq, W, SV)
+    _check_linear(oracle, wq, wt, 1, 4101, sampled=False)
+    for m, sampled in ((8, n * k > 2 ** 27), (4096, True)):
+        a = synth.activation(m, k, seed=4100 + m)
+        y = razer.razer_linear(wt, bf16_bits_to_dev(a))
+        torch.cuda.synchronize()
+        rows = synth.sample_indices(m, 64, 9000)
+        cols = synth.sample_indices(n, 256 if sampled else n, 9001)
+        y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=cols)
+        got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+        err = max_rel_err(got, y64)
+        _say("   linear m=%d n=%d k=%d: %d x %d outputs checked, max rel err %.2e" % (m, n, k, len(rows), len(cols), err))
+        assert err <= TOL, err
+        del y, a
+
+
+def test_config4_llama70b_encoder(oracle):
+    _say("config 4: encoder on 70B-shaped tensors (k 1024x8192 whole, a 2048-row slab of gate 28672x8192)")
+    w = synth.weight(1024, 8192, seed=4001, outlier_frac=0.001)
+    _encode_and_check(oracle, w, W, SV)
+    w = synth.weight(2048, 8192, seed=4004, outlier_frac=0.001)
+    _encode_and_check(oracle, w, W, SV)
+
+
+def test_config5_w4a4(oracle):
+    _say("config 5: activation 4096x4096 encode (E4M3 + 1 bit, +-5) and W4A4 linear vs gate 11008x4096")
+    a = synth.activation(4096, 4096, seed=5000, outlier_frac=0.005, outlier_gain=50.0)
+    at, aq = _encode_and_check(oracle, a, A, (5.0, 0.0))
+    frac = np.mean(((aq[0] & 15) == 8) | ((aq[0] >> 4) == 8))
+    _say("   activation elements on the special value: %.4f" % frac)
+    assert frac > 0.005
+    wq = _rand_packed(11008, 4096, seed=5001)
+    wt = razer.RazerTensor.from_host(*wq, W, SV)
+    y = razer.razer_linear(wt, at)
+    torch.cuda.synchronize()
+    rows = synth.sample_indices(4096, 64, 9000)
+    cols = synth.sample_indices(11008, 256, 9001)
+    y64, _ = oracle.linear(wq, a_q=aq, rows=rows, cols=cols)
+    got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+    err = max_rel_err(got, y64)
+    _say("   w4a4 max rel err %.2e" % err)
+    assert err <= TOL, err
