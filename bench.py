@@ -131,12 +131,20 @@ def main():
         g.manual_seed(seed)
         return torch.randn((m, k), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
 
-    def linear_leg(m, steps, warmup, rotate=True, graph=False):
+    def linear_leg(m, steps, warmup, rotate=True, graph=False, grouped=False):
         acts = {k: make_act(m, k, 2100 + m) for k in {k for _, _, k in layers}}
         outs = [torch.empty((m, n), dtype=torch.bfloat16, device="cuda") for _, n, _ in layers]
 
         def step(i):
             cp = copies[i % n_copies] if rotate else copies[0]
+            if grouped:
+                # the projections that consume the same activation go out as one launch each:
+                # {q,k,v}, o, {gate,up}, down -- the dependency structure of a decoder layer
+                razer.razer_linear_grouped(cp[0:3], acts[cp[0].cols], outs=outs[0:3])
+                razer.razer_linear(cp[3], acts[cp[3].cols], out=outs[3])
+                razer.razer_linear_grouped(cp[4:6], acts[cp[4].cols], outs=outs[4:6])
+                razer.razer_linear(cp[6], acts[cp[6].cols], out=outs[6])
+                return
             for j, t in enumerate(cp):
                 razer.razer_linear(t, acts[t.cols], out=outs[j])
         ms = time_region(step, steps, warmup, graph_period=(n_copies if rotate else 1) if graph else 0)
@@ -146,9 +154,12 @@ def main():
 
     # ---- headline: GEMV at M=1 ----------------------------------------------------------
     use_graph = not args.no_graph
-    ms1, bytes1, _ = linear_leg(1, args.steps, args.warmup, graph=use_graph)
+    ms1, bytes1, _ = linear_leg(1, args.steps, args.warmup, graph=use_graph, grouped=True)
     gbs = bytes1 / ms1 / 1e6
-    ms1c, _, _ = linear_leg(1, max(10, args.steps // 4), 5, rotate=False, graph=use_graph)
+    ms1s, _, _ = linear_leg(1, max(10, args.steps // 4), 5, graph=use_graph)
+    legs["gemv_m1_seven_launches"] = {"GB/s": bytes1 / ms1s / 1e6, "ms_per_step": ms1s,
+                                      "note": "same step as seven razer_linear calls instead of four (no grouping)"}
+    ms1c, _, _ = linear_leg(1, max(10, args.steps // 4), 5, rotate=False, graph=use_graph, grouped=True)
     if use_graph:
         ms1e, _, _ = linear_leg(1, max(10, args.steps // 4), 5)
         legs["gemv_m1_eager_launches"] = {"GB/s": bytes1 / ms1e / 1e6, "ms_per_step": ms1e,
@@ -158,7 +169,7 @@ def main():
     gemm_roof = None
     if args.legs == "all":
         for m in (4, 16):
-            ms, b, _ = linear_leg(m, max(10, args.steps // 4), 5, graph=use_graph)
+            ms, b, _ = linear_leg(m, max(10, args.steps // 4), 5, graph=use_graph, grouped=(m <= 4))
             legs["linear_m%d" % m] = {"GB/s": b / ms / 1e6, "frac_hbm": b / ms / 1e6 / HBM_PEAK_GBS, "ms_per_step": ms}
         for m in (512, 2048):
             ms, _, fl = linear_leg(m, 5, 2)
@@ -215,12 +226,13 @@ def main():
         "dtype": "fp4 codes x bf16 activations, fp32 accumulate", "data": "synthetic",
         "config": {"workload": "configs[1]: Llama-7B-shaped decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; "
                                "down 4096x11008), RaZeR weights (block 16, E3M3 scale + 2 meta bits, sv {5,8}), M=1; "
-                               "one step = the 7 projections once%s; %d packed copies rotated (%.0f MB > 2x LLC)"
+                               "one step = the 7 projections once, as 4 launches: {q,k,v} and {gate,up} share their activation and go through "
+                               "razer_linear_grouped%s; %d packed copies rotated (%.0f MB > 2x LLC)"
                                % (" (replayed as a HIP graph)" if use_graph else "", n_copies, n_copies * layer_bytes / 1e6),
                    "m": 1, "bytes_per_step": bytes1},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "gemv_kernel<M=1> (7 launches per step; achieved = algorithmic bytes of the step / step time)"},
+                     "kernel": "gemv_grouped_kernel<1,4> / gemv_kernel<1,4> (4 launches per step; achieved = algorithmic bytes of the step / step time)"},
         "cpu_baseline": cpu,
         "legs": legs,
     }

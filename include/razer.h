@@ -124,6 +124,17 @@ razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer
                           int64_t m, void *y_bf16, int64_t ld_y,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same layer for several weight matrices that consume the SAME activation rows (fused q/k/v,
+ * gate/up projections; the paper's stripe partition likewise lets one launch span several N
+ * ranges, Sec. 4.3): y_bf16[i] = A w[i]^T for i < count, count <= RAZER_MAX_GROUP.  All w[i] must
+ * have the same cols; W4A16 only.  For m <= 4 and equal special values this is ONE kernel launch
+ * (short decode-regime kernels are launch-latency-bound); otherwise it is the sequence of
+ * razer_linear calls.  y_bf16[i] is device [m][ld_y[i]].  The pointer arrays are HOST arrays. */
+#define RAZER_MAX_GROUP 4
+razer_status razer_linear_grouped(const razer_tensor *const *w, int32_t count, const void *a_bf16,
+                                  int64_t m, void *const *y_bf16, const int64_t *ld_y,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
 const char *razer_status_string(razer_status s);
 
 #ifdef __cplusplus

@@ -17,7 +17,7 @@ OP_QUANTIZE, OP_DEQUANT, OP_LINEAR = 0, 1, 2
 GIVEN_TENSOR_SCALE = 1
 
 EXPORTS = ["razer_workspace_bytes", "razer_quantize", "razer_dequant", "razer_linear",
-           "razer_status_string"]
+           "razer_linear_grouped", "razer_status_string"]
 
 
 class RazerError(RuntimeError):
@@ -64,6 +64,9 @@ def load_library():
     L.razer_linear.restype = ctypes.c_int
     L.razer_linear.argtypes = [ctypes.POINTER(_Tensor), vp, ctypes.POINTER(_Tensor), i64, vp, i64,
                                vp, sz, vp]
+    L.razer_linear_grouped.restype = ctypes.c_int
+    L.razer_linear_grouped.argtypes = [ctypes.POINTER(ctypes.POINTER(_Tensor)), i32, vp, i64,
+                                       ctypes.POINTER(vp), ctypes.POINTER(i64), vp, sz, vp]
     L.razer_status_string.restype = ctypes.c_char_p
     L.razer_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -193,3 +196,22 @@ def razer_linear(w, a, out=None, workspace=None):
     if st != 0:
         raise RazerError(st, "razer_linear")
     return out
+
+
+def razer_linear_grouped(ws, a, outs=None):
+    """y[i] = A ws[i]^T for up to 4 RazerTensors that share K and the bf16 activation rows a [M][K]
+    (fused q/k/v, gate/up): one kernel launch when M <= 4.  Returns the list of bfloat16 outputs."""
+    L = load_library()
+    assert a.is_cuda and a.dtype == torch.bfloat16 and a.dim() == 2 and a.is_contiguous()
+    m, count = a.shape[0], len(ws)
+    if outs is None:
+        outs = [torch.empty((m, w.rows), dtype=torch.bfloat16, device=a.device) for w in ws]
+    structs = [w.c_struct() for w in ws]
+    wptrs = (ctypes.POINTER(_Tensor) * count)(*[ctypes.pointer(s) for s in structs])
+    yptrs = (ctypes.c_void_p * count)(*[o.data_ptr() for o in outs])
+    lds = (ctypes.c_int64 * count)(*[(o.stride(0) if m > 1 else max(o.stride(0), w.rows))
+                                     for o, w in zip(outs, ws)])
+    st = L.razer_linear_grouped(wptrs, count, _ptr(a), m, yptrs, lds, None, 0, _stream())
+    if st != 0:
+        raise RazerError(st, "razer_linear_grouped")
+    return outs

@@ -160,4 +160,41 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
     return e == hipSuccess ? RAZER_OK : RAZER_ERR_HIP;
 }
 
+razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, const void* a_bf16, int64_t m,
+                                  void* const* y_bf16, const int64_t* ld_y, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream)
+{
+    if (!w || !y_bf16 || !ld_y) return RAZER_ERR_NULL;
+    if (count < 1 || count > RAZER_MAX_GROUP) return RAZER_ERR_SHAPE;
+    SvConfig sv0;
+    bool one_launch = (m >= 1 && m <= 4);
+    for (int i = 0; i < count; ++i) {
+        SvConfig sv;
+        razer_status s = check_tensor(w[i], RAZER_FMT_WEIGHT, sv);
+        if (s != RAZER_OK) return s;
+        if (w[i]->cols != w[0]->cols) return RAZER_ERR_SHAPE;
+        if (m < 0 || ld_y[i] < w[i]->rows) return RAZER_ERR_SHAPE;
+        if (m > 0 && w[i]->rows > 0 && !y_bf16[i]) return RAZER_ERR_NULL;
+        if (i == 0) sv0 = sv;
+        else if (sv.sv0 != sv0.sv0 || sv.sv1 != sv0.sv1) one_launch = false;
+        if (w[i]->rows == 0) one_launch = false;
+    }
+    if (m == 0) return RAZER_OK;
+    if (!a_bf16) return RAZER_ERR_NULL;
+    if (w[0]->cols > 0 && !aligned16(a_bf16)) return RAZER_ERR_ALIGN;
+    if (!one_launch || w[0]->cols == 0) {
+        for (int i = 0; i < count; ++i) {
+            razer_status s = razer_linear(w[i], a_bf16, nullptr, m, y_bf16[i], ld_y[i], workspace, workspace_bytes,
+                                          hip_stream);
+            if (s != RAZER_OK) return s;
+        }
+        return RAZER_OK;
+    }
+    GemvProblem p[RAZER_MAX_GROUP];
+    for (int i = 0; i < count; ++i)
+        p[i] = GemvProblem{w[i]->codes, w[i]->scales, w[i]->tensor_scale, w[i]->rows, (uint16_t*)y_bf16[i], ld_y[i]};
+    hipError_t e = launch_gemv_grouped(sv0, count, p, w[0]->cols, (const uint16_t*)a_bf16, m, (hipStream_t)hip_stream);
+    return e == hipSuccess ? RAZER_OK : RAZER_ERR_HIP;
+}
+
 }  // extern "C"

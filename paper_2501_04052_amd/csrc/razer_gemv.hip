@@ -111,18 +111,15 @@ __device__ __forceinline__ void dot_group(const RowGroup<R>& g, const uint4 (&av
 // the slices and write bf16.  The grid is one workgroup per R rows: for the matrices of a decoder
 // layer the whole problem is in flight at once, which is what hides the HBM latency.
 template <int M, int R>
-__global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __restrict__ codes,
-                                                              const uint8_t* __restrict__ scales,
-                                                              const float* __restrict__ w_ts, SvConfig cfg,
-                                                              int64_t n, int64_t k,
-                                                              const uint16_t* __restrict__ a,
-                                                              uint16_t* __restrict__ y, int64_t ld_y)
+__device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+                                          const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
+                                          int64_t k, const uint16_t* __restrict__ a, uint16_t* __restrict__ y,
+                                          int64_t ld_y, int64_t row0)
 {
     __shared__ uint2 lut[256];
     __shared__ float part[kMaxWaves][R][M];
     const float ts = *w_ts;                                               // issued early, used last
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    const int64_t row0 = (int64_t)blockIdx.x * R;
     const int64_t chunks = k / 32;                                        // 16-byte code chunks per row
     const int npass = (int)((chunks + 64 * nwaves - 1) / (64 * nwaves));  // > 1 only when K > 2048 * waves
 
@@ -146,7 +143,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __r
         load_group<R>(grp, codes, scales, row0, n, k, cc);
     };
     issue_loads();
-    fill_weight_lut(lut, cfg.sv0, cfg.sv1);
+    fill_weight_lut(lut, sv0, sv1);
     __syncthreads();                                                      // LUT ready
 
     float tot[R][M];
@@ -187,6 +184,42 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __r
 }
 
 template <int M, int R>
+__global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __restrict__ codes,
+                                                              const uint8_t* __restrict__ scales,
+                                                              const float* __restrict__ w_ts, float sv0, float sv1,
+                                                              int64_t n, int64_t k,
+                                                              const uint16_t* __restrict__ a,
+                                                              uint16_t* __restrict__ y, int64_t ld_y)
+{
+    gemv_body<M, R>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y, (int64_t)blockIdx.x * R);
+}
+
+// Up to four weight matrices that share K, the activation rows and the special values, in one
+// launch (fused q/k/v, gate/up): workgroups [0, g1) serve matrix 0, [g1, g2) matrix 1, ...  Every
+// per-matrix argument is a scalar kernel argument picked with uniform compares: no indexed
+// argument arrays, which would cost a private copy.
+template <int M, int R>
+__global__ __launch_bounds__(64 * kMaxWaves) void gemv_grouped_kernel(
+    const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
+    const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
+    const float* t0, const float* t1, const float* t2, const float* t3,
+    uint16_t* y0, uint16_t* y1, uint16_t* y2, uint16_t* y3,
+    int64_t n0, int64_t n1, int64_t n2, int64_t n3,
+    int64_t l0, int64_t l1, int64_t l2, int64_t l3,
+    unsigned g1, unsigned g2, unsigned g3,
+    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a)
+{
+    const unsigned b = blockIdx.x;
+    const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = t0; uint16_t* y = y0;
+    int64_t n = n0, ld = l0;
+    unsigned first = 0;
+    if (b >= g1) { codes = c1; scales = s1; ts = t1; y = y1; n = n1; ld = l1; first = g1; }
+    if (b >= g2) { codes = c2; scales = s2; ts = t2; y = y2; n = n2; ld = l2; first = g2; }
+    if (b >= g3) { codes = c3; scales = s3; ts = t3; y = y3; n = n3; ld = l3; first = g3; }
+    gemv_body<M, R>(codes, scales, ts, sv0, sv1, n, k, a, y, ld, (int64_t)(b - first) * R);
+}
+
+template <int M, int R>
 static hipError_t launch_gemv_mr(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,
                                  int64_t n, int64_t k, const uint16_t* a, uint16_t* y, int64_t ld_y, hipStream_t st)
 {
@@ -194,7 +227,7 @@ static hipError_t launch_gemv_mr(SvConfig cfg, const uint8_t* codes, const uint8
     const int64_t nslices = (k + kSliceK - 1) / kSliceK;
     const int nwaves = (int)(nslices < kMaxWaves ? nslices : kMaxWaves);
     const unsigned grid = (unsigned)((n + R - 1) / R);
-    gemv_kernel<M, R><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg, n, k, a, y, ld_y);
+    gemv_kernel<M, R><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y);
     return hipGetLastError();
 }
 template <int M>
@@ -203,6 +236,38 @@ static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_
 {
     // 4 rows per workgroup measured best on MI355X over 2 and 8 for every shape of the 7B / 70B layers.
     return launch_gemv_mr<M, 4>(cfg, codes, scales, ts, n, k, a, y, ld_y, st);
+}
+
+template <int M>
+static hipError_t launch_gemv_grouped_m(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
+                                        hipStream_t st)
+{
+    constexpr int R = 4;
+    const int64_t nslices = (k + kSliceK - 1) / kSliceK;
+    const int nwaves = (int)(nslices < kMaxWaves ? nslices : kMaxWaves);
+    GemvProblem q[4];
+    unsigned g[5] = {0, 0, 0, 0, 0};
+    for (int i = 0; i < 4; ++i) {
+        q[i] = p[i < count ? i : count - 1];
+        g[i + 1] = g[i] + (i < count ? (unsigned)((q[i].n + R - 1) / R) : 0u);
+    }
+    gemv_grouped_kernel<M, R><<<g[4], 64 * nwaves, 0, st>>>(
+        q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales,
+        q[0].ts, q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n,
+        q[0].ld_y, q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
+                               int64_t m, hipStream_t st)
+{
+    if (count < 1 || count > 4 || m < 1 || m > 4) return hipErrorInvalidValue;
+    switch (m) {
+        case 1: return launch_gemv_grouped_m<1>(cfg, count, p, k, a, st);
+        case 2: return launch_gemv_grouped_m<2>(cfg, count, p, k, a, st);
+        case 3: return launch_gemv_grouped_m<3>(cfg, count, p, k, a, st);
+        default: return launch_gemv_grouped_m<4>(cfg, count, p, k, a, st);
+    }
 }
 
 hipError_t launch_gemv(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,

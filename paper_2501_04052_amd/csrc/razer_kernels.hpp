@@ -22,6 +22,18 @@ hipError_t launch_gemv(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_s
                        int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
                        hipStream_t st);
 
+// Up to 4 weight matrices sharing K, the activation rows (m <= 4) and the special values, one launch.
+struct GemvProblem {
+    const uint8_t* codes;
+    const uint8_t* scales;
+    const float* ts;
+    int64_t n;
+    uint16_t* y;
+    int64_t ld_y;
+};
+hipError_t launch_gemv_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
+                               int64_t m, hipStream_t st);
+
 // Same contraction on bf16 matrix cores with LDS-staged decoded tiles.  Activations are
 // bf16 (a != nullptr) or RaZeR activation-format (a_codes != nullptr).
 hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,

@@ -86,5 +86,22 @@ def test_bad_arguments_return_status_codes_without_gpu(razer):
     tw = _Tensor(); tw.codes = 0x1000; tw.scales = 0x2000; tw.tensor_scale = 0x3000
     tw.rows = 8; tw.cols = 64; tw.cfg = ca                      # activation format used as weight
     assert L.razer_linear(ctypes.byref(tw), fake, None, 1, fake, 8, None, 0, None) == 4
+    # grouped: null arrays, bad counts, mismatched K
+    PT = ctypes.POINTER(_Tensor)
+    t2 = _Tensor(); t2.codes = 0x1000; t2.scales = 0x2000; t2.tensor_scale = 0x3000
+    t2.rows = 8; t2.cols = 96; t2.cfg = cfg
+    arr = (PT * 2)(ctypes.pointer(t), ctypes.pointer(t2))
+    ys = (ctypes.c_void_p * 2)(0x4000, 0x5000)
+    lds = (ctypes.c_int64 * 2)(8, 8)
+    assert L.razer_linear_grouped(None, 2, fake, 1, ys, lds, None, 0, None) == 1
+    assert L.razer_linear_grouped(arr, 0, fake, 1, ys, lds, None, 0, None) == 2
+    assert L.razer_linear_grouped(arr, 5, fake, 1, ys, lds, None, 0, None) == 2
+    assert L.razer_linear_grouped(arr, 2, fake, 1, ys, lds, None, 0, None) == 2      # cols differ
+    t2.cols = 64
+    lds_bad = (ctypes.c_int64 * 2)(8, 4)
+    assert L.razer_linear_grouped(arr, 2, fake, 1, ys, lds_bad, None, 0, None) == 2
+    assert L.razer_linear_grouped(arr, 2, None, 1, ys, lds, None, 0, None) == 1
+    assert L.razer_linear_grouped(arr, 2, odd, 1, ys, lds, None, 0, None) == 3
+    assert L.razer_linear_grouped(arr, 2, None, 0, ys, lds, None, 0, None) == 0
     # empty problems are fine and launch nothing
     assert L.razer_linear(ctypes.byref(t), fake, None, 0, None, 8, None, 0, None) == 0

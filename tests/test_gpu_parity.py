@@ -230,3 +230,29 @@ def test_linear_strided_output_and_empty(oracle):
         assert torch.all(buf[:, n:] == 3.0)
     y = razer.razer_linear(wt, torch.empty((0, k), dtype=torch.bfloat16, device="cuda"))
     assert y.shape == (0, n)
+
+
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 20])
+def test_linear_grouped_matches_oracle(oracle, m):
+    """Several weight matrices on the same activation rows in one call (one launch for m <= 4)."""
+    print("grouped", m, flush=True)
+    k = 2048 + 96
+    ns = [100, 64, 37, 9]
+    a = synth.activation(m, k, seed=800 + m)
+    a_dev = bf16_bits_to_dev(a)
+    for count in (1, 2, 4):
+        wqs = [oracle.quantize(W, synth.weight(n, k, seed=810 + i, outlier_frac=0.002)) for i, n in enumerate(ns[:count])]
+        wts = [razer.RazerTensor.from_host(*wq, W, (5.0, 8.0)) for wq in wqs]
+        bufs = [torch.full((m, n + 8), 2.0, dtype=torch.bfloat16, device="cuda") for n in ns[:count]]
+        razer.razer_linear_grouped(wts, a_dev, outs=[b[:, :n] for b, n in zip(bufs, ns)])
+        torch.cuda.synchronize()
+        for wq, b, n in zip(wqs, bufs, ns):
+            y64, _ = oracle.linear(wq, a_bf16=a)
+            assert max_rel_err(dev_to_bf16_bits(b[:, :n]), y64) <= TOL
+            assert torch.all(b[:, n:] == 2.0)
+    # different special values per matrix: falls back to one launch each, same results
+    wq2 = oracle.quantize(W, synth.weight(50, k, seed=820), sv=(5.0, 7.0))
+    wts = [razer.RazerTensor.from_host(*wqs[0], W, (5.0, 8.0)), razer.RazerTensor.from_host(*wq2, W, (5.0, 7.0))]
+    ys = razer.razer_linear_grouped(wts, a_dev)
+    assert max_rel_err(dev_to_bf16_bits(ys[1]), oracle.linear(wq2, a_bf16=a, w_sv=(5.0, 7.0))[0]) <= TOL
+    assert max_rel_err(dev_to_bf16_bits(ys[0]), oracle.linear(wqs[0], a_bf16=a)[0]) <= TOL
