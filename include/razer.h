@@ -117,9 +117,11 @@ razer_status razer_dequant(const razer_tensor *t, void *out, int32_t dtype, int6
  *   a_bf16  device bf16 [m][K] dense                      (W4A16), or
  *   a_q     RAZER_FMT_ACT tensor [m][K]                   (W4A4)
  * is non-NULL.  Products are accumulated in fp32 (bf16 matrix cores for large
- * m, wavefront dot products for m <= 16), scaled by the tensor scale(s) and
- * rounded to bf16:  y_bf16 device [m][ld_y], ld_y >= N.
- * workspace: >= razer_workspace_bytes(RAZER_OP_LINEAR, N, K, m) bytes (may be 0). */
+ * m, wavefront dot products for m <= 4, a decode-once MFMA kernel in between), scaled by the
+ * tensor scale(s) and rounded to bf16:  y_bf16 device [m][ld_y], ld_y >= N.
+ * workspace: device, 16-byte aligned, >= razer_workspace_bytes(RAZER_OP_LINEAR, N, K, m) bytes
+ * (non-zero only for W4A16 with 5 <= m <= 32, where K-slices meet in fp32; else may be NULL);
+ * too small -> RAZER_ERR_WORKSPACE. */
 razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer_tensor *a_q,
                           int64_t m, void *y_bf16, int64_t ld_y,
                           void *workspace, size_t workspace_bytes, void *hip_stream);

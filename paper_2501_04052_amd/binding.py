@@ -191,6 +191,10 @@ def razer_linear(w, a, out=None, workspace=None):
         out = torch.empty((m, w.rows), dtype=torch.bfloat16, device=dev)
     ws = w.c_struct()
     ld_y = out.stride(0) if m > 1 else max(out.stride(0), w.rows)
+    if workspace is None and a_ptr is not None:
+        need = razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     st = L.razer_linear(ctypes.byref(ws), a_ptr, aq_ptr, m, _ptr(out), ld_y, _ptr(workspace),
                         0 if workspace is None else workspace.numel(), _stream())
     if st != 0:
@@ -211,7 +215,9 @@ def razer_linear_grouped(ws, a, outs=None):
     yptrs = (ctypes.c_void_p * count)(*[o.data_ptr() for o in outs])
     lds = (ctypes.c_int64 * count)(*[(o.stride(0) if m > 1 else max(o.stride(0), w.rows))
                                      for o, w in zip(outs, ws)])
-    st = L.razer_linear_grouped(wptrs, count, _ptr(a), m, yptrs, lds, None, 0, _stream())
+    need = max(razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m) for w in ws)
+    workspace = torch.empty(need, dtype=torch.uint8, device=a.device) if need else None
+    st = L.razer_linear_grouped(wptrs, count, _ptr(a), m, yptrs, lds, _ptr(workspace), need, _stream())
     if st != 0:
         raise RazerError(st, "razer_linear_grouped")
     return outs

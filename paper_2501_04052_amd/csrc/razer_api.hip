@@ -71,9 +71,9 @@ const char* razer_status_string(razer_status s)
 
 size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m)
 {
-    (void)rows; (void)cols; (void)m;
     switch (op) {
         case RAZER_OP_QUANTIZE: return 256;    // the absmax cell of Eq. 1
+        case RAZER_OP_LINEAR: return skinny_workspace_bytes(rows, cols, m);   // K-slice partial sums, 5 <= m <= 32
         default: return 0;
     }
 }
@@ -126,7 +126,6 @@ razer_status razer_dequant(const razer_tensor* t, void* out, int32_t dtype, int6
 razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer_tensor* a_q, int64_t m,
                           void* y_bf16, int64_t ld_y, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    (void)workspace; (void)workspace_bytes;
     SvConfig wsv, asv = {5.0f, 5.0f};
     razer_status s = check_tensor(w, RAZER_FMT_WEIGHT, wsv);
     if (s != RAZER_OK) return s;
@@ -149,7 +148,12 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
         const int64_t total = m * n;
         fill_zero_bf16_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((uint16_t*)y_bf16, m, n, ld_y);
         e = hipGetLastError();
-    } else if (!a_q && m <= kGemvMaxM) {
+    } else if (!a_q && m > kGemvDirectMaxM && m <= kSkinnyMaxM) {
+        const size_t need = skinny_workspace_bytes(n, k, m);
+        if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return RAZER_ERR_WORKSPACE;
+        e = launch_skinny(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
+                          (uint16_t*)y_bf16, ld_y, (float*)workspace, st);
+    } else if (!a_q && m <= kGemvDirectMaxM) {
         e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
                         (uint16_t*)y_bf16, ld_y, st);
     } else {

@@ -18,6 +18,15 @@ hipError_t launch_dequant(int fmt, SvConfig cfg, const uint8_t* codes, const uin
 
 // Y[m][n] = A[m][:] . W[n][:], m <= kGemvMaxM: wavefront dot products, HBM-bound (4 rows per pass).
 constexpr int kGemvMaxM = 16;
+constexpr int kGemvDirectMaxM = 4;     // rows the GEMV kernel takes in one pass
+constexpr int kSkinnyMaxM = 32;        // above this the tiled GEMM takes over
+
+// 5 <= m <= kSkinnyMaxM: decode-once MFMA kernel; K-slices meet in an fp32 workspace of
+// skinny_workspace_bytes(n, k, m) bytes (0 when a single slice covers K).
+size_t skinny_workspace_bytes(int64_t n, int64_t k, int64_t m);
+hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts, int64_t n,
+                         int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y, float* workspace,
+                         hipStream_t st);
 hipError_t launch_gemv(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
                        int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
                        hipStream_t st);

@@ -1,0 +1,179 @@
+// Weight-only RaZeR linear layer for 5..32 activation rows on gfx950 (small-batch decode, Sec. 4.3 /
+// App. D.2 of arxiv 2501.04052): every packed weight is read from HBM and decoded exactly once, the
+// multiply-accumulate goes to v_mfma_f32_16x16x32_bf16 with the activation rows padded to 16 or 32.
+//
+// A lane's 8 consecutive codes (one dword) decode straight into the 4 registers of an MFMA "A"
+// operand (rows = weight rows n, k = this lane's 8 k's), so the weights never pass through LDS.
+// MFMA operands are invariant under a permutation of k applied to both operands: lane group g of
+// step s, instruction j holds k = 128 s + 32 g + 8 j .. +7, which makes a lane's 4 operands one
+// 16-byte load of codes plus one 16-bit load of scale bytes.  Activations (M x KC bf16, shared by
+// the 4 waves = 64 weight rows of a workgroup) are staged once in LDS, chunk-swizzled with the row.
+//
+// Work split: grid = (N / 64) x (K / KC); K-slices of one output tile are summed in fixed order by
+// a second kernel from an fp32 workspace [slices][M][N] (deterministic, no atomics).
+#include "razer_device.hpp"
+#include "razer_kernels.hpp"
+
+namespace razer {
+
+template <int BYTE>
+__device__ __forceinline__ uint32_t sk_cvt_scaled_pair(uint32_t xflip, float s, uint32_t patch)
+{
+    v2f p = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(xflip, 1.0f, BYTE);   // -element, exact
+    p.x *= s;
+    p.y *= s;
+    v2bf b = __builtin_convertvector(p, v2bf);
+    return patch_zero_halves(__builtin_bit_cast(uint32_t, b), patch);
+}
+__device__ __forceinline__ v8bf sk_decode_dword(uint32_t x, uint2 le)
+{
+    const uint32_t xf = x ^ kRemapXor;
+    const float s = u2f(le.x);
+    const uint4 r = make_uint4(sk_cvt_scaled_pair<0>(xf, s, le.y), sk_cvt_scaled_pair<1>(xf, s, le.y),
+                               sk_cvt_scaled_pair<2>(xf, s, le.y), sk_cvt_scaled_pair<3>(xf, s, le.y));
+    return __builtin_bit_cast(v8bf, r);
+}
+
+constexpr int kSkRows = 64;            // weight rows per workgroup (4 waves x 16)
+
+// NB: activation fragments of 16 rows (M <= 16 NB); STEPS: 128-k steps per workgroup (KC = 128 STEPS).
+template <int NB, int STEPS>
+__global__ __launch_bounds__(256) void skinny_kernel(const uint8_t* __restrict__ codes,
+                                                     const uint8_t* __restrict__ scales,
+                                                     const float* __restrict__ w_ts, float sv0, float sv1,
+                                                     int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
+                                                     uint16_t* __restrict__ y, int64_t ld_y,
+                                                     float* __restrict__ partial, int nslices)
+{
+    constexpr int KC = 128 * STEPS;
+    constexpr int ROWB = KC * 2;                                   // bytes per activation row in LDS
+    __shared__ __align__(16) uint8_t atile[NB * 16 * ROWB];
+    __shared__ uint2 lut[256];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int slice = blockIdx.x % nslices;
+    const int64_t n0 = (int64_t)(blockIdx.x / nslices) * kSkRows;
+    const int64_t k0 = (int64_t)slice * KC;
+    const float ts = *w_ts;
+
+    // this lane's weights: row n0 + 16 wave + (lane % 16), k = k0 + 128 s + 32 (lane / 16) .. +31
+    const int64_t wrow_raw = n0 + 16 * wave + (lane & 15);
+    const int64_t wrow = wrow_raw < n ? wrow_raw : n - 1;
+    uint4 cw[STEPS];
+    uint32_t sw[STEPS];
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+        const int64_t kk = k0 + 128 * s + 32 * (lane >> 4);
+        const bool in = kk < k;
+        const int64_t kc = in ? kk : 0;
+        const uint4 c = *reinterpret_cast<const uint4*>(codes + wrow * (k / 2) + kc / 2);
+        const uint32_t sc = *reinterpret_cast<const uint16_t*>(scales + wrow * (k / 16) + kc / 16);
+        const uint32_t msk = in ? 0xFFFFFFFFu : 0u;               // beyond K: code 0, scale 0 -> weight 0
+        cw[s] = make_uint4(c.x & msk, c.y & msk, c.z & msk, c.w & msk);
+        sw[s] = sc & msk;
+    }
+    // activations [NB*16][KC] -> LDS, 16-byte chunks swizzled with the row
+    constexpr int UNITS = NB * 16 * (KC / 8);
+#pragma unroll
+    for (int i = 0; i < UNITS / 256; ++i) {
+        const int u = tid + i * 256, row = u / (KC / 8), c = u % (KC / 8);
+        const int64_t kk = k0 + c * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (row < m && kk < k) v = *reinterpret_cast<const uint4*>(a + (int64_t)row * k + kk);
+        *reinterpret_cast<uint4*>(atile + row * ROWB + ((c ^ (row & 15)) << 4)) = v;
+    }
+    for (uint32_t sb = tid; sb < 256u; sb += 256) {
+        float s, sv;
+        decode_scale_byte<0>(sb, sv0, sv1, s, sv);
+        const uint32_t p = (uint32_t)f32_to_bf16_rne(-(sv * s));
+        lut[sb] = make_uint2(f2u(s), p | (p << 16));
+    }
+    __syncthreads();
+
+    v4f acc[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) acc[b] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+        const uint2 le0 = lut[sw[s] & 255u], le1 = lut[(sw[s] >> 8) & 255u];
+        const uint32_t xw[4] = {cw[s].x, cw[s].y, cw[s].z, cw[s].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const v8bf wf = sk_decode_dword(xw[j], j < 2 ? le0 : le1);
+            const int c = 16 * s + 4 * (lane >> 4) + j;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int row = 16 * b + (lane & 15);
+                const v8bf af = *reinterpret_cast<const v8bf*>(atile + row * ROWB + ((c ^ (row & 15)) << 4));
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, af, acc[b], 0, 0, 0);
+            }
+        }
+    }
+    // lane holds rows n = 4 (lane / 16) + 0..3 (of this wave's 16), column m = 16 b + lane % 16
+    const int64_t gn = n0 + 16 * wave + 4 * (lane >> 4);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int64_t gm = 16 * b + (lane & 15);
+        if (gm < m && gn < n) {
+            if (nslices == 1) {
+                uint16_t* dst = y + gm * ld_y + gn;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (gn + e < n) dst[e] = f32_to_bf16_rne(-ts * acc[b][e]);
+            } else {
+                float* dst = partial + ((int64_t)slice * m + gm) * n + gn;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (gn + e < n) dst[e] = acc[b][e];
+            }
+        }
+    }
+}
+
+// y[m][n] = bf16(-ts * sum over slices, in slice order, of partial[slice][m][n])
+__global__ __launch_bounds__(256) void skinny_reduce_kernel(const float* __restrict__ partial,
+                                                            const float* __restrict__ w_ts, int64_t m, int64_t n,
+                                                            int nslices, uint16_t* __restrict__ y, int64_t ld_y)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= m * n) return;
+    float t = 0.0f;
+    for (int s = 0; s < nslices; ++s) t += partial[(int64_t)s * m * n + i];
+    const int64_t r = i / n, c = i - r * n;
+    y[r * ld_y + c] = f32_to_bf16_rne(-(*w_ts) * t);
+}
+
+static int skinny_steps(int64_t k, int64_t m)
+{
+    // 512-element K-slices; 1024 for long rows at M <= 16 to bound the number of slices
+    return (m <= 16 && k > 8192) ? 8 : 4;
+}
+
+size_t skinny_workspace_bytes(int64_t n, int64_t k, int64_t m)
+{
+    if (m <= kGemvDirectMaxM || m > kSkinnyMaxM || k == 0) return 0;
+    const int64_t kc = 128 * skinny_steps(k, m);
+    const int64_t nslices = (k + kc - 1) / kc;
+    return nslices > 1 ? (size_t)(nslices * m * n) * sizeof(float) : 0;
+}
+
+hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts, int64_t n,
+                         int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y, float* workspace,
+                         hipStream_t st)
+{
+    const int steps = skinny_steps(k, m);
+    const int64_t kc = 128 * steps;
+    const int nslices = (int)((k + kc - 1) / kc);
+    const unsigned grid = (unsigned)(((n + kSkRows - 1) / kSkRows) * nslices);
+#define RAZER_SK(NB, ST) skinny_kernel<NB, ST><<<grid, 256, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, workspace, nslices)
+    if (m <= 16) { if (steps == 8) RAZER_SK(1, 8); else RAZER_SK(1, 4); }
+    else RAZER_SK(2, 4);
+#undef RAZER_SK
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || nslices == 1) return e;
+    const int64_t total = m * n;
+    skinny_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(workspace, ts, m, n, nslices, y, ld_y);
+    return hipGetLastError();
+}
+
+}  // namespace razer

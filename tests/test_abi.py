@@ -40,6 +40,11 @@ def test_status_strings(razer):
 def test_workspace_sizes(razer):
     assert razer.razer_workspace_bytes(0, 4096, 4096) >= 4
     assert razer.razer_workspace_bytes(1, 4096, 4096) == 0
+    # linear: only the 5..32-row kernel meets its K-slices in a workspace
+    assert razer.razer_workspace_bytes(2, 4096, 4096, 1) == 0
+    assert razer.razer_workspace_bytes(2, 4096, 4096, 2048) == 0
+    assert razer.razer_workspace_bytes(2, 4096, 4096, 16) == 8 * 16 * 4096 * 4
+    assert razer.razer_workspace_bytes(2, 4096, 512, 16) == 0
 
 
 def test_bad_arguments_return_status_codes_without_gpu(razer):
@@ -77,6 +82,10 @@ def test_bad_arguments_return_status_codes_without_gpu(razer):
     assert L.razer_linear(ctypes.byref(t), fake, None, 1, fake, 4, None, 0, None) == 2
     assert L.razer_linear(ctypes.byref(t), fake, None, -1, fake, 8, None, 0, None) == 2
     assert L.razer_linear(ctypes.byref(t), odd, None, 1, fake, 8, None, 0, None) == 3
+    tb = _Tensor(); tb.codes = 0x1000; tb.scales = 0x2000; tb.tensor_scale = 0x3000
+    tb.rows = 8; tb.cols = 1024; tb.cfg = cfg
+    assert L.razer_linear(ctypes.byref(tb), fake, None, 8, fake, 8, None, 0, None) == 5      # needs a workspace
+    assert L.razer_linear(ctypes.byref(tb), fake, None, 8, fake, 8, fake, 16, None) == 5     # too small
     ta = _Tensor(); ta.codes = 0x1000; ta.scales = 0x2000; ta.tensor_scale = 0x3000
     ta.rows = 2; ta.cols = 64; ta.cfg = cfg                      # weight format used as activation
     assert L.razer_linear(ctypes.byref(t), None, ctypes.byref(ta), 2, fake, 8, None, 0, None) == 4
