@@ -197,6 +197,40 @@ def main():
         legs["w4a4_linear_4096x11008x4096"] = {"TFLOP/s": 2.0 * 4096 * 11008 * 4096 / ms_l / 1e9, "ms": ms_l,
                                                "end_to_end_TFLOP/s": 2.0 * 4096 * 11008 * 4096 / (ms_l + ms_e) / 1e9}
 
+    # ---- Llama-70B-shaped layer (configs[3]): 481 MB of packed weights, far beyond the LLC ----
+    if args.legs == "all":
+        del copies
+        torch.cuda.empty_cache()
+        big = []
+        g70 = torch.Generator(device="cuda")
+        g70.manual_seed(4000)
+        for name, n, k in synth.LLAMA_70B_LAYER:
+            # random packed codes / scale bytes: the kernels' speed does not depend on the values
+            codes = torch.randint(0, 256, (n, k // 2), generator=g70, device="cuda", dtype=torch.uint8)
+            scales = torch.randint(0, 256, (n, k // 16), generator=g70, device="cuda", dtype=torch.uint8)
+            big.append(razer.RazerTensor(codes, scales, torch.tensor([1e-3], device="cuda"), n, k, razer.WEIGHT, sv))
+        bytes70 = sum(n * k * 9 // 16 for _, n, k in synth.LLAMA_70B_LAYER)
+        for m in (1, 8):
+            acts = {k: make_act(m, k, 4100 + m) for k in {k for _, _, k in synth.LLAMA_70B_LAYER}}
+            outs = [torch.empty((m, n), dtype=torch.bfloat16, device="cuda") for _, n, _ in synth.LLAMA_70B_LAYER]
+            wsb = max(razer.razer_workspace_bytes(2, t.rows, t.cols, m) for t in big)
+            wsp = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+
+            def step70(i):
+                if m <= 4:
+                    razer.razer_linear_grouped(big[0:3], acts[8192], outs=outs[0:3])
+                    razer.razer_linear(big[3], acts[8192], out=outs[3])
+                    razer.razer_linear_grouped(big[4:6], acts[8192], outs=outs[4:6])
+                    razer.razer_linear(big[6], acts[28672], out=outs[6])
+                else:
+                    for j, t in enumerate(big):
+                        razer.razer_linear(t, acts[t.cols], out=outs[j], workspace=wsp)
+            ms = time_region(step70, 20, 3, graph_period=1 if use_graph else 0)
+            b = bytes70 + sum(2 * m * k + 2 * m * n + 4 for _, n, k in synth.LLAMA_70B_LAYER)
+            legs["llama70b_layer_m%d" % m] = {"GB/s": b / ms / 1e6, "frac_hbm": b / ms / 1e6 / HBM_PEAK_GBS,
+                                             "ms_per_step": ms, "note": "configs[3]: 481 MB packed layer, one pass"}
+        del big
+
     # ---- CPU baseline: the oracle, as it stands, on the host cores ------------------------
     cpu = None
     if not args.no_cpu_baseline:
