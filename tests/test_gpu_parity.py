@@ -153,6 +153,7 @@ def test_linear_gemv_matches_oracle(oracle, m, n, k):
 
 
 @pytest.mark.parametrize("m,n,k", [(5, 40, 64), (8, 300, 1056), (16, 256, 2048), (33, 100, 96), (64, 513, 1024),
+                                   (17, 70, 32), (32, 129, 4096 + 32), (12, 65, 8192 + 512), (31, 64, 544),
                                    (100, 130, 4096), (129, 384, 512), (300, 260, 1120), (512, 512, 1024),
                                    (257, 257, 224)])
 def test_linear_gemm_matches_oracle(oracle, m, n, k):
