@@ -2,13 +2,17 @@
 // regime of Sec. 4.3 / App. D.2 of arxiv 2501.04052): fused decode + dot product,
 // bound by the HBM read of the packed weights (0.5625 B per weight).
 //
-// Mapping.  A workgroup owns R consecutive weight rows; its waves split K into
+// Mapping.  A workgroup owns a few consecutive weight rows; its waves split K into
 // slices of 2048 elements.  In a slice lane l owns the 16-byte code chunk
 // [32 l, 32 l + 32) of every row -- so a wave reads 1 KiB of consecutive codes
 // and 128 B of consecutive scale bytes per row -- and keeps the matching 32
-// activations of each activation row in registers across the R rows.  Kernels
-// this short are latency-bound: every load is issued before anything else
-// happens, and nothing in the kernel may touch the dispatch packet or scratch.
+// activations of each activation row in registers across the rows.  Kernels
+// this short are latency-bound (about 3 us of every launch is fixed cost on
+// MI355X, the rest streams at 5-6 TB/s): loads are issued before anything else
+// happens, the whole problem is in flight at once, and nothing in the kernel may
+// touch the dispatch packet or scratch.  Rows up to 32768 elements take the
+// streaming kernel (groups of 2 rows, next group in flight while one is decoded);
+// longer rows take the multi-pass kernel (4 rows per workgroup).
 //
 // Decode.  The 8 codes of a dword are sign-flipped with one xor, converted to
 // packed bf16 pairs by the hardware FP4 conversion, and the (now all-zero)
@@ -183,6 +187,93 @@ __device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, con
     }
 }
 
+// Streaming variant for rows of at most 16 slices (K <= 32768): a workgroup owns G consecutive
+// groups of R rows and walks them with D register buffers, so that D - 1 groups of packed weights
+// are always in flight while one is decoded.  Wave w owns K-slice w of every row; its 32
+// activations per lane stay in registers for the whole walk.  Slice totals of all G * R rows meet
+// in LDS after ONE barrier.  Row addresses are uniform (scalar) and lane offsets 32-bit.
+template <int M, int R, int G, int D>
+__device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ codes,
+                                                 const uint8_t* __restrict__ scales,
+                                                 const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
+                                                 int64_t k, const uint16_t* __restrict__ a,
+                                                 uint16_t* __restrict__ y, int64_t ld_y, int64_t row0)
+{
+    static_assert(D >= 2 && D <= 3, "buffer count");
+    __shared__ uint2 lut[256];
+    __shared__ float part[G * R * M][kMaxWaves];
+    const float ts = *w_ts;
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const uint32_t chunks = (uint32_t)(k >> 5);                           // 16-byte code chunks per row
+    const uint32_t c = wave * 64u + lane;
+    const bool active = c < chunks;
+    const uint32_t cc = active ? c : 0u;                                  // idle lanes read chunk 0, weight 0
+    const uint32_t amask = active ? 0xFFFFFFFFu : 0u;
+    const int64_t code_ld = k >> 1, scale_ld = k >> 4;
+
+    uint4 av[M][4];
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        const uint8_t* ap = reinterpret_cast<const uint8_t*>(a + (int64_t)m * k);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint4 t = *reinterpret_cast<const uint4*>(ap + (cc * 64u + 16u * j));
+            av[m][j] = make_uint4(t.x & amask, t.y & amask, t.z & amask, t.w & amask);
+        }
+    }
+    RowGroup<R> buf[D];
+    auto load = [&](RowGroup<R>& g, int gi) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            int64_t row = row0 + gi * R + r;
+            row = row < n ? row : n - 1;                                  // tail rows re-read the last row
+            const uint8_t* crow = codes + row * code_ld;
+            const uint8_t* srow = scales + row * scale_ld;
+            g.cw[r] = *reinterpret_cast<const uint4*>(crow + cc * 16u);
+            g.sw[r] = *reinterpret_cast<const uint16_t*>(srow + cc * 2u);
+        }
+    };
+#pragma unroll
+    for (int d = 0; d < D - 1; ++d)
+        if (d < G) load(buf[d], d);
+    fill_weight_lut(lut, sv0, sv1);
+    __syncthreads();                                                      // LUT ready
+
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        if (g + D - 1 < G) load(buf[(g + D - 1) % D], g + D - 1);
+        float acc[R][M];
+        dot_group<M, R>(buf[g % D], av, lut, acc);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const float t = wave_sum_to_lane63(acc[r][m]);
+                if (lane == 63) part[(g * R + r) * M + m][wave] = t;
+            }
+    }
+    __syncthreads();
+    if (threadIdx.x < G * R * M) {
+        const int m = threadIdx.x / (G * R), rr = threadIdx.x - m * (G * R);
+        if (row0 + rr < n) {
+            float t = 0.0f;
+            for (uint32_t w = 0; w < nwaves; ++w) t += part[rr * M + m][w];
+            y[(int64_t)m * ld_y + row0 + rr] = f32_to_bf16_rne(t * ts);
+        }
+    }
+}
+
+template <int M, int R, int G, int D>
+__global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_kernel(const uint8_t* __restrict__ codes,
+                                                                     const uint8_t* __restrict__ scales,
+                                                                     const float* __restrict__ w_ts, float sv0,
+                                                                     float sv1, int64_t n, int64_t k,
+                                                                     const uint16_t* __restrict__ a,
+                                                                     uint16_t* __restrict__ y, int64_t ld_y)
+{
+    gemv_stream_body<M, R, G, D>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y, (int64_t)blockIdx.x * (R * G));
+}
+
 template <int M, int R>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __restrict__ codes,
                                                               const uint8_t* __restrict__ scales,
@@ -219,6 +310,34 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_grouped_kernel(
     gemv_body<M, R>(codes, scales, ts, sv0, sv1, n, k, a, y, ld, (int64_t)(b - first) * R);
 }
 
+template <int M, int R, int G, int D>
+__global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
+    const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
+    const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
+    const float* t0, const float* t1, const float* t2, const float* t3,
+    uint16_t* y0, uint16_t* y1, uint16_t* y2, uint16_t* y3,
+    int64_t n0, int64_t n1, int64_t n2, int64_t n3,
+    int64_t l0, int64_t l1, int64_t l2, int64_t l3,
+    unsigned g1, unsigned g2, unsigned g3,
+    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a)
+{
+    const unsigned b = blockIdx.x;
+    const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = t0; uint16_t* y = y0;
+    int64_t n = n0, ld = l0;
+    unsigned first = 0;
+    if (b >= g1) { codes = c1; scales = s1; ts = t1; y = y1; n = n1; ld = l1; first = g1; }
+    if (b >= g2) { codes = c2; scales = s2; ts = t2; y = y2; n = n2; ld = l2; first = g2; }
+    if (b >= g3) { codes = c3; scales = s3; ts = t3; y = y3; n = n3; ld = l3; first = g3; }
+    gemv_stream_body<M, R, G, D>(codes, scales, ts, sv0, sv1, n, k, a, y, ld, (int64_t)(b - first) * (R * G));
+}
+
+// Rows per group / groups per workgroup of the streaming kernel.  Measured on MI355X over the
+// projection shapes of 7B- and 70B-class decoder layers: 2 rows x 2 groups is best while a
+// workgroup has few waves (K <= 16384); with many waves per workgroup (long K), or 3-4
+// activation rows on more than 4 waves, longer-lived workgroups (8 groups) win by 20-40 %.
+constexpr int kStreamR = 2;
+static inline int stream_groups(int nwaves, int m) { return (nwaves > 8 || (m >= 3 && nwaves > 4)) ? 8 : 2; }
+
 template <int M, int R>
 static hipError_t launch_gemv_mr(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,
                                  int64_t n, int64_t k, const uint16_t* a, uint16_t* y, int64_t ld_y, hipStream_t st)
@@ -234,27 +353,49 @@ template <int M>
 static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,
                                 int64_t n, int64_t k, const uint16_t* a, uint16_t* y, int64_t ld_y, hipStream_t st)
 {
-    // 4 rows per workgroup measured best on MI355X over 2 and 8 for every shape of the 7B / 70B layers.
-    return launch_gemv_mr<M, 4>(cfg, codes, scales, ts, n, k, a, y, ld_y, st);
+    const int64_t nslices = (k + kSliceK - 1) / kSliceK;
+    if (nslices > kMaxWaves)                                              // K > 32768: several passes per wave
+        return launch_gemv_mr<M, 4>(cfg, codes, scales, ts, n, k, a, y, ld_y, st);
+    constexpr int R = kStreamR;
+    const int nwaves = (int)nslices;
+    if (stream_groups(nwaves, M) == 8) {
+        const unsigned grid = (unsigned)((n + R * 8 - 1) / (R * 8));
+        gemv_stream_kernel<M, R, 8, 2><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a,
+                                                                     y, ld_y);
+    } else {
+        const unsigned grid = (unsigned)((n + R * 2 - 1) / (R * 2));
+        gemv_stream_kernel<M, R, 2, 2><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a,
+                                                                     y, ld_y);
+    }
+    return hipGetLastError();
 }
 
 template <int M>
 static hipError_t launch_gemv_grouped_m(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
                                         hipStream_t st)
 {
-    constexpr int R = 4;
     const int64_t nslices = (k + kSliceK - 1) / kSliceK;
-    const int nwaves = (int)(nslices < kMaxWaves ? nslices : kMaxWaves);
+    const bool stream = nslices <= kMaxWaves;
+    const int nwaves = (int)(stream ? nslices : kMaxWaves);
+    const int groups = stream ? stream_groups(nwaves, M) : 1;
+    const int64_t rows_per_wg = stream ? kStreamR * groups : 4;
     GemvProblem q[4];
     unsigned g[5] = {0, 0, 0, 0, 0};
     for (int i = 0; i < 4; ++i) {
         q[i] = p[i < count ? i : count - 1];
-        g[i + 1] = g[i] + (i < count ? (unsigned)((q[i].n + R - 1) / R) : 0u);
+        g[i + 1] = g[i] + (i < count ? (unsigned)((q[i].n + rows_per_wg - 1) / rows_per_wg) : 0u);
     }
-    gemv_grouped_kernel<M, R><<<g[4], 64 * nwaves, 0, st>>>(
-        q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales,
-        q[0].ts, q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n,
-        q[0].ld_y, q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a);
+#define RAZER_GROUPED_ARGS                                                                                       \
+    q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts, \
+        q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,    \
+        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a
+    if (!stream)
+        gemv_grouped_kernel<M, 4><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
+    else if (groups == 8)
+        gemv_stream_grouped_kernel<M, kStreamR, 8, 2><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
+    else
+        gemv_stream_grouped_kernel<M, kStreamR, 2, 2><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
+#undef RAZER_GROUPED_ARGS
     return hipGetLastError();
 }
 

@@ -233,11 +233,12 @@ def test_linear_strided_output_and_empty(oracle):
     assert y.shape == (0, n)
 
 
-@pytest.mark.parametrize("m", [1, 2, 3, 4, 20])
-def test_linear_grouped_matches_oracle(oracle, m):
-    """Several weight matrices on the same activation rows in one call (one launch for m <= 4)."""
-    print("grouped", m, flush=True)
-    k = 2048 + 96
+@pytest.mark.parametrize("m,k", [(1, 2048 + 96), (2, 2048 + 96), (3, 2048 + 96), (4, 2048 + 96), (20, 2048 + 96),
+                                 (1, 11008), (4, 11008), (1, 28672), (2, 2048 * 17 + 64)])
+def test_linear_grouped_matches_oracle(oracle, m, k):
+    """Several weight matrices on the same activation rows in one call (one launch for m <= 4); the
+    K values cover the 2-group and 8-group streaming kernels and the multi-pass kernel for long rows."""
+    print("grouped", m, k, flush=True)
     ns = [100, 64, 37, 9]
     a = synth.activation(m, k, seed=800 + m)
     a_dev = bf16_bits_to_dev(a)
