@@ -22,6 +22,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 LLC_BYTES = 256 << 20          # Infinity Cache
+# HBM bytes per {gate,up} launch from the FETCH_SIZE / WRITE_SIZE counters (profiles/): not measurable live
+GATE_UP_TRAFFIC_BYTES = 24840 * 2 * 1024 + 172 * 1024
 
 
 def parse():
@@ -84,6 +86,31 @@ def time_region(fn, steps, warmup, graph_period=0):
     return e0.elapsed_time(e1) / steps
 
 
+def time_launches(fn, n, warmup):
+    """Average duration (ms) of single launches: one HIP event pair around EACH call of fn(i), on the
+    stream fn launches on, so consecutive launches cannot overlap their ramp-up and drain (this is the
+    figure a kernel trace reports per dispatch); all pairs are read after one final synchronize.
+    Returns (duration net of the markers' own cost, raw pair reading, empty pair reading)."""
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for i, (e0, e1) in enumerate(pairs):
+        e0.record()
+        fn(warmup + i)
+        e1.record()
+    torch.cuda.synchronize()
+    raw = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / n
+    # what an event pair reads with nothing between the two records: the markers' own cost
+    for e0, e1 in pairs:
+        e0.record()
+        e1.record()
+    torch.cuda.synchronize()
+    empty = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / n
+    return raw - empty, raw, empty
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -131,11 +158,24 @@ def main():
         g.manual_seed(seed)
         return torch.randn((m, k), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
 
-    def linear_leg(m, steps, warmup, rotate=True, graph=False, grouped=False):
+    def linear_leg(m, steps, warmup, rotate=True, graph=False, grouped=False, prepared=False):
         acts = {k: make_act(m, k, 2100 + m) for k in {k for _, _, k in layers}}
         outs = [torch.empty((m, n), dtype=torch.bfloat16, device="cuda") for _, n, _ in layers]
+        plans = None
+        if prepared:
+            # the marshalled C-ABI calls are built once per packed copy and re-issued every step:
+            # plain launches on torch's current stream, no graph, no per-call Python marshalling
+            plans = [[razer.prepare_linear_grouped(cp[0:3], acts[cp[0].cols], outs[0:3]),
+                      razer.prepare_linear(cp[3], acts[cp[3].cols], outs[3]),
+                      razer.prepare_linear_grouped(cp[4:6], acts[cp[4].cols], outs[4:6]),
+                      razer.prepare_linear(cp[6], acts[cp[6].cols], outs[6])] for cp in copies]
+            stream = torch.cuda.current_stream().cuda_stream
 
         def step(i):
+            if prepared:
+                for call in plans[i % n_copies if rotate else 0]:
+                    call(stream)
+                return
             cp = copies[i % n_copies] if rotate else copies[0]
             if grouped:
                 # the projections that consume the same activation go out as one launch each:
@@ -154,17 +194,34 @@ def main():
 
     # ---- headline: GEMV at M=1 ----------------------------------------------------------
     use_graph = not args.no_graph
-    ms1, bytes1, _ = linear_leg(1, args.steps, args.warmup, graph=use_graph, grouped=True)
+    ms1, bytes1, _ = linear_leg(1, args.steps, args.warmup, grouped=True, prepared=True)
     gbs = bytes1 / ms1 / 1e6
-    ms1s, _, _ = linear_leg(1, max(10, args.steps // 4), 5, graph=use_graph)
+    quarter = max(10, args.steps // 4)
+    if use_graph:
+        msg, _, _ = linear_leg(1, quarter, 5, graph=True, grouped=True)
+        legs["gemv_m1_graph_replay"] = {"GB/s": bytes1 / msg / 1e6, "ms_per_step": msg,
+                                        "note": "same step captured once per packed copy into a HIP graph and replayed"}
+    ms1s, _, _ = linear_leg(1, quarter, 5, graph=use_graph)
     legs["gemv_m1_seven_launches"] = {"GB/s": bytes1 / ms1s / 1e6, "ms_per_step": ms1s,
                                       "note": "same step as seven razer_linear calls instead of four (no grouping)"}
-    ms1c, _, _ = linear_leg(1, max(10, args.steps // 4), 5, rotate=False, graph=use_graph, grouped=True)
-    if use_graph:
-        ms1e, _, _ = linear_leg(1, max(10, args.steps // 4), 5)
-        legs["gemv_m1_eager_launches"] = {"GB/s": bytes1 / ms1e / 1e6, "ms_per_step": ms1e,
-                                          "note": "same step launched call by call through the Python binding (host-bound)"}
+    ms1c, _, _ = linear_leg(1, quarter, 5, rotate=False, grouped=True, prepared=True)
     legs["gemv_m1_cache_resident"] = {"GB/s": bytes1 / ms1c / 1e6, "note": "same 113.8 MB copy every step: served by the last-level cache, not HBM"}
+    ms1e, _, _ = linear_leg(1, quarter, 5, grouped=True)
+    legs["gemv_m1_unprepared_calls"] = {"GB/s": bytes1 / ms1e / 1e6, "ms_per_step": ms1e,
+                                        "note": "same step with the Python binding marshalling every call (host-bound)"}
+
+    # dominant kernel of the step: the {gate, up} launch (gemv_stream_grouped_kernel<1,2,2,2>, 44 % of
+    # the step's bytes).  Average launch duration from HIP events around a region of back-to-back
+    # launches of that kernel alone, rotating the packed copies, on the stream it is launched on.
+    # (An event pair around every single launch is reported too, with the reading of an empty pair:
+    # the markers cost several microseconds themselves, so that figure only bounds the duration.)
+    a1 = make_act(1, 4096, 2101)
+    o2 = [torch.empty((1, 11008), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    dom = [razer.prepare_linear_grouped(cp[4:6], a1, o2) for cp in copies]
+    dstream = torch.cuda.current_stream().cuda_stream
+    dom_ms, dom_raw_ms, dom_empty_ms = time_launches(lambda i: dom[i % n_copies](dstream), max(100, args.steps), 20)
+    dom_stream_ms = time_region(lambda i: dom[i % n_copies](dstream), max(100, args.steps), 20)
+    dom_bytes = 2 * (11008 * 4096 * 9 // 16 + 2 * 11008 + 4) + 2 * 4096
 
     gemm_roof = None
     if args.legs == "all":
@@ -257,16 +314,22 @@ def main():
         "metric": "RaZeR W4A16 GEMV HBM GB/s at M=1 (Llama-7B-shaped layer set)",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "fp4 codes x bf16 activations, fp32 accumulate", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[1]: Llama-7B-shaped decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; "
                                "down 4096x11008), RaZeR weights (block 16, E3M3 scale + 2 meta bits, sv {5,8}), M=1; "
                                "one step = the 7 projections once, as 4 launches: {q,k,v} and {gate,up} share their activation and go through "
-                               "razer_linear_grouped%s; %d packed copies rotated (%.0f MB > 2x LLC)"
-                               % (" (replayed as a HIP graph)" if use_graph else "", n_copies, n_copies * layer_bytes / 1e6),
+                               "razer_linear_grouped; plain stream launches through the C ABI; %d packed copies rotated (%.0f MB > 2x LLC); "
+                               "fp4 codes x bf16 activations, fp32 accumulate" % (n_copies, n_copies * layer_bytes / 1e6),
                    "m": 1, "bytes_per_step": bytes1},
-        "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "gemv_grouped_kernel<1,4> / gemv_kernel<1,4> (4 launches per step; achieved = algorithmic bytes of the step / step time)"},
+        "roofline": {"bound": "hbm", "achieved": dom_bytes / dom_stream_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": dom_bytes / dom_stream_ms / 1e6 / HBM_PEAK_GBS, "traffic": GATE_UP_TRAFFIC_BYTES,
+                     "kernel": "gemv_stream_grouped_kernel<1,2,2,2> on {gate,up} 2 x 11008x4096 (the step's largest launch)",
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": dom_stream_ms * 1e3,
+                     "timing": "HIP events around a region of back-to-back launches of this kernel alone on its stream, "
+                               "packed copies rotated; region time / launches",
+                     "single_launch_event_pair_us": dom_raw_ms * 1e3, "empty_event_pair_us": dom_empty_ms * 1e3,
+                     "step_frac": gbs / HBM_PEAK_GBS,
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, scaled by a plain copy (profiles/)"},
         "cpu_baseline": cpu,
         "legs": legs,
     }

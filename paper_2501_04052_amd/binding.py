@@ -221,3 +221,50 @@ def razer_linear_grouped(ws, a, outs=None):
     if st != 0:
         raise RazerError(st, "razer_linear_grouped")
     return outs
+
+
+class PreparedCall:
+    """The marshalled arguments of one razer_linear / razer_linear_grouped call, kept so that a
+    serving loop can re-issue the same call without rebuilding them (the library itself keeps no
+    state; this object only holds ctypes values and references to the tensors involved)."""
+
+    def __init__(self, fn, args, keep, where):
+        self._fn, self._args, self._keep, self._where = fn, args, keep, where
+
+    def __call__(self, stream=None):
+        """Enqueue on `stream` (a HIP stream handle as an int) or on torch's current stream."""
+        st = self._fn(*self._args, _stream() if stream is None else ctypes.c_void_p(stream))
+        if st != 0:
+            raise RazerError(st, self._where)
+
+
+def prepare_linear(w, a, out, workspace=None):
+    """razer_linear(w, a, out=out, workspace=workspace) as a PreparedCall (W4A16, bf16 a)."""
+    L = load_library()
+    assert a.is_cuda and a.dtype == torch.bfloat16 and a.dim() == 2 and a.is_contiguous() and a.shape[1] == w.cols
+    m = a.shape[0]
+    assert out.shape == (m, w.rows) and out.dtype == torch.bfloat16
+    need = razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=a.device)
+    ws = w.c_struct()
+    ld_y = out.stride(0) if m > 1 else max(out.stride(0), w.rows)
+    args = (ctypes.byref(ws), _ptr(a), None, m, _ptr(out), ld_y, _ptr(workspace),
+            0 if workspace is None else workspace.numel())
+    return PreparedCall(L.razer_linear, args, (ws, w, a, out, workspace), "razer_linear")
+
+
+def prepare_linear_grouped(ws, a, outs):
+    """razer_linear_grouped(ws, a, outs=outs) as a PreparedCall."""
+    L = load_library()
+    assert a.is_cuda and a.dtype == torch.bfloat16 and a.dim() == 2 and a.is_contiguous()
+    m, count = a.shape[0], len(ws)
+    structs = [w.c_struct() for w in ws]
+    wptrs = (ctypes.POINTER(_Tensor) * count)(*[ctypes.pointer(s) for s in structs])
+    yptrs = (ctypes.c_void_p * count)(*[o.data_ptr() for o in outs])
+    lds = (ctypes.c_int64 * count)(*[(o.stride(0) if m > 1 else max(o.stride(0), w.rows))
+                                     for o, w in zip(outs, ws)])
+    need = max(razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m) for w in ws)
+    workspace = torch.empty(need, dtype=torch.uint8, device=a.device) if need else None
+    args = (wptrs, count, _ptr(a), m, yptrs, lds, _ptr(workspace), need)
+    return PreparedCall(L.razer_linear_grouped, args, (structs, ws, a, outs, workspace), "razer_linear_grouped")
