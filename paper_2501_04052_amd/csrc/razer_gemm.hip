@@ -466,6 +466,278 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
     store_tile<TM, TN, AQ>(acc, w_ts, a_ts, m0 + wm * WTM, n0 + wn * WTN, m, n, y, ld_y, lane);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Weights straight from registers (bf16 activations only).  Wave w of a workgroup owns the 32
+// weight rows n0 + 32 w .. + 31 against ALL 256 activation rows of the tile, so every packed
+// weight is decoded by exactly one wave, in registers, into the MFMA "A" operand it is used in;
+// only the activation tile is shared through LDS.  An MFMA sums over any 16 k as long as both
+// operands agree on them: lane (r, h) takes the 32 codes k = 64 t + 32 h .. + 31 of its row -- 16
+// bytes of codes plus two scale bytes per K-tile -- and step j of the tile uses its dword j, i.e.
+// k = 64 t + 32 h + 8 j .. + 7, against the activation chunk 4 h + j of the staged row.
+// Per step and wave: ~25 VALU ops of decode, 8 LDS fragment reads, 8 MFMAs.
+//
+// Everything that comes from global memory is copied global -> LDS by the load unit itself
+// (global_load_lds: lane l's 16 bytes land at LDS base + 16 l; a 2-byte copy lands zero-extended at base + 4 l), S stages deep: the activation tile
+// (256 rows x 64 k bf16, the xor swizzle of the staged rows applied by choosing which global chunk
+// each lane fetches) and each wave's own packed codes and scale bytes, which the lane that requested
+// them reads back one tile later.  So the K loop holds no register-returning global load, no LDS
+// write and no address arithmetic for staging.  Tile t + S - 1 is requested at the top of iteration
+// t, into the stage that iteration t - 1 finished reading; three quarters through iteration t every
+// wave waits (vmcnt) until its own copies for tile t + 1 have landed, prepares that tile's weights
+// (LUT lookups, decode of step 0) between the last MFMAs, and the barrier ending the iteration makes
+// everybody's activation copies visible.
+//
+// LDS reads are inline assembly with hand-placed s_waitcnt lgkmcnt: the compiler cannot tell the
+// stages apart, so before any LDS load it knows of it would wait for ALL outstanding copies, which
+// would serialise the prefetch.  Each wait is tied to the registers it guards so that their consumers
+// cannot be scheduled above it; sched_barrier keeps the hand-laid slices (one MFMA each) in order.
+template <int NW, int S>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void gemm_rb_kernel(
+    const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
+    float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
+    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m)
+{
+    constexpr int MT = 8;                               // 32-row activation groups per tile
+    constexpr int NT = 64 * NW, BM = 32 * MT, BN = 32 * NW;
+    constexpr int NU_A = BM * 8 / NT;                   // 1-KiB activation copies per wave and K-tile
+    constexpr int D = S - 1;                            // tiles in flight ahead of the one being computed
+    constexpr int L = NU_A + 2;                         // copy instructions per wave and K-tile
+    constexpr int A_STAGE = BM * 128, B_CODES = NW * 1024, B_STAGE = NW * 1280;
+    static_assert((BM * 8) % NT == 0, "activation tile must divide over the threads");
+    static_assert(S >= 2 && S <= 4 && (D - 1) * L < 64, "stage count");
+
+    extern __shared__ __align__(16) uint8_t smem[];
+    uint8_t* As = smem;                                 // S stages x 256 rows x 128 B
+    uint8_t* Bs = smem + S * A_STAGE;                   // S stages x (NW KiB of codes + NW x 256 B of scale-byte pairs)
+    uint2* wlut = reinterpret_cast<uint2*>(smem + S * (A_STAGE + B_STAGE));
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+    const int KT = (int)((k + kBK - 1) / kBK);
+    const int last = KT - 1;
+
+    int64_t wrow = n0 + 32 * wave + r;
+    wrow = wrow < n ? wrow : n - 1;                     // rows past N re-read the last row, never stored
+    const uint8_t* crow = w_codes + wrow * (k / 2) + 16 * h;
+    const uint8_t* srow = w_scales + wrow * (k / 16) + 2 * h;
+
+    // Activation copy i of this wave fills LDS rows 8 (wave NU_A + i) .. + 7 of a stage: lane l writes
+    // physical chunk l % 8 of row 8 (..) + l / 8, which must hold logical chunk (l % 8) ^ swizzle(row).
+    // Rows past M re-read the last row; byte offsets from the tile's first row fit 32 bits.
+    const uint8_t* abase = reinterpret_cast<const uint8_t*>(a + m0 * k);
+    const uint32_t rows_here = (uint32_t)((m - m0 < BM) ? m - m0 : BM);
+    const uint32_t row_bytes = (uint32_t)k * 2u;
+    uint32_t a_src[NU_A];                               // byte offset of (row, k = 0) + 16 * logical chunk
+    uint32_t a_chunk[NU_A];
+#pragma unroll
+    for (int i = 0; i < NU_A; ++i) {
+        const uint32_t row = 8u * (wave * NU_A + i) + (lane >> 3);
+        const uint32_t c = (lane & 7u) ^ ((row >> 1) & 7u);
+        a_chunk[i] = c;
+        a_src[i] = (row < rows_here ? row : rows_here - 1) * row_bytes + c * 16u;
+    }
+    // all copies of K-tile kt into stage st (kt already clamped to the last tile by the caller)
+    auto issue = [&](int kt, int st) {
+#pragma unroll
+        for (int i = 0; i < NU_A; ++i) {
+            const uint32_t kk = (uint32_t)kt * kBK + a_chunk[i] * 8u;
+            const uint32_t off = kk < (uint32_t)k ? a_src[i] + (uint32_t)kt * (kBK * 2u) : a_src[i] - a_chunk[i] * 16u;
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(abase + off),           // past K: any finite data
+                (__attribute__((address_space(3))) void*)(As + st * A_STAGE + (wave * NU_A + i) * 1024), 16, 0, 0);
+        }
+        const int kc = ((int64_t)kt * kBK + 32 * h < k) ? kt : 0;                       // past K: masked where used
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(crow + 32 * kc),
+                                         (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + wave * 1024),
+                                         16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srow + 4 * kc),
+                                         (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + B_CODES + wave * 256),
+                                         2, 0, 0);
+    };
+
+    v16f acc[1][MT];
+#pragma unroll
+    for (int j = 0; j < MT; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[0][j][v] = 0.0f;
+
+    const uint32_t a_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)As;
+    const uint32_t lut_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)wlut;
+    // this lane's own codes / scale bytes inside a B stage
+    const uint32_t bc_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)Bs + wave * 1024 + lane * 16;
+    const uint32_t bs_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)Bs + B_CODES + wave * 256 + lane * 4;
+#define RAZER_LDS_READ128(dst, addr, imm) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(imm))
+#define RAZER_LDS_READ64(dst, addr) asm volatile("ds_read_b64 %0, %1" : "=v"(dst) : "v"(addr))
+#define RAZER_LDS_READ32(dst, addr) asm volatile("ds_read_b32 %0, %1" : "=v"(dst) : "v"(addr))
+#define RAZER_LDS_WAIT(n, reg) asm volatile("s_waitcnt lgkmcnt(" #n ")" : "+v"(reg))
+#define RAZER_LDS_WAIT3(n, r0, r1, r2) asm volatile("s_waitcnt lgkmcnt(" #n ")" : "+v"(r0), "+v"(r1), "+v"(r2))
+    // LDS byte address of this lane's activation chunk in step j (row r of group 0, stage 0; group mi
+    // adds 4096 mi, stage st adds st * A_STAGE)
+    uint32_t aoff[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) aoff[j] = a_lds + lds_off(r, 4 * h + j);
+    // s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, other counters left at max):
+    // at most the copies of the D - 1 newest tiles are still in flight
+    constexpr int kWaitN = (D - 1) * L;
+    constexpr int kWaitImm = (kWaitN & 15) | ((kWaitN >> 4) << 14) | (7 << 4) | (15 << 8);
+
+    // Weights of the tile about to be computed: sign-flipped codes, LUT entries of its two blocks,
+    // decoded pairs of step 0.
+    uint32_t xw[4], wq0[4];
+    uint2 le0, le1;
+    auto flip_and_mask = [&](int kt, const v4u& c, uint32_t& sc) {
+        // past K: code 0, scale byte 0 -> weight 0
+        const uint32_t msk = (kt <= last && (int64_t)kt * kBK + 32 * h < k) ? 0xFFFFFFFFu : 0u;
+        xw[0] = (c.x & msk) ^ kRemapXor;
+        xw[1] = (c.y & msk) ^ kRemapXor;
+        xw[2] = (c.z & msk) ^ kRemapXor;
+        xw[3] = (c.w & msk) ^ kRemapXor;
+        sc &= msk;
+    };
+
+    // One K-tile.  Slices of one MFMA each; between the MFMAs of step j sit the fragment reads and
+    // the decode for step j + 1, and in the last step the preparation of tile kt + 1.  At the MFMA of
+    // (step j < 3, group mi) the 8 fragment reads issued after its own are the only LDS operations
+    // that may still be in flight, so lgkmcnt(7) is enough.
+    auto compute = [&](int kt, int st, int st_next) {
+        const uint32_t sbase = st * A_STAGE;
+        v4u af[2][MT];
+        uint32_t wq[2][4] = {{wq0[0], wq0[1], wq0[2], wq0[3]}, {0, 0, 0, 0}};
+        const uint32_t a0 = aoff[0] + sbase;
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi) RAZER_LDS_READ128(af[0][mi], a0, 4096 * mi);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            const int cb = j & 1, nb = cb ^ 1;
+            const v8bf wf = __builtin_bit_cast(v8bf, make_uint4(wq[cb][0], wq[cb][1], wq[cb][2], wq[cb][3]));
+            const uint2 le = (j + 1 < 2) ? le0 : le1;
+            const uint32_t an = aoff[j + 1] + sbase;
+#pragma unroll
+            for (int mi = 0; mi < MT; ++mi) {
+                RAZER_LDS_READ128(af[nb][mi], an, 4096 * mi);
+                if (mi % 2 == 0) {                                       // one code pair per two MFMAs
+                    const uint32_t x = xw[j + 1];
+                    wq[nb][mi / 2] = (mi == 0) ? cvt_scaled_pair<0>(x, u2f(le.x), le.y)
+                                   : (mi == 2) ? cvt_scaled_pair<1>(x, u2f(le.x), le.y)
+                                   : (mi == 4) ? cvt_scaled_pair<2>(x, u2f(le.x), le.y)
+                                               : cvt_scaled_pair<3>(x, u2f(le.x), le.y);
+                }
+                RAZER_LDS_WAIT(7, af[cb][mi]);
+                acc[0][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(v8bf, af[cb][mi]),
+                                                                     acc[0][mi], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // this wave's copies for tile kt + 1 have landed
+        __builtin_amdgcn_s_waitcnt(kWaitImm);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        {
+            const v8bf wf = __builtin_bit_cast(v8bf, make_uint4(wq[1][0], wq[1][1], wq[1][2], wq[1][3]));
+            const uint32_t bnext = st_next * B_STAGE;
+            v4u cn;
+            uint32_t sn;
+            uint2 l0n, l1n;
+#define RAZER_MFMA(mi) \
+            acc[0][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(v8bf, af[1][mi]), acc[0][mi], 0, 0, 0); \
+            __builtin_amdgcn_sched_barrier(0)
+            // slice 0: request the next tile's codes and scale bytes (this lane's own copy)
+            RAZER_LDS_READ128(cn, bc_lds + bnext, 0);
+            RAZER_LDS_READ32(sn, bs_lds + bnext);
+            RAZER_LDS_WAIT(9, af[1][0]);
+            RAZER_MFMA(0);
+            RAZER_LDS_WAIT(8, af[1][1]);
+            RAZER_MFMA(1);
+            RAZER_LDS_WAIT(7, af[1][2]);
+            RAZER_MFMA(2);
+            // slice 3: everything issued so far has returned; look the two scale bytes up
+            RAZER_LDS_WAIT3(0, af[1][3], cn, sn);
+            flip_and_mask(kt + 1, cn, sn);
+            RAZER_LDS_READ64(l0n, lut_lds + (sn & 255u) * 8u);
+            RAZER_LDS_READ64(l1n, lut_lds + ((sn >> 8) & 255u) * 8u);
+            RAZER_MFMA(3);
+            RAZER_MFMA(4);
+            RAZER_MFMA(5);
+            // slices 6, 7: decode step 0 of the next tile
+            RAZER_LDS_WAIT3(0, l0n, l1n, af[1][6]);
+            le0 = l0n;
+            le1 = l1n;
+            wq0[0] = cvt_scaled_pair<0>(xw[0], u2f(le0.x), le0.y);
+            wq0[1] = cvt_scaled_pair<1>(xw[0], u2f(le0.x), le0.y);
+            RAZER_MFMA(6);
+            wq0[2] = cvt_scaled_pair<2>(xw[0], u2f(le0.x), le0.y);
+            wq0[3] = cvt_scaled_pair<3>(xw[0], u2f(le0.x), le0.y);
+            RAZER_MFMA(7);
+#undef RAZER_MFMA
+        }
+    };
+
+#pragma unroll
+    for (int d = 0; d < D; ++d) issue(d < last ? d : last, d);       // tiles 0 .. D - 1 (short K repeats the last)
+    fill_scaled_lut<0>(wlut, sv0, sv1, tid, NT);
+    __syncthreads();                                    // all copies so far have landed, LUT ready
+    {
+        v4u c0;
+        uint32_t s0;
+        RAZER_LDS_READ128(c0, bc_lds, 0);
+        RAZER_LDS_READ32(s0, bs_lds);
+        RAZER_LDS_WAIT(0, c0);
+        RAZER_LDS_WAIT(0, s0);
+        flip_and_mask(0, c0, s0);
+        RAZER_LDS_READ64(le0, lut_lds + (s0 & 255u) * 8u);
+        RAZER_LDS_READ64(le1, lut_lds + ((s0 >> 8) & 255u) * 8u);
+        RAZER_LDS_WAIT(0, le0);
+        RAZER_LDS_WAIT(0, le1);
+        wq0[0] = cvt_scaled_pair<0>(xw[0], u2f(le0.x), le0.y);
+        wq0[1] = cvt_scaled_pair<1>(xw[0], u2f(le0.x), le0.y);
+        wq0[2] = cvt_scaled_pair<2>(xw[0], u2f(le0.x), le0.y);
+        wq0[3] = cvt_scaled_pair<3>(xw[0], u2f(le0.x), le0.y);
+    }
+    int st = 0;                                         // stage of tile kt; tile kt + D goes to st - 1 (mod S)
+    for (int kt = 0; kt < KT; ++kt) {
+        const int st_load = st == 0 ? S - 1 : st - 1, st_next = st == S - 1 ? 0 : st + 1;
+        issue(kt + D < last ? kt + D : last, st_load);
+        compute(kt, st, st_next);
+        // A bare barrier: __syncthreads() would add a fence that waits for every outstanding copy,
+        // i.e. also for the tiles that are meant to stay in flight.  Every wave has waited for its
+        // own copies of tile kt + 1 and for all its LDS reads of tile kt inside compute().
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        st = st_next;
+    }
+#undef RAZER_LDS_READ128
+#undef RAZER_LDS_READ64
+#undef RAZER_LDS_READ32
+#undef RAZER_LDS_WAIT
+#undef RAZER_LDS_WAIT3
+    store_tile<MT, 1, false>(acc, w_ts, nullptr, m0, n0 + 32 * wave, m, n, y, ld_y, lane);
+}
+
+template <int NW, int S>
+static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
+                            int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
+                            hipStream_t st)
+{
+    constexpr int BM = 256, BN = 32 * NW;
+    constexpr size_t smem = S * (BM * 128 + NW * 1280) + 256 * sizeof(uint2);
+    auto kern = gemm_rb_kernel<NW, S>;
+    static bool attr_set = false;                      // one GPU per process
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
+    kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * NW), smem, st>>>(w_codes, w_scales, w_ts, wcfg.sv0,
+                                                                           wcfg.sv1, n, k, a, m, y, ld_y, tiles_m);
+    return hipGetLastError();
+}
+
 template <int BM, int BN, int WGM, int WGN, bool AQ, bool PP = false>
 static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                              int64_t n, int64_t k, const uint16_t* a, const uint8_t* a_codes,
@@ -505,6 +777,12 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
     // weight-tile width that wastes fewer of the 256 compute units in the last round of workgroups.
     const int64_t tm = (m + 255) / 256;
     const int64_t t256 = tm * ((n + 255) / 256), t128 = tm * ((n + 127) / 128);
+    if constexpr (!AQ) {
+        // Enough tiles for two resident waves per SIMD: the kernel that decodes weights in registers
+        // (measured 5-28 % faster than the LDS-staged one on the 7B projection shapes from M = 2048).
+        if (t256 >= 1024) return launch_rb<8, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+        if (t128 >= 512) return launch_rb<4, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+    }
     auto eff = [](int64_t tiles) { return (double)tiles / (double)(((tiles + 255) / 256) * 256); };
 #define RAZER_GEMM_PP(BM, BN, WGM, WGN) \
     launch_cfg<BM, BN, WGM, WGN, AQ, true>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st)

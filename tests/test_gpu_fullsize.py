@@ -126,3 +126,27 @@ def test_config5_w4a4(oracle):
     err = max_rel_err(got, y64)
     _say("   w4a4 max rel err %.2e" % err)
     assert err <= TOL, err
+
+
+@pytest.mark.parametrize("m,n,k", [(8192, 2048 + 40, 32), (4100, 4096 + 8, 160), (16384, 4096, 96),
+                                   (16300, 4096 + 31, 64 + 32), (2048, 11008, 4096 + 32)])
+def test_linear_many_tiles_register_decode_kernel(oracle, m, n, k):
+    """Shapes with >= 512 output tiles take the GEMM kernel that decodes weights in registers and stages
+    operands with global->LDS copies: ragged M, N and K tails (K = 32: half a K-tile; K % 64 = 32), one
+    to 65 K-tiles.  Sampled rows x columns plus the last rows and columns, all scale bytes."""
+    _say("many-tile GEMM m=%d n=%d k=%d" % (m, n, k))
+    rng = np.random.default_rng(7000 + m + n + k)
+    codes = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
+    scales = rng.integers(0, 256, size=(n, k // 16), dtype=np.uint8)
+    wq = (codes, scales, np.float32(2.0 ** -9))
+    wt = razer.RazerTensor.from_host(*wq, W, SV)
+    a = synth.activation(m, k, seed=7001 + m, outlier_frac=0.005, outlier_gain=50.0)
+    y = razer.razer_linear(wt, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([synth.sample_indices(m, 48, 9100), np.arange(m - 8, m), np.arange(0, 4)]))
+    cols = np.unique(np.concatenate([synth.sample_indices(n, 192, 9101), np.arange(n - 40, n), np.arange(0, 8)]))
+    y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=cols)
+    got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+    err = max_rel_err(got, y64)
+    _say("   max rel err %.2e over %d x %d sampled outputs" % (err, len(rows), len(cols)))
+    assert err <= TOL, err
