@@ -235,7 +235,8 @@ def main():
             if m == 2048:
                 gemm_roof = {"bound": "mfma", "achieved": fl / ms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
                              "unit": "TFLOP/s", "frac": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                             "kernel": "gemm_kernel (M=2048, Llama-7B layer set, flops = 2MNK)"}
+                             "kernel": "gemm_pp_kernel<256,128> (q,k,v,o,down) + gemm_rb_kernel<4,2> (gate,up), M=2048, "
+                                       "Llama-7B layer set as 7 launches, flops = 2MNK, whole-leg time"}
         # decoder leg: packed -> bf16
         t = packed[4]
         out = torch.empty((t.rows, t.cols), dtype=torch.bfloat16, device="cuda")
