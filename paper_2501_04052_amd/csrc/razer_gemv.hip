@@ -187,12 +187,12 @@ __device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, con
     }
 }
 
-// Streaming variant for rows of at most 16 slices (K <= 32768): a workgroup owns G consecutive
-// groups of R rows and walks them with D register buffers, so that D - 1 groups of packed weights
+// Streaming variant for rows of at most 16 slices (K <= 32768): a set of waves owns G consecutive
+// groups of R rows (a workgroup holds P such sets side by side) and walks them with D register buffers, so that D - 1 groups of packed weights
 // are always in flight while one is decoded.  Wave w owns K-slice w of every row; its 32
 // activations per lane stay in registers for the whole walk.  Slice totals of all G * R rows meet
 // in LDS after ONE barrier.  Row addresses are uniform (scalar) and lane offsets 32-bit.
-template <int M, int R, int G, int D>
+template <int M, int R, int G, int D, int P = 1>
 __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ codes,
                                                  const uint8_t* __restrict__ scales,
                                                  const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
@@ -201,9 +201,12 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
 {
     static_assert(D >= 2 && D <= 3, "buffer count");
     __shared__ uint2 lut[256];
-    __shared__ float part[G * R * M][kMaxWaves];
+    __shared__ float part[P * G * R * M][kMaxWaves / P];
     const float ts = *w_ts;
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    // P sets of waves work side by side on P consecutive blocks of G * R rows (fewer, larger workgroups)
+    const uint32_t lane = threadIdx.x & 63u, nwaves = (blockDim.x >> 6) / P;
+    const uint32_t wave = (threadIdx.x >> 6) % nwaves, par = (threadIdx.x >> 6) / nwaves;
+    const int64_t wrow0 = row0 + (int64_t)par * (R * G);
     const uint32_t chunks = (uint32_t)(k >> 5);                           // 16-byte code chunks per row
     const uint32_t c = wave * 64u + lane;
     const bool active = c < chunks;
@@ -225,7 +228,7 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     auto load = [&](RowGroup<R>& g, int gi) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            int64_t row = row0 + gi * R + r;
+            int64_t row = wrow0 + gi * R + r;
             row = row < n ? row : n - 1;                                  // tail rows re-read the last row
             const uint8_t* crow = codes + row * code_ld;
             const uint8_t* srow = scales + row * scale_ld;
@@ -249,12 +252,12 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
 #pragma unroll
             for (int m = 0; m < M; ++m) {
                 const float t = wave_sum_to_lane63(acc[r][m]);
-                if (lane == 63) part[(g * R + r) * M + m][wave] = t;
+                if (lane == 63) part[((par * G + g) * R + r) * M + m][wave] = t;
             }
     }
     __syncthreads();
-    if (threadIdx.x < G * R * M) {
-        const int m = threadIdx.x / (G * R), rr = threadIdx.x - m * (G * R);
+    if (threadIdx.x < P * G * R * M) {
+        const int m = threadIdx.x / (P * G * R), rr = threadIdx.x - m * (P * G * R);
         if (row0 + rr < n) {
             float t = 0.0f;
             for (uint32_t w = 0; w < nwaves; ++w) t += part[rr * M + m][w];
@@ -263,7 +266,7 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     }
 }
 
-template <int M, int R, int G, int D>
+template <int M, int R, int G, int D, int P = 1>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_kernel(const uint8_t* __restrict__ codes,
                                                                      const uint8_t* __restrict__ scales,
                                                                      const float* __restrict__ w_ts, float sv0,
@@ -271,7 +274,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_kernel(const uint8
                                                                      const uint16_t* __restrict__ a,
                                                                      uint16_t* __restrict__ y, int64_t ld_y)
 {
-    gemv_stream_body<M, R, G, D>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y, (int64_t)blockIdx.x * (R * G));
+    gemv_stream_body<M, R, G, D, P>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y, (int64_t)blockIdx.x * (P * R * G));
 }
 
 template <int M, int R>
@@ -310,7 +313,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_grouped_kernel(
     gemv_body<M, R>(codes, scales, ts, sv0, sv1, n, k, a, y, ld, (int64_t)(b - first) * R);
 }
 
-template <int M, int R, int G, int D>
+template <int M, int R, int G, int D, int P = 1>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
@@ -328,7 +331,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
     if (b >= g1) { codes = c1; scales = s1; ts = t1; y = y1; n = n1; ld = l1; first = g1; }
     if (b >= g2) { codes = c2; scales = s2; ts = t2; y = y2; n = n2; ld = l2; first = g2; }
     if (b >= g3) { codes = c3; scales = s3; ts = t3; y = y3; n = n3; ld = l3; first = g3; }
-    gemv_stream_body<M, R, G, D>(codes, scales, ts, sv0, sv1, n, k, a, y, ld, (int64_t)(b - first) * (R * G));
+    gemv_stream_body<M, R, G, D, P>(codes, scales, ts, sv0, sv1, n, k, a, y, ld, (int64_t)(b - first) * (P * R * G));
 }
 
 // Rows per group / groups per workgroup of the streaming kernel.  Measured on MI355X over the
@@ -337,6 +340,15 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
 // activation rows on more than 4 waves, longer-lived workgroups (8 groups) win by 20-40 %.
 constexpr int kStreamR = 2;
 static inline int stream_groups(int nwaves, int m) { return (nwaves > 8 || (m >= 3 && nwaves > 4)) ? 8 : 2; }
+// Two sets of waves per workgroup (half as many, larger workgroups) measured 5-8 % faster for rows of
+// 1-3 and 5-8 slices (K = 4096, 11008), slower for 4 slices (K = 8192): dispatching workgroups is part
+// of the cost of these short kernels.
+#ifdef RAZER_GEMV_PROBE
+static int g_probe_sets = 0;
+static inline int stream_sets(int nwaves, int groups) { return (groups == 2 && nwaves <= 8) ? (g_probe_sets ? g_probe_sets : ((nwaves != 4) ? 2 : 1)) : 1; }
+#else
+static inline int stream_sets(int nwaves, int groups) { return (groups == 2 && nwaves <= 8 && nwaves != 4) ? 2 : 1; }
+#endif
 
 template <int M, int R>
 static hipError_t launch_gemv_mr(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,
@@ -358,15 +370,17 @@ static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_
         return launch_gemv_mr<M, 4>(cfg, codes, scales, ts, n, k, a, y, ld_y, st);
     constexpr int R = kStreamR;
     const int nwaves = (int)nslices;
-    if (stream_groups(nwaves, M) == 8) {
-        const unsigned grid = (unsigned)((n + R * 8 - 1) / (R * 8));
-        gemv_stream_kernel<M, R, 8, 2><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a,
-                                                                     y, ld_y);
-    } else {
-        const unsigned grid = (unsigned)((n + R * 2 - 1) / (R * 2));
-        gemv_stream_kernel<M, R, 2, 2><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a,
-                                                                     y, ld_y);
-    }
+    const int groups = stream_groups(nwaves, M), sets = stream_sets(nwaves, groups);
+    const unsigned grid = (unsigned)((n + sets * R * groups - 1) / (sets * R * groups));
+    if (groups == 8)
+        gemv_stream_kernel<M, R, 8, 2, 1><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a,
+                                                                        y, ld_y);
+    else if (sets == 2)
+        gemv_stream_kernel<M, R, 2, 2, 2><<<grid, 128 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a,
+                                                                         y, ld_y);
+    else
+        gemv_stream_kernel<M, R, 2, 2, 1><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a,
+                                                                        y, ld_y);
     return hipGetLastError();
 }
 
@@ -378,7 +392,8 @@ static hipError_t launch_gemv_grouped_m(SvConfig cfg, int count, const GemvProbl
     const bool stream = nslices <= kMaxWaves;
     const int nwaves = (int)(stream ? nslices : kMaxWaves);
     const int groups = stream ? stream_groups(nwaves, M) : 1;
-    const int64_t rows_per_wg = stream ? kStreamR * groups : 4;
+    const int sets = stream ? stream_sets(nwaves, groups) : 1;
+    const int64_t rows_per_wg = stream ? sets * kStreamR * groups : 4;
     GemvProblem q[4];
     unsigned g[5] = {0, 0, 0, 0, 0};
     for (int i = 0; i < 4; ++i) {
@@ -392,9 +407,11 @@ static hipError_t launch_gemv_grouped_m(SvConfig cfg, int count, const GemvProbl
     if (!stream)
         gemv_grouped_kernel<M, 4><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
     else if (groups == 8)
-        gemv_stream_grouped_kernel<M, kStreamR, 8, 2><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
+        gemv_stream_grouped_kernel<M, kStreamR, 8, 2, 1><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
+    else if (sets == 2)
+        gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 2><<<g[4], 128 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
     else
-        gemv_stream_grouped_kernel<M, kStreamR, 2, 2><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
+        gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 1><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
 #undef RAZER_GROUPED_ARGS
     return hipGetLastError();
 }
