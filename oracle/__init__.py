@@ -61,11 +61,11 @@ def lib():
         L.oracle_f64_to_bf16.restype = ctypes.c_uint16; L.oracle_f64_to_bf16.argtypes = [d]
         L.oracle_tensor_scale.restype = f; L.oracle_tensor_scale.argtypes = [i, vp, i, i64]
         L.oracle_quantize.restype = i
-        L.oracle_quantize.argtypes = [i, d, d, i, vp, i, i64, i64, vp, vp, vp, i, vp]
+        L.oracle_quantize.argtypes = [i, d, d, i, vp, i, i64, i64, i, vp, vp, vp, i, vp]
         L.oracle_dequant.restype = i
-        L.oracle_dequant.argtypes = [i, d, d, vp, vp, f, i64, i64, vp, vp, vp]
+        L.oracle_dequant.argtypes = [i, d, d, vp, vp, f, i64, i64, i, vp, vp, vp]
         L.oracle_linear.restype = i
-        L.oracle_linear.argtypes = [d, d, vp, vp, f, i64, i64, vp, d, vp, vp, f, i64,
+        L.oracle_linear.argtypes = [d, d, vp, vp, f, i64, i64, i, vp, d, vp, vp, f, i, i64,
                                     vp, i64, vp, i64, vp, vp]
         L.oracle_two_pass_split.restype = i
         L.oracle_two_pass_split.argtypes = [i, i, i, ctypes.POINTER(i), ctypes.POINTER(i),
@@ -123,24 +123,24 @@ def tensor_scale(fmt, x):
     return float(lib().oracle_tensor_scale(fmt, _p(x), int(is_bf16), x.size))
 
 
-def quantize(fmt, x, sv=(5.0, 8.0), nsv=-1, given_tensor_scale=None, want_sse=False):
+def quantize(fmt, x, sv=(5.0, 8.0), nsv=-1, given_tensor_scale=None, want_sse=False, block=BLOCK):
     """Encode x [rows][cols] (float32, or uint16 holding bf16).
 
-    Returns (codes u8 [rows][cols/2], scales u8 [rows][cols/16], tensor_scale
-    float32 scalar[, block_sse f64 [rows][cols/16]]).  nsv=0 -> plain NVFP4
-    under the same block-scale format."""
+    Returns (codes u8 [rows][cols/2], scales u8 [rows][cols/block], tensor_scale
+    float32 scalar[, block_sse f64 [rows][cols/block]]).  nsv=0 -> plain NVFP4
+    under the same block-scale format.  block: 16 (the evaluated format), 32, 64 or 128."""
     x = np.ascontiguousarray(x)
     is_bf16 = x.dtype == np.uint16
     assert is_bf16 or x.dtype == np.float32
     rows, cols = x.shape
     codes = np.empty((rows, cols // 2), np.uint8)
-    scales = np.empty((rows, cols // BLOCK), np.uint8)
+    scales = np.empty((rows, cols // block), np.uint8)
     ts = np.zeros(1, np.float32)
     if given_tensor_scale is not None:
         ts[0] = given_tensor_scale
-    sse = np.empty((rows, cols // BLOCK), np.float64) if want_sse else None
+    sse = np.empty((rows, cols // block), np.float64) if want_sse else None
     rc = lib().oracle_quantize(fmt, float(sv[0]), float(sv[1]), int(nsv), _p(x), int(is_bf16),
-                               rows, cols, _p(codes), _p(scales), _p(ts),
+                               rows, cols, int(block), _p(codes), _p(scales), _p(ts),
                                int(given_tensor_scale is not None), _p(sse))
     if rc != 0:
         raise ValueError("oracle_quantize: bad shape")
@@ -148,16 +148,18 @@ def quantize(fmt, x, sv=(5.0, 8.0), nsv=-1, given_tensor_scale=None, want_sse=Fa
 
 
 def dequant(fmt, codes, scales, ts, sv=(5.0, 8.0), want=("f32",)):
-    """Decode to any of 'f32', 'bf16' (uint16 bits), 'sq' (f64 scale*element)."""
+    """Decode to any of 'f32', 'bf16' (uint16 bits), 'sq' (f64 scale*element).
+    The block size is read off the shapes: cols / scales.shape[1]."""
     codes = _c(codes, np.uint8); scales = _c(scales, np.uint8)
     rows, half = codes.shape
     cols = half * 2
+    block = cols // scales.shape[1] if scales.shape[1] else BLOCK
     out = {}
     f32 = np.empty((rows, cols), np.float32) if "f32" in want else None
     b16 = np.empty((rows, cols), np.uint16) if "bf16" in want else None
     sq = np.empty((rows, cols), np.float64) if "sq" in want else None
     rc = lib().oracle_dequant(fmt, float(sv[0]), float(sv[1]), _p(codes), _p(scales), float(ts),
-                              rows, cols, _p(f32), _p(b16), _p(sq))
+                              rows, cols, int(block), _p(f32), _p(b16), _p(sq))
     if rc != 0:
         raise ValueError("oracle_dequant: bad shape")
     for k, v in (("f32", f32), ("bf16", b16), ("sq", sq)):
@@ -170,26 +172,30 @@ def linear(w, a_bf16=None, a_q=None, w_sv=(5.0, 8.0), a_sv0=5.0, rows=None, cols
     """Y = A W^T.  w = (codes, scales, ts) in the weight format; exactly one of
     a_bf16 (uint16 [m][k]) and a_q = (codes, scales, ts) in the activation
     format.  rows / cols: optional int64 index arrays selecting the output
-    rows (of M) and columns (of N) to compute.  Returns (y_f64, y_bf16)."""
+    rows (of M) and columns (of N) to compute.  Block sizes are read off the
+    shapes of the scale arrays.  Returns (y_f64, y_bf16)."""
     wc, ws, wts = w
     wc = _c(wc, np.uint8); ws = _c(ws, np.uint8)
     n, k = wc.shape[0], wc.shape[1] * 2
     ac = asc = ab = None
     ats = 0.0
+    w_block = k // ws.shape[1] if ws.shape[1] else BLOCK
+    a_block = BLOCK
     if a_bf16 is not None:
         ab = _c(a_bf16, np.uint16); m = ab.shape[0]; assert ab.shape[1] == k
     else:
         ac, asc, ats = a_q
         ac = _c(ac, np.uint8); asc = _c(asc, np.uint8); m = ac.shape[0]
         assert ac.shape[1] * 2 == k
+        a_block = k // asc.shape[1] if asc.shape[1] else BLOCK
     rs = None if rows is None else np.ascontiguousarray(rows, np.int64)
     cs = None if cols is None else np.ascontiguousarray(cols, np.int64)
     mm = m if rs is None else rs.size
     nn = n if cs is None else cs.size
     y64 = np.empty((mm, nn), np.float64)
     y16 = np.empty((mm, nn), np.uint16)
-    rc = lib().oracle_linear(float(w_sv[0]), float(w_sv[1]), _p(wc), _p(ws), float(wts), n, k,
-                             _p(ab), float(a_sv0), _p(ac), _p(asc), float(ats), m,
+    rc = lib().oracle_linear(float(w_sv[0]), float(w_sv[1]), _p(wc), _p(ws), float(wts), n, k, int(w_block),
+                             _p(ab), float(a_sv0), _p(ac), _p(asc), float(ats), int(a_block), m,
                              _p(rs), mm, _p(cs), nn, _p(y64), _p(y16))
     if rc != 0:
         raise ValueError("oracle_linear: bad arguments")

@@ -27,7 +27,11 @@
 #include <stddef.h>
 #include <string.h>
 
-#define RAZER_BLOCK 16           /* elements per block (Sec. 3, Sec. 5.1) */
+#define RAZER_BLOCK 16           /* elements per block of the evaluated format (Sec. 3, Sec. 5.1) */
+#define RAZER_MAX_BLOCK 128      /* largest block of the block-size study (Sec. 5.4, "Impact of Block Size") */
+
+/* Block sizes of the paper's block-size study: 16, 32, 64, 128 (Sec. 5.4). */
+static int block_ok(int block) { return block == 16 || block == 32 || block == 64 || block == 128; }
 #define REMAP_CODE 0x8           /* the redundant zero: sign=1, E=0, M=0   */
 
 enum { FMT_WEIGHT = 0, FMT_ACT = 1 };
@@ -218,18 +222,33 @@ float oracle_tensor_scale(int fmt, const void *x, int x_is_bf16, int64_t n)
     return amax / denom;
 }
 
-/* One block of 16: Eq. 2 (block scale), the scaling that defines X^Scaled,
- * Eq. 4 (special-value search) and Eq. 5 (final rounding).
+/* One block of `block` elements (16 in the evaluated format; 32, 64, 128 in the
+ * block-size study of Sec. 5.4): Eq. 2 (block scale), the scaling that defines
+ * X^Scaled, Eq. 4 (special-value search) and Eq. 5 (final rounding).
  *   delta32 : the tensor scale.   nsv: number of candidates searched
  *   (0 = plain NVFP4 under the same scale).
- * Outputs: 16 codes, the 6/7-bit scale code, the metadata index, and the
- * block's squared error in the scaled domain (fp64, summed k = 0..15).     */
-static void encode_block(int fmt, const double cand[4], int nsv, float delta32,
-                         const float xb[RAZER_BLOCK], uint8_t codes[RAZER_BLOCK],
+ * Outputs: the codes, the 6/7-bit scale code, the metadata index, and the
+ * block's squared error in the scaled domain.  Reading taken for the order of
+ * the fp64 error sum (the paper is silent): the squared errors of each run of
+ * 16 consecutive elements are summed in index order, and the runs' sums are
+ * added in run order -- for a block of 16 that is the plain sum k = 0..15.   */
+static double sse_in_runs(const double *e2, int block)
+{
+    double total = 0.0;
+    for (int r0 = 0; r0 < block; r0 += RAZER_BLOCK) {
+        double run = 0.0;
+        for (int k = 0; k < RAZER_BLOCK; ++k) run += e2[r0 + k];
+        total = (r0 == 0) ? run : total + run;
+    }
+    return total;
+}
+
+static void encode_block(int fmt, const double cand[4], int nsv, float delta32, int block,
+                         const float *xb, uint8_t *codes,
                          int *scale_code, int *meta, double *sse_out)
 {
     float bmax = 0.0f;
-    for (int k = 0; k < RAZER_BLOCK; ++k) { float a = fabsf(xb[k]); if (a > bmax) bmax = a; }
+    for (int k = 0; k < block; ++k) { float a = fabsf(xb[k]); if (a > bmax) bmax = a; }
 
     /* Eq. 2: t = bmax / (delta32 * Qmax^FP4), rounded to the scale grid. */
     float d = delta32 * 6.0f;
@@ -239,36 +258,35 @@ static void encode_block(int fmt, const double cand[4], int nsv, float delta32,
     *scale_code = sc;
     *meta = 0;
     if (s == 0.0f) {                                 /* scale underflowed to 0: block decodes to zeros */
-        double sse = 0.0;
-        for (int k = 0; k < RAZER_BLOCK; ++k) { codes[k] = 0; }
-        *sse_out = sse;
+        for (int k = 0; k < block; ++k) { codes[k] = 0; }
+        *sse_out = 0.0;
         return;
     }
     /* X^Scaled = X / (delta32 * delta8)  (denominator of Eq. 3). */
     float den = delta32 * s;
-    float xs[RAZER_BLOCK];
-    for (int k = 0; k < RAZER_BLOCK; ++k) xs[k] = xb[k] / den;
+    float xs[RAZER_MAX_BLOCK];
+    double e2[RAZER_MAX_BLOCK];
+    for (int k = 0; k < block; ++k) xs[k] = xb[k] / den;
 
     if (nsv == 0) {                                  /* Eq. 3 alone: NVFP4 */
-        double sse = 0.0;
-        for (int k = 0; k < RAZER_BLOCK; ++k) {
-            double e; codes[k] = (uint8_t)round_elem(xs[k], 0, 0.0, &e); sse += e * e;
+        for (int k = 0; k < block; ++k) {
+            double e; codes[k] = (uint8_t)round_elem(xs[k], 0, 0.0, &e); e2[k] = e * e;
         }
-        *sse_out = sse;
+        *sse_out = sse_in_runs(e2, block);
         return;
     }
     /* Eq. 4: try every allowed special value, keep the smallest squared
      * error; on equal error the smallest metadata index.                  */
     double best_sse = 0.0; int best_m = -1;
     for (int m = 0; m < nsv; ++m) {
-        double sse = 0.0;
-        for (int k = 0; k < RAZER_BLOCK; ++k) {
-            double e; (void)round_elem(xs[k], 1, cand[m], &e); sse += e * e;
+        for (int k = 0; k < block; ++k) {
+            double e; (void)round_elem(xs[k], 1, cand[m], &e); e2[k] = e * e;
         }
+        double sse = sse_in_runs(e2, block);
         if (best_m < 0 || sse < best_sse) { best_sse = sse; best_m = m; }
     }
     /* Eq. 5: quantize the block with the chosen special value. */
-    for (int k = 0; k < RAZER_BLOCK; ++k) {
+    for (int k = 0; k < block; ++k) {
         double e; codes[k] = (uint8_t)round_elem(xs[k], 1, cand[best_m], &e);
     }
     *meta = best_m;
@@ -276,35 +294,35 @@ static void encode_block(int fmt, const double cand[4], int nsv, float delta32,
 }
 
 /* Whole-tensor encoder.  x is [rows][cols] dense, fp32 or bf16 (widened
- * exactly); blocks of 16 run along cols.  Layout written:
- *   codes  [rows][cols/2]  element k even -> low nibble, odd -> high nibble
- *   scales [rows][cols/16] weights: meta<<6 | E3M3; activations: meta<<7 | E4M3
- *   *tensor_scale          Eq. 1 (taken as input when given_scale != 0)
- *   block_sse (optional)   [rows][cols/16] squared error in the scaled domain
+ * exactly); blocks of `block` elements run along cols.  Layout written:
+ *   codes  [rows][cols/2]      element k even -> low nibble, odd -> high nibble
+ *   scales [rows][cols/block]  weights: meta<<6 | E3M3; activations: meta<<7 | E4M3
+ *   *tensor_scale              Eq. 1 (taken as input when given_scale != 0)
+ *   block_sse (optional)       [rows][cols/block] squared error in the scaled domain
  * nsv_override < 0 searches the format's full candidate set; 0 = NVFP4.
- * Returns 0, or -1 on a bad shape.                                         */
+ * Returns 0, or -1 on a bad shape or block size.                           */
 int oracle_quantize(int fmt, double sv0, double sv1, int nsv_override,
-                    const void *x, int x_is_bf16, int64_t rows, int64_t cols,
+                    const void *x, int x_is_bf16, int64_t rows, int64_t cols, int block,
                     uint8_t *codes, uint8_t *scales, float *tensor_scale,
                     int given_scale, double *block_sse)
 {
-    if (rows < 0 || cols < 0 || cols % RAZER_BLOCK) return -1;
+    if (!block_ok(block) || rows < 0 || cols < 0 || cols % block) return -1;
     double sv[2] = { sv0, sv1 }, cand[4];
     int nsv = candidates(fmt, sv, nsv_override, cand);
     float delta32 = given_scale ? *tensor_scale : oracle_tensor_scale(fmt, x, x_is_bf16, rows * cols);
     if (!given_scale) *tensor_scale = delta32;
-    int64_t nb = cols / RAZER_BLOCK;
+    int64_t nb = cols / block;
     #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r) {
         for (int64_t b = 0; b < nb; ++b) {
-            float xb[RAZER_BLOCK]; uint8_t cb[RAZER_BLOCK]; int sc, meta; double sse;
-            for (int k = 0; k < RAZER_BLOCK; ++k) {
-                int64_t idx = r * cols + b * RAZER_BLOCK + k;
+            float xb[RAZER_MAX_BLOCK]; uint8_t cb[RAZER_MAX_BLOCK]; int sc, meta; double sse;
+            for (int k = 0; k < block; ++k) {
+                int64_t idx = r * cols + b * block + k;
                 xb[k] = x_is_bf16 ? bf16_to_f32(((const uint16_t *)x)[idx]) : ((const float *)x)[idx];
             }
-            encode_block(fmt, cand, nsv, delta32, xb, cb, &sc, &meta, &sse);
-            for (int k = 0; k < RAZER_BLOCK; k += 2)
-                codes[(r * cols + b * RAZER_BLOCK + k) / 2] = (uint8_t)(cb[k] | (cb[k + 1] << 4));
+            encode_block(fmt, cand, nsv, delta32, block, xb, cb, &sc, &meta, &sse);
+            for (int k = 0; k < block; k += 2)
+                codes[(r * cols + b * block + k) / 2] = (uint8_t)(cb[k] | (cb[k + 1] << 4));
             scales[r * nb + b] = (uint8_t)((meta << meta_shift(fmt)) | sc);
             if (block_sse) block_sse[r * nb + b] = sse;
         }
@@ -323,18 +341,18 @@ int oracle_quantize(int fmt, double sv0, double sv1, int nsv_override,
  * returns the unscaled product delta8_i * xbar in out_sq when not NULL.     */
 int oracle_dequant(int fmt, double sv0, double sv1,
                    const uint8_t *codes, const uint8_t *scales, float tensor_scale,
-                   int64_t rows, int64_t cols,
+                   int64_t rows, int64_t cols, int block,
                    float *out_f32, uint16_t *out_bf16, double *out_sq)
 {
-    if (rows < 0 || cols < 0 || cols % RAZER_BLOCK) return -1;
-    int64_t nb = cols / RAZER_BLOCK;
+    if (!block_ok(block) || rows < 0 || cols < 0 || cols % block) return -1;
+    int64_t nb = cols / block;
     int sh = meta_shift(fmt);
     #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r) {
         for (int64_t k = 0; k < cols; ++k) {
             uint8_t byte = codes[(r * cols + k) / 2];
             int code = (k & 1) ? (byte >> 4) : (byte & 15);
-            uint8_t sb = scales[r * nb + k / RAZER_BLOCK];
+            uint8_t sb = scales[r * nb + k / block];
             int meta = sb >> sh, sc = sb & ((1 << sh) - 1);
             double sq = oracle_scale_value(fmt, sc) * oracle_element_value(fmt, sv0, sv1, code, meta);
             float w = (float)((double)tensor_scale * sq);   /* exact product rounded once */
@@ -357,20 +375,23 @@ int oracle_dequant(int fmt, double sv0, double sv1,
  *   a_bf16 != NULL : W4A16, activations [m][k] bf16.
  *   a_codes != NULL: W4A4, activations RaZeR-quantized in the activation
  *                    format with special value a_sv0.
+ * w_block / a_block: elements per block scale of each operand (16 in the
+ * evaluated format; Sec. 5.4 also studies 32, 64, 128).
  * Outputs y_f64 [m][n] (optional) and y_bf16 [m][n] (optional).  When
  * n_cols_sel > 0 only the listed output columns / rows are computed
  * (sampled check of large problems); outputs are then [m_sel][n_sel].      */
 int oracle_linear(double w_sv0, double w_sv1,
                   const uint8_t *w_codes, const uint8_t *w_scales, float w_tensor_scale,
-                  int64_t n, int64_t k,
+                  int64_t n, int64_t k, int w_block,
                   const uint16_t *a_bf16,
                   double a_sv0, const uint8_t *a_codes, const uint8_t *a_scales, float a_tensor_scale,
-                  int64_t m,
+                  int a_block, int64_t m,
                   const int64_t *row_sel, int64_t m_sel, const int64_t *col_sel, int64_t n_sel,
                   double *y_f64, uint16_t *y_bf16)
 {
-    if (k % RAZER_BLOCK || (!a_bf16 == !a_codes)) return -1;
-    int64_t nb = k / RAZER_BLOCK;
+    if (!block_ok(w_block) || k % w_block || (!a_bf16 == !a_codes)) return -1;
+    if (a_codes && (!block_ok(a_block) || k % a_block)) return -1;
+    int64_t nb = k / w_block, nba = a_codes ? k / a_block : 0;
     int64_t mm = row_sel ? m_sel : m, nn = col_sel ? n_sel : n;
     #pragma omp parallel for schedule(static)
     for (int64_t jn = 0; jn < nn; ++jn) {
@@ -381,7 +402,7 @@ int oracle_linear(double w_sv0, double w_sv1,
             for (int64_t kk = 0; kk < k; ++kk) {
                 uint8_t wb = w_codes[(col * k + kk) / 2];
                 int wc = (kk & 1) ? (wb >> 4) : (wb & 15);
-                uint8_t ws = w_scales[col * nb + kk / RAZER_BLOCK];
+                uint8_t ws = w_scales[col * nb + kk / w_block];
                 double wq = oracle_scale_value(FMT_WEIGHT, ws & 63) *
                             oracle_element_value(FMT_WEIGHT, w_sv0, w_sv1, wc, ws >> 6);
                 double av;
@@ -390,7 +411,7 @@ int oracle_linear(double w_sv0, double w_sv1,
                 } else {
                     uint8_t ab = a_codes[(row * k + kk) / 2];
                     int ac = (kk & 1) ? (ab >> 4) : (ab & 15);
-                    uint8_t as = a_scales[row * nb + kk / RAZER_BLOCK];
+                    uint8_t as = a_scales[row * nba + kk / a_block];
                     av = oracle_scale_value(FMT_ACT, as & 127) *
                          oracle_element_value(FMT_ACT, a_sv0, 0.0, ac, as >> 7);
                 }
