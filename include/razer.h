@@ -7,7 +7,8 @@
  *   element   FP4-E2M1 code S|EE|M (Sec. 4.1, FP4 equation): +-{0,.5,1,1.5,2,3,4,6};
  *             code 0x8 (negative zero) is the remapped one (Sec. 4.2).
  *   block     16 consecutive elements along the last (contraction) axis share one
- *             scale byte (Sec. 3; Sec. 5.1 "block size of 16 with 8-bit block scale"):
+ *             scale byte (Sec. 3; Sec. 5.1 "block size of 16 with 8-bit block scale");
+ *             32, 64 and 128 are accepted too (block-size study of Sec. 5.4):
  *               weights      bit7 = special-value sign, bit6 = special-value selector,
  *                            bits5:0 = E3M3 scale EEE|MMM, value 2^(E-3)(1+M/8), E=0: M/32
  *                            (Sec. 4.1 adopts E3M3 for weights; 2 freed bits, Sec. 4.2)
@@ -20,10 +21,11 @@
  *   value     x^ = tensor_scale * block_scale * (code == 0x8 ? special : FP4[code]).
  *
  * Storage (dense, row-major, all DEVICE memory, caller-owned):
- *   codes  [rows][cols/2]   uint8, element k even in the LOW nibble, k odd in the high
- *   scales [rows][cols/16]  uint8 as above
- *   tensor_scale            one float
- * i.e. 4.5 bits per element plus 4 bytes, the NVFP4 footprint (Sec. 4.2).
+ *   codes  [rows][cols/2]      uint8, element k even in the LOW nibble, k odd in the high
+ *   scales [rows][cols/block]  uint8 as above
+ *   tensor_scale               one float
+ * i.e. 4.5 bits per element plus 4 bytes at block 16, the NVFP4 footprint (Sec. 4.2);
+ * 4 + 8 / block bits in general.
  *
  * Every entry point only enqueues kernels on the HIP stream passed in
  * (hipStream_t cast to void*, NULL = default stream); nothing allocates,
@@ -65,6 +67,8 @@ typedef enum { RAZER_F32 = 0, RAZER_BF16 = 1 } razer_dtype;
 typedef struct {
     int32_t format;            /* razer_format */
     float sv[2];
+    int32_t block;             /* elements per scale byte: 16, 32, 64 or 128; 0 means 16.  cols must be
+                                  a multiple of max(32, block).                                         */
 } razer_config;
 
 /* A quantized tensor: device pointers + shape + configuration. */
@@ -94,6 +98,8 @@ size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m);
  * (round-to-nearest on Q_FP4 U {special}; ties between FP4 values go to the
  * even code, an FP4 value beats the special value on a tie, zero is always
  * code 0).  A block whose scale rounds to 0 is written as all-zero codes.
+ * For blocks longer than 16 the fp64 error sum of Eq. 4 runs over each 16 consecutive
+ * elements in index order and adds those sums in order.
  *   x       device, [rows][ld] elements of dtype (fp32 or bf16), cols used per row
  *   codes, scales, tensor_scale   device outputs (tensor_scale input with the flag)
  *   workspace  device, >= razer_workspace_bytes(RAZER_OP_QUANTIZE, ...) bytes, 16-aligned
@@ -129,7 +135,7 @@ razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer
 /* The same layer for several weight matrices that consume the SAME activation rows (fused q/k/v,
  * gate/up projections; the paper's stripe partition likewise lets one launch span several N
  * ranges, Sec. 4.3): y_bf16[i] = A w[i]^T for i < count, count <= RAZER_MAX_GROUP.  All w[i] must
- * have the same cols; W4A16 only.  For m <= 4 and equal special values this is ONE kernel launch
+ * have the same cols; W4A16 only.  For m <= 4, block 16 and equal special values this is ONE kernel launch
  * (short decode-regime kernels are launch-latency-bound); otherwise it is the sequence of
  * razer_linear calls.  y_bf16[i] is device [m][ld_y[i]].  The pointer arrays are HOST arrays. */
 #define RAZER_MAX_GROUP 4

@@ -27,7 +27,7 @@ class RazerError(RuntimeError):
 
 
 class _Config(ctypes.Structure):
-    _fields_ = [("format", ctypes.c_int32), ("sv", ctypes.c_float * 2)]
+    _fields_ = [("format", ctypes.c_int32), ("sv", ctypes.c_float * 2), ("block", ctypes.c_int32)]
 
 
 class _Tensor(ctypes.Structure):
@@ -89,20 +89,21 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-def _cfg(fmt, sv):
+def _cfg(fmt, sv, block=16):
     c = _Config()
     c.format = fmt
     c.sv[0] = float(sv[0])
     c.sv[1] = float(sv[1]) if len(sv) > 1 else 0.0
+    c.block = int(block)
     return c
 
 
 class RazerTensor:
     """A quantized tensor: device buffers + shape + configuration (razer_tensor in the ABI)."""
 
-    def __init__(self, codes, scales, tensor_scale, rows, cols, fmt, sv):
+    def __init__(self, codes, scales, tensor_scale, rows, cols, fmt, sv, block=16):
         self.codes, self.scales, self.tensor_scale = codes, scales, tensor_scale
-        self.rows, self.cols, self.fmt, self.sv = int(rows), int(cols), fmt, tuple(sv)
+        self.rows, self.cols, self.fmt, self.sv, self.block = int(rows), int(cols), fmt, tuple(sv), int(block)
 
     def c_struct(self):
         t = _Tensor()
@@ -110,25 +111,28 @@ class RazerTensor:
         t.scales = self.scales.data_ptr()
         t.tensor_scale = self.tensor_scale.data_ptr()
         t.rows, t.cols = self.rows, self.cols
-        t.cfg = _cfg(self.fmt, self.sv)
+        t.cfg = _cfg(self.fmt, self.sv, self.block)
         return t
 
     @staticmethod
     def from_host(codes, scales, tensor_scale, fmt, sv, device="cuda"):
-        """Upload numpy codes [rows][cols/2], scales [rows][cols/16] and a scalar tensor scale."""
+        """Upload numpy codes [rows][cols/2], scales [rows][cols/block] and a scalar tensor scale
+        (the block size is read off the shapes)."""
         import numpy as np
         rows, cols = codes.shape[0], codes.shape[1] * 2
+        block = cols // scales.shape[1] if scales.shape[1] else 16
         return RazerTensor(torch.from_numpy(np.ascontiguousarray(codes)).to(device),
                            torch.from_numpy(np.ascontiguousarray(scales)).to(device),
                            torch.tensor([float(tensor_scale)], dtype=torch.float32, device=device),
-                           rows, cols, fmt, sv)
+                           rows, cols, fmt, sv, block)
 
 
-def razer_quantize(x, fmt=WEIGHT, sv=(5.0, 8.0), tensor_scale=None, out=None, workspace=None, cols=None):
+def razer_quantize(x, fmt=WEIGHT, sv=(5.0, 8.0), tensor_scale=None, out=None, workspace=None, cols=None, block=16):
     """Encode a 2-D device tensor x (float32 or bfloat16); blocks of 16 run along the last axis.
 
     tensor_scale: optional 1-element float32 device tensor used as a given (static) scale.
     cols: number of leading columns to encode when x's rows are longer (x.stride(0) is the ld).
+    block: elements per scale byte (16, 32, 64 or 128).
     Returns a RazerTensor whose buffers live on x's device."""
     L = load_library()
     assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1
@@ -138,7 +142,7 @@ def razer_quantize(x, fmt=WEIGHT, sv=(5.0, 8.0), tensor_scale=None, out=None, wo
     dev = x.device
     if out is None:
         codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=dev)
-        scales = torch.empty((rows, cols // 16), dtype=torch.uint8, device=dev)
+        scales = torch.empty((rows, cols // block), dtype=torch.uint8, device=dev)
         ts = torch.empty(1, dtype=torch.float32, device=dev) if tensor_scale is None else tensor_scale
     else:
         codes, scales, ts = out.codes, out.scales, out.tensor_scale
@@ -148,14 +152,14 @@ def razer_quantize(x, fmt=WEIGHT, sv=(5.0, 8.0), tensor_scale=None, out=None, wo
     need = razer_workspace_bytes(OP_QUANTIZE, rows, cols)
     if workspace is None and not flags:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
-    cfg = _cfg(fmt, sv)
+    cfg = _cfg(fmt, sv, block)
     ld = x.stride(0) if rows > 1 else max(x.stride(0), cols)
     st = L.razer_quantize(ctypes.byref(cfg), _ptr(x), dtype, rows, cols, ld, _ptr(codes), _ptr(scales),
                           _ptr(ts), flags, _ptr(workspace), 0 if workspace is None else workspace.numel(),
                           _stream())
     if st != 0:
         raise RazerError(st, "razer_quantize")
-    return RazerTensor(codes, scales, ts, rows, cols, fmt, sv)
+    return RazerTensor(codes, scales, ts, rows, cols, fmt, sv, block)
 
 
 def razer_dequant(t, dtype=torch.float32, out=None):

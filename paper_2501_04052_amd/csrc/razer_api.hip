@@ -27,15 +27,25 @@ razer_status check_cfg(const razer_config& c, SvConfig& out)
     if (c.format == RAZER_FMT_WEIGHT && !sv_ok(c.sv[1])) return RAZER_ERR_CONFIG;
     out.sv0 = c.sv[0];
     out.sv1 = (c.format == RAZER_FMT_WEIGHT) ? c.sv[1] : c.sv[0];
+    switch (c.block) {
+        case 0: case 16: out.lb = 4; break;
+        case 32: out.lb = 5; break;
+        case 64: out.lb = 6; break;
+        case 128: out.lb = 7; break;
+        default: return RAZER_ERR_CONFIG;
+    }
     return RAZER_OK;
 }
+
+// cols must hold whole blocks and whole 16-byte code chunks
+bool cols_ok(int64_t cols, const SvConfig& c) { return cols >= 0 && cols % 32 == 0 && cols % ((int64_t)1 << c.lb) == 0; }
 
 razer_status check_tensor(const razer_tensor* t, int want_fmt, SvConfig& cfg)
 {
     if (!t) return RAZER_ERR_NULL;
-    if (t->rows < 0 || t->cols < 0 || t->cols % 32 != 0) return RAZER_ERR_SHAPE;
     razer_status s = check_cfg(t->cfg, cfg);
     if (s != RAZER_OK) return s;
+    if (t->rows < 0 || !cols_ok(t->cols, cfg)) return RAZER_ERR_SHAPE;
     if (want_fmt >= 0 && t->cfg.format != want_fmt) return RAZER_ERR_CONFIG;
     if (!t->tensor_scale) return RAZER_ERR_NULL;
     if (t->rows > 0 && t->cols > 0) {
@@ -88,7 +98,7 @@ razer_status razer_quantize(const razer_config* cfg, const void* x, int32_t dtyp
     if (s != RAZER_OK) return s;
     if (dtype != RAZER_F32 && dtype != RAZER_BF16) return RAZER_ERR_CONFIG;
     if (flags & ~RAZER_GIVEN_TENSOR_SCALE) return RAZER_ERR_CONFIG;
-    if (rows < 0 || cols < 0 || cols % 32 != 0 || ld < cols) return RAZER_ERR_SHAPE;
+    if (rows < 0 || !cols_ok(cols, sv) || ld < cols) return RAZER_ERR_SHAPE;
     const size_t esz = (dtype == RAZER_F32) ? 4 : 2;
     if (rows > 0 && cols > 0) {
         if (!x || !codes || !scales) return RAZER_ERR_NULL;
@@ -181,6 +191,7 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
         if (m > 0 && w[i]->rows > 0 && !y_bf16[i]) return RAZER_ERR_NULL;
         if (i == 0) sv0 = sv;
         else if (sv.sv0 != sv0.sv0 || sv.sv1 != sv0.sv1) one_launch = false;
+        if (sv.lb != 4) one_launch = false;
         if (w[i]->rows == 0) one_launch = false;
     }
     if (m == 0) return RAZER_OK;

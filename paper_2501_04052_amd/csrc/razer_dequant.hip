@@ -6,7 +6,8 @@
 
 namespace razer {
 
-// One thread decodes one block of 16 elements (8 code bytes + 1 scale byte).
+// One thread decodes 16 consecutive elements (8 code bytes) with the scale byte of their block
+// (16, 32, 64 or 128 elements: cfg.lb = log2 of the block size).
 template <int FMT, bool OUT_BF16>
 __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict__ codes,
                                                       const uint8_t* __restrict__ scales,
@@ -21,7 +22,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict_
     const float ts = *tensor_scale;
     const uint2 cw = *reinterpret_cast<const uint2*>(codes + r * (cols / 2) + b * 8);
     float s, sv;
-    decode_scale_byte<FMT>(scales[r * nb + b], cfg.sv0, cfg.sv1, s, sv);
+    decode_scale_byte<FMT>(scales[r * (nb >> (cfg.lb - 4)) + (b >> (cfg.lb - 4))], cfg.sv0, cfg.sv1, s, sv);
     const float ssv = s * sv;                                   // exact: <= 9 significant bits
     float w[kBlock];
 #pragma unroll

@@ -21,9 +21,22 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef unsigned short v2us __attribute__((ext_vector_type(2)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
-struct SvConfig {          // special-value magnitudes, already validated on the host
+struct SvConfig {          // special-value magnitudes and log2(block size), already validated on the host
     float sv0, sv1;
+    int lb = 4;
 };
+
+// The two scale bytes (low byte first) that govern the 32 consecutive elements starting at element
+// k0 (a multiple of 32) of a row whose scale bytes start at srow.  GB = false: blocks of 16, one
+// 16-bit load.  GB = true: blocks of 2^lb elements chosen at run time; from 32 up both runs of 16
+// share one byte.
+template <bool GB>
+__device__ __forceinline__ uint32_t load_scale_pair(const uint8_t* __restrict__ srow, int64_t k0, int lb)
+{
+    if (!GB || lb == 4) return *reinterpret_cast<const uint16_t*>(srow + (k0 >> 4));
+    const uint32_t b = srow[k0 >> lb];
+    return b | (b << 8);
+}
 
 __device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }

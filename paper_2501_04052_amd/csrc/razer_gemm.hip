@@ -104,7 +104,7 @@ __device__ __forceinline__ void store_tile(const v16f (&acc)[TN][TM], const floa
         }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AQ>
+template <int BM, int BN, int WGM, int WGN, bool AQ, bool GB>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     SvConfig wcfg, int64_t n, int64_t k, const uint16_t* __restrict__ a, const uint8_t* __restrict__ a_codes,
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
                 rsa[i] = 0;
                 if (u < BM * 2 && gr < m && kk < k) {
                     ra[i] = *reinterpret_cast<const uint4*>(a_codes + gr * (k / 2) + kk / 2);
-                    rsa[i] = *reinterpret_cast<const uint16_t*>(a_scales + gr * (k / 16) + kk / 16);
+                    rsa[i] = load_scale_pair<GB>(a_scales + gr * (k >> acfg.lb), kk, acfg.lb);
                 }
             }
         } else {
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
             rsb[i] = 0;
             if (u < BN * 2 && gr < n && kk < k) {
                 rb[i] = *reinterpret_cast<const uint4*>(w_codes + gr * (k / 2) + kk / 2);
-                rsb[i] = *reinterpret_cast<const uint16_t*>(w_scales + gr * (k / 16) + kk / 16);
+                rsb[i] = load_scale_pair<GB>(w_scales + gr * (k >> wcfg.lb), kk, wcfg.lb);
             }
         }
     };
@@ -263,7 +263,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
 // One barrier ends every slot.  Tile i+1 is complete at the end of slot 2i+1 and is first read in
 // slot 2i+2; the stage it overwrites was last read in slot 2i-1.  Global loads for a group's half of
 // tile i+2 are issued right after it stored tile i+1 and land during its next MFMA slot.
-template <int BM, int BN, int WGM, int WGN, bool AQ>
+template <int BM, int BN, int WGM, int WGN, bool AQ, bool GB>
 __global__ __launch_bounds__(512) void gemm_pp_kernel(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     SvConfig wcfg, int64_t n, int64_t k, const uint16_t* __restrict__ a, const uint8_t* __restrict__ a_codes,
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
                 pf.rsa[i] = 0;
                 if (gr < m && kk < k) {
                     pf.rqa[i] = *reinterpret_cast<const uint2*>(a_codes + gr * (k / 2) + kk / 2);
-                    pf.rsa[i] = a_scales[gr * (k / 16) + kk / 16];
+                    pf.rsa[i] = a_scales[gr * (k >> acfg.lb) + (kk >> acfg.lb)];
                 }
             }
         } else {
@@ -349,12 +349,12 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
             if (gr < n && kk < k) {
                 if (UB == 2) {
                     pf.rb[i] = *reinterpret_cast<const uint4*>(w_codes + gr * (k / 2) + kk / 2);
-                    pf.rsb[i] = *reinterpret_cast<const uint16_t*>(w_scales + gr * (k / 16) + kk / 16);
+                    pf.rsb[i] = load_scale_pair<GB>(w_scales + gr * (k >> wcfg.lb), kk, wcfg.lb);
                 } else {
                     const uint2 t2 = *reinterpret_cast<const uint2*>(w_codes + gr * (k / 2) + kk / 2);
                     pf.rb[i].x = t2.x;
                     pf.rb[i].y = t2.y;
-                    pf.rsb[i] = w_scales[gr * (k / 16) + kk / 16];
+                    pf.rsb[i] = w_scales[gr * (k >> wcfg.lb) + (kk >> wcfg.lb)];
                 }
             }
         }
@@ -738,7 +738,7 @@ static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, con
     return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AQ, bool PP = false>
+template <int BM, int BN, int WGM, int WGN, bool AQ, bool PP = false, bool GB = false>
 static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                              int64_t n, int64_t k, const uint16_t* a, const uint8_t* a_codes,
                              const uint8_t* a_scales, const float* a_ts, SvConfig acfg, int64_t m, uint16_t* y,
@@ -747,8 +747,8 @@ static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, co
     constexpr size_t smem = 2 * (BM + BN) * 128 + 2 * 256 * sizeof(uint2);
     void (*kern)(const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, int64_t, const uint16_t*,
                  const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, uint16_t*, int64_t, int);
-    if constexpr (PP) kern = gemm_pp_kernel<BM, BN, WGM, WGN, AQ>;
-    else kern = gemm_kernel<BM, BN, WGM, WGN, AQ>;
+    if constexpr (PP) kern = gemm_pp_kernel<BM, BN, WGM, WGN, AQ, GB>;
+    else kern = gemm_kernel<BM, BN, WGM, WGN, AQ, GB>;
     static bool attr_set = false;                      // one GPU per process
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -762,14 +762,14 @@ static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, co
     return hipGetLastError();
 }
 
-template <bool AQ>
+template <bool AQ, bool GB>
 static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                                 int64_t n, int64_t k, const uint16_t* a, const uint8_t* a_codes,
                                 const uint8_t* a_scales, const float* a_ts, SvConfig acfg, int64_t m, uint16_t* y,
                                 int64_t ld_y, hipStream_t st)
 {
 #define RAZER_GEMM(BM, BN, WGM, WGN) \
-    launch_cfg<BM, BN, WGM, WGN, AQ>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st)
+    launch_cfg<BM, BN, WGM, WGN, AQ, false, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st)
     if (m <= 32) return RAZER_GEMM(32, 256, 1, 4);
     if (m <= 64) return RAZER_GEMM(64, 256, 1, 4);
     if (m <= 128) return RAZER_GEMM(128, 128, 2, 2);
@@ -777,7 +777,7 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
     // weight-tile width that wastes fewer of the 256 compute units in the last round of workgroups.
     const int64_t tm = (m + 255) / 256;
     const int64_t t256 = tm * ((n + 255) / 256), t128 = tm * ((n + 127) / 128);
-    if constexpr (!AQ) {
+    if constexpr (!AQ && !GB) {
         // Enough tiles for two resident waves per SIMD: the kernel that decodes weights in registers
         // (measured 5-28 % faster than the LDS-staged one on the 7B projection shapes from M = 2048).
         if (t256 >= 1024) return launch_rb<8, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
@@ -785,7 +785,7 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
     }
     auto eff = [](int64_t tiles) { return (double)tiles / (double)(((tiles + 255) / 256) * 256); };
 #define RAZER_GEMM_PP(BM, BN, WGM, WGN) \
-    launch_cfg<BM, BN, WGM, WGN, AQ, true>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st)
+    launch_cfg<BM, BN, WGM, WGN, AQ, true, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st)
     if (eff(t256) >= eff(t128)) return RAZER_GEMM_PP(256, 256, 2, 4);
     return RAZER_GEMM_PP(256, 128, 4, 2);
 #undef RAZER_GEMM_PP
@@ -798,9 +798,12 @@ hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_s
                        hipStream_t st)
 {
     if (n == 0 || m == 0) return hipSuccess;
-    if (a_codes)
-        return launch_gemm_t<true>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st);
-    return launch_gemm_t<false>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st);
+    // blocks of 32, 64, 128 (either operand) take the variants whose scale-byte loads index by block
+    const bool generic = wcfg.lb != 4 || (a_codes && acfg.lb != 4);
+#define RAZER_GEMM_ARGS w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st
+    if (a_codes) return generic ? launch_gemm_t<true, true>(RAZER_GEMM_ARGS) : launch_gemm_t<true, false>(RAZER_GEMM_ARGS);
+    return generic ? launch_gemm_t<false, true>(RAZER_GEMM_ARGS) : launch_gemm_t<false, false>(RAZER_GEMM_ARGS);
+#undef RAZER_GEMM_ARGS
 }
 
 }  // namespace razer

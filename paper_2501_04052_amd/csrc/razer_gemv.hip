@@ -57,16 +57,16 @@ struct RowGroup {
     uint32_t sw[R];
 };
 
-template <int R>
+template <int R, bool GB>
 __device__ __forceinline__ void load_group(RowGroup<R>& g, const uint8_t* __restrict__ codes,
                                            const uint8_t* __restrict__ scales, int64_t row0, int64_t n,
-                                           int64_t k, int64_t c)
+                                           int64_t k, int64_t c, int lb)
 {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int64_t row = (row0 + r < n) ? row0 + r : n - 1;           // clamp: tail rows re-read the last row
         g.cw[r] = *reinterpret_cast<const uint4*>(codes + row * (k / 2) + c * 16);
-        g.sw[r] = *reinterpret_cast<const uint16_t*>(scales + row * (k / 16) + c * 2);
+        g.sw[r] = load_scale_pair<GB>(scales + row * (k >> lb), c * 32, lb);
     }
 }
 
@@ -114,11 +114,11 @@ __device__ __forceinline__ void dot_group(const RowGroup<R>& g, const uint4 (&av
 // over the 64 lanes and the slice totals parked in LDS; after one barrier the first threads add
 // the slices and write bf16.  The grid is one workgroup per R rows: for the matrices of a decoder
 // layer the whole problem is in flight at once, which is what hides the HBM latency.
-template <int M, int R>
+template <int M, int R, bool GB = false>
 __device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                           const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
                                           int64_t k, const uint16_t* __restrict__ a, uint16_t* __restrict__ y,
-                                          int64_t ld_y, int64_t row0)
+                                          int64_t ld_y, int64_t row0, int lb = 4)
 {
     __shared__ uint2 lut[256];
     __shared__ float part[kMaxWaves][R][M];
@@ -144,7 +144,7 @@ __device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, con
                 av[m][j] = make_uint4(t.x & amask, t.y & amask, t.z & amask, t.w & amask);
             }
         }
-        load_group<R>(grp, codes, scales, row0, n, k, cc);
+        load_group<R, GB>(grp, codes, scales, row0, n, k, cc, lb);
     };
     issue_loads();
     fill_weight_lut(lut, sv0, sv1);
@@ -192,12 +192,12 @@ __device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, con
 // are always in flight while one is decoded.  Wave w owns K-slice w of every row; its 32
 // activations per lane stay in registers for the whole walk.  Slice totals of all G * R rows meet
 // in LDS after ONE barrier.  Row addresses are uniform (scalar) and lane offsets 32-bit.
-template <int M, int R, int G, int D, int P = 1>
+template <int M, int R, int G, int D, int P = 1, bool GB = false>
 __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ codes,
                                                  const uint8_t* __restrict__ scales,
                                                  const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
                                                  int64_t k, const uint16_t* __restrict__ a,
-                                                 uint16_t* __restrict__ y, int64_t ld_y, int64_t row0)
+                                                 uint16_t* __restrict__ y, int64_t ld_y, int64_t row0, int lb = 4)
 {
     static_assert(D >= 2 && D <= 3, "buffer count");
     __shared__ uint2 lut[256];
@@ -212,7 +212,7 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     const bool active = c < chunks;
     const uint32_t cc = active ? c : 0u;                                  // idle lanes read chunk 0, weight 0
     const uint32_t amask = active ? 0xFFFFFFFFu : 0u;
-    const int64_t code_ld = k >> 1, scale_ld = k >> 4;
+    const int64_t code_ld = k >> 1, scale_ld = k >> lb;
 
     uint4 av[M][4];
 #pragma unroll
@@ -233,7 +233,7 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
             const uint8_t* crow = codes + row * code_ld;
             const uint8_t* srow = scales + row * scale_ld;
             g.cw[r] = *reinterpret_cast<const uint4*>(crow + cc * 16u);
-            g.sw[r] = *reinterpret_cast<const uint16_t*>(srow + cc * 2u);
+            g.sw[r] = load_scale_pair<GB>(srow, (int64_t)cc * 32, lb);
         }
     };
 #pragma unroll
@@ -266,26 +266,27 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     }
 }
 
-template <int M, int R, int G, int D, int P = 1>
+template <int M, int R, int G, int D, int P = 1, bool GB = false>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_kernel(const uint8_t* __restrict__ codes,
                                                                      const uint8_t* __restrict__ scales,
                                                                      const float* __restrict__ w_ts, float sv0,
                                                                      float sv1, int64_t n, int64_t k,
                                                                      const uint16_t* __restrict__ a,
-                                                                     uint16_t* __restrict__ y, int64_t ld_y)
+                                                                     uint16_t* __restrict__ y, int64_t ld_y, int lb)
 {
-    gemv_stream_body<M, R, G, D, P>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y, (int64_t)blockIdx.x * (P * R * G));
+    gemv_stream_body<M, R, G, D, P, GB>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y,
+                                        (int64_t)blockIdx.x * (P * R * G), lb);
 }
 
-template <int M, int R>
+template <int M, int R, bool GB = false>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __restrict__ codes,
                                                               const uint8_t* __restrict__ scales,
                                                               const float* __restrict__ w_ts, float sv0, float sv1,
                                                               int64_t n, int64_t k,
                                                               const uint16_t* __restrict__ a,
-                                                              uint16_t* __restrict__ y, int64_t ld_y)
+                                                              uint16_t* __restrict__ y, int64_t ld_y, int lb)
 {
-    gemv_body<M, R>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y, (int64_t)blockIdx.x * R);
+    gemv_body<M, R, GB>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y, (int64_t)blockIdx.x * R, lb);
 }
 
 // Up to four weight matrices that share K, the activation rows and the special values, in one
@@ -358,7 +359,8 @@ static hipError_t launch_gemv_mr(SvConfig cfg, const uint8_t* codes, const uint8
     const int64_t nslices = (k + kSliceK - 1) / kSliceK;
     const int nwaves = (int)(nslices < kMaxWaves ? nslices : kMaxWaves);
     const unsigned grid = (unsigned)((n + R - 1) / R);
-    gemv_kernel<M, R><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y);
+    if (cfg.lb == 4) gemv_kernel<M, R, false><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, 4);
+    else gemv_kernel<M, R, true><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, cfg.lb);
     return hipGetLastError();
 }
 template <int M>
@@ -370,17 +372,21 @@ static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_
         return launch_gemv_mr<M, 4>(cfg, codes, scales, ts, n, k, a, y, ld_y, st);
     constexpr int R = kStreamR;
     const int nwaves = (int)nslices;
-    const int groups = stream_groups(nwaves, M), sets = stream_sets(nwaves, groups);
+    const int groups = stream_groups(nwaves, M);
+    const int sets = cfg.lb == 4 ? stream_sets(nwaves, groups) : 1;      // blocks of 32..128: the single-set kernels
     const unsigned grid = (unsigned)((n + sets * R * groups - 1) / (sets * R * groups));
-    if (groups == 8)
-        gemv_stream_kernel<M, R, 8, 2, 1><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a,
-                                                                        y, ld_y);
-    else if (sets == 2)
-        gemv_stream_kernel<M, R, 2, 2, 2><<<grid, 128 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a,
-                                                                         y, ld_y);
-    else
-        gemv_stream_kernel<M, R, 2, 2, 1><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a,
-                                                                        y, ld_y);
+#define RAZER_GEMV_ARGS codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, cfg.lb
+    if (cfg.lb != 4) {
+        if (groups == 8) gemv_stream_kernel<M, R, 8, 2, 1, true><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
+        else gemv_stream_kernel<M, R, 2, 2, 1, true><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
+    } else if (groups == 8) {
+        gemv_stream_kernel<M, R, 8, 2, 1><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
+    } else if (sets == 2) {
+        gemv_stream_kernel<M, R, 2, 2, 2><<<grid, 128 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
+    } else {
+        gemv_stream_kernel<M, R, 2, 2, 1><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
+    }
+#undef RAZER_GEMV_ARGS
     return hipGetLastError();
 }
 

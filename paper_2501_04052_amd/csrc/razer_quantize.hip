@@ -3,8 +3,10 @@
 //
 // Bit-exactness contract: every fp32 operation below is a single IEEE operation
 // (true division, no reciprocal, no contraction), squared errors are summed in
-// fp64 over the 16 elements in index order, and ties are broken as documented
-// in razer.h.  Compile without fast-math.
+// fp64 over the 16 elements in index order (for blocks of 32, 64, 128 -- the
+// block-size study of Sec. 5.4 -- over each run of 16 in index order, the runs'
+// sums then added in run order), and ties are broken as documented in razer.h.
+// Compile without fast-math.
 #include "razer_device.hpp"
 #include "razer_kernels.hpp"
 
@@ -77,8 +79,10 @@ __device__ __forceinline__ uint32_t round_scale(float t)
 }
 
 // ---------------------------------------------------------------- block encoder
-// One thread encodes one block of 16 elements.
-template <typename T, int FMT>
+// One thread encodes one run of 16 elements; G = block / 16 consecutive lanes share a block: they
+// agree on the block maximum (hence on the scale) and on the special value by exchanging their
+// run's maximum and squared-error sums within the wavefront.
+template <typename T, int FMT, int G>
 __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
                                                      int64_t ld, SvConfig cfg,
                                                      const uint32_t* __restrict__ absmax_ws,
@@ -127,6 +131,8 @@ __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, in
     float bmax = 0.0f;
 #pragma unroll
     for (int k = 0; k < kBlock; ++k) bmax = fmaxf(bmax, fabsf(xv[k]));
+#pragma unroll
+    for (int off = 1; off < G; off <<= 1) bmax = fmaxf(bmax, __shfl_xor(bmax, off));   // the block's maximum
 
     // Eq. 2
     const float d = delta32 * 6.0f;
@@ -166,6 +172,17 @@ __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, in
                 take[m] |= (uint32_t)sp << k;
             }
         }
+        if (G > 1) {
+            // block error = run sums added in run order; every lane of the block forms the same sum
+            const int base = (int)(threadIdx.x & 63u) & ~(G - 1);
+#pragma unroll
+            for (int m = 0; m < NC; ++m) {
+                double tot = __shfl(sse[m], base);
+#pragma unroll
+                for (int c = 1; c < G; ++c) tot += __shfl(sse[m], base + c);
+                sse[m] = tot;
+            }
+        }
         // Eq. 4: smallest error, ties to the smallest metadata index
         double best = sse[0];
 #pragma unroll
@@ -182,10 +199,25 @@ __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, in
         }
     }
     *reinterpret_cast<uint2*>(codes + r * (cols / 2) + b * 8) = make_uint2(lo, hi);
-    scales[r * nb + b] = (uint8_t)((meta << (FMT == 0 ? 6 : 7)) | sc);
+    if ((b & (G - 1)) == 0) scales[r * (nb / G) + b / G] = (uint8_t)((meta << (FMT == 0 ? 6 : 7)) | sc);
 }
 
 // ---------------------------------------------------------------- host launchers
+template <typename T, int FMT>
+static void launch_encode(int lb, unsigned grid, unsigned threads, hipStream_t st, const T* x, int64_t rows,
+                          int64_t cols, int64_t ld, SvConfig cfg, const uint32_t* ws, float* tensor_scale, int given,
+                          uint8_t* codes, uint8_t* scales)
+{
+#define RAZER_ENC(G) encode_kernel<T, FMT, G><<<grid, threads, 0, st>>>(x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales)
+    switch (lb) {
+        case 4: RAZER_ENC(1); break;
+        case 5: RAZER_ENC(2); break;
+        case 6: RAZER_ENC(4); break;
+        default: RAZER_ENC(8); break;
+    }
+#undef RAZER_ENC
+}
+
 template <typename T>
 static hipError_t launch_quantize_t(int fmt, SvConfig cfg, const T* x, int64_t rows, int64_t cols, int64_t ld,
                                     uint8_t* codes, uint8_t* scales, float* tensor_scale, int given,
@@ -194,8 +226,8 @@ static hipError_t launch_quantize_t(int fmt, SvConfig cfg, const T* x, int64_t r
     if (rows == 0 || cols == 0) {
         if (!given) {                       // an empty tensor gets the all-zero tensor's scale of 1
             absmax_init_kernel<<<1, 1, 0, st>>>(ws);
-            if (fmt == 0) encode_kernel<T, 0><<<1, 64, 0, st>>>(x, 0, 16, 16, cfg, ws, tensor_scale, 0, codes, scales);
-            else encode_kernel<T, 1><<<1, 64, 0, st>>>(x, 0, 16, 16, cfg, ws, tensor_scale, 0, codes, scales);
+            if (fmt == 0) launch_encode<T, 0>(4, 1, 64, st, x, 0, 16, 16, cfg, ws, tensor_scale, 0, codes, scales);
+            else launch_encode<T, 1>(4, 1, 64, st, x, 0, 16, 16, cfg, ws, tensor_scale, 0, codes, scales);
         }
         return hipGetLastError();
     }
@@ -209,10 +241,8 @@ static hipError_t launch_quantize_t(int fmt, SvConfig cfg, const T* x, int64_t r
     }
     int64_t nblk = rows * (cols / kBlock);
     unsigned grid = (unsigned)((nblk + 255) / 256);
-    if (fmt == 0)
-        encode_kernel<T, 0><<<grid, 256, 0, st>>>(x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
-    else
-        encode_kernel<T, 1><<<grid, 256, 0, st>>>(x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
+    if (fmt == 0) launch_encode<T, 0>(cfg.lb, grid, 256, st, x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
+    else launch_encode<T, 1>(cfg.lb, grid, 256, st, x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
     return hipGetLastError();
 }
 

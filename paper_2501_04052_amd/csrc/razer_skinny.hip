@@ -37,13 +37,13 @@ __device__ __forceinline__ v8bf sk_decode_dword(uint32_t x, uint2 le)
 constexpr int kSkRows = 64;            // weight rows per workgroup (4 waves x 16)
 
 // NB: activation fragments of 16 rows (M <= 16 NB); STEPS: 128-k steps per workgroup (KC = 128 STEPS).
-template <int NB, int STEPS>
+template <int NB, int STEPS, bool GB>
 __global__ __launch_bounds__(256) void skinny_kernel(const uint8_t* __restrict__ codes,
                                                      const uint8_t* __restrict__ scales,
                                                      const float* __restrict__ w_ts, float sv0, float sv1,
                                                      int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
                                                      uint16_t* __restrict__ y, int64_t ld_y,
-                                                     float* __restrict__ partial, int nslices)
+                                                     float* __restrict__ partial, int nslices, int lb)
 {
     constexpr int KC = 128 * STEPS;
     constexpr int ROWB = KC * 2;                                   // bytes per activation row in LDS
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void skinny_kernel(const uint8_t* __restrict__
         const bool in = kk < k;
         const int64_t kc = in ? kk : 0;
         const uint4 c = *reinterpret_cast<const uint4*>(codes + wrow * (k / 2) + kc / 2);
-        const uint32_t sc = *reinterpret_cast<const uint16_t*>(scales + wrow * (k / 16) + kc / 16);
+        const uint32_t sc = load_scale_pair<GB>(scales + wrow * (k >> lb), kc, lb);
         const uint32_t msk = in ? 0xFFFFFFFFu : 0u;               // beyond K: code 0, scale 0 -> weight 0
         cw[s] = make_uint4(c.x & msk, c.y & msk, c.z & msk, c.w & msk);
         sw[s] = sc & msk;
@@ -165,9 +165,14 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
     const int64_t kc = 128 * steps;
     const int nslices = (int)((k + kc - 1) / kc);
     const unsigned grid = (unsigned)(((n + kSkRows - 1) / kSkRows) * nslices);
-#define RAZER_SK(NB, ST) skinny_kernel<NB, ST><<<grid, 256, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, workspace, nslices)
-    if (m <= 16) { if (steps == 8) RAZER_SK(1, 8); else RAZER_SK(1, 4); }
-    else RAZER_SK(2, 4);
+#define RAZER_SK(NB, ST, GB) skinny_kernel<NB, ST, GB><<<grid, 256, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, workspace, nslices, cfg.lb)
+    if (cfg.lb == 4) {
+        if (m <= 16) { if (steps == 8) RAZER_SK(1, 8, false); else RAZER_SK(1, 4, false); }
+        else RAZER_SK(2, 4, false);
+    } else {                                                            // blocks of 32, 64, 128
+        if (m <= 16) { if (steps == 8) RAZER_SK(1, 8, true); else RAZER_SK(1, 4, true); }
+        else RAZER_SK(2, 4, true);
+    }
 #undef RAZER_SK
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nslices == 1) return e;

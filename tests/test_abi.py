@@ -67,6 +67,10 @@ def test_bad_arguments_return_status_codes_without_gpu(razer):
         assert q(cfg=ctypes.byref(c2)) == 4
     c3 = _Config(); c3.format = 3; c3.sv[0] = 5.0; c3.sv[1] = 8.0
     assert q(cfg=ctypes.byref(c3)) == 4
+    # block sizes: 0 (= 16), 16, 32, 64, 128 only; cols must hold whole blocks
+    for blk, cols, want in ((48, 96, 4), (8, 64, 4), (256, 256, 4), (-16, 64, 4), (64, 96, 2), (128, 64, 2)):
+        c4 = _Config(); c4.format = 0; c4.sv[0] = 5.0; c4.sv[1] = 8.0; c4.block = blk
+        assert q(cfg=ctypes.byref(c4), cols=cols, ld=cols) == want, (blk, cols)
 
     t = _Tensor(); t.codes = 0x1000; t.scales = 0x2000; t.tensor_scale = 0x3000
     t.rows = 8; t.cols = 64; t.cfg = cfg
@@ -75,6 +79,11 @@ def test_bad_arguments_return_status_codes_without_gpu(razer):
     assert L.razer_dequant(ctypes.byref(t), fake, 0, 32, None) == 2
     assert L.razer_dequant(ctypes.byref(t), odd, 0, 64, None) == 3
     assert L.razer_dequant(ctypes.byref(t), fake, 5, 64, None) == 4
+    cb = _Config(); cb.format = 0; cb.sv[0] = 5.0; cb.sv[1] = 8.0; cb.block = 128
+    t128 = _Tensor(); t128.codes = 0x1000; t128.scales = 0x2000; t128.tensor_scale = 0x3000
+    t128.rows = 8; t128.cols = 64; t128.cfg = cb                  # 64 columns cannot hold a block of 128
+    assert L.razer_dequant(ctypes.byref(t128), fake, 0, 64, None) == 2
+    assert L.razer_linear(ctypes.byref(t128), fake, None, 1, fake, 8, None, 0, None) == 2
     # linear: both or neither activation operand, wrong formats, shape mismatches
     assert L.razer_linear(ctypes.byref(t), None, None, 1, fake, 8, None, 0, None) == 1
     assert L.razer_linear(ctypes.byref(t), None, None, 0, None, 8, None, 0, None) == 0

@@ -258,3 +258,91 @@ def test_linear_grouped_matches_oracle(oracle, m, k):
     ys = razer.razer_linear_grouped(wts, a_dev)
     assert max_rel_err(dev_to_bf16_bits(ys[1]), oracle.linear(wq2, a_bf16=a, w_sv=(5.0, 7.0))[0]) <= TOL
     assert max_rel_err(dev_to_bf16_bits(ys[0]), oracle.linear(wqs[0], a_bf16=a)[0]) <= TOL
+
+
+# ------------------------------------------------------------------ block sizes 32, 64, 128 (Sec. 5.4)
+BLOCKS = [32, 64, 128]
+
+
+def _rand_tensor_b(rng, fmt, rows, cols, block):
+    codes = rng.integers(0, 256, size=(rows, cols // 2), dtype=np.uint8)
+    scales = rng.integers(0, 256, size=(rows, cols // block), dtype=np.uint8)
+    if fmt == A:
+        scales[(scales & 127) == 127] = 126
+    return codes, scales, np.float32(rng.uniform(1e-4, 1e-2))
+
+
+@pytest.mark.parametrize("block", BLOCKS)
+@pytest.mark.parametrize("fmt,sv", [(W, (5.0, 8.0)), (A, (5.0, 0.0))])
+def test_block_sizes_quantize_and_dequant_bit_exact(oracle, block, fmt, sv):
+    print("block encode/decode", block, fmt, flush=True)
+    for rows, cols, seed in ((37, 3 * 128, 1), (5, 128, 2), (130, 1024 + 128, 3)):
+        if fmt == W:
+            x = synth.weight(rows, cols, seed=900 + seed + block, outlier_frac=0.01)
+            x[0, :block] = 0.0                                          # an all-zero block
+            x[1, block:2 * block] *= np.float32(1e-4)                   # a block whose scale rounds to 0
+        else:
+            x = synth.activation(rows, cols, seed=901 + seed + block, outlier_frac=0.01)
+        x_dev = bf16_bits_to_dev(x) if x.dtype == np.uint16 else torch.from_numpy(x).cuda()
+        t = razer.razer_quantize(x_dev, fmt, sv, block=block)
+        torch.cuda.synchronize()
+        codes, scales, ts = tensor_to_host(t)
+        rc, rs, rts = oracle.quantize(fmt, x, sv=sv, block=block)
+        assert np.float32(ts).view(np.uint32) == np.float32(rts).view(np.uint32)
+        assert scales.shape == rs.shape and np.array_equal(scales, rs), "scale bytes differ"
+        assert np.array_equal(codes, rc), "codes differ"
+        ref = oracle.dequant(fmt, rc, rs, rts, sv=sv, want=("f32", "bf16"))
+        assert np.array_equal(razer.razer_dequant(t, torch.float32).cpu().numpy().view(np.uint32), ref["f32"].view(np.uint32))
+        assert np.array_equal(dev_to_bf16_bits(razer.razer_dequant(t, torch.bfloat16)), ref["bf16"])
+    # random scale bytes (every code, every metadata value) through the decoder
+    rng = np.random.default_rng(77 + block)
+    codes, scales, ts = _rand_tensor_b(rng, fmt, 19, 512, block)
+    t = razer.RazerTensor.from_host(codes, scales, ts, fmt, sv)
+    assert t.block == block
+    ref = oracle.dequant(fmt, codes, scales, ts, sv=sv, want=("f32",))["f32"]
+    assert np.array_equal(razer.razer_dequant(t, torch.float32).cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("block", BLOCKS)
+@pytest.mark.parametrize("m,n,k", [(1, 130, 2048 + 256), (3, 66, 11008), (4, 20, 28672),
+                                   (2, 12, 2048 * 17 + 128), (8, 300, 1024 + 128), (20, 70, 8192 + 512),
+                                   (40, 100, 256), (200, 260, 1152), (300, 513, 1024), (64, 257, 128)])
+def test_block_sizes_linear_matches_oracle(oracle, block, m, n, k):
+    """Every kernel family (GEMV streaming / multi-pass, small batch, tiled GEMM) with 32-, 64- and
+    128-element blocks, random codes and scale bytes."""
+    print("block linear", block, m, n, k, flush=True)
+    rng = np.random.default_rng(1200 + block + m + n)
+    wq = _rand_tensor_b(rng, W, n, k, block)
+    wt = razer.RazerTensor.from_host(*wq, W, (5.0, 8.0))
+    a = synth.activation(m, k, seed=1300 + m, outlier_frac=0.005)
+    y = razer.razer_linear(wt, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    y64, _ = oracle.linear(wq, a_bf16=a)
+    assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
+
+
+@pytest.mark.parametrize("wb,ab", [(32, 16), (16, 64), (64, 64), (128, 32)])
+@pytest.mark.parametrize("m,n,k", [(3, 40, 256), (100, 130, 1152), (300, 260, 512)])
+def test_block_sizes_w4a4_matches_oracle(oracle, wb, ab, m, n, k):
+    print("block w4a4", wb, ab, m, n, k, flush=True)
+    wq = oracle.quantize(W, synth.weight(n, k, seed=1400 + wb, outlier_frac=0.01), block=wb)
+    a_bits = synth.activation(m, k, seed=1401 + ab, outlier_frac=0.01)
+    at = razer.razer_quantize(bf16_bits_to_dev(a_bits), A, (5.0, 0.0), block=ab)
+    aq = tensor_to_host(at)
+    ra = oracle.quantize(A, a_bits, sv=(5.0, 0.0), block=ab)
+    assert np.array_equal(aq[0], ra[0]) and np.array_equal(aq[1], ra[1])
+    wt = razer.RazerTensor.from_host(*wq, W, (5.0, 8.0))
+    y = razer.razer_linear(wt, at)
+    torch.cuda.synchronize()
+    y64, _ = oracle.linear(wq, a_q=ra)
+    assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
+
+
+def test_block_sizes_grouped_falls_back_to_single_launches(oracle):
+    k = 512
+    a = synth.activation(2, k, seed=1500)
+    wqs = [oracle.quantize(W, synth.weight(n, k, seed=1501 + n), block=64) for n in (33, 50)]
+    wts = [razer.RazerTensor.from_host(*wq, W, (5.0, 8.0)) for wq in wqs]
+    ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a))
+    for wq, y in zip(wqs, ys):
+        assert max_rel_err(dev_to_bf16_bits(y), oracle.linear(wq, a_bf16=a)[0]) <= TOL
