@@ -88,7 +88,8 @@ enum { RAZER_OP_QUANTIZE = 0, RAZER_OP_DEQUANT = 1, RAZER_OP_LINEAR = 2 };
 
 /* Bytes of device workspace the given operation needs for these sizes
  * (rows x cols operand; m = activation rows for RAZER_OP_LINEAR, else 0).
- * Never more than a few MiB; 0 means the workspace may be NULL.            */
+ * At most 8 * m * rows floats (problems too small to occupy the GPU split K and
+ * add the slices in a fixed order); 0 means the workspace may be NULL.       */
 size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m);
 
 /* Encoder: Eq. 1 (tensor scale), Eq. 2 (block scale, round-to-nearest-even on
@@ -126,8 +127,8 @@ razer_status razer_dequant(const razer_tensor *t, void *out, int32_t dtype, int6
  * m, wavefront dot products for m <= 4, a decode-once MFMA kernel in between), scaled by the
  * tensor scale(s) and rounded to bf16:  y_bf16 device [m][ld_y], ld_y >= N.
  * workspace: device, 16-byte aligned, >= razer_workspace_bytes(RAZER_OP_LINEAR, N, K, m) bytes
- * (non-zero only for W4A16 with 5 <= m <= 32, where K-slices meet in fp32; else may be NULL);
- * too small -> RAZER_ERR_WORKSPACE. */
+ * (non-zero where K is split over workgroups and the slices meet in fp32: W4A16 with 5 <= m <= 32,
+ * and m > 32 with fewer than 128 output tiles; else may be NULL); too small -> RAZER_ERR_WORKSPACE. */
 razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer_tensor *a_q,
                           int64_t m, void *y_bf16, int64_t ld_y,
                           void *workspace, size_t workspace_bytes, void *hip_stream);

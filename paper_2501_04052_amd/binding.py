@@ -195,7 +195,7 @@ def razer_linear(w, a, out=None, workspace=None):
         out = torch.empty((m, w.rows), dtype=torch.bfloat16, device=dev)
     ws = w.c_struct()
     ld_y = out.stride(0) if m > 1 else max(out.stride(0), w.rows)
-    if workspace is None and a_ptr is not None:
+    if workspace is None:
         need = razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m)
         if need:
             workspace = torch.empty(need, dtype=torch.uint8, device=dev)

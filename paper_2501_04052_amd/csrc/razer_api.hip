@@ -83,7 +83,10 @@ size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m)
 {
     switch (op) {
         case RAZER_OP_QUANTIZE: return 256;    // the absmax cell of Eq. 1
-        case RAZER_OP_LINEAR: return skinny_workspace_bytes(rows, cols, m);   // K-slice partial sums, 5 <= m <= 32
+        case RAZER_OP_LINEAR: {                // fp32 partial sums of K-slices (small batch; GEMMs with few tiles)
+            const size_t a = skinny_workspace_bytes(rows, cols, m), b = gemm_workspace_bytes(rows, cols, m);
+            return a > b ? a : b;
+        }
         default: return 0;
     }
 }
@@ -167,9 +170,12 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
         e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
                         (uint16_t*)y_bf16, ld_y, st);
     } else {
+        const size_t need = gemm_workspace_bytes(n, k, m);
+        if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return RAZER_ERR_WORKSPACE;
         e = launch_gemm(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, asv,
                         a_q ? a_q->codes : nullptr, a_q ? a_q->scales : nullptr,
-                        a_q ? a_q->tensor_scale : nullptr, m, (uint16_t*)y_bf16, ld_y, st);
+                        a_q ? a_q->tensor_scale : nullptr, m, (uint16_t*)y_bf16, ld_y,
+                        need > 0 ? (float*)workspace : nullptr, st);
     }
     return e == hipSuccess ? RAZER_OK : RAZER_ERR_HIP;
 }

@@ -104,12 +104,42 @@ __device__ __forceinline__ void store_tile(const v16f (&acc)[TN][TM], const floa
         }
 }
 
+// Split-K epilogue: the raw fp32 accumulators of one K-slice go to partial[m][n] (dense, ld = n);
+// a second kernel adds the slices in order and applies the tensor scale(s).  Same lane layout as
+// store_tile: lane l holds row l % 32 and, per group g of 4 registers, columns 8 g + 4 (l / 32) + 0..3.
+template <int TM, int TN>
+__device__ __forceinline__ void store_tile_partial(const v16f (&acc)[TN][TM], int64_t wm0, int64_t wn0, int64_t m,
+                                                   int64_t n, float* __restrict__ partial, int lane)
+{
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int64_t gm = wm0 + j * 32 + (lane & 31);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int64_t gn = wn0 + i * 32 + 8 * g + 4 * (lane >> 5);
+                if (gm < m && gn < n) {
+                    float* dst = partial + gm * n + gn;
+                    if (gn + 3 < n && ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0)) {
+                        *reinterpret_cast<float4*>(dst) = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1],
+                                                                      acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (gn + e < n) dst[e] = acc[i][j][4 * g + e];
+                    }
+                }
+            }
+        }
+}
+
 template <int BM, int BN, int WGM, int WGN, bool AQ, bool GB>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     SvConfig wcfg, int64_t n, int64_t k, const uint16_t* __restrict__ a, const uint8_t* __restrict__ a_codes,
     const uint8_t* __restrict__ a_scales, const float* __restrict__ a_ts, SvConfig acfg, int64_t m,
-    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m)
+    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m, float* __restrict__ partial)
 {
     constexpr int NT = 64 * WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
@@ -128,7 +158,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
     const int wm = wave % WGM, wn = wave / WGM;
     const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    const int KT = (int)((k + kBK - 1) / kBK);
+    // blockIdx.y = K-slice (split-K for problems with few output tiles): K-tiles [kt0, kt0 + KT)
+    const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int kt0 = (int)blockIdx.y * kt_per;
+    const int KT = kt_all - kt0 < kt_per ? kt_all - kt0 : kt_per;
 
     fill_scaled_lut<0>(wlut, wcfg.sv0, wcfg.sv1, tid, NT);
     if (AQ) fill_scaled_lut<1>(alut, acfg.sv0, acfg.sv1, tid, NT);
@@ -147,7 +180,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
     uint32_t rsb[NU_B];
 
     auto load_tiles = [&](int kt) {
-        const int64_t kbase = (int64_t)kt * kBK;
+        const int64_t kbase = (int64_t)(kt0 + kt) * kBK;
         if (AQ) {
 #pragma unroll
             for (int i = 0; i < NU_A; ++i) {
@@ -247,7 +280,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
         __syncthreads();
     }
 
-    store_tile<TM, TN, AQ>(acc, w_ts, a_ts, m0 + wm * WTM, n0 + wn * WTN, m, n, y, ld_y, lane);
+    if (partial)
+        store_tile_partial<TM, TN>(acc, m0 + wm * WTM, n0 + wn * WTN, m, n, partial + (int64_t)blockIdx.y * m * n, lane);
+    else
+        store_tile<TM, TN, AQ>(acc, w_ts, a_ts, m0 + wm * WTM, n0 + wn * WTN, m, n, y, ld_y, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -268,7 +304,7 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     SvConfig wcfg, int64_t n, int64_t k, const uint16_t* __restrict__ a, const uint8_t* __restrict__ a_codes,
     const uint8_t* __restrict__ a_scales, const float* __restrict__ a_ts, SvConfig acfg, int64_t m,
-    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m)
+    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m, float* __restrict__ partial)
 {
     static_assert(WGM * WGN == 8, "two groups of four waves");
     constexpr int GT = 256;                                            // threads per group
@@ -293,7 +329,9 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
     const int wm = wave % WGM, wn = wave / WGM;
     const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    const int KT = (int)((k + kBK - 1) / kBK);
+    const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int kt0 = (int)blockIdx.y * kt_per;                          // K-slice of this workgroup (split-K)
+    const int KT = kt_all - kt0 < kt_per ? kt_all - kt0 : kt_per;
 
     fill_scaled_lut<0>(wlut, wcfg.sv0, wcfg.sv1, tid, 512);
     if (AQ) fill_scaled_lut<1>(alut, acfg.sv0, acfg.sv1, tid, 512);
@@ -318,7 +356,7 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
     Prefetch pf0, pf1;
 
     auto gload = [&](Prefetch& pf, int kt) {
-        const int64_t kbase = (int64_t)kt * kBK;
+        const int64_t kbase = (int64_t)(kt0 + kt) * kBK;
         if (AQ) {
 #pragma unroll
             for (int i = 0; i < A_PT; ++i) {
@@ -463,7 +501,10 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
             __syncthreads();
         }
     }
-    store_tile<TM, TN, AQ>(acc, w_ts, a_ts, m0 + wm * WTM, n0 + wn * WTN, m, n, y, ld_y, lane);
+    if (partial)
+        store_tile_partial<TM, TN>(acc, m0 + wm * WTM, n0 + wn * WTN, m, n, partial + (int64_t)blockIdx.y * m * n, lane);
+    else
+        store_tile<TM, TN, AQ>(acc, w_ts, a_ts, m0 + wm * WTM, n0 + wn * WTN, m, n, y, ld_y, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -742,11 +783,11 @@ template <int BM, int BN, int WGM, int WGN, bool AQ, bool PP = false, bool GB = 
 static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                              int64_t n, int64_t k, const uint16_t* a, const uint8_t* a_codes,
                              const uint8_t* a_scales, const float* a_ts, SvConfig acfg, int64_t m, uint16_t* y,
-                             int64_t ld_y, hipStream_t st)
+                             int64_t ld_y, int split, float* workspace, hipStream_t st)
 {
     constexpr size_t smem = 2 * (BM + BN) * 128 + 2 * 256 * sizeof(uint2);
     void (*kern)(const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, int64_t, const uint16_t*,
-                 const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, uint16_t*, int64_t, int);
+                 const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, uint16_t*, int64_t, int, float*);
     if constexpr (PP) kern = gemm_pp_kernel<BM, BN, WGM, WGN, AQ, GB>;
     else kern = gemm_kernel<BM, BN, WGM, WGN, AQ, GB>;
     static bool attr_set = false;                      // one GPU per process
@@ -757,50 +798,99 @@ static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, co
         attr_set = true;
     }
     const int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
-    kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WGM * WGN), smem, st>>>(
-        w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, tiles_m);
-    return hipGetLastError();
+    // every K-slice must hold at least one K-tile: slices = ceil(KT / ceil(KT / split))
+    const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + split - 1) / split;
+    const int slices = (kt_all + kt_per - 1) / kt_per;
+    kern<<<dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(64 * WGM * WGN), smem, st>>>(
+        w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, tiles_m,
+        slices > 1 ? workspace : nullptr);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || slices == 1) return e;
+    return launch_slice_reduce(workspace, w_ts, AQ ? a_ts : nullptr, m, n, slices, y, ld_y, st);
+}
+
+// Which kernel and how many K-slices.  Tiles: 0 = 32x256, 1 = 64x256, 2 = 128x128 (one stage pair, all
+// waves alike), 3 = 256x256 and 4 = 256x128 (two wave groups out of phase), 5 / 6 = register-decode
+// kernel with 256x256 / 256x128 tiles.  A K-tile costs about 1 us of latency however small the tile, so
+// when the output tiles cannot occupy the 256 compute units K is split until they do (at most 8 ways,
+// at least 8 K-tiles per slice); the slices meet in the workspace.
+struct GemmPlan {
+    int tile;
+    int split;
+};
+static GemmPlan gemm_plan(int64_t m, int64_t n, int64_t k, bool register_decode_ok)
+{
+    GemmPlan p{0, 1};
+    int64_t tiles;
+    if (m <= 32) { p.tile = 0; tiles = (n + 255) / 256; }
+    else if (m <= 64) { p.tile = 1; tiles = (n + 255) / 256; }
+    else if (m <= 128) { p.tile = 2; tiles = ((m + 127) / 128) * ((n + 127) / 128); }
+    else {
+        // 256-row activation tiles so every weight is decoded once per 256 rows
+        const int64_t tm = (m + 255) / 256;
+        const int64_t t256 = tm * ((n + 255) / 256), t128 = tm * ((n + 127) / 128);
+        // enough tiles for two resident waves per SIMD: the kernel that decodes weights in registers
+        // (measured 5-28 % faster than the LDS-staged one on the 7B projection shapes from M = 2048)
+        if (register_decode_ok && t256 >= 1024) return GemmPlan{5, 1};
+        if (register_decode_ok && t128 >= 512) return GemmPlan{6, 1};
+        // else the weight-tile width that wastes fewer compute units in the last round of workgroups
+        auto eff = [](int64_t t) { return (double)t / (double)(((t + 255) / 256) * 256); };
+        if (eff(t256) >= eff(t128)) { p.tile = 3; tiles = t256; }
+        else { p.tile = 4; tiles = t128; }
+    }
+    const int64_t kt_all = (k + kBK - 1) / kBK;
+    int64_t split = 256 / tiles;
+    if (split > 8) split = 8;
+    if (split > kt_all / 8) split = kt_all / 8;
+    p.split = split >= 2 ? (int)split : 1;
+    return p;
+}
+
+size_t gemm_workspace_bytes(int64_t n, int64_t k, int64_t m)
+{
+    if (m <= kSkinnyMaxM || n == 0 || k == 0) return 0;          // (W4A4 with m <= 32 is planned below too)
+    const GemmPlan p = gemm_plan(m, n, k, false);                // the register-decode kernel never splits
+    if (p.split == 1) return 0;
+    const int64_t kt_all = (k + kBK - 1) / kBK, kt_per = (kt_all + p.split - 1) / p.split;
+    const int64_t slices = (kt_all + kt_per - 1) / kt_per;
+    return (size_t)(slices * m * n) * sizeof(float);
 }
 
 template <bool AQ, bool GB>
 static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                                 int64_t n, int64_t k, const uint16_t* a, const uint8_t* a_codes,
                                 const uint8_t* a_scales, const float* a_ts, SvConfig acfg, int64_t m, uint16_t* y,
-                                int64_t ld_y, hipStream_t st)
+                                int64_t ld_y, float* workspace, hipStream_t st)
 {
-#define RAZER_GEMM(BM, BN, WGM, WGN) \
-    launch_cfg<BM, BN, WGM, WGN, AQ, false, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st)
-    if (m <= 32) return RAZER_GEMM(32, 256, 1, 4);
-    if (m <= 64) return RAZER_GEMM(64, 256, 1, 4);
-    if (m <= 128) return RAZER_GEMM(128, 128, 2, 2);
-    // Large m: 256-row activation tiles so every weight is decoded once per 256 rows.  Pick the
-    // weight-tile width that wastes fewer of the 256 compute units in the last round of workgroups.
-    const int64_t tm = (m + 255) / 256;
-    const int64_t t256 = tm * ((n + 255) / 256), t128 = tm * ((n + 127) / 128);
-    if constexpr (!AQ && !GB) {
-        // Enough tiles for two resident waves per SIMD: the kernel that decodes weights in registers
-        // (measured 5-28 % faster than the LDS-staged one on the 7B projection shapes from M = 2048).
-        if (t256 >= 1024) return launch_rb<8, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
-        if (t128 >= 512) return launch_rb<4, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+    GemmPlan p = gemm_plan(m, n, k, !AQ && !GB);
+    if (m <= kSkinnyMaxM || !workspace) p.split = 1;             // small m is not sized a workspace
+#define RAZER_GEMM(BM, BN, WGM, WGN, PP) \
+    launch_cfg<BM, BN, WGM, WGN, AQ, PP, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, p.split, workspace, st)
+    switch (p.tile) {
+        case 0: return RAZER_GEMM(32, 256, 1, 4, false);
+        case 1: return RAZER_GEMM(64, 256, 1, 4, false);
+        case 2: return RAZER_GEMM(128, 128, 2, 2, false);
+        case 3: return RAZER_GEMM(256, 256, 2, 4, true);
+        case 4: return RAZER_GEMM(256, 128, 4, 2, true);
+        default: break;
     }
-    auto eff = [](int64_t tiles) { return (double)tiles / (double)(((tiles + 255) / 256) * 256); };
-#define RAZER_GEMM_PP(BM, BN, WGM, WGN) \
-    launch_cfg<BM, BN, WGM, WGN, AQ, true, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st)
-    if (eff(t256) >= eff(t128)) return RAZER_GEMM_PP(256, 256, 2, 4);
-    return RAZER_GEMM_PP(256, 128, 4, 2);
-#undef RAZER_GEMM_PP
 #undef RAZER_GEMM
+    if constexpr (!AQ && !GB) {
+        if (p.tile == 5) return launch_rb<8, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+        return launch_rb<4, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
                        int64_t n, int64_t k, const uint16_t* a, SvConfig acfg, const uint8_t* a_codes,
                        const uint8_t* a_scales, const float* a_ts, int64_t m, uint16_t* y, int64_t ld_y,
-                       hipStream_t st)
+                       float* workspace, hipStream_t st)
 {
     if (n == 0 || m == 0) return hipSuccess;
     // blocks of 32, 64, 128 (either operand) take the variants whose scale-byte loads index by block
     const bool generic = wcfg.lb != 4 || (a_codes && acfg.lb != 4);
-#define RAZER_GEMM_ARGS w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, st
+#define RAZER_GEMM_ARGS w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, workspace, st
     if (a_codes) return generic ? launch_gemm_t<true, true>(RAZER_GEMM_ARGS) : launch_gemm_t<true, false>(RAZER_GEMM_ARGS);
     return generic ? launch_gemm_t<false, true>(RAZER_GEMM_ARGS) : launch_gemm_t<false, false>(RAZER_GEMM_ARGS);
 #undef RAZER_GEMM_ARGS

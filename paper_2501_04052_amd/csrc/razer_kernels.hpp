@@ -27,6 +27,10 @@ size_t skinny_workspace_bytes(int64_t n, int64_t k, int64_t m);
 hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts, int64_t n,
                          int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y, float* workspace,
                          hipStream_t st);
+// y = bf16(scale * sum of the K-slices' fp32 partial sums [slices][m][n], in slice order); scale = -ts_w,
+// or ts_w * ts_a when a_ts is given.
+hipError_t launch_slice_reduce(const float* partial, const float* w_ts, const float* a_ts, int64_t m, int64_t n,
+                               int nslices, uint16_t* y, int64_t ld_y, hipStream_t st);
 hipError_t launch_gemv(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
                        int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
                        hipStream_t st);
@@ -45,9 +49,12 @@ hipError_t launch_gemv_grouped(SvConfig cfg, int count, const GemvProblem* p, in
 
 // Same contraction on bf16 matrix cores with LDS-staged decoded tiles.  Activations are
 // bf16 (a != nullptr) or RaZeR activation-format (a_codes != nullptr).
+// Problems with few output tiles split K over workgroups; the slices meet in an fp32 workspace of
+// gemm_workspace_bytes(n, k, m) bytes (0 when K is not split).
+size_t gemm_workspace_bytes(int64_t n, int64_t k, int64_t m);
 hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
                        int64_t n, int64_t k, const uint16_t* a, SvConfig acfg, const uint8_t* a_codes,
                        const uint8_t* a_scales, const float* a_ts, int64_t m, uint16_t* y, int64_t ld_y,
-                       hipStream_t st);
+                       float* workspace, hipStream_t st);
 
 }  // namespace razer

@@ -10,7 +10,7 @@
 // the 4 waves = 64 weight rows of a workgroup) are staged once in LDS, chunk-swizzled with the row.
 //
 // Work split: grid = (N / 64) x (K / KC); K-slices of one output tile are summed in fixed order by
-// a second kernel from an fp32 workspace [slices][M][N] (deterministic, no atomics).
+// a second kernel (slice_reduce_kernel) from an fp32 workspace [slices][M][N] (deterministic, no atomics).
 #include "razer_device.hpp"
 #include "razer_kernels.hpp"
 
@@ -130,17 +130,44 @@ __global__ __launch_bounds__(256) void skinny_kernel(const uint8_t* __restrict__
     }
 }
 
-// y[m][n] = bf16(-ts * sum over slices, in slice order, of partial[slice][m][n])
-__global__ __launch_bounds__(256) void skinny_reduce_kernel(const float* __restrict__ partial,
-                                                            const float* __restrict__ w_ts, int64_t m, int64_t n,
-                                                            int nslices, uint16_t* __restrict__ y, int64_t ld_y)
+// y[m][n] = bf16(scale * sum over slices, in slice order, of partial[slice][m][n]); scale = -ts_w
+// (weight-only: the decode carries a global negation) or ts_w * ts_a (both operands decoded).
+// VEC = 4: four consecutive columns per thread (n and ld_y multiples of 4).
+template <int VEC>
+__global__ __launch_bounds__(256) void slice_reduce_kernel(const float* __restrict__ partial,
+                                                           const float* __restrict__ w_ts,
+                                                           const float* __restrict__ a_ts, int64_t m, int64_t n,
+                                                           int nslices, uint16_t* __restrict__ y, int64_t ld_y)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC;
     if (i >= m * n) return;
-    float t = 0.0f;
-    for (int s = 0; s < nslices; ++s) t += partial[(int64_t)s * m * n + i];
+    const float scale = a_ts ? (*w_ts) * (*a_ts) : -(*w_ts);
     const int64_t r = i / n, c = i - r * n;
-    y[r * ld_y + c] = f32_to_bf16_rne(-(*w_ts) * t);
+    if (VEC == 4) {
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s = 0; s < nslices; ++s) {
+            const float4 p = *reinterpret_cast<const float4*>(partial + (int64_t)s * m * n + i);
+            t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+        }
+        const uint32_t lo = (uint32_t)f32_to_bf16_rne(scale * t.x) | ((uint32_t)f32_to_bf16_rne(scale * t.y) << 16);
+        const uint32_t hi = (uint32_t)f32_to_bf16_rne(scale * t.z) | ((uint32_t)f32_to_bf16_rne(scale * t.w) << 16);
+        *reinterpret_cast<uint2*>(y + r * ld_y + c) = make_uint2(lo, hi);
+    } else {
+        float t = 0.0f;
+        for (int s = 0; s < nslices; ++s) t += partial[(int64_t)s * m * n + i];
+        y[r * ld_y + c] = f32_to_bf16_rne(scale * t);
+    }
+}
+
+hipError_t launch_slice_reduce(const float* partial, const float* w_ts, const float* a_ts, int64_t m, int64_t n,
+                               int nslices, uint16_t* y, int64_t ld_y, hipStream_t st)
+{
+    const int64_t total = m * n;
+    if (n % 4 == 0 && ld_y % 4 == 0 && (reinterpret_cast<uintptr_t>(y) & 7u) == 0)
+        slice_reduce_kernel<4><<<(unsigned)((total / 4 + 255) / 256), 256, 0, st>>>(partial, w_ts, a_ts, m, n, nslices, y, ld_y);
+    else
+        slice_reduce_kernel<1><<<(unsigned)((total + 255) / 256), 256, 0, st>>>(partial, w_ts, a_ts, m, n, nslices, y, ld_y);
+    return hipGetLastError();
 }
 
 static int skinny_steps(int64_t k, int64_t m)
@@ -176,9 +203,7 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
 #undef RAZER_SK
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nslices == 1) return e;
-    const int64_t total = m * n;
-    skinny_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(workspace, ts, m, n, nslices, y, ld_y);
-    return hipGetLastError();
+    return launch_slice_reduce(workspace, ts, nullptr, m, n, nslices, y, ld_y, st);
 }
 
 }  // namespace razer

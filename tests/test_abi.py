@@ -95,6 +95,12 @@ def test_bad_arguments_return_status_codes_without_gpu(razer):
     tb.rows = 8; tb.cols = 1024; tb.cfg = cfg
     assert L.razer_linear(ctypes.byref(tb), fake, None, 8, fake, 8, None, 0, None) == 5      # needs a workspace
     assert L.razer_linear(ctypes.byref(tb), fake, None, 8, fake, 8, fake, 16, None) == 5     # too small
+    # a GEMM with few output tiles splits K and needs the workspace as well
+    assert L.razer_workspace_bytes(2, 8, 1024, 512) == 2 * 512 * 8 * 4
+    assert L.razer_linear(ctypes.byref(tb), fake, None, 512, fake, 8, None, 0, None) == 5
+    assert L.razer_workspace_bytes(2, 4096, 4096, 512) == 4 * 512 * 4096 * 4
+    assert L.razer_workspace_bytes(2, 4096, 4096, 2048) == 0     # 256 tiles: no split
+    assert L.razer_workspace_bytes(2, 11008, 4096, 2048) == 0
     ta = _Tensor(); ta.codes = 0x1000; ta.scales = 0x2000; ta.tensor_scale = 0x3000
     ta.rows = 2; ta.cols = 64; ta.cfg = cfg                      # weight format used as activation
     assert L.razer_linear(ctypes.byref(t), None, ctypes.byref(ta), 2, fake, 8, None, 0, None) == 4
