@@ -346,3 +346,19 @@ def test_block_sizes_grouped_falls_back_to_single_launches(oracle):
     ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a))
     for wq, y in zip(wqs, ys):
         assert max_rel_err(dev_to_bf16_bits(y), oracle.linear(wq, a_bf16=a)[0]) <= TOL
+
+
+def test_special_value_sweep_tool_agrees_with_oracle(oracle):
+    """The selection tool (error of every allowed pair through the HIP encoder + decoder) ranks the
+    pairs like the oracle does and picks +-5 first."""
+    from paper_2501_04052_amd import sv_sweep
+    w = synth.weight(64, 1024, seed=1600, outlier_frac=0.002)
+    x = torch.from_numpy(w).cuda()
+    (v0, v1), one, two = sv_sweep.best_pairs(x)
+    assert v0 == 5.0 and v1 != 5.0
+    for v in (4.5, 5.0, 7.0):
+        c, s, t = oracle.quantize(W, w, sv=(v, v))
+        d = oracle.dequant(W, c, s, t, sv=(v, v))["f32"].astype(np.float64)
+        ref = float(((w - d) ** 2).sum())
+        got = sv_sweep.quantization_error(x, W, (v, v))
+        assert abs(got - ref) <= 1e-9 * ref

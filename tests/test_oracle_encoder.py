@@ -272,3 +272,25 @@ def test_error_bound_half_grid_gap(oracle):
     gap = np.select([a <= 2, a <= 4, a <= 6], [0.25, 0.5, 1.0], default=np.inf)
     assert np.all(np.abs(xs - q)[ok] <= gap[ok] + 1e-12)
     assert a[ok].max() <= 6.0 * (1 + 1 / 16) + 1e-6      # RNE block scale keeps the block max near 6
+
+
+def test_single_pair_error_is_lowest_at_5_and_never_above_plain_fp4(oracle):
+    """Sec. 4.2 (discussion of the special-value error figure): adding one pair of special values to
+    NVFP4 lowers the quantization error for every allowed pair, with the minimum at +-5, for weights
+    and for activations alike."""
+    w = synth.weight(128, 2048, seed=31, outlier_frac=0.001)
+    a = synth.bf16_bits_to_f32(synth.activation(128, 2048, seed=32, outlier_frac=0.005))
+
+    def err(fmt, x, v, nsv):
+        sv = (v, v) if fmt == W else (v, 0.0)
+        c, s, t = oracle.quantize(fmt, x, sv=sv, nsv=nsv)
+        d = oracle.dequant(fmt, c, s, t, sv=sv)["f32"].astype(np.float64)
+        return float(((x - d) ** 2).sum())
+
+    for fmt, x in ((W, w), (A, a)):
+        base = err(fmt, x, 5.0, 0)
+        rel = {v: err(fmt, x, v, -1) / base for v in (2.5, 3.5, 4.5, 5.0, 5.5, 6.5, 7.0, 8.0, 9.5)}
+        assert all(r <= 1.0 for r in rel.values())
+        assert min(rel, key=rel.get) == 5.0
+        assert rel[5.0] < 0.95 and rel[4.5] < rel[3.5] and rel[5.5] < rel[6.5]     # a dip around 5
+        assert rel[8.0] > 0.999                       # beyond 6.375 a pair (almost) never gets used
