@@ -362,3 +362,50 @@ def test_special_value_sweep_tool_agrees_with_oracle(oracle):
         ref = float(((w - d) ** 2).sum())
         got = sv_sweep.quantization_error(x, W, (v, v))
         assert abs(got - ref) <= 1e-9 * ref
+
+
+# ------------------------------------------------------------------ streams, graphs, determinism
+def test_linear_on_side_stream_and_under_graph_replay(oracle):
+    """Every kernel family on a non-default stream, captured into a HIP graph and replayed with the
+    program's own eager work in between: each replay must equal the eager result bit for bit."""
+    rng = np.random.default_rng(1700)
+    k = 2048 + 64
+    wq = _rand_tensor(rng, W, 300, k)
+    wt = razer.RazerTensor.from_host(*wq, W, (5.0, 8.0))
+    side = torch.cuda.Stream()
+    for m in (1, 4, 12, 40, 300):                     # GEMV, small batch (workspace), GEMM, split-K GEMM
+        a_dev = bf16_bits_to_dev(synth.activation(m, k, seed=1701 + m))
+        out = torch.empty((m, 300), dtype=torch.bfloat16, device="cuda")
+        need = razer.razer_workspace_bytes(razer.binding.OP_LINEAR, 300, k, m)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        eager = razer.razer_linear(wt, a_dev, workspace=ws).clone()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            razer.razer_linear(wt, a_dev, out=out, workspace=ws)          # warm-up on the side stream
+            side.synchronize()
+            assert torch.equal(out, eager)
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                razer.razer_linear(wt, a_dev, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            out.fill_(float(rep))                                         # eager work between replays
+            ws.random_(0, 255)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager), (m, rep)
+    y64, _ = oracle.linear(wq, a_bf16=synth.activation(300, k, seed=1701 + 300))
+    assert max_rel_err(dev_to_bf16_bits(eager), y64) <= TOL
+
+
+def test_linear_is_deterministic(oracle):
+    """The kernels that split K (small batch, GEMM with few tiles) add their slices in a fixed order."""
+    rng = np.random.default_rng(1800)
+    wq = _rand_tensor(rng, W, 200, 4096)
+    wt = razer.RazerTensor.from_host(*wq, W, (5.0, 8.0))
+    for m in (8, 100, 260):
+        a_dev = bf16_bits_to_dev(synth.activation(m, 4096, seed=1801 + m))
+        ref = razer.razer_linear(wt, a_dev)
+        for _ in range(4):
+            assert torch.equal(razer.razer_linear(wt, a_dev), ref)
