@@ -231,17 +231,20 @@ def main():
     gemm_roof = None
     if args.legs == "all":
         for m in (4, 16):
-            ms, b, _ = linear_leg(m, max(10, args.steps // 4), 5, graph=use_graph, grouped=(m <= 4))
+            ms, b, _ = linear_leg(m, max(10, args.steps // 4), 5, graph=use_graph, grouped=True)
             legs["linear_m%d" % m] = {"GB/s": b / ms / 1e6, "frac_hbm": b / ms / 1e6 / HBM_PEAK_GBS, "ms_per_step": ms}
         for m in (512, 2048):
-            ms, _, fl = linear_leg(m, 5, 2, prepared_single=True)
+            # {q,k,v}, o, {gate,up}, down as four prepared calls, like the decode step
+            ms, _, fl = linear_leg(m, 5, 2, prepared=True)
             legs["gemm_m%d" % m] = {"TFLOP/s": fl / ms / 1e9, "frac_mfma_bf16": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
                                     "ms_per_step": ms}
+            ms7, _, _ = linear_leg(m, 5, 2, prepared_single=True)
+            legs["gemm_m%d_seven_calls" % m] = {"TFLOP/s": fl / ms7 / 1e9, "ms_per_step": ms7}
             if m == 2048:
                 gemm_roof = {"bound": "mfma", "achieved": fl / ms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
                              "unit": "TFLOP/s", "frac": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                             "kernel": "gemm_pp_kernel<256,128> (q,k,v,o,down) + gemm_rb_kernel<4,2> (gate,up), M=2048, "
-                                       "Llama-7B layer set as 7 launches, flops = 2MNK, whole-leg time"}
+                             "kernel": "gemm_rb_grouped_kernel<4,2> ({q,k,v}, {gate,up}) + gemm_pp_kernel<256,128> (o, down), "
+                                       "M=2048, Llama-7B layer set as 4 calls, flops = 2MNK, whole-leg time"}
         # decoder leg: packed -> bf16
         t = packed[4]
         out = torch.empty((t.rows, t.cols), dtype=torch.bfloat16, device="cuda")
@@ -276,19 +279,16 @@ def main():
         for m in (1, 8):
             acts = {k: make_act(m, k, 4100 + m) for k in {k for _, _, k in synth.LLAMA_70B_LAYER}}
             outs = [torch.empty((m, n), dtype=torch.bfloat16, device="cuda") for _, n, _ in synth.LLAMA_70B_LAYER]
-            wsb = max(razer.razer_workspace_bytes(2, t.rows, t.cols, m) for t in big)
-            wsp = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+            plans70 = [razer.prepare_linear_grouped(big[0:3], acts[8192], outs[0:3]),
+                       razer.prepare_linear(big[3], acts[8192], outs[3]),
+                       razer.prepare_linear_grouped(big[4:6], acts[8192], outs[4:6]),
+                       razer.prepare_linear(big[6], acts[28672], outs[6])]
+            st70 = torch.cuda.current_stream().cuda_stream
 
             def step70(i):
-                if m <= 4:
-                    razer.razer_linear_grouped(big[0:3], acts[8192], outs=outs[0:3])
-                    razer.razer_linear(big[3], acts[8192], out=outs[3])
-                    razer.razer_linear_grouped(big[4:6], acts[8192], outs=outs[4:6])
-                    razer.razer_linear(big[6], acts[28672], out=outs[6])
-                else:
-                    for j, t in enumerate(big):
-                        razer.razer_linear(t, acts[t.cols], out=outs[j], workspace=wsp)
-            ms = time_region(step70, 20, 3, graph_period=1 if use_graph else 0)
+                for call in plans70:
+                    call(st70)
+            ms = time_region(step70, 20, 3)
             b = bytes70 + sum(2 * m * k + 2 * m * n + 4 for _, n, k in synth.LLAMA_70B_LAYER)
             legs["llama70b_layer_m%d" % m] = {"GB/s": b / ms / 1e6, "frac_hbm": b / ms / 1e6 / HBM_PEAK_GBS,
                                              "ms_per_step": ms, "note": "configs[3]: 481 MB packed layer, one pass"}
@@ -296,8 +296,10 @@ def main():
         m = 4096
         acts = {k: make_act(m, k, 4100 + m) for k in {k for _, _, k in synth.LLAMA_70B_LAYER}}
         outs = [torch.empty((m, n), dtype=torch.bfloat16, device="cuda") for _, n, _ in synth.LLAMA_70B_LAYER]
-        plans70 = [razer.prepare_linear(t, acts[t.cols], outs[j]) for j, t in enumerate(big)]
-        st70 = torch.cuda.current_stream().cuda_stream
+        plans70 = [razer.prepare_linear_grouped(big[0:3], acts[8192], outs[0:3]),
+                   razer.prepare_linear(big[3], acts[8192], outs[3]),
+                   razer.prepare_linear_grouped(big[4:6], acts[8192], outs[4:6]),
+                   razer.prepare_linear(big[6], acts[28672], outs[6])]
 
         def step70p(i):
             for call in plans70:
@@ -305,7 +307,7 @@ def main():
         ms = time_region(step70p, 3, 1)
         fl = sum(2.0 * m * n * k for _, n, k in synth.LLAMA_70B_LAYER)
         legs["llama70b_layer_m4096"] = {"TFLOP/s": fl / ms / 1e9, "frac_mfma_bf16": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-                                        "ms_per_step": ms, "note": "configs[3] at M=4096, 7 launches"}
+                                        "ms_per_step": ms, "note": "configs[3] at M=4096, 4 calls"}
         del big, plans70, acts, outs
 
     # ---- block sizes 32, 64, 128 (the paper's block-size study): M=1 decode step, 7 launches -------

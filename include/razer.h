@@ -136,9 +136,16 @@ razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer
 /* The same layer for several weight matrices that consume the SAME activation rows (fused q/k/v,
  * gate/up projections; the paper's stripe partition likewise lets one launch span several N
  * ranges, Sec. 4.3): y_bf16[i] = A w[i]^T for i < count, count <= RAZER_MAX_GROUP.  All w[i] must
- * have the same cols; W4A16 only.  For m <= 4, block 16 and equal special values this is ONE kernel launch
- * (short decode-regime kernels are launch-latency-bound); otherwise it is the sequence of
- * razer_linear calls.  y_bf16[i] is device [m][ld_y[i]].  The pointer arrays are HOST arrays. */
+ * have the same cols; W4A16 only.  With 16-element blocks, equal special values and no empty matrix
+ * this is ONE kernel launch (short kernels are launch-latency-bound, and one launch fills the last
+ * round of workgroups of a GEMM better than one per matrix) when
+ *   m <= 4;
+ *   5 <= m <= 32, every rows[i] and ld_y[i] a multiple of 4, y_bf16[i] 8-byte aligned, and the
+ *     workspace holds the SUM over i of razer_workspace_bytes(RAZER_OP_LINEAR, rows[i], cols, m)
+ *     (plus one launch that adds the K-slices up);
+ *   m > 32 and the matrices together have >= 512 output tiles of 256 x 128 (no workspace).
+ * Otherwise it is the sequence of razer_linear calls with the same workspace (which then must
+ * satisfy each call).  y_bf16[i] is device [m][ld_y[i]].  The pointer arrays are HOST arrays. */
 #define RAZER_MAX_GROUP 4
 razer_status razer_linear_grouped(const razer_tensor *const *w, int32_t count, const void *a_bf16,
                                   int64_t m, void *const *y_bf16, const int64_t *ld_y,

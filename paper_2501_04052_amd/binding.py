@@ -219,7 +219,7 @@ def razer_linear_grouped(ws, a, outs=None):
     yptrs = (ctypes.c_void_p * count)(*[o.data_ptr() for o in outs])
     lds = (ctypes.c_int64 * count)(*[(o.stride(0) if m > 1 else max(o.stride(0), w.rows))
                                      for o, w in zip(outs, ws)])
-    need = max(razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m) for w in ws)
+    need = sum(razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m) for w in ws)
     workspace = torch.empty(need, dtype=torch.uint8, device=a.device) if need else None
     st = L.razer_linear_grouped(wptrs, count, _ptr(a), m, yptrs, lds, _ptr(workspace), need, _stream())
     if st != 0:
@@ -268,7 +268,7 @@ def prepare_linear_grouped(ws, a, outs):
     yptrs = (ctypes.c_void_p * count)(*[o.data_ptr() for o in outs])
     lds = (ctypes.c_int64 * count)(*[(o.stride(0) if m > 1 else max(o.stride(0), w.rows))
                                      for o, w in zip(outs, ws)])
-    need = max(razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m) for w in ws)
+    need = sum(razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m) for w in ws)
     workspace = torch.empty(need, dtype=torch.uint8, device=a.device) if need else None
     args = (wptrs, count, _ptr(a), m, yptrs, lds, _ptr(workspace), need)
     return PreparedCall(L.razer_linear_grouped, args, (structs, ws, a, outs, workspace), "razer_linear_grouped")

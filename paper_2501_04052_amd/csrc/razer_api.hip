@@ -187,7 +187,7 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
     if (!w || !y_bf16 || !ld_y) return RAZER_ERR_NULL;
     if (count < 1 || count > RAZER_MAX_GROUP) return RAZER_ERR_SHAPE;
     SvConfig sv0;
-    bool one_launch = (m >= 1 && m <= 4);
+    bool one_launch = m >= 1;
     for (int i = 0; i < count; ++i) {
         SvConfig sv;
         razer_status s = check_tensor(w[i], RAZER_FMT_WEIGHT, sv);
@@ -202,19 +202,44 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
     }
     if (m == 0) return RAZER_OK;
     if (!a_bf16) return RAZER_ERR_NULL;
-    if (w[0]->cols > 0 && !aligned16(a_bf16)) return RAZER_ERR_ALIGN;
-    if (!one_launch || w[0]->cols == 0) {
-        for (int i = 0; i < count; ++i) {
-            razer_status s = razer_linear(w[i], a_bf16, nullptr, m, y_bf16[i], ld_y[i], workspace, workspace_bytes,
-                                          hip_stream);
-            if (s != RAZER_OK) return s;
-        }
-        return RAZER_OK;
-    }
+    const int64_t k = w[0]->cols;
+    if (k > 0 && !aligned16(a_bf16)) return RAZER_ERR_ALIGN;
     GemvProblem p[RAZER_MAX_GROUP];
     for (int i = 0; i < count; ++i)
         p[i] = GemvProblem{w[i]->codes, w[i]->scales, w[i]->tensor_scale, w[i]->rows, (uint16_t*)y_bf16[i], ld_y[i]};
-    hipError_t e = launch_gemv_grouped(sv0, count, p, w[0]->cols, (const uint16_t*)a_bf16, m, (hipStream_t)hip_stream);
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (k == 0) one_launch = false;
+    // which single-launch kernel, if any
+    enum { SEQUENCE, GEMV, SKINNY, GEMM } path = SEQUENCE;
+    if (one_launch) {
+        if (m <= kGemvDirectMaxM) {
+            path = GEMV;
+        } else if (m <= kSkinnyMaxM) {
+            // the K-slices of all matrices live in the workspace side by side
+            size_t need = 0;
+            bool ok = true;
+            for (int i = 0; i < count; ++i) {
+                need += skinny_workspace_bytes(p[i].n, k, m);
+                if (p[i].n % 4 != 0 || (reinterpret_cast<uintptr_t>(p[i].y) & 7u) != 0 || p[i].ld_y % 4 != 0) ok = false;
+            }
+            if (ok && (need == 0 || (workspace && workspace_bytes >= need && aligned16(workspace)))) path = SKINNY;
+        } else if (gemm_grouped_fits(count, p, m)) {
+            path = GEMM;
+        }
+    }
+    hipError_t e = hipSuccess;
+    switch (path) {
+        case GEMV: e = launch_gemv_grouped(sv0, count, p, k, (const uint16_t*)a_bf16, m, st); break;
+        case SKINNY: e = launch_skinny_grouped(sv0, count, p, k, (const uint16_t*)a_bf16, m, (float*)workspace, st); break;
+        case GEMM: e = launch_gemm_grouped(sv0, count, p, k, (const uint16_t*)a_bf16, m, st); break;
+        case SEQUENCE:
+            for (int i = 0; i < count; ++i) {
+                razer_status s = razer_linear(w[i], a_bf16, nullptr, m, y_bf16[i], ld_y[i], workspace, workspace_bytes,
+                                              hip_stream);
+                if (s != RAZER_OK) return s;
+            }
+            return RAZER_OK;
+    }
     return e == hipSuccess ? RAZER_OK : RAZER_ERR_HIP;
 }
 

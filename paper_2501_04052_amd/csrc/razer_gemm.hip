@@ -533,10 +533,10 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
 // would serialise the prefetch.  Each wait is tied to the registers it guards so that their consumers
 // cannot be scheduled above it; sched_barrier keeps the hand-laid slices (one MFMA each) in order.
 template <int NW, int S>
-__global__ __launch_bounds__(64 * NW, 8 / NW) void gemm_rb_kernel(
+__device__ __forceinline__ void gemm_rb_body(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
-    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m)
+    uint16_t* __restrict__ y, int64_t ld_y, int tile_m, int tile_n)
 {
     constexpr int MT = 8;                               // 32-row activation groups per tile
     constexpr int NT = 64 * NW, BM = 32 * MT, BN = 32 * NW;
@@ -554,7 +554,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void gemm_rb_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, h = lane >> 5;
-    const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int KT = (int)((k + kBK - 1) / kBK);
     const int last = KT - 1;
@@ -759,6 +758,41 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void gemm_rb_kernel(
 }
 
 template <int NW, int S>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void gemm_rb_kernel(
+    const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
+    float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
+    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m)
+{
+    gemm_rb_body<NW, S>(w_codes, w_scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, (int)(blockIdx.x % tiles_m),
+                        (int)(blockIdx.x / tiles_m));
+}
+
+// Up to four weight matrices against the same activations in one launch (fused q/k/v, gate/up): the
+// column tiles of the matrices are numbered one after another, t1..t3 are the first tile of matrices
+// 1..3 (equal to the total for matrices that are absent).  One launch fills the last round of
+// workgroups better than one launch per matrix.
+template <int NW, int S>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void gemm_rb_grouped_kernel(
+    const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
+    const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
+    const float* f0, const float* f1, const float* f2, const float* f3,
+    uint16_t* y0, uint16_t* y1, uint16_t* y2, uint16_t* y3,
+    int64_t n0, int64_t n1, int64_t n2, int64_t n3,
+    int64_t l0, int64_t l1, int64_t l2, int64_t l3,
+    int t1, int t2, int t3,
+    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int64_t m, int tiles_m)
+{
+    const int tile_m = (int)(blockIdx.x % tiles_m), t = (int)(blockIdx.x / tiles_m);
+    const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = f0; uint16_t* y = y0;
+    int64_t n = n0, ld = l0;
+    int first = 0;
+    if (t >= t1) { codes = c1; scales = s1; ts = f1; y = y1; n = n1; ld = l1; first = t1; }
+    if (t >= t2) { codes = c2; scales = s2; ts = f2; y = y2; n = n2; ld = l2; first = t2; }
+    if (t >= t3) { codes = c3; scales = s3; ts = f3; y = y3; n = n3; ld = l3; first = t3; }
+    gemm_rb_body<NW, S>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, tile_m, t - first);
+}
+
+template <int NW, int S>
 static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                             int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
                             hipStream_t st)
@@ -879,6 +913,65 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
         if (p.tile == 5) return launch_rb<8, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
         return launch_rb<4, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
     }
+    return hipErrorInvalidValue;
+}
+
+// The grouped launch uses the register-decode kernel only, so the matrices together must offer the
+// tile counts that kernel is chosen at (see gemm_plan); a weight-tile width that does not divide a
+// matrix's rows just leaves its last tile partly empty.
+static int grouped_tile_width(int count, const GemvProblem* p, int64_t m)
+{
+    if (m <= kSkinnyMaxM) return 0;
+    const int64_t tm = (m + 255) / 256;
+    int64_t t256 = 0, t128 = 0;
+    for (int i = 0; i < count; ++i) {
+        t256 += tm * ((p[i].n + 255) / 256);
+        t128 += tm * ((p[i].n + 127) / 128);
+    }
+    if (t256 >= 1024) return 256;
+    if (t128 >= 512) return 128;
+    return 0;
+}
+bool gemm_grouped_fits(int count, const GemvProblem* p, int64_t m)
+{
+    return count >= 1 && count <= 4 && grouped_tile_width(count, p, m) != 0;
+}
+
+template <int NW, int S>
+static hipError_t launch_rb_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
+                                    int64_t m, hipStream_t st)
+{
+    constexpr int BM = 256, BN = 32 * NW;
+    constexpr size_t smem = S * (BM * 128 + NW * 1280) + 256 * sizeof(uint2);
+    auto kern = gemm_rb_grouped_kernel<NW, S>;
+    static bool attr_set = false;                      // one GPU per process
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (int)((m + BM - 1) / BM);
+    GemvProblem q[4];
+    int t[5] = {0, 0, 0, 0, 0};
+    for (int i = 0; i < 4; ++i) {
+        q[i] = p[i < count ? i : count - 1];
+        t[i + 1] = t[i] + (i < count ? (int)((q[i].n + BN - 1) / BN) : 0);
+    }
+    kern<<<dim3((unsigned)(tiles_m * t[4])), dim3(64 * NW), smem, st>>>(
+        q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts,
+        q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,
+        q[1].ld_y, q[2].ld_y, q[3].ld_y, t[1], t[2], t[3], cfg.sv0, cfg.sv1, k, a, m, tiles_m);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
+                               int64_t m, hipStream_t st)
+{
+    if (count < 1 || count > 4 || cfg.lb != 4) return hipErrorInvalidValue;
+    const int w = grouped_tile_width(count, p, m);
+    if (w == 256) return launch_rb_grouped<8, 2>(cfg, count, p, k, a, m, st);
+    if (w == 128) return launch_rb_grouped<4, 2>(cfg, count, p, k, a, m, st);
     return hipErrorInvalidValue;
 }
 

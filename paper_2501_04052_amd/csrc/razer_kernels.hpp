@@ -35,7 +35,7 @@ hipError_t launch_gemv(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_s
                        int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
                        hipStream_t st);
 
-// Up to 4 weight matrices sharing K, the activation rows (m <= 4) and the special values, one launch.
+// Up to 4 weight matrices sharing K, the activation rows and the special values, one launch (m <= 4 here).
 struct GemvProblem {
     const uint8_t* codes;
     const uint8_t* scales;
@@ -56,5 +56,17 @@ hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_s
                        int64_t n, int64_t k, const uint16_t* a, SvConfig acfg, const uint8_t* a_codes,
                        const uint8_t* a_scales, const float* a_ts, int64_t m, uint16_t* y, int64_t ld_y,
                        float* workspace, hipStream_t st);
+
+// Grouped form of launch_skinny (5 <= m <= 32, 16-element blocks, every n a positive multiple of 4);
+// workspace = the matrices' skinny_workspace_bytes added up, matrix after matrix.
+hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
+                                 int64_t m, float* workspace, hipStream_t st);
+
+// Up to 4 weight matrices (16-element blocks, equal special values, every n > 0, k > 0) against the
+// same bf16 activations in one launch of the register-decode GEMM kernel; possible when
+// gemm_grouped_fits() says the matrices together have enough output tiles for it.
+bool gemm_grouped_fits(int count, const GemvProblem* p, int64_t m);
+hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
+                               int64_t m, hipStream_t st);
 
 }  // namespace razer

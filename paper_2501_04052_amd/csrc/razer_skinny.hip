@@ -38,12 +38,11 @@ constexpr int kSkRows = 64;            // weight rows per workgroup (4 waves x 1
 
 // NB: activation fragments of 16 rows (M <= 16 NB); STEPS: 128-k steps per workgroup (KC = 128 STEPS).
 template <int NB, int STEPS, bool GB>
-__global__ __launch_bounds__(256) void skinny_kernel(const uint8_t* __restrict__ codes,
-                                                     const uint8_t* __restrict__ scales,
-                                                     const float* __restrict__ w_ts, float sv0, float sv1,
-                                                     int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
-                                                     uint16_t* __restrict__ y, int64_t ld_y,
-                                                     float* __restrict__ partial, int nslices, int lb)
+__device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+                                            const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
+                                            int64_t k, const uint16_t* __restrict__ a, int64_t m,
+                                            uint16_t* __restrict__ y, int64_t ld_y, float* __restrict__ partial,
+                                            int nslices, int lb, unsigned block)
 {
     constexpr int KC = 128 * STEPS;
     constexpr int ROWB = KC * 2;                                   // bytes per activation row in LDS
@@ -51,8 +50,8 @@ __global__ __launch_bounds__(256) void skinny_kernel(const uint8_t* __restrict__
     __shared__ uint2 lut[256];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int slice = blockIdx.x % nslices;
-    const int64_t n0 = (int64_t)(blockIdx.x / nslices) * kSkRows;
+    const int slice = block % nslices;
+    const int64_t n0 = (int64_t)(block / nslices) * kSkRows;
     const int64_t k0 = (int64_t)slice * KC;
     const float ts = *w_ts;
 
@@ -130,6 +129,43 @@ __global__ __launch_bounds__(256) void skinny_kernel(const uint8_t* __restrict__
     }
 }
 
+template <int NB, int STEPS, bool GB>
+__global__ __launch_bounds__(256) void skinny_kernel(const uint8_t* __restrict__ codes,
+                                                     const uint8_t* __restrict__ scales,
+                                                     const float* __restrict__ w_ts, float sv0, float sv1,
+                                                     int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
+                                                     uint16_t* __restrict__ y, int64_t ld_y,
+                                                     float* __restrict__ partial, int nslices, int lb)
+{
+    skinny_body<NB, STEPS, GB>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, partial, nslices, lb, blockIdx.x);
+}
+
+// Up to four weight matrices against the same activations in one launch: workgroups are numbered
+// through the matrices one after another (g1..g3 = first workgroup of matrices 1..3); matrix i keeps
+// its K-slices in the workspace behind those of matrices 0 .. i-1.
+template <int NB, int STEPS>
+__global__ __launch_bounds__(256) void skinny_grouped_kernel(
+    const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
+    const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
+    const float* f0, const float* f1, const float* f2, const float* f3,
+    uint16_t* y0, uint16_t* y1, uint16_t* y2, uint16_t* y3,
+    int64_t n0, int64_t n1, int64_t n2, int64_t n3,
+    int64_t l0, int64_t l1, int64_t l2, int64_t l3,
+    unsigned g1, unsigned g2, unsigned g3,
+    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int64_t m, float* __restrict__ partial,
+    int nslices)
+{
+    const unsigned b = blockIdx.x;
+    const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = f0; uint16_t* y = y0;
+    int64_t n = n0, ld = l0, before = 0;
+    unsigned first = 0;
+    if (b >= g1) { codes = c1; scales = s1; ts = f1; y = y1; n = n1; ld = l1; first = g1; before = n0; }
+    if (b >= g2) { codes = c2; scales = s2; ts = f2; y = y2; n = n2; ld = l2; first = g2; before = n0 + n1; }
+    if (b >= g3) { codes = c3; scales = s3; ts = f3; y = y3; n = n3; ld = l3; first = g3; before = n0 + n1 + n2; }
+    skinny_body<NB, STEPS, false>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld,
+                                  partial ? partial + (int64_t)nslices * m * before : nullptr, nslices, 4, b - first);
+}
+
 // y[m][n] = bf16(scale * sum over slices, in slice order, of partial[slice][m][n]); scale = -ts_w
 // (weight-only: the decode carries a global negation) or ts_w * ts_a (both operands decoded).
 // VEC = 4: four consecutive columns per thread (n and ld_y multiples of 4).
@@ -170,6 +206,35 @@ hipError_t launch_slice_reduce(const float* partial, const float* w_ts, const fl
     return hipGetLastError();
 }
 
+// The same reduction for the matrices of a grouped launch: thread index space = the 4-column groups
+// of matrix 0, then of matrix 1, ... (e1..e3 = first group of matrices 1..3; every n a multiple of 4).
+__global__ __launch_bounds__(256) void slice_reduce_grouped_kernel(
+    const float* __restrict__ partial, const float* f0, const float* f1, const float* f2, const float* f3,
+    uint16_t* y0, uint16_t* y1, uint16_t* y2, uint16_t* y3, int64_t n0, int64_t n1, int64_t n2, int64_t n3,
+    int64_t l0, int64_t l1, int64_t l2, int64_t l3, int64_t e1, int64_t e2, int64_t e3, int64_t e4, int64_t m,
+    int nslices)
+{
+    const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= e4) return;
+    const float* ts = f0; uint16_t* y = y0;
+    int64_t n = n0, ld = l0, first = 0, before = 0;
+    if (g >= e1) { ts = f1; y = y1; n = n1; ld = l1; first = e1; before = n0; }
+    if (g >= e2) { ts = f2; y = y2; n = n2; ld = l2; first = e2; before = n0 + n1; }
+    if (g >= e3) { ts = f3; y = y3; n = n3; ld = l3; first = e3; before = n0 + n1 + n2; }
+    const int64_t i = (g - first) * 4;
+    const int64_t r = i / n, c = i - r * n;
+    const float* src = partial + (int64_t)nslices * m * before + i;
+    const float scale = -(*ts);
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < nslices; ++s) {
+        const float4 p = *reinterpret_cast<const float4*>(src + (int64_t)s * m * n);
+        t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+    }
+    const uint32_t lo = (uint32_t)f32_to_bf16_rne(scale * t.x) | ((uint32_t)f32_to_bf16_rne(scale * t.y) << 16);
+    const uint32_t hi = (uint32_t)f32_to_bf16_rne(scale * t.z) | ((uint32_t)f32_to_bf16_rne(scale * t.w) << 16);
+    *reinterpret_cast<uint2*>(y + r * ld + c) = make_uint2(lo, hi);      // y 8-byte aligned, ld a multiple of 4
+}
+
 static int skinny_steps(int64_t k, int64_t m)
 {
     // 512-element K-slices; 1024 for long rows at M <= 16 to bound the number of slices
@@ -204,6 +269,41 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nslices == 1) return e;
     return launch_slice_reduce(workspace, ts, nullptr, m, n, nslices, y, ld_y, st);
+}
+
+// One launch (plus one reduction launch when K is sliced) for up to 4 matrices sharing K, the
+// activation rows (5..32), 16-element blocks and the special values; every n a positive multiple of 4.
+// Workspace: skinny_workspace_bytes of the matrices, added up.
+hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
+                                 int64_t m, float* workspace, hipStream_t st)
+{
+    if (count < 1 || count > 4 || cfg.lb != 4 || m <= kGemvDirectMaxM || m > kSkinnyMaxM) return hipErrorInvalidValue;
+    const int steps = skinny_steps(k, m);
+    const int64_t kc = 128 * steps;
+    const int nslices = (int)((k + kc - 1) / kc);
+    GemvProblem q[4];
+    unsigned g[5] = {0, 0, 0, 0, 0};
+    int64_t e[5] = {0, 0, 0, 0, 0};
+    for (int i = 0; i < 4; ++i) {
+        q[i] = p[i < count ? i : count - 1];
+        if (q[i].n % 4 != 0 || q[i].n <= 0) return hipErrorInvalidValue;
+        g[i + 1] = g[i] + (i < count ? (unsigned)((q[i].n + kSkRows - 1) / kSkRows) * nslices : 0u);
+        e[i + 1] = e[i] + (i < count ? m * q[i].n / 4 : 0);
+    }
+    float* partial = nslices > 1 ? workspace : nullptr;
+#define RAZER_SKG(NB, ST) skinny_grouped_kernel<NB, ST><<<g[4], 256, 0, st>>>(                                      \
+        q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts, \
+        q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,        \
+        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m, partial, nslices)
+    if (m <= 16) { if (steps == 8) RAZER_SKG(1, 8); else RAZER_SKG(1, 4); }
+    else RAZER_SKG(2, 4);
+#undef RAZER_SKG
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || nslices == 1) return err;
+    slice_reduce_grouped_kernel<<<(unsigned)((e[4] + 255) / 256), 256, 0, st>>>(
+        partial, q[0].ts, q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n,
+        q[0].ld_y, q[1].ld_y, q[2].ld_y, q[3].ld_y, e[1], e[2], e[3], e[4], m, nslices);
+    return hipGetLastError();
 }
 
 }  // namespace razer

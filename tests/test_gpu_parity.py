@@ -260,6 +260,47 @@ def test_linear_grouped_matches_oracle(oracle, m, k):
     assert max_rel_err(dev_to_bf16_bits(ys[0]), oracle.linear(wqs[0], a_bf16=a)[0]) <= TOL
 
 
+@pytest.mark.parametrize("m,k", [(5, 512 + 64), (16, 11008), (17, 1024), (32, 512 + 64)])
+def test_linear_grouped_small_batch_one_launch(oracle, m, k):
+    """5 <= m <= 32: the matrices' K-slices share one workspace and one reduction launch."""
+    print("grouped small batch", m, k, flush=True)
+    rng = np.random.default_rng(2000 + m)
+    ns = [132, 64, 200]
+    a = synth.activation(m, k, seed=2001 + m)
+    a_dev = bf16_bits_to_dev(a)
+    wqs = [_rand_tensor(rng, W, n, k) for n in ns]
+    wts = [razer.RazerTensor.from_host(*wq, W, (5.0, 8.0)) for wq in wqs]
+    bufs = [torch.full((m, n + 4), 2.0, dtype=torch.bfloat16, device="cuda") for n in ns]
+    razer.razer_linear_grouped(wts, a_dev, outs=[b[:, :n] for b, n in zip(bufs, ns)])
+    torch.cuda.synchronize()
+    for wt, wq, b, n in zip(wts, wqs, bufs, ns):
+        y64, _ = oracle.linear(wq, a_bf16=a)
+        assert max_rel_err(dev_to_bf16_bits(b[:, :n]), y64) <= TOL
+        assert torch.all(b[:, n:] == 2.0)
+        # the same kernels, one matrix per call: identical bits (same slices, same order)
+        assert torch.equal(b[:, :n], razer.razer_linear(wt, a_dev))
+
+
+@pytest.mark.parametrize("ns,k", [([2760, 2688, 2944], 160), ([8200, 8192, 8192, 8448], 64)])
+def test_linear_grouped_gemm_one_launch(oracle, ns, k):
+    """m > 32 with enough output tiles over all matrices: one launch of the register-decode GEMM
+    (128-wide weight tiles in the first case, 256-wide in the second); ragged m, n and K-tile."""
+    print("grouped gemm", ns, k, flush=True)
+    m = 2000
+    rng = np.random.default_rng(2100 + k)
+    a = synth.activation(m, k, seed=2101 + k)
+    a_dev = bf16_bits_to_dev(a)
+    wqs = [_rand_tensor(rng, W, n, k) for n in ns]
+    wts = [razer.RazerTensor.from_host(*wq, W, (5.0, 8.0)) for wq in wqs]
+    bufs = [torch.full((m, n + 8), 2.0, dtype=torch.bfloat16, device="cuda") for n in ns]
+    razer.razer_linear_grouped(wts, a_dev, outs=[b[:, :n] for b, n in zip(bufs, ns)])
+    torch.cuda.synchronize()
+    for wq, b, n in zip(wqs, bufs, ns):
+        y64, _ = oracle.linear(wq, a_bf16=a)
+        assert max_rel_err(dev_to_bf16_bits(b[:, :n]), y64) <= TOL
+        assert torch.all(b[:, n:] == 2.0)
+
+
 # ------------------------------------------------------------------ block sizes 32, 64, 128 (Sec. 5.4)
 BLOCKS = [32, 64, 128]
 
