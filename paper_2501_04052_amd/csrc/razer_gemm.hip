@@ -528,37 +528,48 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
 // (LUT lookups, decode of step 0) between the last MFMAs, and the barrier ending the iteration makes
 // everybody's activation copies visible.
 //
+// KG = 2 (for problems with about one 256 x 128 tile per compute unit): eight waves as two K groups of
+// four; group g runs the same loop over its half of the K-tiles with its own activation stages, both
+// groups meet at the same barriers, and at the end the two partial sums of every output meet through
+// LDS -- each wave finishes half of the 256 rows.  The sum of the two halves is rounded once more than
+// a single pass over K would be (fp32), which is inside the output tolerance.
+//
 // LDS reads are inline assembly with hand-placed s_waitcnt lgkmcnt: the compiler cannot tell the
 // stages apart, so before any LDS load it knows of it would wait for ALL outstanding copies, which
 // would serialise the prefetch.  Each wait is tied to the registers it guards so that their consumers
 // cannot be scheduled above it; sched_barrier keeps the hand-laid slices (one MFMA each) in order.
-template <int NW, int S>
+template <int NW, int S, int KG = 1>
 __device__ __forceinline__ void gemm_rb_body(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
     uint16_t* __restrict__ y, int64_t ld_y, int tile_m, int tile_n)
 {
     constexpr int MT = 8;                               // 32-row activation groups per tile
-    constexpr int NT = 64 * NW, BM = 32 * MT, BN = 32 * NW;
-    constexpr int NU_A = BM * 8 / NT;                   // 1-KiB activation copies per wave and K-tile
+    constexpr int NWN = NW / KG;                        // waves side by side along N; KG groups of them split K
+    constexpr int NT = 64 * NW, BM = 32 * MT, BN = 32 * NWN;
+    constexpr int NU_A = BM * 8 / (64 * NWN);           // 1-KiB activation copies per wave and K-tile
     constexpr int D = S - 1;                            // tiles in flight ahead of the one being computed
     constexpr int L = NU_A + 2;                         // copy instructions per wave and K-tile
     constexpr int A_STAGE = BM * 128, B_CODES = NW * 1024, B_STAGE = NW * 1280;
-    static_assert((BM * 8) % NT == 0, "activation tile must divide over the threads");
+    static_assert((BM * 8) % (64 * NWN) == 0, "activation tile must divide over the threads");
     static_assert(S >= 2 && S <= 4 && (D - 1) * L < 64, "stage count");
+    static_assert(KG == 1 || (KG == 2 && S == 2 && NWN == 4), "K groups: two, of four waves, two stages each");
 
     extern __shared__ __align__(16) uint8_t smem[];
-    uint8_t* As = smem;                                 // S stages x 256 rows x 128 B
-    uint8_t* Bs = smem + S * A_STAGE;                   // S stages x (NW KiB of codes + NW x 256 B of scale-byte pairs)
-    uint2* wlut = reinterpret_cast<uint2*>(smem + S * (A_STAGE + B_STAGE));
+    uint8_t* As = smem;                                 // KG x S stages x 256 rows x 128 B
+    uint8_t* Bs = smem + KG * S * A_STAGE;              // S stages x (NW KiB of codes + NW x 256 B of scale-byte pairs)
+    uint2* wlut = reinterpret_cast<uint2*>(smem + KG * S * A_STAGE + S * B_STAGE);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int kg = wave / NWN, wn = wave % NWN;         // K group, position along N
     const int r = lane & 31, h = lane >> 5;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int KT = (int)((k + kBK - 1) / kBK);
     const int last = KT - 1;
+    // K group g computes the K-tiles g KTH .. (g + 1) KTH - 1; tiles past the last one contribute zero weights
+    const int KTH = (KT + KG - 1) / KG, kbase = kg * KTH;
 
-    int64_t wrow = n0 + 32 * wave + r;
+    int64_t wrow = n0 + 32 * wn + r;
     wrow = wrow < n ? wrow : n - 1;                     // rows past N re-read the last row, never stored
     const uint8_t* crow = w_codes + wrow * (k / 2) + 16 * h;
     const uint8_t* srow = w_scales + wrow * (k / 16) + 2 * h;
@@ -573,7 +584,7 @@ __device__ __forceinline__ void gemm_rb_body(
     uint32_t a_chunk[NU_A];
 #pragma unroll
     for (int i = 0; i < NU_A; ++i) {
-        const uint32_t row = 8u * (wave * NU_A + i) + (lane >> 3);
+        const uint32_t row = 8u * (wn * NU_A + i) + (lane >> 3);
         const uint32_t c = (lane & 7u) ^ ((row >> 1) & 7u);
         a_chunk[i] = c;
         a_src[i] = (row < rows_here ? row : rows_here - 1) * row_bytes + c * 16u;
@@ -586,7 +597,7 @@ __device__ __forceinline__ void gemm_rb_body(
             const uint32_t off = kk < (uint32_t)k ? a_src[i] + (uint32_t)kt * (kBK * 2u) : a_src[i] - a_chunk[i] * 16u;
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void*)(abase + off),           // past K: any finite data
-                (__attribute__((address_space(3))) void*)(As + st * A_STAGE + (wave * NU_A + i) * 1024), 16, 0, 0);
+                (__attribute__((address_space(3))) void*)(As + (kg * S + st) * A_STAGE + (wn * NU_A + i) * 1024), 16, 0, 0);
         }
         const int kc = ((int64_t)kt * kBK + 32 * h < k) ? kt : 0;                       // past K: masked where used
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(crow + 32 * kc),
@@ -603,7 +614,7 @@ __device__ __forceinline__ void gemm_rb_body(
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[0][j][v] = 0.0f;
 
-    const uint32_t a_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)As;
+    const uint32_t a_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)As + kg * S * A_STAGE;
     const uint32_t lut_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)wlut;
     // this lane's own codes / scale bytes inside a B stage
     const uint32_t bc_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)Bs + wave * 1024 + lane * 16;
@@ -716,7 +727,7 @@ __device__ __forceinline__ void gemm_rb_body(
     };
 
 #pragma unroll
-    for (int d = 0; d < D; ++d) issue(d < last ? d : last, d);       // tiles 0 .. D - 1 (short K repeats the last)
+    for (int d = 0; d < D; ++d) issue(kbase + d < last ? kbase + d : last, d);   // first D tiles (short K repeats the last)
     fill_scaled_lut<0>(wlut, sv0, sv1, tid, NT);
     __syncthreads();                                    // all copies so far have landed, LUT ready
     {
@@ -726,7 +737,7 @@ __device__ __forceinline__ void gemm_rb_body(
         RAZER_LDS_READ32(s0, bs_lds);
         RAZER_LDS_WAIT(0, c0);
         RAZER_LDS_WAIT(0, s0);
-        flip_and_mask(0, c0, s0);
+        flip_and_mask(kbase, c0, s0);
         RAZER_LDS_READ64(le0, lut_lds + (s0 & 255u) * 8u);
         RAZER_LDS_READ64(le1, lut_lds + ((s0 >> 8) & 255u) * 8u);
         RAZER_LDS_WAIT(0, le0);
@@ -737,7 +748,7 @@ __device__ __forceinline__ void gemm_rb_body(
         wq0[3] = cvt_scaled_pair<3>(xw[0], u2f(le0.x), le0.y);
     }
     int st = 0;                                         // stage of tile kt; tile kt + D goes to st - 1 (mod S)
-    for (int kt = 0; kt < KT; ++kt) {
+    for (int kt = kbase; kt < kbase + KTH; ++kt) {
         const int st_load = st == 0 ? S - 1 : st - 1, st_next = st == S - 1 ? 0 : st + 1;
         issue(kt + D < last ? kt + D : last, st_load);
         compute(kt, st, st_next);
@@ -754,16 +765,57 @@ __device__ __forceinline__ void gemm_rb_body(
 #undef RAZER_LDS_READ32
 #undef RAZER_LDS_WAIT
 #undef RAZER_LDS_WAIT3
-    store_tile<MT, 1, false>(acc, w_ts, nullptr, m0, n0 + 32 * wave, m, n, y, ld_y, lane);
+    if constexpr (KG == 1) {
+        store_tile<MT, 1, false>(acc, w_ts, nullptr, m0, n0 + 32 * wave, m, n, y, ld_y, lane);
+    } else {
+        // The two K groups hold partial sums of the same 256 x 32 outputs.  Every copy has landed and every
+        // fragment read has returned (the waits inside compute(), then the barrier), so the activation
+        // stages are free: each wave hands the half of its accumulators that its partner (same rows, other
+        // K group) will finish -- 16 KiB per wave, [group][4 registers][lane] -- and finishes the other half.
+        float4* mine = reinterpret_cast<float4*>(As + wave * 16384);
+        const float4* theirs = reinterpret_cast<const float4*>(As + (wave ^ NWN) * 16384);
+        v16f keep[1][MT / 2];
+        if (kg == 0) {
+#pragma unroll
+            for (int j = 0; j < MT / 2; ++j) {
+                keep[0][j] = acc[0][j];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    mine[(j * 4 + q) * 64 + lane] = make_float4(acc[0][MT / 2 + j][4 * q], acc[0][MT / 2 + j][4 * q + 1],
+                                                                acc[0][MT / 2 + j][4 * q + 2], acc[0][MT / 2 + j][4 * q + 3]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < MT / 2; ++j) {
+                keep[0][j] = acc[0][MT / 2 + j];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    mine[(j * 4 + q) * 64 + lane] = make_float4(acc[0][j][4 * q], acc[0][j][4 * q + 1],
+                                                                acc[0][j][4 * q + 2], acc[0][j][4 * q + 3]);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < MT / 2; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 t = theirs[(j * 4 + q) * 64 + lane];
+                keep[0][j][4 * q] += t.x;
+                keep[0][j][4 * q + 1] += t.y;
+                keep[0][j][4 * q + 2] += t.z;
+                keep[0][j][4 * q + 3] += t.w;
+            }
+        store_tile<MT / 2, 1, false>(keep, w_ts, nullptr, m0 + 128 * kg, n0 + 32 * wn, m, n, y, ld_y, lane);
+    }
 }
 
-template <int NW, int S>
-__global__ __launch_bounds__(64 * NW, 8 / NW) void gemm_rb_kernel(
+template <int NW, int S, int KG = 1>
+__global__ __launch_bounds__(64 * NW, KG == 1 ? 8 / NW : 1) void gemm_rb_kernel(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
     uint16_t* __restrict__ y, int64_t ld_y, int tiles_m)
 {
-    gemm_rb_body<NW, S>(w_codes, w_scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, (int)(blockIdx.x % tiles_m),
+    gemm_rb_body<NW, S, KG>(w_codes, w_scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, (int)(blockIdx.x % tiles_m),
                         (int)(blockIdx.x / tiles_m));
 }
 
@@ -792,14 +844,14 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void gemm_rb_grouped_kernel(
     gemm_rb_body<NW, S>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, tile_m, t - first);
 }
 
-template <int NW, int S>
+template <int NW, int S, int KG = 1>
 static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                             int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
                             hipStream_t st)
 {
-    constexpr int BM = 256, BN = 32 * NW;
-    constexpr size_t smem = S * (BM * 128 + NW * 1280) + 256 * sizeof(uint2);
-    auto kern = gemm_rb_kernel<NW, S>;
+    constexpr int BM = 256, BN = 32 * NW / KG;
+    constexpr size_t smem = S * (KG * BM * 128 + NW * 1280) + 256 * sizeof(uint2);
+    auto kern = gemm_rb_kernel<NW, S, KG>;
     static bool attr_set = false;                      // one GPU per process
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -845,7 +897,8 @@ static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, co
 
 // Which kernel and how many K-slices.  Tiles: 0 = 32x256, 1 = 64x256, 2 = 128x128 (one stage pair, all
 // waves alike), 3 = 256x256 and 4 = 256x128 (two wave groups out of phase), 5 / 6 = register-decode
-// kernel with 256x256 / 256x128 tiles.  A K-tile costs about 1 us of latency however small the tile, so
+// kernel with 256x256 / 256x128 tiles, 7 = register-decode kernel, 256x128 tiles, K halved inside
+// the workgroup.  A K-tile costs about 1 us of latency however small the tile, so
 // when the output tiles cannot occupy the 256 compute units K is split until they do (at most 8 ways,
 // at least 8 K-tiles per slice); the slices meet in the workspace.
 struct GemmPlan {
@@ -867,6 +920,10 @@ static GemmPlan gemm_plan(int64_t m, int64_t n, int64_t k, bool register_decode_
         // (measured 5-28 % faster than the LDS-staged one on the 7B projection shapes from M = 2048)
         if (register_decode_ok && t256 >= 1024) return GemmPlan{5, 1};
         if (register_decode_ok && t128 >= 512) return GemmPlan{6, 1};
+        // one round of 256x128 tiles (one workgroup per compute unit): the register-decode kernel with
+        // two K groups of four waves keeps two waves on every SIMD (measured 9-10 % over the LDS-staged
+        // kernel on 2048 x 4096 x {4096, 11008}; slower than it when the tiles need a second round)
+        if (register_decode_ok && t128 > 192 && t128 <= 256 && k >= 16 * kBK) return GemmPlan{7, 1};
         // else the weight-tile width that wastes fewer compute units in the last round of workgroups
         auto eff = [](int64_t t) { return (double)t / (double)(((t + 255) / 256) * 256); };
         if (eff(t256) >= eff(t128)) { p.tile = 3; tiles = t256; }
@@ -911,6 +968,7 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
 #undef RAZER_GEMM
     if constexpr (!AQ && !GB) {
         if (p.tile == 5) return launch_rb<8, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+        if (p.tile == 7) return launch_rb<8, 2, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
         return launch_rb<4, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
     }
     return hipErrorInvalidValue;

@@ -129,11 +129,14 @@ def test_config5_w4a4(oracle):
 
 
 @pytest.mark.parametrize("m,n,k", [(8192, 2048 + 40, 32), (4100, 4096 + 8, 160), (16384, 4096, 96),
-                                   (16300, 4096 + 31, 64 + 32), (2048, 11008, 4096 + 32)])
+                                   (16300, 4096 + 31, 64 + 32), (2048, 11008, 4096 + 32),
+                                   # about one 256 x 128 tile per compute unit: K halved inside the workgroup
+                                   (2048, 4096, 4096), (2048, 4096, 11008), (300, 12776, 1088), (2000, 4000, 1056)])
 def test_linear_many_tiles_register_decode_kernel(oracle, m, n, k):
     """Shapes with >= 512 output tiles take the GEMM kernel that decodes weights in registers and stages
     operands with global->LDS copies: ragged M, N and K tails (K = 32: half a K-tile; K % 64 = 32), one
-    to 65 K-tiles.  Sampled rows x columns plus the last rows and columns, all scale bytes."""
+    to 172 K-tiles (odd counts leave the second K group of the one-round variant an empty tile).  Sampled
+    rows x columns plus the last rows and columns, all scale bytes."""
     _say("many-tile GEMM m=%d n=%d k=%d" % (m, n, k))
     rng = np.random.default_rng(7000 + m + n + k)
     codes = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
