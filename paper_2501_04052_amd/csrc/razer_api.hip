@@ -223,7 +223,7 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
                 if (p[i].n % 4 != 0 || (reinterpret_cast<uintptr_t>(p[i].y) & 7u) != 0 || p[i].ld_y % 4 != 0) ok = false;
             }
             if (ok && (need == 0 || (workspace && workspace_bytes >= need && aligned16(workspace)))) path = SKINNY;
-        } else if (gemm_grouped_fits(count, p, m)) {
+        } else if (gemm_grouped_fits(count, p, m, k)) {
             path = GEMM;
         }
     }

@@ -823,8 +823,8 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 8 / NW : 1) void gemm_rb_kernel(
 // column tiles of the matrices are numbered one after another, t1..t3 are the first tile of matrices
 // 1..3 (equal to the total for matrices that are absent).  One launch fills the last round of
 // workgroups better than one launch per matrix.
-template <int NW, int S>
-__global__ __launch_bounds__(64 * NW, 8 / NW) void gemm_rb_grouped_kernel(
+template <int NW, int S, int KG = 1>
+__global__ __launch_bounds__(64 * NW, KG == 1 ? 8 / NW : 1) void gemm_rb_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
     const float* f0, const float* f1, const float* f2, const float* f3,
@@ -841,7 +841,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void gemm_rb_grouped_kernel(
     if (t >= t1) { codes = c1; scales = s1; ts = f1; y = y1; n = n1; ld = l1; first = t1; }
     if (t >= t2) { codes = c2; scales = s2; ts = f2; y = y2; n = n2; ld = l2; first = t2; }
     if (t >= t3) { codes = c3; scales = s3; ts = f3; y = y3; n = n3; ld = l3; first = t3; }
-    gemm_rb_body<NW, S>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, tile_m, t - first);
+    gemm_rb_body<NW, S, KG>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, tile_m, t - first);
 }
 
 template <int NW, int S, int KG = 1>
@@ -923,7 +923,7 @@ static GemmPlan gemm_plan(int64_t m, int64_t n, int64_t k, bool register_decode_
         // one round of 256x128 tiles (one workgroup per compute unit): the register-decode kernel with
         // two K groups of four waves keeps two waves on every SIMD (measured 9-10 % over the LDS-staged
         // kernel on 2048 x 4096 x {4096, 11008}; slower than it when the tiles need a second round)
-        if (register_decode_ok && t128 > 192 && t128 <= 256 && k >= 16 * kBK) return GemmPlan{7, 1};
+        if (register_decode_ok && t128 >= 192 && t128 <= 256 && k >= 16 * kBK) return GemmPlan{7, 1};
         // else the weight-tile width that wastes fewer compute units in the last round of workgroups
         auto eff = [](int64_t t) { return (double)t / (double)(((t + 255) / 256) * 256); };
         if (eff(t256) >= eff(t128)) { p.tile = 3; tiles = t256; }
@@ -977,7 +977,9 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
 // The grouped launch uses the register-decode kernel only, so the matrices together must offer the
 // tile counts that kernel is chosen at (see gemm_plan); a weight-tile width that does not divide a
 // matrix's rows just leaves its last tile partly empty.
-static int grouped_tile_width(int count, const GemvProblem* p, int64_t m)
+// Returns 256 / 128 (tile width of the plain kernel), 129 (128-wide tiles, two K groups: one round of
+// tiles on at least three quarters of the compute units) or 0 (no grouped launch).
+static int grouped_tile_width(int count, const GemvProblem* p, int64_t m, int64_t k)
 {
     if (m <= kSkinnyMaxM) return 0;
     const int64_t tm = (m + 255) / 256;
@@ -988,20 +990,21 @@ static int grouped_tile_width(int count, const GemvProblem* p, int64_t m)
     }
     if (t256 >= 1024) return 256;
     if (t128 >= 512) return 128;
+    if (t128 >= 192 && t128 <= 256 && k >= 16 * kBK) return 129;
     return 0;
 }
-bool gemm_grouped_fits(int count, const GemvProblem* p, int64_t m)
+bool gemm_grouped_fits(int count, const GemvProblem* p, int64_t m, int64_t k)
 {
-    return count >= 1 && count <= 4 && grouped_tile_width(count, p, m) != 0;
+    return count >= 1 && count <= 4 && grouped_tile_width(count, p, m, k) != 0;
 }
 
-template <int NW, int S>
+template <int NW, int S, int KG = 1>
 static hipError_t launch_rb_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
                                     int64_t m, hipStream_t st)
 {
-    constexpr int BM = 256, BN = 32 * NW;
-    constexpr size_t smem = S * (BM * 128 + NW * 1280) + 256 * sizeof(uint2);
-    auto kern = gemm_rb_grouped_kernel<NW, S>;
+    constexpr int BM = 256, BN = 32 * NW / KG;
+    constexpr size_t smem = S * (KG * BM * 128 + NW * 1280) + 256 * sizeof(uint2);
+    auto kern = gemm_rb_grouped_kernel<NW, S, KG>;
     static bool attr_set = false;                      // one GPU per process
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1027,9 +1030,10 @@ hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, in
                                int64_t m, hipStream_t st)
 {
     if (count < 1 || count > 4 || cfg.lb != 4) return hipErrorInvalidValue;
-    const int w = grouped_tile_width(count, p, m);
+    const int w = grouped_tile_width(count, p, m, k);
     if (w == 256) return launch_rb_grouped<8, 2>(cfg, count, p, k, a, m, st);
     if (w == 128) return launch_rb_grouped<4, 2>(cfg, count, p, k, a, m, st);
+    if (w == 129) return launch_rb_grouped<8, 2, 2>(cfg, count, p, k, a, m, st);
     return hipErrorInvalidValue;
 }
 

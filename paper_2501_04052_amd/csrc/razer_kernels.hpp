@@ -65,7 +65,7 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
 // Up to 4 weight matrices (16-element blocks, equal special values, every n > 0, k > 0) against the
 // same bf16 activations in one launch of the register-decode GEMM kernel; possible when
 // gemm_grouped_fits() says the matrices together have enough output tiles for it.
-bool gemm_grouped_fits(int count, const GemvProblem* p, int64_t m);
+bool gemm_grouped_fits(int count, const GemvProblem* p, int64_t m, int64_t k);
 hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
                                int64_t m, hipStream_t st);
 

@@ -281,12 +281,13 @@ def test_linear_grouped_small_batch_one_launch(oracle, m, k):
         assert torch.equal(b[:, :n], razer.razer_linear(wt, a_dev))
 
 
-@pytest.mark.parametrize("ns,k", [([2760, 2688, 2944], 160), ([8200, 8192, 8192, 8448], 64)])
-def test_linear_grouped_gemm_one_launch(oracle, ns, k):
+@pytest.mark.parametrize("m,ns,k", [(2000, [2760, 2688, 2944], 160), (2000, [8200, 8192, 8192, 8448], 64),
+                                    (300, [4100, 4096, 4200], 1088)])
+def test_linear_grouped_gemm_one_launch(oracle, m, ns, k):
     """m > 32 with enough output tiles over all matrices: one launch of the register-decode GEMM
-    (128-wide weight tiles in the first case, 256-wide in the second); ragged m, n and K-tile."""
-    print("grouped gemm", ns, k, flush=True)
-    m = 2000
+    (128-wide weight tiles in the first case, 256-wide in the second, one round of 128-wide tiles
+    with K halved inside the workgroup in the third); ragged m, n and K-tile."""
+    print("grouped gemm", m, ns, k, flush=True)
     rng = np.random.default_rng(2100 + k)
     a = synth.activation(m, k, seed=2101 + k)
     a_dev = bf16_bits_to_dev(a)
