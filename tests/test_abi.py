@@ -127,5 +127,9 @@ def test_bad_arguments_return_status_codes_without_gpu(razer):
     assert L.razer_linear_grouped(arr, 2, None, 1, ys, lds, None, 0, None) == 1
     assert L.razer_linear_grouped(arr, 2, odd, 1, ys, lds, None, 0, None) == 3
     assert L.razer_linear_grouped(arr, 2, None, 0, ys, lds, None, 0, None) == 0
+    # grouped small batch without the workspace of even one matrix: the sequence of single calls reports it
+    arr_b = (PT * 2)(ctypes.pointer(tb), ctypes.pointer(tb))
+    assert L.razer_linear_grouped(arr_b, 2, fake, 8, ys, lds, None, 0, None) == 5
+    assert L.razer_linear_grouped(arr_b, 2, fake, 8, ys, lds, fake, 16, None) == 5
     # empty problems are fine and launch nothing
     assert L.razer_linear(ctypes.byref(t), fake, None, 0, None, 8, None, 0, None) == 0
