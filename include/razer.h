@@ -143,7 +143,7 @@ razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer
  *   5 <= m <= 32, every rows[i] and ld_y[i] a multiple of 4, y_bf16[i] 8-byte aligned, and the
  *     workspace holds the SUM over i of razer_workspace_bytes(RAZER_OP_LINEAR, rows[i], cols, m)
  *     (plus one launch that adds the K-slices up);
- *   m > 32 and the matrices together have >= 512 output tiles of 256 x 128, or 192..256 of them
+ *   m > 128 and the matrices together have >= 512 output tiles of 256 x 128, or 192..256 of them
  *     with cols >= 1024 (no workspace).
  * Otherwise it is the sequence of razer_linear calls with the same workspace (which then must
  * satisfy each call).  y_bf16[i] is device [m][ld_y[i]].  The pointer arrays are HOST arrays. */

@@ -981,7 +981,7 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
 // tiles on at least three quarters of the compute units) or 0 (no grouped launch).
 static int grouped_tile_width(int count, const GemvProblem* p, int64_t m, int64_t k)
 {
-    if (m <= kSkinnyMaxM) return 0;
+    if (m <= 128) return 0;                             // fewer rows take the smaller tiles of the single calls
     const int64_t tm = (m + 255) / 256;
     int64_t t256 = 0, t128 = 0;
     for (int i = 0; i < count; ++i) {
