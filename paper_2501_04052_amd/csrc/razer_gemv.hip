@@ -344,12 +344,7 @@ static inline int stream_groups(int nwaves, int m) { return (nwaves > 8 || (m >=
 // Two sets of waves per workgroup (half as many, larger workgroups) measured 5-8 % faster for rows of
 // 1-3 and 5-8 slices (K = 4096, 11008), slower for 4 slices (K = 8192): dispatching workgroups is part
 // of the cost of these short kernels.
-#ifdef RAZER_GEMV_PROBE
-static int g_probe_sets = 0;
-static inline int stream_sets(int nwaves, int groups) { return (groups == 2 && nwaves <= 8) ? (g_probe_sets ? g_probe_sets : ((nwaves != 4) ? 2 : 1)) : 1; }
-#else
 static inline int stream_sets(int nwaves, int groups) { return (groups == 2 && nwaves <= 8 && nwaves != 4) ? 2 : 1; }
-#endif
 
 template <int M, int R>
 static hipError_t launch_gemv_mr(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,

@@ -260,12 +260,15 @@ def test_linear_grouped_matches_oracle(oracle, m, k):
     assert max_rel_err(dev_to_bf16_bits(ys[0]), oracle.linear(wqs[0], a_bf16=a)[0]) <= TOL
 
 
-@pytest.mark.parametrize("m,k", [(5, 512 + 64), (16, 11008), (17, 1024), (32, 512 + 64)])
-def test_linear_grouped_small_batch_one_launch(oracle, m, k):
+@pytest.mark.parametrize("m,k,ns", [(5, 512 + 64, [132, 64, 200]), (16, 11008, [132, 64, 200]),
+                                    (17, 1024, [132, 64, 200]), (32, 512 + 64, [132, 64, 200]),
+                                    # enough workgroups that each walks through two 64-row blocks; 4100 rows
+                                    # leave the last workgroup of the first matrix one ragged block
+                                    (8, 8192, [4100, 4096])])
+def test_linear_grouped_small_batch_one_launch(oracle, m, k, ns):
     """5 <= m <= 32: the matrices' K-slices share one workspace and one reduction launch."""
-    print("grouped small batch", m, k, flush=True)
+    print("grouped small batch", m, k, ns, flush=True)
     rng = np.random.default_rng(2000 + m)
-    ns = [132, 64, 200]
     a = synth.activation(m, k, seed=2001 + m)
     a_dev = bf16_bits_to_dev(a)
     wqs = [_rand_tensor(rng, W, n, k) for n in ns]
