@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "razer_oracle.c")
 _LIB = os.path.join(_HERE, "librazer_oracle.so")
 
-WEIGHT, ACT = 0, 1
+WEIGHT, ACT, WEIGHT_F16 = 0, 1, 2      # WEIGHT_F16: blocks of 128, one FP16 scale word (Sec. 4.3 kernel format)
 REMAP_CODE = 0x8
 BLOCK = 16
 
@@ -48,6 +48,7 @@ def lib():
         L.oracle_fp4_value.restype = d; L.oracle_fp4_value.argtypes = [i]
         L.oracle_e4m3_value.restype = d; L.oracle_e4m3_value.argtypes = [i]
         L.oracle_e3m3_value.restype = d; L.oracle_e3m3_value.argtypes = [i]
+        L.oracle_e4m10_value.restype = d; L.oracle_e4m10_value.argtypes = [i]
         L.oracle_scale_value.restype = d; L.oracle_scale_value.argtypes = [i, i]
         L.oracle_scale_max.restype = d; L.oracle_scale_max.argtypes = [i]
         L.oracle_round_scale.restype = i; L.oracle_round_scale.argtypes = [i, f]
@@ -65,7 +66,7 @@ def lib():
         L.oracle_dequant.restype = i
         L.oracle_dequant.argtypes = [i, d, d, vp, vp, f, i64, i64, i, vp, vp, vp]
         L.oracle_linear.restype = i
-        L.oracle_linear.argtypes = [d, d, vp, vp, f, i64, i64, i, vp, d, vp, vp, f, i, i64,
+        L.oracle_linear.argtypes = [i, d, d, vp, vp, f, i64, i64, i, vp, d, vp, vp, f, i, i64,
                                     vp, i64, vp, i64, vp, vp]
         L.oracle_two_pass_split.restype = i
         L.oracle_two_pass_split.argtypes = [i, i, i, ctypes.POINTER(i), ctypes.POINTER(i),
@@ -87,6 +88,7 @@ def _c(a, dtype):
 def fp4_value(code): return lib().oracle_fp4_value(int(code))
 def e4m3_value(code): return lib().oracle_e4m3_value(int(code))
 def e3m3_value(code): return lib().oracle_e3m3_value(int(code))
+def e4m10_value(code): return lib().oracle_e4m10_value(int(code))
 def scale_value(fmt, code): return lib().oracle_scale_value(fmt, int(code))
 def scale_max(fmt): return lib().oracle_scale_max(fmt)
 def round_scale(fmt, t): return lib().oracle_round_scale(fmt, float(np.float32(t)))
@@ -128,13 +130,16 @@ def quantize(fmt, x, sv=(5.0, 8.0), nsv=-1, given_tensor_scale=None, want_sse=Fa
 
     Returns (codes u8 [rows][cols/2], scales u8 [rows][cols/block], tensor_scale
     float32 scalar[, block_sse f64 [rows][cols/block]]).  nsv=0 -> plain NVFP4
-    under the same block-scale format.  block: 16 (the evaluated format), 32, 64 or 128."""
+    under the same block-scale format.  block: 16 (the evaluated format), 32, 64 or 128.
+    fmt = WEIGHT_F16: blocks of 128, scales are uint16 words (little-endian in memory)."""
     x = np.ascontiguousarray(x)
     is_bf16 = x.dtype == np.uint16
     assert is_bf16 or x.dtype == np.float32
     rows, cols = x.shape
+    if fmt == WEIGHT_F16:
+        block = 128
     codes = np.empty((rows, cols // 2), np.uint8)
-    scales = np.empty((rows, cols // block), np.uint8)
+    scales = np.empty((rows, cols // block), np.uint16 if fmt == WEIGHT_F16 else np.uint8)
     ts = np.zeros(1, np.float32)
     if given_tensor_scale is not None:
         ts[0] = given_tensor_scale
@@ -150,7 +155,7 @@ def quantize(fmt, x, sv=(5.0, 8.0), nsv=-1, given_tensor_scale=None, want_sse=Fa
 def dequant(fmt, codes, scales, ts, sv=(5.0, 8.0), want=("f32",)):
     """Decode to any of 'f32', 'bf16' (uint16 bits), 'sq' (f64 scale*element).
     The block size is read off the shapes: cols / scales.shape[1]."""
-    codes = _c(codes, np.uint8); scales = _c(scales, np.uint8)
+    codes = _c(codes, np.uint8); scales = _c(scales, np.uint16 if fmt == WEIGHT_F16 else np.uint8)
     rows, half = codes.shape
     cols = half * 2
     block = cols // scales.shape[1] if scales.shape[1] else BLOCK
@@ -175,7 +180,9 @@ def linear(w, a_bf16=None, a_q=None, w_sv=(5.0, 8.0), a_sv0=5.0, rows=None, cols
     rows (of M) and columns (of N) to compute.  Block sizes are read off the
     shapes of the scale arrays.  Returns (y_f64, y_bf16)."""
     wc, ws, wts = w
-    wc = _c(wc, np.uint8); ws = _c(ws, np.uint8)
+    wc = _c(wc, np.uint8)
+    w_fmt = WEIGHT_F16 if np.asarray(ws).dtype == np.uint16 else WEIGHT     # the scale words tell the format
+    ws = _c(ws, np.uint16 if w_fmt == WEIGHT_F16 else np.uint8)
     n, k = wc.shape[0], wc.shape[1] * 2
     ac = asc = ab = None
     ats = 0.0
@@ -194,7 +201,7 @@ def linear(w, a_bf16=None, a_q=None, w_sv=(5.0, 8.0), a_sv0=5.0, rows=None, cols
     nn = n if cs is None else cs.size
     y64 = np.empty((mm, nn), np.float64)
     y16 = np.empty((mm, nn), np.uint16)
-    rc = lib().oracle_linear(float(w_sv[0]), float(w_sv[1]), _p(wc), _p(ws), float(wts), n, k, int(w_block),
+    rc = lib().oracle_linear(w_fmt, float(w_sv[0]), float(w_sv[1]), _p(wc), _p(ws), float(wts), n, k, int(w_block),
                              _p(ab), float(a_sv0), _p(ac), _p(asc), float(ats), int(a_block), m,
                              _p(rs), mm, _p(cs), nn, _p(y64), _p(y16))
     if rc != 0:

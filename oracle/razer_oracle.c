@@ -34,7 +34,10 @@
 static int block_ok(int block) { return block == 16 || block == 32 || block == 64 || block == 128; }
 #define REMAP_CODE 0x8           /* the redundant zero: sign=1, E=0, M=0   */
 
-enum { FMT_WEIGHT = 0, FMT_ACT = 1 };
+/* FMT_WEIGHT_F16: the format of the paper's own weight-only kernel (Sec. 4.3): blocks of 128 with one
+ * FP16 scale whose sign bit and most significant exponent bit hold the 2 metadata bits. */
+enum { FMT_WEIGHT = 0, FMT_ACT = 1, FMT_WEIGHT_F16 = 2 };
+static int is_weight(int fmt) { return fmt != FMT_ACT; }
 
 /* ------------------------------------------------------------------ */
 /* Number formats                                                      */
@@ -70,11 +73,22 @@ double oracle_e3m3_value(int code6)
     return (E != 0) ? ldexp(1.0 + M / 8.0, E - 3) : ldexp(M / 8.0, -2);
 }
 
+/* FP16 magnitude with its most significant exponent bit given away (Sec. 4.3: "sign bit and the most
+ * significant exponent bit ... store the 2-bit metadata"): the 14 bits EEEE|MMMMMMMMMM of an IEEE half
+ * whose exponent field is below 16, i.e. bias 15:
+ *   E != 0: 2^(E-15) (1 + M/1024);   E == 0: 2^-14 M/1024.      max = 2 - 2^-10, all codes finite   */
+double oracle_e4m10_value(int code14)
+{
+    int E = (code14 >> 10) & 15, M = code14 & 1023;
+    return (E != 0) ? ldexp(1.0 + M / 1024.0, E - 15) : ldexp(M / 1024.0, -14);
+}
+
 /* Number of usable scale codes and the scale decoder per format. */
-static int scale_ncodes(int fmt) { return fmt == FMT_WEIGHT ? 64 : 127; }
+static int scale_ncodes(int fmt) { return fmt == FMT_WEIGHT ? 64 : fmt == FMT_ACT ? 127 : 16384; }
 double oracle_scale_value(int fmt, int code)
 {
-    return fmt == FMT_WEIGHT ? oracle_e3m3_value(code) : oracle_e4m3_value(code);
+    return fmt == FMT_WEIGHT ? oracle_e3m3_value(code) : fmt == FMT_ACT ? oracle_e4m3_value(code)
+                                                                          : oracle_e4m10_value(code);
 }
 /* Q_max^FP8 of Eq. 1: the largest block-scale value. */
 double oracle_scale_max(int fmt) { return oracle_scale_value(fmt, scale_ncodes(fmt) - 1); }
@@ -121,9 +135,9 @@ int oracle_offset_reg_from_sv(double mag)
  * -> {+sv0, -sv0}.  nsv == 0 gives plain NVFP4 (no remap) as a comparator.  */
 static int candidates(int fmt, const double sv[2], int nsv_override, double cand[4])
 {
-    int n = (fmt == FMT_WEIGHT) ? 4 : 2;
+    int n = is_weight(fmt) ? 4 : 2;
     if (nsv_override >= 0 && nsv_override < n) n = nsv_override;
-    if (fmt == FMT_WEIGHT) { cand[0] = sv[0]; cand[1] = sv[1]; cand[2] = -sv[0]; cand[3] = -sv[1]; }
+    if (is_weight(fmt)) { cand[0] = sv[0]; cand[1] = sv[1]; cand[2] = -sv[0]; cand[3] = -sv[1]; }
     else                   { cand[0] = sv[0]; cand[1] = -sv[0]; cand[2] = cand[3] = 0; }
     return n;
 }
@@ -134,7 +148,17 @@ double oracle_candidate(int fmt, double sv0, double sv1, int meta)
     return cand[meta & 3];
 }
 
-static int meta_shift(int fmt) { return fmt == FMT_WEIGHT ? 6 : 7; }
+static int meta_shift(int fmt) { return fmt == FMT_WEIGHT ? 6 : fmt == FMT_ACT ? 7 : 14; }
+/* Scale storage: one byte per block, or one little-endian 16-bit word for the FP16-scale format. */
+static int get_scale_word(int fmt, const uint8_t *scales, int64_t idx)
+{
+    return fmt == FMT_WEIGHT_F16 ? (scales[2 * idx] | (scales[2 * idx + 1] << 8)) : scales[idx];
+}
+static void put_scale_word(int fmt, uint8_t *scales, int64_t idx, int word)
+{
+    if (fmt == FMT_WEIGHT_F16) { scales[2 * idx] = (uint8_t)(word & 255); scales[2 * idx + 1] = (uint8_t)(word >> 8); }
+    else scales[idx] = (uint8_t)word;
+}
 
 /* Decoded element of a block (Sec. 4.4 step 3): the remapped zero code gives
  * the block's special value, every other code its FP4 value.               */
@@ -296,7 +320,8 @@ static void encode_block(int fmt, const double cand[4], int nsv, float delta32, 
 /* Whole-tensor encoder.  x is [rows][cols] dense, fp32 or bf16 (widened
  * exactly); blocks of `block` elements run along cols.  Layout written:
  *   codes  [rows][cols/2]      element k even -> low nibble, odd -> high nibble
- *   scales [rows][cols/block]  weights: meta<<6 | E3M3; activations: meta<<7 | E4M3
+ *   scales [rows][cols/block]  weights: meta<<6 | E3M3; activations: meta<<7 | E4M3;
+ *                              FP16-scale weights: 16-bit words meta<<14 | E4M10
  *   *tensor_scale              Eq. 1 (taken as input when given_scale != 0)
  *   block_sse (optional)       [rows][cols/block] squared error in the scaled domain
  * nsv_override < 0 searches the format's full candidate set; 0 = NVFP4.
@@ -307,6 +332,7 @@ int oracle_quantize(int fmt, double sv0, double sv1, int nsv_override,
                     int given_scale, double *block_sse)
 {
     if (!block_ok(block) || rows < 0 || cols < 0 || cols % block) return -1;
+    if (fmt == FMT_WEIGHT_F16 && block != 128) return -1;       /* Sec. 4.3: block size 128 */
     double sv[2] = { sv0, sv1 }, cand[4];
     int nsv = candidates(fmt, sv, nsv_override, cand);
     float delta32 = given_scale ? *tensor_scale : oracle_tensor_scale(fmt, x, x_is_bf16, rows * cols);
@@ -323,7 +349,7 @@ int oracle_quantize(int fmt, double sv0, double sv1, int nsv_override,
             encode_block(fmt, cand, nsv, delta32, block, xb, cb, &sc, &meta, &sse);
             for (int k = 0; k < block; k += 2)
                 codes[(r * cols + b * block + k) / 2] = (uint8_t)(cb[k] | (cb[k + 1] << 4));
-            scales[r * nb + b] = (uint8_t)((meta << meta_shift(fmt)) | sc);
+            put_scale_word(fmt, scales, r * nb + b, (meta << meta_shift(fmt)) | sc);
             if (block_sse) block_sse[r * nb + b] = sse;
         }
     }
@@ -352,7 +378,7 @@ int oracle_dequant(int fmt, double sv0, double sv1,
         for (int64_t k = 0; k < cols; ++k) {
             uint8_t byte = codes[(r * cols + k) / 2];
             int code = (k & 1) ? (byte >> 4) : (byte & 15);
-            uint8_t sb = scales[r * nb + k / block];
+            int sb = get_scale_word(fmt, scales, r * nb + k / block);
             int meta = sb >> sh, sc = sb & ((1 << sh) - 1);
             double sq = oracle_scale_value(fmt, sc) * oracle_element_value(fmt, sv0, sv1, code, meta);
             float w = (float)((double)tensor_scale * sq);   /* exact product rounded once */
@@ -380,7 +406,7 @@ int oracle_dequant(int fmt, double sv0, double sv1,
  * Outputs y_f64 [m][n] (optional) and y_bf16 [m][n] (optional).  When
  * n_cols_sel > 0 only the listed output columns / rows are computed
  * (sampled check of large problems); outputs are then [m_sel][n_sel].      */
-int oracle_linear(double w_sv0, double w_sv1,
+int oracle_linear(int w_fmt, double w_sv0, double w_sv1,
                   const uint8_t *w_codes, const uint8_t *w_scales, float w_tensor_scale,
                   int64_t n, int64_t k, int w_block,
                   const uint16_t *a_bf16,
@@ -389,7 +415,8 @@ int oracle_linear(double w_sv0, double w_sv1,
                   const int64_t *row_sel, int64_t m_sel, const int64_t *col_sel, int64_t n_sel,
                   double *y_f64, uint16_t *y_bf16)
 {
-    if (!block_ok(w_block) || k % w_block || (!a_bf16 == !a_codes)) return -1;
+    if (!block_ok(w_block) || k % w_block || (!a_bf16 == !a_codes) || !is_weight(w_fmt)) return -1;
+    const int wsh = meta_shift(w_fmt);
     if (a_codes && (!block_ok(a_block) || k % a_block)) return -1;
     int64_t nb = k / w_block, nba = a_codes ? k / a_block : 0;
     int64_t mm = row_sel ? m_sel : m, nn = col_sel ? n_sel : n;
@@ -402,9 +429,9 @@ int oracle_linear(double w_sv0, double w_sv1,
             for (int64_t kk = 0; kk < k; ++kk) {
                 uint8_t wb = w_codes[(col * k + kk) / 2];
                 int wc = (kk & 1) ? (wb >> 4) : (wb & 15);
-                uint8_t ws = w_scales[col * nb + kk / w_block];
-                double wq = oracle_scale_value(FMT_WEIGHT, ws & 63) *
-                            oracle_element_value(FMT_WEIGHT, w_sv0, w_sv1, wc, ws >> 6);
+                int ws = get_scale_word(w_fmt, w_scales, col * nb + kk / w_block);
+                double wq = oracle_scale_value(w_fmt, ws & ((1 << wsh) - 1)) *
+                            oracle_element_value(w_fmt, w_sv0, w_sv1, wc, ws >> wsh);
                 double av;
                 if (a_bf16) {
                     av = (double)bf16_to_f32(a_bf16[row * k + kk]);
