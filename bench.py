@@ -347,16 +347,20 @@ def main():
     # ---- block sizes 32, 64, 128 (the paper's block-size study): M=1 decode step, 7 launches -------
     if args.legs == "all":
         torch.cuda.empty_cache()
-        for block in (32, 64, 128):
+        for block in (32, 64, 128, "f16"):
+            # "f16": the paper's own kernel format -- blocks of 128 with one FP16 scale word
+            f16 = block == "f16"
+            if f16:
+                block = 128
             gb = torch.Generator(device="cuda")
-            gb.manual_seed(6000 + block)
+            gb.manual_seed(6000 + block + f16)
             sets = []
             for _ in range(n_copies):
                 ts1 = torch.tensor([1e-3], device="cuda")
                 sets.append([razer.RazerTensor(
                     torch.randint(0, 256, (n, k // 2), generator=gb, device="cuda", dtype=torch.uint8),
-                    torch.randint(0, 256, (n, k // block), generator=gb, device="cuda", dtype=torch.uint8),
-                    ts1, n, k, razer.WEIGHT, sv, block) for _, n, k in layers])
+                    torch.randint(0, 256, (n, k // block * (2 if f16 else 1)), generator=gb, device="cuda", dtype=torch.uint8),
+                    ts1, n, k, razer.WEIGHT_F16 if f16 else razer.WEIGHT, sv, block) for _, n, k in layers])
             acts = {k: make_act(1, k, 2101) for k in {k for _, _, k in layers}}
             outs = [torch.empty((1, n), dtype=torch.bfloat16, device="cuda") for _, n, _ in layers]
             plans = [[razer.prepare_linear(t, acts[t.cols], outs[j]) for j, t in enumerate(cp)] for cp in sets]
@@ -366,10 +370,12 @@ def main():
                 for call in plans[i % n_copies]:
                     call(stream)
             ms = time_region(stepb, max(10, args.steps // 4), 5)
-            b = sum(n * k // 2 + n * k // block + 2 * k + 2 * n + 4 for _, n, k in layers)
-            legs["gemv_m1_block%d" % block] = {"GB/s": b / ms / 1e6, "ms_per_step": ms,
-                                               "bits_per_weight": 4 + 8.0 / block,
-                                               "note": "same layer shapes with %d-element blocks, random packed bytes, 7 launches" % block}
+            sbytes = 2 if f16 else 1
+            b = sum(n * k // 2 + n * k // block * sbytes + 2 * k + 2 * n + 4 for _, n, k in layers)
+            legs["gemv_m1_block128_fp16_scale" if f16 else "gemv_m1_block%d" % block] = {
+                "GB/s": b / ms / 1e6, "ms_per_step": ms, "bits_per_weight": 4 + 8.0 * sbytes / block,
+                "note": "same layer shapes with %d-element blocks%s, random packed bytes, 7 launches"
+                        % (block, " and one FP16 scale word per block (the format of the paper's own kernel)" if f16 else "")}
             del sets, plans
             torch.cuda.empty_cache()
 

@@ -54,7 +54,16 @@ typedef enum {
 
 typedef enum {
     RAZER_FMT_WEIGHT = 0,      /* E3M3 scale + 2 metadata bits, 4 special values    */
-    RAZER_FMT_ACT = 1          /* E4M3 scale + 1 metadata bit, 2 special values     */
+    RAZER_FMT_ACT = 1,         /* E4M3 scale + 1 metadata bit, 2 special values     */
+    /* The format of the paper's own weight-only kernel (Sec. 4.3): blocks of 128 elements with ONE
+     * FP16 scale whose sign bit and most significant exponent bit hold the 2 metadata bits (4 special
+     * values, 4.125 bits per weight).  scales is then [rows][cols/128] little-endian 16-bit words:
+     * bit 15 = special-value sign, bit 14 = selector, bits 13..0 = the low 14 bits of an IEEE half
+     * (exponent below 16: values up to 2 - 2^-10; the tensor scale of Eq. 1 uses that maximum).
+     * block must be 0 or 128; cols a multiple of 128.  A weight format: accepted wherever
+     * RAZER_FMT_WEIGHT is, except that razer_linear takes bf16 activations only and runs every m
+     * through the kernels built for m <= 4 (passes of 4 activation rows, no workspace). */
+    RAZER_FMT_WEIGHT_F16 = 2
 } razer_format;
 
 typedef enum { RAZER_F32 = 0, RAZER_BF16 = 1 } razer_dtype;
@@ -74,7 +83,7 @@ typedef struct {
 /* A quantized tensor: device pointers + shape + configuration. */
 typedef struct {
     const uint8_t *codes;        /* [rows][cols/2]  */
-    const uint8_t *scales;       /* [rows][cols/16] */
+    const uint8_t *scales;       /* [rows][cols/block] bytes (16-bit words for RAZER_FMT_WEIGHT_F16) */
     const float *tensor_scale;   /* device float    */
     int64_t rows, cols;
     razer_config cfg;
@@ -120,7 +129,7 @@ razer_status razer_dequant(const razer_tensor *t, void *out, int32_t dtype, int6
                            void *hip_stream);
 
 /* Quantized linear layer Y = A W^T (Sec. 4.3 weight-only kernels; App. D.3
- * weight-activation).  w is [N][K] in RAZER_FMT_WEIGHT.  Exactly one of
+ * weight-activation).  w is [N][K] in a weight format.  Exactly one of
  *   a_bf16  device bf16 [m][K] dense                      (W4A16), or
  *   a_q     RAZER_FMT_ACT tensor [m][K]                   (W4A4)
  * is non-NULL.  Products are accumulated in fp32 (bf16 matrix cores for large

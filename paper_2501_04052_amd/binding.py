@@ -11,7 +11,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "librazer_hip.so")
 
-WEIGHT, ACT = 0, 1
+WEIGHT, ACT, WEIGHT_F16 = 0, 1, 2
 F32, BF16 = 0, 1
 OP_QUANTIZE, OP_DEQUANT, OP_LINEAR = 0, 1, 2
 GIVEN_TENSOR_SCALE = 1
@@ -121,8 +121,12 @@ class RazerTensor:
         import numpy as np
         rows, cols = codes.shape[0], codes.shape[1] * 2
         block = cols // scales.shape[1] if scales.shape[1] else 16
+        scales = np.ascontiguousarray(scales)
+        if scales.dtype == np.uint16:                  # WEIGHT_F16: 16-bit scale words travel as int16
+            assert fmt == WEIGHT_F16
+            scales = scales.view(np.int16)
         return RazerTensor(torch.from_numpy(np.ascontiguousarray(codes)).to(device),
-                           torch.from_numpy(np.ascontiguousarray(scales)).to(device),
+                           torch.from_numpy(scales).to(device),
                            torch.tensor([float(tensor_scale)], dtype=torch.float32, device=device),
                            rows, cols, fmt, sv, block)
 
@@ -133,6 +137,7 @@ def razer_quantize(x, fmt=WEIGHT, sv=(5.0, 8.0), tensor_scale=None, out=None, wo
     tensor_scale: optional 1-element float32 device tensor used as a given (static) scale.
     cols: number of leading columns to encode when x's rows are longer (x.stride(0) is the ld).
     block: elements per scale byte (16, 32, 64 or 128).
+    fmt = WEIGHT_F16: blocks of 128 with one 16-bit scale word each (scales is an int16 tensor).
     Returns a RazerTensor whose buffers live on x's device."""
     L = load_library()
     assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1
@@ -140,9 +145,11 @@ def razer_quantize(x, fmt=WEIGHT, sv=(5.0, 8.0), tensor_scale=None, out=None, wo
     cols = x.shape[1] if cols is None else cols
     dtype = {torch.float32: F32, torch.bfloat16: BF16}[x.dtype]
     dev = x.device
+    if fmt == WEIGHT_F16:
+        block = 128
     if out is None:
         codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=dev)
-        scales = torch.empty((rows, cols // block), dtype=torch.uint8, device=dev)
+        scales = torch.empty((rows, cols // block), dtype=torch.int16 if fmt == WEIGHT_F16 else torch.uint8, device=dev)
         ts = torch.empty(1, dtype=torch.float32, device=dev) if tensor_scale is None else tensor_scale
     else:
         codes, scales, ts = out.codes, out.scales, out.tensor_scale

@@ -22,11 +22,19 @@ bool sv_ok(float v)
 
 razer_status check_cfg(const razer_config& c, SvConfig& out)
 {
-    if (c.format != RAZER_FMT_WEIGHT && c.format != RAZER_FMT_ACT) return RAZER_ERR_CONFIG;
+    if (c.format != RAZER_FMT_WEIGHT && c.format != RAZER_FMT_ACT && c.format != RAZER_FMT_WEIGHT_F16)
+        return RAZER_ERR_CONFIG;
     if (!sv_ok(c.sv[0])) return RAZER_ERR_CONFIG;
-    if (c.format == RAZER_FMT_WEIGHT && !sv_ok(c.sv[1])) return RAZER_ERR_CONFIG;
+    if (c.format != RAZER_FMT_ACT && !sv_ok(c.sv[1])) return RAZER_ERR_CONFIG;
     out.sv0 = c.sv[0];
-    out.sv1 = (c.format == RAZER_FMT_WEIGHT) ? c.sv[1] : c.sv[0];
+    out.sv1 = (c.format != RAZER_FMT_ACT) ? c.sv[1] : c.sv[0];
+    out.f16 = 0;
+    if (c.format == RAZER_FMT_WEIGHT_F16) {                     // blocks of 128 only, 16-bit scale words
+        if (c.block != 0 && c.block != 128) return RAZER_ERR_CONFIG;
+        out.lb = 7;
+        out.f16 = 1;
+        return RAZER_OK;
+    }
     switch (c.block) {
         case 0: case 16: out.lb = 4; break;
         case 32: out.lb = 5; break;
@@ -46,7 +54,9 @@ razer_status check_tensor(const razer_tensor* t, int want_fmt, SvConfig& cfg)
     razer_status s = check_cfg(t->cfg, cfg);
     if (s != RAZER_OK) return s;
     if (t->rows < 0 || !cols_ok(t->cols, cfg)) return RAZER_ERR_SHAPE;
-    if (want_fmt >= 0 && t->cfg.format != want_fmt) return RAZER_ERR_CONFIG;
+    // a weight operand may be in either weight format
+    const int fmt_class = (t->cfg.format == RAZER_FMT_WEIGHT_F16) ? RAZER_FMT_WEIGHT : t->cfg.format;
+    if (want_fmt >= 0 && fmt_class != want_fmt) return RAZER_ERR_CONFIG;
     if (!t->tensor_scale) return RAZER_ERR_NULL;
     if (t->rows > 0 && t->cols > 0) {
         if (!t->codes || !t->scales) return RAZER_ERR_NULL;
@@ -161,6 +171,12 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
         const int64_t total = m * n;
         fill_zero_bf16_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((uint16_t*)y_bf16, m, n, ld_y);
         e = hipGetLastError();
+    } else if (wsv.f16) {
+        // FP16-scale format: built for the decode regime; more activation rows go through the same
+        // kernels in passes of 4
+        if (a_q) return RAZER_ERR_CONFIG;
+        e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
+                        (uint16_t*)y_bf16, ld_y, st);
     } else if (!a_q && m > kGemvDirectMaxM && m <= kSkinnyMaxM) {
         const size_t need = skinny_workspace_bytes(n, k, m);
         if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return RAZER_ERR_WORKSPACE;

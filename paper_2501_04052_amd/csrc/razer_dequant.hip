@@ -22,8 +22,11 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict_
     const float ts = *tensor_scale;
     const uint2 cw = *reinterpret_cast<const uint2*>(codes + r * (cols / 2) + b * 8);
     float s, sv;
-    decode_scale_byte<FMT>(scales[r * (nb >> (cfg.lb - 4)) + (b >> (cfg.lb - 4))], cfg.sv0, cfg.sv1, s, sv);
-    const float ssv = s * sv;                                   // exact: <= 9 significant bits
+    if (FMT == 2)                                               // one 16-bit scale word per 128 elements
+        decode_scale_word(reinterpret_cast<const uint16_t*>(scales)[r * (nb >> 3) + (b >> 3)], cfg.sv0, cfg.sv1, s, sv);
+    else
+        decode_scale_byte<FMT>(scales[r * (nb >> (cfg.lb - 4)) + (b >> (cfg.lb - 4))], cfg.sv0, cfg.sv1, s, sv);
+    const float ssv = s * sv;                                   // exact: <= 9 significant bits (<= 16 with a half scale)
     float w[kBlock];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -65,8 +68,9 @@ hipError_t launch_dequant(int fmt, SvConfig cfg, const uint8_t* codes, const uin
     if (nblk == 0) return hipSuccess;
     const unsigned grid = (unsigned)((nblk + 255) / 256);
 #define RAZER_DQ(F, B) dequant_kernel<F, B><<<grid, 256, 0, st>>>(codes, scales, tensor_scale, cfg, rows, cols, out, ld)
-    if (fmt == 0) { if (dtype_bf16) RAZER_DQ(0, true); else RAZER_DQ(0, false); }
-    else          { if (dtype_bf16) RAZER_DQ(1, true); else RAZER_DQ(1, false); }
+    if (fmt == 0)      { if (dtype_bf16) RAZER_DQ(0, true); else RAZER_DQ(0, false); }
+    else if (fmt == 1) { if (dtype_bf16) RAZER_DQ(1, true); else RAZER_DQ(1, false); }
+    else               { if (dtype_bf16) RAZER_DQ(2, true); else RAZER_DQ(2, false); }
 #undef RAZER_DQ
     return hipGetLastError();
 }

@@ -24,6 +24,7 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 struct SvConfig {          // special-value magnitudes and log2(block size), already validated on the host
     float sv0, sv1;
     int lb = 4;
+    int f16 = 0;           // 1: one 16-bit scale word per block of 128 (sign | selector | 14 low bits of an IEEE half)
 };
 
 // The two scale bytes (low byte first) that govern the 32 consecutive elements starting at element
@@ -71,6 +72,20 @@ __device__ __forceinline__ void decode_scale_byte(uint32_t sb, float sv0, float 
         s = e4m3_value(sb & 127u);
         sv = u2f(f2u(sv0) | ((sb & 0x80u) << 24));
     }
+}
+
+// The FP16-scale weight format of the paper's weight-only kernel (Sec. 4.3): the low 14 bits of the
+// scale word are an IEEE half with its exponent MSB clear (values below 2), bit 15 the sign of the
+// special value, bit 14 its selector.
+__device__ __forceinline__ float half14_value(uint32_t w)
+{
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0x3FFFu));
+}
+__device__ __forceinline__ void decode_scale_word(uint32_t w, float sv0, float sv1, float& s, float& sv)
+{
+    s = half14_value(w);
+    const uint32_t mag = (w & 0x4000u) ? f2u(sv1) : f2u(sv0);
+    sv = u2f(mag | ((w & 0x8000u) << 16));
 }
 
 // fp32 -> bf16 bits, round to nearest even (finite inputs; NaN kept quiet).

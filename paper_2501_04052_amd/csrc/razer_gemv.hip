@@ -57,7 +57,19 @@ struct RowGroup {
     uint32_t sw[R];
 };
 
-template <int R, bool GB>
+// SF = 0: scale bytes, looked up in the LDS table (decoding them in registers instead was measured
+// 12-20 % slower for blocks of 16 and no faster for larger blocks: these kernels feel every VALU op).
+// SF = 1: the FP16-scale format (one 16-bit word per 128 elements) -- sw holds the word of the block
+// that contains this lane's 32 elements; a half converts to fp32 in one instruction, no table.
+template <bool GB, int SF>
+__device__ __forceinline__ uint32_t load_scale_bits(const uint8_t* __restrict__ scales, int64_t row, int64_t k,
+                                                    int64_t k0, int lb)
+{
+    if (SF == 1) return reinterpret_cast<const uint16_t*>(scales)[row * (k >> 7) + (k0 >> 7)];
+    return load_scale_pair<GB>(scales + row * (k >> lb), k0, lb);
+}
+
+template <int R, bool GB, int SF>
 __device__ __forceinline__ void load_group(RowGroup<R>& g, const uint8_t* __restrict__ codes,
                                            const uint8_t* __restrict__ scales, int64_t row0, int64_t n,
                                            int64_t k, int64_t c, int lb)
@@ -66,14 +78,14 @@ __device__ __forceinline__ void load_group(RowGroup<R>& g, const uint8_t* __rest
     for (int r = 0; r < R; ++r) {
         const int64_t row = (row0 + r < n) ? row0 + r : n - 1;           // clamp: tail rows re-read the last row
         g.cw[r] = *reinterpret_cast<const uint4*>(codes + row * (k / 2) + c * 16);
-        g.sw[r] = load_scale_pair<GB>(scales + row * (k >> lb), c * 32, lb);
+        g.sw[r] = load_scale_bits<GB, SF>(scales, row, k, c * 32, lb);
     }
 }
 
 // sum_k a[m][k] * (scale * element) over this lane's 32 k's, for the R rows of a group.
-template <int M, int R>
+template <int M, int R, int SF = 0>
 __device__ __forceinline__ void dot_group(const RowGroup<R>& g, const uint4 (&av)[M][4], const uint2* lut,
-                                          float (&acc)[R][M])
+                                          float (&acc)[R][M], float sv0 = 0.0f, float sv1 = 0.0f)
 {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -82,7 +94,15 @@ __device__ __forceinline__ void dot_group(const RowGroup<R>& g, const uint4 (&av
         for (int m = 0; m < M; ++m) acc[r][m] = 0.0f;
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
-            const uint2 le = lut[(g.sw[r] >> (8 * blk)) & 255u];
+            uint2 le;
+            if (SF == 1) {                                                // one scale word for all 32 elements
+                float s, sv;
+                decode_scale_word(g.sw[r], sv0, sv1, s, sv);
+                const uint32_t nsv = (uint32_t)f32_to_bf16_rne(-sv);
+                le = make_uint2(f2u(-s), nsv | (nsv << 16));
+            } else {
+                le = lut[(g.sw[r] >> (8 * blk)) & 255u];
+            }
             const float ns = u2f(le.x);
             float p[M];
 #pragma unroll
@@ -114,7 +134,7 @@ __device__ __forceinline__ void dot_group(const RowGroup<R>& g, const uint4 (&av
 // over the 64 lanes and the slice totals parked in LDS; after one barrier the first threads add
 // the slices and write bf16.  The grid is one workgroup per R rows: for the matrices of a decoder
 // layer the whole problem is in flight at once, which is what hides the HBM latency.
-template <int M, int R, bool GB = false>
+template <int M, int R, bool GB = false, int SF = 0>
 __device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                           const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
                                           int64_t k, const uint16_t* __restrict__ a, uint16_t* __restrict__ y,
@@ -144,7 +164,7 @@ __device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, con
                 av[m][j] = make_uint4(t.x & amask, t.y & amask, t.z & amask, t.w & amask);
             }
         }
-        load_group<R, GB>(grp, codes, scales, row0, n, k, cc, lb);
+        load_group<R, GB, SF>(grp, codes, scales, row0, n, k, cc, lb);
     };
     issue_loads();
     fill_weight_lut(lut, sv0, sv1);
@@ -163,7 +183,7 @@ __device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, con
             issue_loads();
         }
         float acc[R][M];
-        dot_group<M, R>(grp, av, lut, acc);
+        dot_group<M, R, SF>(grp, av, lut, acc, sv0, sv1);
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -192,7 +212,7 @@ __device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, con
 // are always in flight while one is decoded.  Wave w owns K-slice w of every row; its 32
 // activations per lane stay in registers for the whole walk.  Slice totals of all G * R rows meet
 // in LDS after ONE barrier.  Row addresses are uniform (scalar) and lane offsets 32-bit.
-template <int M, int R, int G, int D, int P = 1, bool GB = false>
+template <int M, int R, int G, int D, int P = 1, bool GB = false, int SF = 0>
 __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ codes,
                                                  const uint8_t* __restrict__ scales,
                                                  const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
@@ -212,7 +232,7 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     const bool active = c < chunks;
     const uint32_t cc = active ? c : 0u;                                  // idle lanes read chunk 0, weight 0
     const uint32_t amask = active ? 0xFFFFFFFFu : 0u;
-    const int64_t code_ld = k >> 1, scale_ld = k >> lb;
+    const int64_t code_ld = k >> 1;
 
     uint4 av[M][4];
 #pragma unroll
@@ -231,22 +251,23 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
             int64_t row = wrow0 + gi * R + r;
             row = row < n ? row : n - 1;                                  // tail rows re-read the last row
             const uint8_t* crow = codes + row * code_ld;
-            const uint8_t* srow = scales + row * scale_ld;
             g.cw[r] = *reinterpret_cast<const uint4*>(crow + cc * 16u);
-            g.sw[r] = load_scale_pair<GB>(srow, (int64_t)cc * 32, lb);
+            g.sw[r] = load_scale_bits<GB, SF>(scales, row, k, (int64_t)cc * 32, lb);
         }
     };
 #pragma unroll
     for (int d = 0; d < D - 1; ++d)
         if (d < G) load(buf[d], d);
-    fill_weight_lut(lut, sv0, sv1);
-    __syncthreads();                                                      // LUT ready
+    if (SF == 0) {
+        fill_weight_lut(lut, sv0, sv1);
+        __syncthreads();                                                  // LUT ready
+    }
 
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         if (g + D - 1 < G) load(buf[(g + D - 1) % D], g + D - 1);
         float acc[R][M];
-        dot_group<M, R>(buf[g % D], av, lut, acc);
+        dot_group<M, R, SF>(buf[g % D], av, lut, acc, sv0, sv1);
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -266,7 +287,7 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     }
 }
 
-template <int M, int R, int G, int D, int P = 1, bool GB = false>
+template <int M, int R, int G, int D, int P = 1, bool GB = false, int SF = 0>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_kernel(const uint8_t* __restrict__ codes,
                                                                      const uint8_t* __restrict__ scales,
                                                                      const float* __restrict__ w_ts, float sv0,
@@ -274,11 +295,11 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_kernel(const uint8
                                                                      const uint16_t* __restrict__ a,
                                                                      uint16_t* __restrict__ y, int64_t ld_y, int lb)
 {
-    gemv_stream_body<M, R, G, D, P, GB>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y,
-                                        (int64_t)blockIdx.x * (P * R * G), lb);
+    gemv_stream_body<M, R, G, D, P, GB, SF>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y,
+                                            (int64_t)blockIdx.x * (P * R * G), lb);
 }
 
-template <int M, int R, bool GB = false>
+template <int M, int R, bool GB = false, int SF = 0>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __restrict__ codes,
                                                               const uint8_t* __restrict__ scales,
                                                               const float* __restrict__ w_ts, float sv0, float sv1,
@@ -286,7 +307,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __r
                                                               const uint16_t* __restrict__ a,
                                                               uint16_t* __restrict__ y, int64_t ld_y, int lb)
 {
-    gemv_body<M, R, GB>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y, (int64_t)blockIdx.x * R, lb);
+    gemv_body<M, R, GB, SF>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y, (int64_t)blockIdx.x * R, lb);
 }
 
 // Up to four weight matrices that share K, the activation rows and the special values, in one
@@ -354,7 +375,8 @@ static hipError_t launch_gemv_mr(SvConfig cfg, const uint8_t* codes, const uint8
     const int64_t nslices = (k + kSliceK - 1) / kSliceK;
     const int nwaves = (int)(nslices < kMaxWaves ? nslices : kMaxWaves);
     const unsigned grid = (unsigned)((n + R - 1) / R);
-    if (cfg.lb == 4) gemv_kernel<M, R, false><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, 4);
+    if (cfg.f16) gemv_kernel<M, R, true, 1><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, 7);
+    else if (cfg.lb == 4) gemv_kernel<M, R, false><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, 4);
     else gemv_kernel<M, R, true><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, cfg.lb);
     return hipGetLastError();
 }
@@ -371,7 +393,10 @@ static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_
     const int sets = cfg.lb == 4 ? stream_sets(nwaves, groups) : 1;      // blocks of 32..128: the single-set kernels
     const unsigned grid = (unsigned)((n + sets * R * groups - 1) / (sets * R * groups));
 #define RAZER_GEMV_ARGS codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, cfg.lb
-    if (cfg.lb != 4) {
+    if (cfg.f16) {
+        if (groups == 8) gemv_stream_kernel<M, R, 8, 2, 1, true, 1><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
+        else gemv_stream_kernel<M, R, 2, 2, 1, true, 1><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
+    } else if (cfg.lb != 4) {
         if (groups == 8) gemv_stream_kernel<M, R, 8, 2, 1, true><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
         else gemv_stream_kernel<M, R, 2, 2, 1, true><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
     } else if (groups == 8) {

@@ -63,6 +63,12 @@ __global__ __launch_bounds__(256) void absmax_kernel(const T* __restrict__ x, in
 template <int FMT>
 __device__ __forceinline__ uint32_t round_scale(float t)
 {
+    if (FMT == 2) {
+        // the hardware's round-to-nearest-even cast to half; anything that would land on 2.0 or
+        // above saturates at the largest 14-bit code
+        const uint32_t h = __builtin_bit_cast(uint16_t, (_Float16)t);
+        return (t >= 2.0f || h > 0x3FFFu) ? 0x3FFFu : h;
+    }
     constexpr float kMinNormal = (FMT == 0) ? 0.25f : 0.015625f;          // 2^-2 / 2^-6
     constexpr float kSubScale = (FMT == 0) ? 32.0f : 512.0f;              // 1 / subnormal step
     constexpr uint32_t kBiasAdj = (FMT == 0) ? (124u << 3) : (120u << 3);
@@ -89,7 +95,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, in
                                                      float* __restrict__ tensor_scale, int given_scale,
                                                      uint8_t* __restrict__ codes, uint8_t* __restrict__ scales)
 {
-    constexpr int NC = (FMT == 0) ? 4 : 2;
+    constexpr int NC = (FMT == 1) ? 2 : 4;
     const int64_t nb = cols / kBlock;
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
 
@@ -98,7 +104,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, in
         delta32 = *tensor_scale;
     } else {
         float amax = u2f(*absmax_ws);
-        constexpr float kDenom = (FMT == 0) ? 180.0f : 2688.0f;           // Qmax_scale * 6
+        constexpr float kDenom = (FMT == 0) ? 180.0f : (FMT == 1) ? 2688.0f : 11.994140625f;   // Qmax_scale * 6
         delta32 = (amax == 0.0f) ? 1.0f : amax / kDenom;
         if (gid == 0) *tensor_scale = delta32;
     }
@@ -138,13 +144,13 @@ __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, in
     const float d = delta32 * 6.0f;
     const float t = bmax / d;
     const uint32_t sc = round_scale<FMT>(t);
-    const float s = (FMT == 0) ? e3m3_value(sc) : e4m3_value(sc);
+    const float s = (FMT == 0) ? e3m3_value(sc) : (FMT == 1) ? e4m3_value(sc) : half14_value(sc);
 
     uint32_t lo = 0, hi = 0, meta = 0;                                    // 16 nibbles, low dword = k 0..7
     if (s != 0.0f) {
         const float den = delta32 * s;
         double cand[NC];
-        if (FMT == 0) { cand[0] = cfg.sv0; cand[1] = cfg.sv1; cand[2] = -cfg.sv0; cand[3] = -cfg.sv1; }
+        if (FMT != 1) { cand[0] = cfg.sv0; cand[1] = cfg.sv1; cand[2] = -cfg.sv0; cand[3] = -cfg.sv1; }
         else { cand[0] = cfg.sv0; cand[1] = -cfg.sv0; }
         double sse[NC];
         uint32_t take[NC];                                                // bit k: element k takes the special value
@@ -217,7 +223,10 @@ __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, in
         hi = finish(hi, (tk >> 8) & 0xFFu);
     }
     *reinterpret_cast<uint2*>(codes + r * (cols / 2) + b * 8) = make_uint2(lo, hi);
-    if ((b & (G - 1)) == 0) scales[r * (nb / G) + b / G] = (uint8_t)((meta << (FMT == 0 ? 6 : 7)) | sc);
+    if ((b & (G - 1)) == 0) {
+        if (FMT == 2) reinterpret_cast<uint16_t*>(scales)[r * (nb / G) + b / G] = (uint16_t)((meta << 14) | sc);
+        else scales[r * (nb / G) + b / G] = (uint8_t)((meta << (FMT == 0 ? 6 : 7)) | sc);
+    }
 }
 
 // ---------------------------------------------------------------- host launchers
@@ -260,7 +269,8 @@ static hipError_t launch_quantize_t(int fmt, SvConfig cfg, const T* x, int64_t r
     int64_t nblk = rows * (cols / kBlock);
     unsigned grid = (unsigned)((nblk + 255) / 256);
     if (fmt == 0) launch_encode<T, 0>(cfg.lb, grid, 256, st, x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
-    else launch_encode<T, 1>(cfg.lb, grid, 256, st, x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
+    else if (fmt == 1) launch_encode<T, 1>(cfg.lb, grid, 256, st, x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
+    else encode_kernel<T, 2, 8><<<grid, 256, 0, st>>>(x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
     return hipGetLastError();
 }
 

@@ -27,4 +27,7 @@ def max_rel_err(y_gpu_bits, y_ref_f64):
 
 
 def tensor_to_host(t):
-    return (t.codes.cpu().numpy(), t.scales.cpu().numpy(), np.float32(t.tensor_scale.cpu().numpy()[0]))
+    scales = t.scales.cpu().numpy()
+    if scales.dtype == np.int16:                       # 16-bit scale words of the FP16-scale format
+        scales = scales.view(np.uint16)
+    return (t.codes.cpu().numpy(), scales, np.float32(t.tensor_scale.cpu().numpy()[0]))

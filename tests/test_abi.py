@@ -84,6 +84,12 @@ def test_bad_arguments_return_status_codes_without_gpu(razer):
     t128.rows = 8; t128.cols = 64; t128.cfg = cb                  # 64 columns cannot hold a block of 128
     assert L.razer_dequant(ctypes.byref(t128), fake, 0, 64, None) == 2
     assert L.razer_linear(ctypes.byref(t128), fake, None, 1, fake, 8, None, 0, None) == 2
+    # the FP16-scale weight format: blocks of 128 only, columns in whole blocks
+    for blk, cols, want in ((16, 128, 4), (64, 128, 4), (32, 256, 4), (0, 192, 2), (128, 64, 2)):
+        c5 = _Config(); c5.format = 2; c5.sv[0] = 5.0; c5.sv[1] = 8.0; c5.block = blk
+        assert q(cfg=ctypes.byref(c5), cols=cols, ld=cols) == want, (blk, cols)
+    c6 = _Config(); c6.format = 2; c6.sv[0] = 5.0; c6.sv[1] = 6.0                    # second special value invalid
+    assert q(cfg=ctypes.byref(c6), cols=128, ld=128) == 4
     # linear: both or neither activation operand, wrong formats, shape mismatches
     assert L.razer_linear(ctypes.byref(t), None, None, 1, fake, 8, None, 0, None) == 1
     assert L.razer_linear(ctypes.byref(t), None, None, 0, None, 8, None, 0, None) == 0
