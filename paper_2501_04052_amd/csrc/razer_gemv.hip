@@ -227,16 +227,19 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     // The wave index is uniform over the wavefront: telling the compiler so moves the row arithmetic
     // (clamps, 64-bit row offsets; ~90 of ~540 vector instructions) to the scalar unit.  Measured 3-7 %
     // faster on the long launches of a 70B-shaped layer (one wave set) and 5 % slower on the shortest
-    // 7B launch (two wave sets, 4 us: the scalar chain delays the first loads), hence only for P = 1.
+    // 7B launch (two wave sets, 4 us: the scalar chain delays the first loads) and 2-3 % slower with 8
+    // groups per workgroup, hence only for P = 1, G = 2.
     const uint32_t lane = threadIdx.x & 63u, nwaves = (blockDim.x >> 6) / P;
-    const uint32_t wid = (P == 1) ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) : (threadIdx.x >> 6);
+    const uint32_t wid = (P == 1 && G == 2) ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) : (threadIdx.x >> 6);
     const uint32_t wave = wid % nwaves, par = wid / nwaves;
     const int64_t wrow0 = row0 + (int64_t)par * (R * G);
     const uint32_t chunks = (uint32_t)(k >> 5);                           // 16-byte code chunks per row
     const uint32_t c = wave * 64u + lane;
     const bool active = c < chunks;
-    const uint32_t cc = active ? c : 0u;                                  // idle lanes read chunk 0, weight 0
-    const uint32_t amask = active ? 0xFFFFFFFFu : 0u;
+    // Idle lanes (K not a multiple of 2048) read chunk 0 of everything and get their scale bits
+    // cleared: scale code 0 decodes to 0.0, so whatever they accumulate is multiplied by zero.
+    const uint32_t cc = active ? c : 0u;
+    const uint32_t smask = active ? 0xFFFFFFFFu : 0u;
     const int64_t code_ld = k >> 1;
 
     uint4 av[M][4];
@@ -244,10 +247,7 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     for (int m = 0; m < M; ++m) {
         const uint8_t* ap = reinterpret_cast<const uint8_t*>(a + (int64_t)m * k);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint4 t = *reinterpret_cast<const uint4*>(ap + (cc * 64u + 16u * j));
-            av[m][j] = make_uint4(t.x & amask, t.y & amask, t.z & amask, t.w & amask);
-        }
+        for (int j = 0; j < 4; ++j) av[m][j] = *reinterpret_cast<const uint4*>(ap + (cc * 64u + 16u * j));
     }
     RowGroup<R> buf[D];
     auto load = [&](RowGroup<R>& g, int gi) {
@@ -257,7 +257,7 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
             row = row < n ? row : n - 1;                                  // tail rows re-read the last row
             const uint8_t* crow = codes + row * code_ld;
             g.cw[r] = *reinterpret_cast<const uint4*>(crow + cc * 16u);
-            g.sw[r] = load_scale_bits<GB, SF>(scales, row, k, (int64_t)cc * 32, lb);
+            g.sw[r] = load_scale_bits<GB, SF>(scales, row, k, (int64_t)cc * 32, lb) & smask;
         }
     };
 #pragma unroll
