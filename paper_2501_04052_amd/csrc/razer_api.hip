@@ -92,7 +92,7 @@ const char* razer_status_string(razer_status s)
 size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m)
 {
     switch (op) {
-        case RAZER_OP_QUANTIZE: return 256;    // the absmax cell of Eq. 1
+        case RAZER_OP_QUANTIZE: return 256;    // the 64 running-maximum cells of Eq. 1
         case RAZER_OP_LINEAR: {                // fp32 partial sums of K-slices (small batch; GEMMs with few tiles)
             const size_t a = skinny_workspace_bytes(rows, cols, m), b = gemm_workspace_bytes(rows, cols, m);
             return a > b ? a : b;

@@ -13,11 +13,21 @@
 namespace razer {
 
 // ---------------------------------------------------------------- absmax (Eq. 1)
-__global__ void absmax_init_kernel(uint32_t* ws) { ws[0] = 0u; }
-
-// One atomic per workgroup and at most kAbsmaxBlocks workgroups: atomics on a single address
-// serialize at roughly 10 ns each, so thousands of them would dominate the pass.
+// The running maximum lives in kAbsmaxCells cells of the workspace (workgroup b updates cell
+// b % kAbsmaxCells): atomics on a single address serialize at roughly 10 ns each, so a thousand
+// workgroups on one cell cost more than the pass over a 32 MB tensor itself.
+constexpr int kAbsmaxCells = 64;
 constexpr int kAbsmaxBlocks = 1024;
+__global__ void absmax_init_kernel(uint32_t* ws) { ws[threadIdx.x] = 0u; }
+
+// max over the cells, by every wavefront that needs it (64 lanes, one cell each)
+__device__ __forceinline__ float absmax_from_cells(const uint32_t* __restrict__ ws)
+{
+    uint32_t m = ws[threadIdx.x & 63u];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+    return u2f(m);
+}
 
 template <typename T>
 __global__ __launch_bounds__(256) void absmax_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
@@ -55,7 +65,7 @@ __global__ __launch_bounds__(256) void absmax_kernel(const T* __restrict__ x, in
     for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
     if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = m;
     __syncthreads();
-    if (threadIdx.x == 0) atomicMax(ws, max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3])));
+    if (threadIdx.x == 0) atomicMax(ws + (blockIdx.x % kAbsmaxCells), max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3])));
 }
 
 // ---------------------------------------------------------------- scale rounding (Eq. 2)
@@ -103,7 +113,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, in
     if (given_scale) {
         delta32 = *tensor_scale;
     } else {
-        float amax = u2f(*absmax_ws);
+        float amax = absmax_from_cells(absmax_ws);
         constexpr float kDenom = (FMT == 0) ? 180.0f : (FMT == 1) ? 2688.0f : 11.994140625f;   // Qmax_scale * 6
         delta32 = (amax == 0.0f) ? 1.0f : amax / kDenom;
         if (gid == 0) *tensor_scale = delta32;
@@ -252,14 +262,14 @@ static hipError_t launch_quantize_t(int fmt, SvConfig cfg, const T* x, int64_t r
 {
     if (rows == 0 || cols == 0) {
         if (!given) {                       // an empty tensor gets the all-zero tensor's scale of 1
-            absmax_init_kernel<<<1, 1, 0, st>>>(ws);
+            absmax_init_kernel<<<1, kAbsmaxCells, 0, st>>>(ws);
             if (fmt == 0) launch_encode<T, 0>(4, 1, 64, st, x, 0, 16, 16, cfg, ws, tensor_scale, 0, codes, scales);
             else launch_encode<T, 1>(4, 1, 64, st, x, 0, 16, 16, cfg, ws, tensor_scale, 0, codes, scales);
         }
         return hipGetLastError();
     }
     if (!given) {
-        absmax_init_kernel<<<1, 1, 0, st>>>(ws);
+        absmax_init_kernel<<<1, kAbsmaxCells, 0, st>>>(ws);
         constexpr int VEC = 16 / sizeof(T);
         int64_t total = rows * (cols / VEC);
         int64_t blocks = (total + 255) / 256;
