@@ -152,6 +152,21 @@ def test_linear_gemv_matches_oracle(oracle, m, n, k):
     assert err <= TOL, err
 
 
+@pytest.mark.parametrize("m,n,k", [(3, 16400, 544), (4, 16389, 8192 + 512), (4, 16384, 2048)])
+def test_linear_gemv_many_rows_matches_oracle(oracle, m, n, k):
+    """3-4 activation rows against at least 16384 weight rows: the matrix-instruction GEMV with 8
+    groups of rows per workgroup (one and two 512-element runs per lane), ragged last workgroup."""
+    print("gemv many rows", m, n, k, flush=True)
+    rng = np.random.default_rng(450 + m + k)
+    wq = _rand_tensor(rng, W, n, k)
+    wt = razer.RazerTensor.from_host(*wq, W, (5.0, 8.0))
+    a = synth.activation(m, k, seed=451 + m)
+    y = razer.razer_linear(wt, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    y64, _ = oracle.linear(wq, a_bf16=a)
+    assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
+
+
 @pytest.mark.parametrize("m,n,k", [(5, 40, 64), (8, 300, 1056), (16, 256, 2048), (33, 100, 96), (64, 513, 1024),
                                    (17, 70, 32), (32, 129, 4096 + 32), (12, 65, 8192 + 512), (31, 64, 544),
                                    (100, 130, 4096), (129, 384, 512), (300, 260, 1120), (512, 512, 1024),
