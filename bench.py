@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the RaZeR W4A16 / W4A4 linear path on one MI355X.
 
-Headline (the benchmark spec): HBM GB/s of the fused-decode GEMV at M=1 over a
+Headline: HBM GB/s of the fused-decode GEMV at M=1 over a
 Llama-7B-shaped decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; down
 4096x11008), weights resident in HBM in RaZeR form.  One timed "step" is one
 pass over the seven projections at M=1; enough distinct copies of the packed
