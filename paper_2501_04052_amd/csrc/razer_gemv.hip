@@ -376,7 +376,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
 // of 512 elements), walks G groups of four rows with the next group's loads in flight, partial sums
 // of the waves meet in LDS.  Idle lanes (K tail) are silenced through their scale bits; activation
 // rows past M are never masked, their product columns are simply not stored.
-template <int C, int G, int D, int P, int MS>
+template <int C, int G, int D, int P, int MS, int PS = 1>
 __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                                const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
                                                int64_t k, const uint16_t* __restrict__ a, int64_t m,
@@ -394,103 +394,113 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
     const int64_t wrow0 = row0 + (int64_t)par * (R * G);
     const int64_t code_ld = k >> 1, scale_ld = k >> 4;
 
-    uint32_t koff[C], smask[C];                        // element offset of this lane's run c; 0 / all-ones
-#pragma unroll
-    for (int c = 0; c < C; ++c) {
-        const uint32_t kk = (wave * C + c) * 512u + 32u * b;
-        const bool in = kk < (uint32_t)k;
-        koff[c] = in ? kk : 0u;
-        smask[c] = in ? 0xFFFFFFFFu : 0u;
-    }
-    uint4 av[MS][C][4];                                // activation row 4 s + q, this lane's runs
-#pragma unroll
-    for (int s = 0; s < MS; ++s) {
-        const int64_t mrow = (4 * s + (int)q < m) ? 4 * s + (int)q : 0;      // rows past M re-read row 0
-        const uint8_t* ap = reinterpret_cast<const uint8_t*>(a + mrow * k);
-#pragma unroll
-        for (int c = 0; c < C; ++c)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) av[s][c][j] = *reinterpret_cast<const uint4*>(ap + (koff[c] * 2u + 16u * j));
-    }
     struct Quad {
         uint4 cw[C];
         uint32_t sw[C];
     };
-    Quad buf[D];
-    auto load = [&](Quad& g, int gi) {
-        int64_t row = wrow0 + gi * R + q;
-        row = row < n ? row : n - 1;                                      // tail rows re-read the last row
-        const uint8_t* crow = codes + row * code_ld;
-        const uint8_t* srow = scales + row * scale_ld;
+    v4f acc[G][MS];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int s = 0; s < MS; ++s) acc[g][s] = v4f{0.f, 0.f, 0.f, 0.f};
+    // A wave's K-slice is PS passes of C runs of 512 elements; the activations of one pass are in
+    // registers at a time and every pass walks all G groups, adding to their running sums.
+#pragma unroll 1                                       // a real loop: unrolled, the second pass's loads get hoisted and spill
+    for (int ps = 0; ps < PS; ++ps) {
+        uint32_t koff[C], smask[C];                    // element offset of this lane's run c; 0 / all-ones
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            g.cw[c] = *reinterpret_cast<const uint4*>(crow + (koff[c] >> 1));
-            g.sw[c] = *reinterpret_cast<const uint16_t*>(srow + (koff[c] >> 4)) & smask[c];
+            const uint32_t kk = ((wave * PS + ps) * C + c) * 512u + 32u * b;
+            const bool in = kk < (uint32_t)k;
+            koff[c] = in ? kk : 0u;
+            smask[c] = in ? 0xFFFFFFFFu : 0u;
         }
-    };
-    load(buf[0], 0);
-    fill_weight_lut(lut, sv0, sv1);
-    __syncthreads();                                                      // LUT ready
-
+        uint4 av[MS][C][4];                            // activation row 4 s + q, this lane's runs
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        if (g + 1 < G) load(buf[(g + 1) % D], g + 1);
-        const Quad& cur = buf[g % D];
-        v4f acc[MS];
+        for (int s = 0; s < MS; ++s) {
+            const int64_t mrow = (4 * s + (int)q < m) ? 4 * s + (int)q : 0;      // rows past M re-read row 0
+            const uint8_t* ap = reinterpret_cast<const uint8_t*>(a + mrow * k);
 #pragma unroll
-        for (int s = 0; s < MS; ++s) acc[s] = v4f{0.f, 0.f, 0.f, 0.f};
+            for (int c = 0; c < C; ++c)
 #pragma unroll
-        for (int c = 0; c < C; ++c) {
-            const uint32_t xw[4] = {cur.cw[c].x, cur.cw[c].y, cur.cw[c].z, cur.cw[c].w};
+                for (int j = 0; j < 4; ++j) av[s][c][j] = *reinterpret_cast<const uint4*>(ap + (koff[c] * 2u + 16u * j));
+        }
+        Quad buf[D];
+        auto load = [&](Quad& g, int gi) {
+            int64_t row = wrow0 + gi * R + q;
+            row = row < n ? row : n - 1;                                  // tail rows re-read the last row
+            const uint8_t* crow = codes + row * code_ld;
+            const uint8_t* srow = scales + row * scale_ld;
 #pragma unroll
-            for (int blk = 0; blk < 2; ++blk) {
-                const uint2 le = lut[(cur.sw[c] >> (8 * blk)) & 255u];
-                v4f tmp[MS];
+            for (int c = 0; c < C; ++c) {
+                g.cw[c] = *reinterpret_cast<const uint4*>(crow + (koff[c] >> 1));
+                g.sw[c] = *reinterpret_cast<const uint16_t*>(srow + (koff[c] >> 4)) & smask[c];
+            }
+        };
+        load(buf[0], 0);
+        if (ps == 0) {                                                    // the first loads are in flight meanwhile
+            fill_weight_lut(lut, sv0, sv1);
+            __syncthreads();                                              // LUT ready
+        }
 #pragma unroll
-                for (int s = 0; s < MS; ++s) tmp[s] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int g = 0; g < G; ++g) {
+            if (g + 1 < G) load(buf[(g + 1) % D], g + 1);
+            const Quad& cur = buf[g % D];
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const uint32_t x = xw[2 * blk + h] ^ kRemapXor;
-                    const uint32_t w0 = patch_zero_halves(cvt_pair<0>(x), le.y);
-                    const uint32_t w1 = patch_zero_halves(cvt_pair<1>(x), le.y);
-                    const uint32_t w2 = patch_zero_halves(cvt_pair<2>(x), le.y);
-                    const uint32_t w3 = patch_zero_halves(cvt_pair<3>(x), le.y);
-                    const v4bf wa = __builtin_bit_cast(v4bf, make_uint2(w0, w1));
-                    const v4bf wb = __builtin_bit_cast(v4bf, make_uint2(w2, w3));
+            for (int c = 0; c < C; ++c) {
+                const uint32_t xw[4] = {cur.cw[c].x, cur.cw[c].y, cur.cw[c].z, cur.cw[c].w};
+#pragma unroll
+                for (int blk = 0; blk < 2; ++blk) {
+                    const uint2 le = lut[(cur.sw[c] >> (8 * blk)) & 255u];
+                    v4f tmp[MS];
+#pragma unroll
+                    for (int s = 0; s < MS; ++s) tmp[s] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t x = xw[2 * blk + h] ^ kRemapXor;
+                        const uint32_t w0 = patch_zero_halves(cvt_pair<0>(x), le.y);
+                        const uint32_t w1 = patch_zero_halves(cvt_pair<1>(x), le.y);
+                        const uint32_t w2 = patch_zero_halves(cvt_pair<2>(x), le.y);
+                        const uint32_t w3 = patch_zero_halves(cvt_pair<3>(x), le.y);
+                        const v4bf wa = __builtin_bit_cast(v4bf, make_uint2(w0, w1));
+                        const v4bf wb = __builtin_bit_cast(v4bf, make_uint2(w2, w3));
+#pragma unroll
+                        for (int s = 0; s < MS; ++s) {
+                            const uint4 aq = av[s][c][2 * blk + h];
+                            tmp[s] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(wa, __builtin_bit_cast(v4bf, make_uint2(aq.x, aq.y)), tmp[s], 0, 0, 0);
+                            tmp[s] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(wb, __builtin_bit_cast(v4bf, make_uint2(aq.z, aq.w)), tmp[s], 0, 0, 0);
+                        }
+                    }
+                    // register i of tmp belongs to weight row i, whose (negated) block scale sits in quad lane i
+                    const int nsb = (int)le.x;
+                    const float s0 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0x00, 0xF, 0xF, false));
+                    const float s1 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0x55, 0xF, 0xF, false));
+                    const float s2 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0xAA, 0xF, 0xF, false));
+                    const float s3 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0xFF, 0xF, 0xF, false));
 #pragma unroll
                     for (int s = 0; s < MS; ++s) {
-                        const uint4 aq = av[s][c][2 * blk + h];
-                        tmp[s] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(wa, __builtin_bit_cast(v4bf, make_uint2(aq.x, aq.y)), tmp[s], 0, 0, 0);
-                        tmp[s] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(wb, __builtin_bit_cast(v4bf, make_uint2(aq.z, aq.w)), tmp[s], 0, 0, 0);
+                        acc[g][s][0] = __builtin_fmaf(s0, tmp[s][0], acc[g][s][0]);
+                        acc[g][s][1] = __builtin_fmaf(s1, tmp[s][1], acc[g][s][1]);
+                        acc[g][s][2] = __builtin_fmaf(s2, tmp[s][2], acc[g][s][2]);
+                        acc[g][s][3] = __builtin_fmaf(s3, tmp[s][3], acc[g][s][3]);
                     }
                 }
-                // register i of tmp belongs to weight row i, whose (negated) block scale sits in quad lane i
-                const int nsb = (int)le.x;
-                const float s0 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0x00, 0xF, 0xF, false));
-                const float s1 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0x55, 0xF, 0xF, false));
-                const float s2 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0xAA, 0xF, 0xF, false));
-                const float s3 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0xFF, 0xF, 0xF, false));
+            }
+            if (ps == PS - 1) {
+                // sum over the 16 runs of the wavefront: within each row of 16 lanes by DPP, across the rows by shuffles
 #pragma unroll
-                for (int s = 0; s < MS; ++s) {
-                    acc[s][0] = __builtin_fmaf(s0, tmp[s][0], acc[s][0]);
-                    acc[s][1] = __builtin_fmaf(s1, tmp[s][1], acc[s][1]);
-                    acc[s][2] = __builtin_fmaf(s2, tmp[s][2], acc[s][2]);
-                    acc[s][3] = __builtin_fmaf(s3, tmp[s][3], acc[s][3]);
-                }
+                for (int s = 0; s < MS; ++s)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float v = acc[g][s][i];
+                        v = dpp_add<0x114>(v);                            // row_shr:4
+                        v = dpp_add<0x118>(v);                            // row_shr:8 -> lanes 12..15 of each row
+                        v += __shfl_xor(v, 16);
+                        v += __shfl_xor(v, 32);
+                        if ((lane & 60u) == 12u) part[((par * G + g) * R + i) * (4 * MS) + 4 * s + q][wave] = v;
+                    }
             }
         }
-        // sum over the 16 runs of the wavefront: within each row of 16 lanes by DPP, across the rows by shuffles
-#pragma unroll
-        for (int s = 0; s < MS; ++s)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float v = acc[s][i];
-                v = dpp_add<0x114>(v);                                    // row_shr:4
-                v = dpp_add<0x118>(v);                                    // row_shr:8 -> lanes 12..15 of each row
-                v += __shfl_xor(v, 16);
-                v += __shfl_xor(v, 32);
-                if ((lane & 60u) == 12u) part[((par * G + g) * R + i) * (4 * MS) + 4 * s + q][wave] = v;
-            }
     }
     __syncthreads();
     for (uint32_t t = threadIdx.x; t < (uint32_t)(P * G * R * 4 * MS); t += blockDim.x) {
@@ -503,18 +513,18 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
     }
 }
 
-template <int C, int G, int D, int P, int MS>
+template <int C, int G, int D, int P, int MS, int PS = 1>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_kernel(const uint8_t* __restrict__ codes,
                                                                    const uint8_t* __restrict__ scales,
                                                                    const float* __restrict__ w_ts, float sv0, float sv1,
                                                                    int64_t n, int64_t k, const uint16_t* __restrict__ a,
                                                                    int64_t m, uint16_t* __restrict__ y, int64_t ld_y)
 {
-    gemv_quad_body<C, G, D, P, MS>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y,
-                                   (int64_t)blockIdx.x * (P * 4 * G));
+    gemv_quad_body<C, G, D, P, MS, PS>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y,
+                                       (int64_t)blockIdx.x * (P * 4 * G));
 }
 
-template <int C, int G, int D, int P, int MS>
+template <int C, int G, int D, int P, int MS, int PS = 1>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
@@ -532,31 +542,35 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_grouped_kernel(
     if (b >= g1) { codes = c1; scales = s1; ts = t1; y = y1; n = n1; ld = l1; first = g1; }
     if (b >= g2) { codes = c2; scales = s2; ts = t2; y = y2; n = n2; ld = l2; first = g2; }
     if (b >= g3) { codes = c3; scales = s3; ts = t3; y = y3; n = n3; ld = l3; first = g3; }
-    gemv_quad_body<C, G, D, P, MS>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, (int64_t)(b - first) * (P * 4 * G));
+    gemv_quad_body<C, G, D, P, MS, PS>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, (int64_t)(b - first) * (P * 4 * G));
 }
 
 // The matrix-instruction kernel serves 3 and 4 activation rows (at 1-2 the dot-product kernel is as
 // fast): measured 7-32 % faster at M = 4 over the projection shapes of 7B- and 70B-class layers.  One
-// 512-element run per lane while that needs at most 16 waves (K <= 8192), two up to K = 16384; longer
-// rows stay with the dot-product kernel (four runs per lane do not fit the register budget of a
-// 16-wave workgroup).  4 groups of 4 rows per workgroup, 8 when the launch has at least 16384 rows.
+// 512-element run per lane while that needs at most 16 waves (K <= 8192), two up to K = 16384, two
+// passes of two up to K = 32768 (four runs at once do not fit the register budget of a 16-wave
+// workgroup); longer rows stay with the dot-product kernel.  4 groups of 4 rows per workgroup, 8 when
+// the launch has at least 16384 rows.
 static inline bool quad_fits(const SvConfig& cfg, int64_t k, int64_t m)
 {
-    return (m == 3 || m == 4) && cfg.lb == 4 && !cfg.f16 && k <= 16384;
+    return (m == 3 || m == 4) && cfg.lb == 4 && !cfg.f16 && k <= 32768;
 }
 static inline int quad_runs(int64_t k) { return (k + 511) / 512 <= kMaxWaves ? 1 : 2; }
+static inline int quad_passes(int64_t k) { return k <= 16384 ? 1 : 2; }
 static inline int quad_groups(int64_t rows) { return rows >= 16384 ? 8 : 4; }
 
 static hipError_t launch_gemv_quad(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,
                                    int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
                                    hipStream_t st)
 {
-    const int runs = quad_runs(k), groups = quad_groups(n);
-    const int nwaves = (int)((k + 512 * runs - 1) / (512 * runs));
+    const int runs = quad_runs(k), passes = quad_passes(k);
+    const int groups = passes == 2 ? 4 : quad_groups(n);         // two passes keep G running sums: 8 groups would spill
+    const int nwaves = (int)((k + 512 * runs * passes - 1) / (512 * runs * passes));
     const unsigned grid = (unsigned)((n + 4 * groups - 1) / (4 * groups));
-#define RAZER_QUAD(C, G) gemv_quad_kernel<C, G, 2, 1, 1><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y)
-    if (runs == 1) { if (groups == 8) RAZER_QUAD(1, 8); else RAZER_QUAD(1, 4); }
-    else           { if (groups == 8) RAZER_QUAD(2, 8); else RAZER_QUAD(2, 4); }
+#define RAZER_QUAD(C, G, PS) gemv_quad_kernel<C, G, 2, 1, 1, PS><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y)
+    if (passes == 2)    { RAZER_QUAD(2, 4, 2); }
+    else if (runs == 1) { if (groups == 8) RAZER_QUAD(1, 8, 1); else RAZER_QUAD(1, 4, 1); }
+    else                { if (groups == 8) RAZER_QUAD(2, 8, 1); else RAZER_QUAD(2, 4, 1); }
 #undef RAZER_QUAD
     return hipGetLastError();
 }
@@ -566,8 +580,9 @@ static hipError_t launch_gemv_quad_grouped(SvConfig cfg, int count, const GemvPr
 {
     int64_t rows = 0;
     for (int i = 0; i < count; ++i) rows += p[i].n;
-    const int runs = quad_runs(k), groups = quad_groups(rows);
-    const int nwaves = (int)((k + 512 * runs - 1) / (512 * runs));
+    const int runs = quad_runs(k), passes = quad_passes(k);
+    const int groups = passes == 2 ? 4 : quad_groups(rows);
+    const int nwaves = (int)((k + 512 * runs * passes - 1) / (512 * runs * passes));
     const int64_t rows_per_wg = 4 * groups;
     GemvProblem q[4];
     unsigned g[5] = {0, 0, 0, 0, 0};
@@ -575,12 +590,13 @@ static hipError_t launch_gemv_quad_grouped(SvConfig cfg, int count, const GemvPr
         q[i] = p[i < count ? i : count - 1];
         g[i + 1] = g[i] + (i < count ? (unsigned)((q[i].n + rows_per_wg - 1) / rows_per_wg) : 0u);
     }
-#define RAZER_QUADG(C, G) gemv_quad_grouped_kernel<C, G, 2, 1, 1><<<g[4], 64 * nwaves, 0, st>>>(                      \
+#define RAZER_QUADG(C, G, PS) gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS><<<g[4], 64 * nwaves, 0, st>>>(                      \
         q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts, \
         q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,        \
         q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m)
-    if (runs == 1) { if (groups == 8) RAZER_QUADG(1, 8); else RAZER_QUADG(1, 4); }
-    else           { if (groups == 8) RAZER_QUADG(2, 8); else RAZER_QUADG(2, 4); }
+    if (passes == 2)    { RAZER_QUADG(2, 4, 2); }
+    else if (runs == 1) { if (groups == 8) RAZER_QUADG(1, 8, 1); else RAZER_QUADG(1, 4, 1); }
+    else                { if (groups == 8) RAZER_QUADG(2, 8, 1); else RAZER_QUADG(2, 4, 1); }
 #undef RAZER_QUADG
     return hipGetLastError();
 }
