@@ -14,6 +14,10 @@
 // streaming kernel (groups of 2 rows, next group in flight while one is decoded);
 // longer rows take the multi-pass kernel (4 rows per workgroup).
 //
+// Three and four activation rows take a variant of the streaming kernel that multiplies on the
+// 4x4x4 matrix instruction (gemv_quad_kernel, further down): with v_dot2 every activation row costs
+// another half operation per weight and the kernel turns VALU-bound.
+//
 // Decode.  The 8 codes of a dword are sign-flipped with one xor, converted to
 // packed bf16 pairs by the hardware FP4 conversion, and the (now all-zero)
 // remapped slots are patched with the block's special value by two packed
