@@ -153,3 +153,50 @@ def test_linear_many_tiles_register_decode_kernel(oracle, m, n, k):
     err = max_rel_err(got, y64)
     _say("   max rel err %.2e over %d x %d sampled outputs" % (err, len(rows), len(cols)))
     assert err <= TOL, err
+
+
+@pytest.mark.parametrize("m", [1, 4, 16, 512, 2048])
+def test_config2_3_grouped_launches_as_benchmarked(oracle, m):
+    """The launch configuration bench.py times: {q,k,v} and {gate,up} of the Llama-7B-shaped layer each
+    as ONE razer_linear_grouped call (grouped GEMV, matrix-instruction GEMV, grouped small-batch kernel
+    with its grouped reduction, grouped register-decode GEMM).  Whole outputs up to M = 16, sampled
+    rows x columns beyond."""
+    _say("grouped launches at full size, m=%d" % m)
+    a = synth.activation(m, 4096, seed=2100 + m)
+    a_dev = bf16_bits_to_dev(a)
+    for name, n, count, seed in (("qkv", 4096, 3, 8000), ("gate_up", 11008, 2, 8100)):
+        wqs = [_rand_packed(n, 4096, seed=seed + i + m) for i in range(count)]
+        wts = [razer.RazerTensor.from_host(*wq, W, SV) for wq in wqs]
+        ys = razer.razer_linear_grouped(wts, a_dev)
+        torch.cuda.synchronize()
+        if m <= 16:
+            rows, cols = np.arange(m), np.arange(n)
+        else:
+            rows = np.unique(np.concatenate([synth.sample_indices(m, 32, 9200), [0, m - 1]]))
+            cols = np.unique(np.concatenate([synth.sample_indices(n, 128, 9201), [0, n - 1]]))
+        for wq, y in zip(wqs, ys):
+            y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=cols)
+            got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+            err = max_rel_err(got, y64)
+            _say("   %s m=%d: %d x %d outputs, max rel err %.2e" % (name, m, len(rows), len(cols), err))
+            assert err <= TOL, err
+
+
+def test_config4_grouped_launches_as_benchmarked(oracle):
+    """70B-shaped {q,k,v} (8192 + 1024 + 1024 rows) as one grouped call at M = 1, 8 and 4096."""
+    wqs = [_rand_packed(n, 8192, seed=8200 + i) for i, n in enumerate((8192, 1024, 1024))]
+    wts = [razer.RazerTensor.from_host(*wq, W, SV) for wq in wqs]
+    for m in (1, 8, 4096):
+        _say("70B grouped q,k,v m=%d" % m)
+        a = synth.activation(m, 8192, seed=4100 + m)
+        ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a))
+        torch.cuda.synchronize()
+        rows = np.arange(m) if m <= 8 else np.unique(np.concatenate([synth.sample_indices(m, 32, 9300), [0, m - 1]]))
+        for wq, y in zip(wqs, ys):
+            n = wq[0].shape[0]
+            cols = np.unique(np.concatenate([synth.sample_indices(n, 128, 9301), [0, n - 1]]))
+            y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=cols)
+            got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+            err = max_rel_err(got, y64)
+            _say("   n=%d: max rel err %.2e" % (n, err))
+            assert err <= TOL, err
