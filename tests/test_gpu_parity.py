@@ -459,6 +459,42 @@ def test_linear_on_side_stream_and_under_graph_replay(oracle):
     assert max_rel_err(dev_to_bf16_bits(eager), y64) <= TOL
 
 
+def test_grouped_linear_under_graph_replay(oracle):
+    """The grouped launches (grouped GEMV, matrix-instruction GEMV, grouped small-batch kernel with
+    its grouped reduction through the prepared-call path) captured into a HIP graph: every replay,
+    with eager work in between, equals the eager result bit for bit."""
+    rng = np.random.default_rng(1750)
+    k = 1024 + 64
+    ns = [132, 64, 200]
+    wqs = [_rand_tensor(rng, W, n, k) for n in ns]
+    wts = [razer.RazerTensor.from_host(*wq, W, (5.0, 8.0)) for wq in wqs]
+    side = torch.cuda.Stream()
+    for m in (1, 4, 12):
+        a = synth.activation(m, k, seed=1751 + m)
+        a_dev = bf16_bits_to_dev(a)
+        eager = [y.clone() for y in razer.razer_linear_grouped(wts, a_dev)]
+        outs = [torch.empty((m, n), dtype=torch.bfloat16, device="cuda") for n in ns]
+        call = razer.prepare_linear_grouped(wts, a_dev, outs)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            call(side.cuda_stream)
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                call(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for o in outs:
+                o.fill_(float(rep))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for o, e in zip(outs, eager):
+                assert torch.equal(o, e), (m, rep)
+        for wq, e in zip(wqs, eager):
+            assert max_rel_err(dev_to_bf16_bits(e), oracle.linear(wq, a_bf16=a)[0]) <= TOL
+
+
 def test_linear_is_deterministic(oracle):
     """The kernels that split K (small batch, GEMM with few tiles) add their slices in a fixed order."""
     rng = np.random.default_rng(1800)
