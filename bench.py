@@ -31,7 +31,7 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=200)
     p.add_argument("--warmup", type=int, default=20)
-    p.add_argument("--legs", default="all", help="all | gemv (headline only)")
+    p.add_argument("--legs", default="all", help="all | gemv (headline only) | gemm (headline + the M=2048 GEMM leg)")
     p.add_argument("--ramp-ms", type=float, default=250.0,
                    help="untimed load before every measurement, so it runs at sustained clocks (short for profiler runs)")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -248,22 +248,32 @@ def main():
     dom_bytes = 2 * (11008 * 4096 * 9 // 16 + 2 * 11008 + 4) + 2 * 4096
 
     gemm_roof = None
+
+    def gemm_leg(m):
+        # {q,k,v}, o, {gate,up}, down as four prepared calls, like the decode step
+        ms, _, fl = linear_leg(m, 5, 2, prepared=True)
+        legs["gemm_m%d" % m] = {"TFLOP/s": fl / ms / 1e9, "frac_mfma_bf16": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                                "ms_per_step": ms}
+        return ms, fl
+
+    def gemm_roofline(ms, fl):
+        return {"bound": "mfma", "achieved": fl / ms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "kernel": "gemm_rb_grouped_kernel<4,2,1> ({q,k,v}, {gate,up}) + gemm_rb_kernel<8,2,2> (o, down), "
+                          "M=2048, Llama-7B layer set as 4 calls, flops = 2MNK, whole-leg time"}
+
+    if args.legs == "gemm":                                  # profiler runs: only the M=2048 GEMM leg
+        gemm_roof = gemm_roofline(*gemm_leg(2048))
     if args.legs == "all":
         for m in (4, 16):
             ms, b, _ = linear_leg(m, max(10, args.steps // 4), 5, graph=use_graph, grouped=True)
             legs["linear_m%d" % m] = {"GB/s": b / ms / 1e6, "frac_hbm": b / ms / 1e6 / HBM_PEAK_GBS, "ms_per_step": ms}
         for m in (512, 2048):
-            # {q,k,v}, o, {gate,up}, down as four prepared calls, like the decode step
-            ms, _, fl = linear_leg(m, 5, 2, prepared=True)
-            legs["gemm_m%d" % m] = {"TFLOP/s": fl / ms / 1e9, "frac_mfma_bf16": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-                                    "ms_per_step": ms}
+            ms, fl = gemm_leg(m)
             ms7, _, _ = linear_leg(m, 5, 2, prepared_single=True)
             legs["gemm_m%d_seven_calls" % m] = {"TFLOP/s": fl / ms7 / 1e9, "ms_per_step": ms7}
             if m == 2048:
-                gemm_roof = {"bound": "mfma", "achieved": fl / ms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
-                             "unit": "TFLOP/s", "frac": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                             "kernel": "gemm_rb_grouped_kernel<4,2> ({q,k,v}, {gate,up}) + gemm_pp_kernel<256,128> (o, down), "
-                                       "M=2048, Llama-7B layer set as 4 calls, flops = 2MNK, whole-leg time"}
+                gemm_roof = gemm_roofline(ms, fl)
         # context, not product: the vendor library's dense bf16 GEMM (torch.matmul -> hipBLASLt) on the same
         # seven shapes at M=2048 with already-decoded bf16 weights, i.e. the same contraction with no decode
         dense_w = {(n, k): torch.randn((n, k), generator=gen, device="cuda").to(torch.bfloat16) * 0.02
