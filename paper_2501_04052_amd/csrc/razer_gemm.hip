@@ -569,7 +569,9 @@ __device__ __forceinline__ void gemm_rb_body(
     uint8_t* Bs = smem + KG * S * A_STAGE;              // S stages x (NW KiB of codes + NW x 256 B of scale-byte pairs)
     uint2* wlut = reinterpret_cast<uint2*>(smem + KG * S * A_STAGE + S * B_STAGE);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the wave index is uniform: as a scalar it keeps the LDS destinations of the copies (M0) and the
+    // base addresses below on the scalar unit
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kg = wave / NWN, wn = wave % NWN;         // K group, position along N
     const int r = lane & 31, h = lane >> 5;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
@@ -582,6 +584,14 @@ __device__ __forceinline__ void gemm_rb_body(
     wrow = wrow < n ? wrow : n - 1;                     // rows past N re-read the last row, never stored
     const uint8_t* crow = w_codes + wrow * (k / 2) + 16 * h;
     const uint8_t* srow = w_scales + wrow * (k / 16) + 2 * h;
+    // the same addresses as a uniform base (first row of the wave, advanced per K-tile on the scalar
+    // unit) plus a 32-bit lane offset that never changes: a full K-tile's copies need no vector
+    // address arithmetic at all
+    const int64_t wrow_first = (n0 + 32 * wn < n) ? n0 + 32 * wn : n - 1;
+    const uint8_t* cfirst = w_codes + wrow_first * (k / 2);
+    const uint8_t* sfirst = w_scales + wrow_first * (k / 16);
+    const uint32_t c_off = (uint32_t)(wrow - wrow_first) * (uint32_t)(k / 2) + 16u * h;
+    const uint32_t s_off = (uint32_t)(wrow - wrow_first) * (uint32_t)(k / 16) + 2u * h;
 
     // Activation copy i of this wave fills LDS rows 8 (wave NU_A + i) .. + 7 of a stage: lane l writes
     // physical chunk l % 8 of row 8 (..) + l / 8, which must hold logical chunk (l % 8) ^ swizzle(row).
@@ -600,6 +610,21 @@ __device__ __forceinline__ void gemm_rb_body(
     }
     // all copies of K-tile kt into stage st (kt already clamped to the last tile by the caller)
     auto issue = [&](int kt, int st) {
+        if ((int64_t)(kt + 1) * kBK <= k) {             // a full K-tile (uniform): scalar base + constant lane offsets
+            const uint8_t* ab = abase + (size_t)kt * (kBK * 2);
+#pragma unroll
+            for (int i = 0; i < NU_A; ++i)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(ab + a_src[i]),
+                    (__attribute__((address_space(3))) void*)(As + (kg * S + st) * A_STAGE + (wn * NU_A + i) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(cfirst + (size_t)kt * 32 + c_off),
+                                             (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + wave * 1024),
+                                             16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(sfirst + (size_t)kt * 4 + s_off),
+                                             (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + B_CODES + wave * 256),
+                                             2, 0, 0);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < NU_A; ++i) {
             const uint32_t kk = (uint32_t)kt * kBK + a_chunk[i] * 8u;
