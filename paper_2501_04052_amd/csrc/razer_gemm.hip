@@ -952,7 +952,9 @@ static GemmPlan gemm_plan(int64_t m, int64_t n, int64_t k, bool register_decode_
         const int64_t t256 = tm * ((n + 255) / 256), t128 = tm * ((n + 127) / 128);
         // enough tiles for two resident waves per SIMD: the kernel that decodes weights in registers
         // (measured 5-28 % faster than the LDS-staged one on the 7B projection shapes from M = 2048)
-        if (register_decode_ok && t256 >= 1024) return GemmPlan{5, 1};
+        // (256-wide weight tiles from four rounds of workgroups up, or when they fill whole rounds: 4 % over
+        // the 128-wide ones on 4096 x 8192 x 8192)
+        if (register_decode_ok && (t256 >= 1024 || (t256 >= 512 && t256 % 256 == 0))) return GemmPlan{5, 1};
         if (register_decode_ok && t128 >= 512) return GemmPlan{6, 1};
         // one round of 256x128 tiles (one workgroup per compute unit): the register-decode kernel with
         // two K groups of four waves keeps two waves on every SIMD (measured 9-10 % over the LDS-staged
@@ -1022,7 +1024,7 @@ static int grouped_tile_width(int count, const GemvProblem* p, int64_t m, int64_
         t256 += tm * ((p[i].n + 255) / 256);
         t128 += tm * ((p[i].n + 127) / 128);
     }
-    if (t256 >= 1024) return 256;
+    if (t256 >= 1024 || (t256 >= 512 && t256 % 256 == 0)) return 256;
     if (t128 >= 512) return 128;
     if (t128 >= 192 && t128 <= 256 && k >= 16 * kBK) return 129;
     return 0;
