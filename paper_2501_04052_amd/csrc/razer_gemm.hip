@@ -531,11 +531,14 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
 // (256 rows x 64 k bf16, the xor swizzle of the staged rows applied by choosing which global chunk
 // each lane fetches) and each wave's own packed codes and scale bytes, which the lane that requested
 // them reads back one tile later.  So the K loop holds no register-returning global load, no LDS
-// write and no address arithmetic for staging.  Tile t + S - 1 is requested at the top of iteration
-// t, into the stage that iteration t - 1 finished reading; three quarters through iteration t every
-// wave waits (vmcnt) until its own copies for tile t + 1 have landed, prepares that tile's weights
-// (LUT lookups, decode of step 0) between the last MFMAs, and the barrier ending the iteration makes
-// everybody's activation copies visible.
+// write and no address arithmetic for staging.  Three quarters through iteration t every wave waits
+// (vmcnt) until its own copies for tile t + 1 have landed and (lgkmcnt) until its last fragment reads
+// of tile t have returned, then meets the others at the iteration's one barrier: past it tile t + 1
+// is complete in LDS and tile t's stage is free, so the wave requests tile t + S into that stage and,
+// between the last five MFMAs of tile t, prepares tile t + 1 (LUT lookups, decode of step 0, the
+// fragment reads of step 0).  The next iteration therefore starts with its operands on the way: with
+// the barrier at the end of the iteration instead, all waves of a workgroup started every K-tile
+// with an empty LDS queue at the same moment (2-4 % slower).
 //
 // KG = 2 (for problems with about one 256 x 128 tile per compute unit): eight waves as two K groups of
 // four; group g runs the same loop over its half of the K-tiles with its own activation stages, both
@@ -686,14 +689,10 @@ __device__ __forceinline__ void gemm_rb_body(
     // the decode for step j + 1, and in the last step the preparation of tile kt + 1.  At the MFMA of
     // (step j < 3, group mi) the 8 fragment reads issued after its own are the only LDS operations
     // that may still be in flight, so lgkmcnt(7) is enough.
+    v4u af[2][MT];                                      // af[0] enters compute() holding step 0 of its tile (requested, not yet waited for)
     auto compute = [&](int kt, int st, int st_next) {
         const uint32_t sbase = st * A_STAGE;
-        v4u af[2][MT];
         uint32_t wq[2][4] = {{wq0[0], wq0[1], wq0[2], wq0[3]}, {0, 0, 0, 0}};
-        const uint32_t a0 = aoff[0] + sbase;
-#pragma unroll
-        for (int mi = 0; mi < MT; ++mi) RAZER_LDS_READ128(af[0][mi], a0, 4096 * mi);
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < 3; ++j) {
             const int cb = j & 1, nb = cb ^ 1;
@@ -738,16 +737,36 @@ __device__ __forceinline__ void gemm_rb_body(
             RAZER_MFMA(1);
             RAZER_LDS_WAIT(7, af[1][2]);
             RAZER_MFMA(2);
-            // slice 3: everything issued so far has returned; look the two scale bytes up
+            // slice 3: everything issued so far has returned -- this wave is done reading tile kt's stage,
+            // and it has seen its own copies of tile kt + 1 land.  Once every wave is here, tile kt + 1 is
+            // complete in LDS and tile kt's stage can be overwritten.  A bare barrier: __syncthreads()
+            // would add a fence that waits for every outstanding copy, i.e. also for the tiles that are
+            // meant to stay in flight.
             RAZER_LDS_WAIT3(0, af[1][3], cn, sn);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            issue(kt + S < last ? kt + S : last, st);
             flip_and_mask(kt + 1, cn, sn);
             RAZER_LDS_READ64(l0n, lut_lds + (sn & 255u) * 8u);
             RAZER_LDS_READ64(l1n, lut_lds + ((sn >> 8) & 255u) * 8u);
+            // slices 3..5: request step 0 of tile kt + 1, so that the next iteration starts with its
+            // fragments on the way instead of with an empty LDS queue
+            const uint32_t a0n = aoff[0] + st_next * A_STAGE;
+            RAZER_LDS_READ128(af[0][0], a0n, 4096 * 0);
+            RAZER_LDS_READ128(af[0][1], a0n, 4096 * 1);
             RAZER_MFMA(3);
+            RAZER_LDS_READ128(af[0][2], a0n, 4096 * 2);
+            RAZER_LDS_READ128(af[0][3], a0n, 4096 * 3);
+            RAZER_LDS_READ128(af[0][4], a0n, 4096 * 4);
             RAZER_MFMA(4);
+            RAZER_LDS_READ128(af[0][5], a0n, 4096 * 5);
+            RAZER_LDS_READ128(af[0][6], a0n, 4096 * 6);
+            RAZER_LDS_READ128(af[0][7], a0n, 4096 * 7);
             RAZER_MFMA(5);
-            // slices 6, 7: decode step 0 of the next tile
-            RAZER_LDS_WAIT3(0, l0n, l1n, af[1][6]);
+            // slices 6, 7: decode step 0 of the next tile (the two table entries were requested before the
+            // 8 fragment reads)
+            RAZER_LDS_WAIT3(8, l0n, l1n, af[1][6]);
             le0 = l0n;
             le1 = l1n;
             wq0[0] = cvt_scaled_pair<0>(xw[0], u2f(le0.x), le0.y);
@@ -760,10 +779,11 @@ __device__ __forceinline__ void gemm_rb_body(
         }
     };
 
-#pragma unroll
-    for (int d = 0; d < D; ++d) issue(kbase + d < last ? kbase + d : last, d);   // first D tiles (short K repeats the last)
+    issue(kbase < last ? kbase : last, 0);              // (short K repeats the last tile)
     fill_scaled_lut<0>(wlut, sv0, sv1, tid, NT);
-    __syncthreads();                                    // all copies so far have landed, LUT ready
+    __syncthreads();                                    // the first tile has landed, LUT ready
+#pragma unroll
+    for (int d = 1; d < S; ++d) issue(kbase + d < last ? kbase + d : last, d);
     {
         v4u c0;
         uint32_t s0;
@@ -780,20 +800,18 @@ __device__ __forceinline__ void gemm_rb_body(
         wq0[1] = cvt_scaled_pair<1>(xw[0], u2f(le0.x), le0.y);
         wq0[2] = cvt_scaled_pair<2>(xw[0], u2f(le0.x), le0.y);
         wq0[3] = cvt_scaled_pair<3>(xw[0], u2f(le0.x), le0.y);
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi) RAZER_LDS_READ128(af[0][mi], aoff[0], 4096 * mi);
     }
-    int st = 0;                                         // stage of tile kt; tile kt + D goes to st - 1 (mod S)
+    int st = 0;                                         // stage of tile kt; tile kt + S follows it into the same stage
     for (int kt = kbase; kt < kbase + KTH; ++kt) {
-        const int st_load = st == 0 ? S - 1 : st - 1, st_next = st == S - 1 ? 0 : st + 1;
-        issue(kt + D < last ? kt + D : last, st_load);
+        const int st_next = st == S - 1 ? 0 : st + 1;
         compute(kt, st, st_next);
-        // A bare barrier: __syncthreads() would add a fence that waits for every outstanding copy,
-        // i.e. also for the tiles that are meant to stay in flight.  Every wave has waited for its
-        // own copies of tile kt + 1 and for all its LDS reads of tile kt inside compute().
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
         st = st_next;
     }
+    // copies and fragment reads requested for tiles past the end: let them finish before the registers
+    // and the stages they target are used for anything else
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 #undef RAZER_LDS_READ128
 #undef RAZER_LDS_READ64
 #undef RAZER_LDS_READ32
@@ -802,10 +820,11 @@ __device__ __forceinline__ void gemm_rb_body(
     if constexpr (KG == 1) {
         store_tile<MT, 1, false>(acc, w_ts, nullptr, m0, n0 + 32 * wave, m, n, y, ld_y, lane);
     } else {
-        // The two K groups hold partial sums of the same 256 x 32 outputs.  Every copy has landed and every
-        // fragment read has returned (the waits inside compute(), then the barrier), so the activation
+        // The two K groups hold partial sums of the same 256 x 32 outputs.  Once every wave's copies have
+        // landed and its fragment reads have returned (the wait above, then this barrier) the activation
         // stages are free: each wave hands the half of its accumulators that its partner (same rows, other
         // K group) will finish -- 16 KiB per wave, [group][4 registers][lane] -- and finishes the other half.
+        __syncthreads();
         float4* mine = reinterpret_cast<float4*>(As + wave * 16384);
         const float4* theirs = reinterpret_cast<const float4*>(As + (wave ^ NWN) * 16384);
         v16f keep[1][MT / 2];
