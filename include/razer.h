@@ -145,15 +145,16 @@ razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer
 /* The same layer for several weight matrices that consume the SAME activation rows (fused q/k/v,
  * gate/up projections; the paper's stripe partition likewise lets one launch span several N
  * ranges, Sec. 4.3): y_bf16[i] = A w[i]^T for i < count, count <= RAZER_MAX_GROUP.  All w[i] must
- * have the same cols; W4A16 only.  With 16-element blocks, equal special values and no empty matrix
- * this is ONE kernel launch (short kernels are launch-latency-bound, and one launch fills the last
- * round of workgroups of a GEMM better than one per matrix) when
- *   m <= 4;
- *   5 <= m <= 32, every rows[i] and ld_y[i] a multiple of 4, y_bf16[i] 8-byte aligned, and the
- *     workspace holds the SUM over i of razer_workspace_bytes(RAZER_OP_LINEAR, rows[i], cols, m)
- *     (plus one launch that adds the K-slices up);
- *   m > 128 and the matrices together have >= 512 output tiles of 256 x 128, or 192..256 of them
- *     with cols >= 1024 (no workspace).
+ * have the same cols; W4A16 only.  With equal format, block size and special values and no empty
+ * matrix this is ONE kernel launch (short kernels are launch-latency-bound, and one launch fills the
+ * last round of workgroups of a GEMM better than one per matrix) when
+ *   m <= 4 (any block size, RAZER_FMT_WEIGHT or RAZER_FMT_WEIGHT_F16);
+ *   16-element blocks, 5 <= m <= 32, every rows[i] and ld_y[i] a multiple of 4, y_bf16[i] 8-byte
+ *     aligned, and the workspace holds the SUM over i of
+ *     razer_workspace_bytes(RAZER_OP_LINEAR, rows[i], cols, m) (plus one launch that adds the
+ *     K-slices up);
+ *   16-element blocks, m > 128 and the matrices together have >= 512 output tiles of 256 x 128, or
+ *     192..256 of them with cols >= 1024 (no workspace).
  * Otherwise it is the sequence of razer_linear calls with the same workspace (which then must
  * satisfy each call).  y_bf16[i] is device [m][ld_y[i]].  The pointer arrays are HOST arrays. */
 #define RAZER_MAX_GROUP 4

@@ -212,8 +212,7 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
         if (m < 0 || ld_y[i] < w[i]->rows) return RAZER_ERR_SHAPE;
         if (m > 0 && w[i]->rows > 0 && !y_bf16[i]) return RAZER_ERR_NULL;
         if (i == 0) sv0 = sv;
-        else if (sv.sv0 != sv0.sv0 || sv.sv1 != sv0.sv1) one_launch = false;
-        if (sv.lb != 4) one_launch = false;
+        else if (sv.sv0 != sv0.sv0 || sv.sv1 != sv0.sv1 || sv.lb != sv0.lb || sv.f16 != sv0.f16) one_launch = false;
         if (w[i]->rows == 0) one_launch = false;
     }
     if (m == 0) return RAZER_OK;
@@ -229,7 +228,9 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
     enum { SEQUENCE, GEMV, SKINNY, GEMM } path = SEQUENCE;
     if (one_launch) {
         if (m <= kGemvDirectMaxM) {
-            path = GEMV;
+            path = GEMV;                                 // every block size and both weight formats
+        } else if (sv0.lb != 4 || sv0.f16) {
+            path = SEQUENCE;                             // the grouped MFMA kernels read one scale byte per 16 elements
         } else if (m <= kSkinnyMaxM) {
             // the K-slices of all matrices live in the workspace side by side
             size_t need = 0;

@@ -70,7 +70,10 @@ __device__ __forceinline__ uint32_t load_scale_bits(const uint8_t* __restrict__ 
                                                     int64_t k0, int lb)
 {
     if (SF == 1) return reinterpret_cast<const uint16_t*>(scales)[row * (k >> 7) + (k0 >> 7)];
-    return load_scale_pair<GB>(scales + row * (k >> lb), k0, lb);
+    // GB kernels are launched for blocks of 32 and more only: the 32 elements share one scale byte
+    // (no run-time choice between two load widths, which would put a branch between the loads)
+    if (GB) return scales[row * (k >> lb) + (k0 >> lb)];
+    return load_scale_pair<false>(scales + row * (k >> 4), k0, 4);
 }
 
 template <int R, bool GB, int SF>
@@ -87,19 +90,22 @@ __device__ __forceinline__ void load_group(RowGroup<R>& g, const uint8_t* __rest
 }
 
 // sum_k a[m][k] * (scale * element) over this lane's 32 k's, for the R rows of a group.
-template <int M, int R, int SF = 0>
+// ONE: the 32 elements share one scale (blocks of 32 and more, the FP16-scale format) -- one table
+// lookup or conversion and one multiplication by the scale per row instead of two.
+template <int M, int R, int SF = 0, bool ONE = false>
 __device__ __forceinline__ void dot_group(const RowGroup<R>& g, const uint4 (&av)[M][4], const uint2* lut,
                                           float (&acc)[R][M], float sv0 = 0.0f, float sv1 = 0.0f)
 {
+    constexpr int NBLK = ONE ? 1 : 2, NH = ONE ? 4 : 2;                   // scales per lane, dwords of codes per scale
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const uint32_t xw[4] = {g.cw[r].x, g.cw[r].y, g.cw[r].z, g.cw[r].w};
 #pragma unroll
         for (int m = 0; m < M; ++m) acc[r][m] = 0.0f;
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
+        for (int blk = 0; blk < NBLK; ++blk) {
             uint2 le;
-            if (SF == 1) {                                                // one scale word for all 32 elements
+            if (SF == 1) {
                 float s, sv;
                 decode_scale_word(g.sw[r], sv0, sv1, s, sv);
                 const uint32_t nsv = (uint32_t)f32_to_bf16_rne(-sv);
@@ -112,15 +118,15 @@ __device__ __forceinline__ void dot_group(const RowGroup<R>& g, const uint4 (&av
 #pragma unroll
             for (int m = 0; m < M; ++m) p[m] = 0.0f;
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint32_t x = xw[2 * blk + h] ^ kRemapXor;
+            for (int h = 0; h < NH; ++h) {
+                const uint32_t x = xw[NH * blk + h] ^ kRemapXor;
                 const uint32_t w0 = patch_zero_halves(cvt_pair<0>(x), le.y);
                 const uint32_t w1 = patch_zero_halves(cvt_pair<1>(x), le.y);
                 const uint32_t w2 = patch_zero_halves(cvt_pair<2>(x), le.y);
                 const uint32_t w3 = patch_zero_halves(cvt_pair<3>(x), le.y);
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
-                    const uint4 aq = av[m][2 * blk + h];
+                    const uint4 aq = av[m][NH * blk + h];
                     p[m] = dot2(w0, aq.x, p[m]);
                     p[m] = dot2(w1, aq.y, p[m]);
                     p[m] = dot2(w2, aq.z, p[m]);
@@ -128,7 +134,7 @@ __device__ __forceinline__ void dot_group(const RowGroup<R>& g, const uint4 (&av
                 }
             }
 #pragma unroll
-            for (int m = 0; m < M; ++m) acc[r][m] = __builtin_fmaf(ns, p[m], acc[r][m]);
+            for (int m = 0; m < M; ++m) acc[r][m] = ONE ? ns * p[m] : __builtin_fmaf(ns, p[m], acc[r][m]);
         }
     }
 }
@@ -187,7 +193,7 @@ __device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, con
             issue_loads();
         }
         float acc[R][M];
-        dot_group<M, R, SF>(grp, av, lut, acc, sv0, sv1);
+        dot_group<M, R, SF, GB || SF == 1>(grp, av, lut, acc, sv0, sv1);
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -276,7 +282,7 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     for (int g = 0; g < G; ++g) {
         if (g + D - 1 < G) load(buf[(g + D - 1) % D], g + D - 1);
         float acc[R][M];
-        dot_group<M, R, SF>(buf[g % D], av, lut, acc, sv0, sv1);
+        dot_group<M, R, SF, GB || SF == 1>(buf[g % D], av, lut, acc, sv0, sv1);
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -323,7 +329,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_kernel(const uint8_t* __r
 // launch (fused q/k/v, gate/up): workgroups [0, g1) serve matrix 0, [g1, g2) matrix 1, ...  Every
 // per-matrix argument is a scalar kernel argument picked with uniform compares: no indexed
 // argument arrays, which would cost a private copy.
-template <int M, int R>
+template <int M, int R, bool GB = false, int SF = 0>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
@@ -332,7 +338,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_grouped_kernel(
     int64_t n0, int64_t n1, int64_t n2, int64_t n3,
     int64_t l0, int64_t l1, int64_t l2, int64_t l3,
     unsigned g1, unsigned g2, unsigned g3,
-    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a)
+    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int lb)
 {
     const unsigned b = blockIdx.x;
     const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = t0; uint16_t* y = y0;
@@ -341,10 +347,10 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_grouped_kernel(
     if (b >= g1) { codes = c1; scales = s1; ts = t1; y = y1; n = n1; ld = l1; first = g1; }
     if (b >= g2) { codes = c2; scales = s2; ts = t2; y = y2; n = n2; ld = l2; first = g2; }
     if (b >= g3) { codes = c3; scales = s3; ts = t3; y = y3; n = n3; ld = l3; first = g3; }
-    gemv_body<M, R>(codes, scales, ts, sv0, sv1, n, k, a, y, ld, (int64_t)(b - first) * R);
+    gemv_body<M, R, GB, SF>(codes, scales, ts, sv0, sv1, n, k, a, y, ld, (int64_t)(b - first) * R, lb);
 }
 
-template <int M, int R, int G, int D, int P = 1>
+template <int M, int R, int G, int D, int P = 1, bool GB = false, int SF = 0>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
@@ -353,7 +359,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
     int64_t n0, int64_t n1, int64_t n2, int64_t n3,
     int64_t l0, int64_t l1, int64_t l2, int64_t l3,
     unsigned g1, unsigned g2, unsigned g3,
-    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a)
+    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int lb)
 {
     const unsigned b = blockIdx.x;
     const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = t0; uint16_t* y = y0;
@@ -362,7 +368,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
     if (b >= g1) { codes = c1; scales = s1; ts = t1; y = y1; n = n1; ld = l1; first = g1; }
     if (b >= g2) { codes = c2; scales = s2; ts = t2; y = y2; n = n2; ld = l2; first = g2; }
     if (b >= g3) { codes = c3; scales = s3; ts = t3; y = y3; n = n3; ld = l3; first = g3; }
-    gemv_stream_body<M, R, G, D, P>(codes, scales, ts, sv0, sv1, n, k, a, y, ld, (int64_t)(b - first) * (P * R * G));
+    gemv_stream_body<M, R, G, D, P, GB, SF>(codes, scales, ts, sv0, sv1, n, k, a, y, ld,
+                                            (int64_t)(b - first) * (P * R * G), lb);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -639,22 +646,19 @@ static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_
     constexpr int R = kStreamR;
     const int nwaves = (int)nslices;
     const int groups = stream_groups(nwaves, M);
-    const int sets = cfg.lb == 4 ? stream_sets(nwaves, groups) : 1;      // blocks of 32..128: the single-set kernels
+    const int sets = stream_sets(nwaves, groups);
     const unsigned grid = (unsigned)((n + sets * R * groups - 1) / (sets * R * groups));
 #define RAZER_GEMV_ARGS codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, cfg.lb
-    if (cfg.f16) {
-        if (groups == 8) gemv_stream_kernel<M, R, 8, 2, 1, true, 1><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
-        else gemv_stream_kernel<M, R, 2, 2, 1, true, 1><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
-    } else if (cfg.lb != 4) {
-        if (groups == 8) gemv_stream_kernel<M, R, 8, 2, 1, true><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
-        else gemv_stream_kernel<M, R, 2, 2, 1, true><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
-    } else if (groups == 8) {
-        gemv_stream_kernel<M, R, 8, 2, 1><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
-    } else if (sets == 2) {
-        gemv_stream_kernel<M, R, 2, 2, 2><<<grid, 128 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
-    } else {
-        gemv_stream_kernel<M, R, 2, 2, 1><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);
-    }
+#define RAZER_GEMV_SHAPES(GB, SF)                                                                              \
+    do {                                                                                                       \
+        if (groups == 8) gemv_stream_kernel<M, R, 8, 2, 1, GB, SF><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);  \
+        else if (sets == 2) gemv_stream_kernel<M, R, 2, 2, 2, GB, SF><<<grid, 128 * nwaves, 0, st>>>(RAZER_GEMV_ARGS); \
+        else gemv_stream_kernel<M, R, 2, 2, 1, GB, SF><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);              \
+    } while (0)
+    if (cfg.f16) RAZER_GEMV_SHAPES(true, 1);
+    else if (cfg.lb != 4) RAZER_GEMV_SHAPES(true, 0);
+    else RAZER_GEMV_SHAPES(false, 0);
+#undef RAZER_GEMV_SHAPES
 #undef RAZER_GEMV_ARGS
     return hipGetLastError();
 }
@@ -678,15 +682,22 @@ static hipError_t launch_gemv_grouped_m(SvConfig cfg, int count, const GemvProbl
 #define RAZER_GROUPED_ARGS                                                                                       \
     q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts, \
         q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,    \
-        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a
-    if (!stream)
-        gemv_grouped_kernel<M, 4><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
-    else if (groups == 8)
-        gemv_stream_grouped_kernel<M, kStreamR, 8, 2, 1><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
-    else if (sets == 2)
-        gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 2><<<g[4], 128 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
-    else
-        gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 1><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);
+        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, cfg.lb
+#define RAZER_GROUPED_SHAPES(GB, SF)                                                                                      \
+    do {                                                                                                                  \
+        if (!stream)                                                                                                      \
+            gemv_grouped_kernel<M, 4, GB, SF><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);                          \
+        else if (groups == 8)                                                                                             \
+            gemv_stream_grouped_kernel<M, kStreamR, 8, 2, 1, GB, SF><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);   \
+        else if (sets == 2)                                                                                               \
+            gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 2, GB, SF><<<g[4], 128 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);  \
+        else                                                                                                              \
+            gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 1, GB, SF><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);   \
+    } while (0)
+    if (cfg.f16) RAZER_GROUPED_SHAPES(true, 1);
+    else if (cfg.lb != 4) RAZER_GROUPED_SHAPES(true, 0);
+    else RAZER_GROUPED_SHAPES(false, 0);
+#undef RAZER_GROUPED_SHAPES
 #undef RAZER_GROUPED_ARGS
     return hipGetLastError();
 }

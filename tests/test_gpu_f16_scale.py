@@ -108,15 +108,35 @@ def test_linear_on_encoded_weights_full_layer_shape(oracle):
         assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
 
 
+@pytest.mark.parametrize("m,k,ns", [(1, 4096, (40, 9, 64)), (1, 11008, (70, 35)), (4, 8192, (24, 24, 24, 5)), (2, 34816, (10, 7))])
+def test_grouped_small_batch_one_launch(oracle, m, k, ns):
+    print("f16 grouped", m, k, ns, flush=True)
+    rng = np.random.default_rng(3600 + m)
+    a = synth.activation(m, k, seed=3601 + m)
+    wqs = [_rand_tensor(rng, n, k) for n in ns]
+    for wq in wqs:
+        wq[1][:] = (wq[1] & 0xC000) | (0x2C00 + (wq[1] & 0x0FFF))    # scales 2^-4 .. 2^-1: sums stay well conditioned
+    wts = [razer.RazerTensor.from_host(*wq, F16, (5.0, 8.0)) for wq in wqs]
+    ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    for wq, wt, y in zip(wqs, wts, ys):
+        assert max_rel_err(dev_to_bf16_bits(y), oracle.linear(wq, a_bf16=a)[0]) <= TOL
+        assert torch.equal(y, razer.razer_linear(wt, bf16_bits_to_dev(a)))
+
+
 def test_grouped_and_error_paths(oracle):
     rng = np.random.default_rng(3500)
     k = 512
     a = synth.activation(2, k, seed=3501)
     wqs = [_rand_tensor(rng, n, k) for n in (33, 50)]
     wts = [razer.RazerTensor.from_host(*wq, F16, (5.0, 8.0)) for wq in wqs]
-    ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a))          # one launch per matrix
+    ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a))          # one launch (m <= 4)
     for wq, y in zip(wqs, ys):
         assert max_rel_err(dev_to_bf16_bits(y), oracle.linear(wq, a_bf16=a)[0]) <= TOL
+    a9 = synth.activation(9, k, seed=3503)
+    ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a9))         # matrix by matrix, passes of 4 rows
+    for wq, y in zip(wqs, ys):
+        assert max_rel_err(dev_to_bf16_bits(y), oracle.linear(wq, a_bf16=a9)[0]) <= TOL
     # W4A4 is not built for this weight format
     aq = razer.razer_quantize(bf16_bits_to_dev(synth.activation(2, k, seed=3502)), razer.ACT, (5.0, 0.0))
     with pytest.raises(razer.RazerError) as e:

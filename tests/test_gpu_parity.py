@@ -398,10 +398,35 @@ def test_block_sizes_w4a4_matches_oracle(oracle, wb, ab, m, n, k):
     assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
 
 
-def test_block_sizes_grouped_falls_back_to_single_launches(oracle):
+@pytest.mark.parametrize("block", [32, 64, 128])
+@pytest.mark.parametrize("m,k,ns", [(1, 512, (33, 50)), (2, 4096, (40, 9, 64)), (1, 11008, (70, 35)), (4, 8192, (24, 24, 24, 5)),
+                                    (3, 34816, (10, 7))])
+def test_block_sizes_grouped_small_batch_one_launch(oracle, block, m, k, ns):
+    """m <= 4: matrices of one block size share a launch (one, two and many K-slices per row, a ragged
+    last slice, rows longer than a workgroup covers in one pass)."""
+    print("block grouped", block, m, k, ns, flush=True)
+    a = synth.activation(m, k, seed=1500 + m)
+    wqs = [oracle.quantize(W, synth.weight(n, k, seed=1501 + n + i), block=block) for i, n in enumerate(ns)]
+    wts = [razer.RazerTensor.from_host(*wq, W, (5.0, 8.0)) for wq in wqs]
+    ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    for wq, wt, y in zip(wqs, wts, ys):
+        assert max_rel_err(dev_to_bf16_bits(y), oracle.linear(wq, a_bf16=a)[0]) <= TOL
+        # and bit for bit what the single-matrix call gives
+        assert torch.equal(y, razer.razer_linear(wt, bf16_bits_to_dev(a)))
+
+
+def test_block_sizes_grouped_mixed_geometry_is_a_sequence(oracle):
     k = 512
-    a = synth.activation(2, k, seed=1500)
-    wqs = [oracle.quantize(W, synth.weight(n, k, seed=1501 + n), block=64) for n in (33, 50)]
+    a = synth.activation(2, k, seed=1520)
+    wqs = [oracle.quantize(W, synth.weight(n, k, seed=1521 + n), block=b) for n, b in ((33, 64), (50, 16), (20, 128))]
+    wts = [razer.RazerTensor.from_host(*wq, W, (5.0, 8.0)) for wq in wqs]
+    ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a))
+    for wq, y in zip(wqs, ys):
+        assert max_rel_err(dev_to_bf16_bits(y), oracle.linear(wq, a_bf16=a)[0]) <= TOL
+    # larger batches of a block size other than 16 run matrix by matrix
+    a = synth.activation(40, k, seed=1530)
+    wqs = [oracle.quantize(W, synth.weight(n, k, seed=1531 + n), block=32) for n in (36, 64)]
     wts = [razer.RazerTensor.from_host(*wq, W, (5.0, 8.0)) for wq in wqs]
     ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a))
     for wq, y in zip(wqs, ys):
