@@ -21,6 +21,8 @@
 //                    there is about one tile per compute unit; the grouped form runs up to four
 //                    matrices (fused q/k/v, gate/up) as one launch
 // Problems with too few tiles split K over workgroups (fp32 slices in the caller's workspace).
+#include <type_traits>
+
 #include "razer_device.hpp"
 #include "razer_kernels.hpp"
 
@@ -550,13 +552,15 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
 // stages apart, so before any LDS load it knows of it would wait for ALL outstanding copies, which
 // would serialise the prefetch.  Each wait is tied to the registers it guards so that their consumers
 // cannot be scheduled above it; sched_barrier keeps the hand-laid slices (one MFMA each) in order.
-template <int NW, int S, int KG = 1>
+template <int NW, int S, int KG = 1, int MT = 8>
 __device__ __forceinline__ void gemm_rb_body(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
-    uint16_t* __restrict__ y, int64_t ld_y, int tile_m, int tile_n)
+    uint16_t* __restrict__ y, int64_t ld_y, int tile_m, int tile_n, float* __restrict__ partial = nullptr,
+    int kslice = 0, int kt_per_slice = 0x7FFFFFFF)
 {
-    constexpr int MT = 8;                               // 32-row activation groups per tile
+    // MT: 32-row activation groups per tile (8, or 4 / 2 for at most 128 / 64 activation rows)
+    static_assert(MT == 8 || ((MT == 4 || MT == 2) && KG == 1), "activation tile height");
     constexpr int NWN = NW / KG;                        // waves side by side along N; KG groups of them split K
     constexpr int NT = 64 * NW, BM = 32 * MT, BN = 32 * NWN;
     constexpr int NU_A = BM * 8 / (64 * NWN);           // 1-KiB activation copies per wave and K-tile
@@ -580,8 +584,12 @@ __device__ __forceinline__ void gemm_rb_body(
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int KT = (int)((k + kBK - 1) / kBK);
     const int last = KT - 1;
-    // K group g computes the K-tiles g KTH .. (g + 1) KTH - 1; tiles past the last one contribute zero weights
-    const int KTH = (KT + KG - 1) / KG, kbase = kg * KTH;
+    // This workgroup's K-tiles: slice kslice of the grid (kt_per_slice tiles; all of them without a
+    // workspace), of which K group g computes tiles g KTH .. (g + 1) KTH - 1; tiles past the end of the
+    // slice contribute zero weights
+    const int kt0 = kslice * kt_per_slice;
+    const int kend = (KT - kt0 < kt_per_slice) ? KT : kt0 + kt_per_slice;
+    const int KTH = (kend - kt0 + KG - 1) / KG, kbase = kt0 + kg * KTH;
 
     int64_t wrow = n0 + 32 * wn + r;
     wrow = wrow < n ? wrow : n - 1;                     // rows past N re-read the last row, never stored
@@ -661,6 +669,16 @@ __device__ __forceinline__ void gemm_rb_body(
 #define RAZER_LDS_READ32(dst, addr) asm volatile("ds_read_b32 %0, %1" : "=v"(dst) : "v"(addr))
 #define RAZER_LDS_WAIT(n, reg) asm volatile("s_waitcnt lgkmcnt(" #n ")" : "+v"(reg))
 #define RAZER_LDS_WAIT3(n, r0, r1, r2) asm volatile("s_waitcnt lgkmcnt(" #n ")" : "+v"(r0), "+v"(r1), "+v"(r2))
+    // the same with the count as a constant expression
+    auto lds_wait = [](auto cnt, v4u& reg) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(reg) : "n"(decltype(cnt)::value)); };
+    auto decode_pair = [](int p, uint32_t x, uint2 le) -> uint32_t {
+        switch (p) {
+            case 0: return cvt_scaled_pair<0>(x, u2f(le.x), le.y);
+            case 1: return cvt_scaled_pair<1>(x, u2f(le.x), le.y);
+            case 2: return cvt_scaled_pair<2>(x, u2f(le.x), le.y);
+            default: return cvt_scaled_pair<3>(x, u2f(le.x), le.y);
+        }
+    };
     // LDS byte address of this lane's activation chunk in step j (row r of group 0, stage 0; group mi
     // adds 4096 mi, stage st adds st * A_STAGE)
     uint32_t aoff[4];
@@ -677,7 +695,7 @@ __device__ __forceinline__ void gemm_rb_body(
     uint2 le0, le1;
     auto flip_and_mask = [&](int kt, const v4u& c, uint32_t& sc) {
         // past K: code 0, scale byte 0 -> weight 0
-        const uint32_t msk = (kt <= last && (int64_t)kt * kBK + 32 * h < k) ? 0xFFFFFFFFu : 0u;
+        const uint32_t msk = (kt < kend && (int64_t)kt * kBK + 32 * h < k) ? 0xFFFFFFFFu : 0u;
         xw[0] = (c.x & msk) ^ kRemapXor;
         xw[1] = (c.y & msk) ^ kRemapXor;
         xw[2] = (c.z & msk) ^ kRemapXor;
@@ -686,9 +704,9 @@ __device__ __forceinline__ void gemm_rb_body(
     };
 
     // One K-tile.  Slices of one MFMA each; between the MFMAs of step j sit the fragment reads and
-    // the decode for step j + 1, and in the last step the preparation of tile kt + 1.  At the MFMA of
-    // (step j < 3, group mi) the 8 fragment reads issued after its own are the only LDS operations
-    // that may still be in flight, so lgkmcnt(7) is enough.
+    // the decode for step j + 1 (4 code pairs spread over the MT slices), and in the last step the
+    // preparation of tile kt + 1.  At the MFMA of (step j < 3, group mi) the MT fragment reads issued
+    // after its own are the only LDS operations that may still be in flight, so lgkmcnt(MT - 1) is enough.
     v4u af[2][MT];                                      // af[0] enters compute() holding step 0 of its tile (requested, not yet waited for)
     auto compute = [&](int kt, int st, int st_next) {
         const uint32_t sbase = st * A_STAGE;
@@ -702,14 +720,15 @@ __device__ __forceinline__ void gemm_rb_body(
 #pragma unroll
             for (int mi = 0; mi < MT; ++mi) {
                 RAZER_LDS_READ128(af[nb][mi], an, 4096 * mi);
-                if (mi % 2 == 0) {                                       // one code pair per two MFMAs
-                    const uint32_t x = xw[j + 1];
-                    wq[nb][mi / 2] = (mi == 0) ? cvt_scaled_pair<0>(x, u2f(le.x), le.y)
-                                   : (mi == 2) ? cvt_scaled_pair<1>(x, u2f(le.x), le.y)
-                                   : (mi == 4) ? cvt_scaled_pair<2>(x, u2f(le.x), le.y)
-                                               : cvt_scaled_pair<3>(x, u2f(le.x), le.y);
+                if (MT == 8) {                                           // one code pair per two MFMAs
+                    if (mi % 2 == 0) wq[nb][mi / 2] = decode_pair(mi / 2, xw[j + 1], le);
+                } else if (MT == 4) {
+                    wq[nb][mi] = decode_pair(mi, xw[j + 1], le);
+                } else {
+                    wq[nb][2 * mi] = decode_pair(2 * mi, xw[j + 1], le);
+                    wq[nb][2 * mi + 1] = decode_pair(2 * mi + 1, xw[j + 1], le);
                 }
-                RAZER_LDS_WAIT(7, af[cb][mi]);
+                lds_wait(std::integral_constant<int, MT - 1>{}, af[cb][mi]);
                 acc[0][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(v8bf, af[cb][mi]),
                                                                      acc[0][mi], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
@@ -728,21 +747,25 @@ __device__ __forceinline__ void gemm_rb_body(
 #define RAZER_MFMA(mi) \
             acc[0][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(v8bf, af[1][mi]), acc[0][mi], 0, 0, 0); \
             __builtin_amdgcn_sched_barrier(0)
-            // slice 0: request the next tile's codes and scale bytes (this lane's own copy)
+            // slice 0: request the next tile's codes and scale bytes (this lane's own copy); the first
+            // MFMAs wait for their fragments only (MT + 2 LDS operations are in flight)
+            constexpr int E = (MT == 8) ? 3 : 1;                         // MFMAs ahead of the barrier
             RAZER_LDS_READ128(cn, bc_lds + bnext, 0);
             RAZER_LDS_READ32(sn, bs_lds + bnext);
-            RAZER_LDS_WAIT(9, af[1][0]);
+            lds_wait(std::integral_constant<int, MT + 1>{}, af[1][0]);
             RAZER_MFMA(0);
-            RAZER_LDS_WAIT(8, af[1][1]);
-            RAZER_MFMA(1);
-            RAZER_LDS_WAIT(7, af[1][2]);
-            RAZER_MFMA(2);
-            // slice 3: everything issued so far has returned -- this wave is done reading tile kt's stage,
-            // and it has seen its own copies of tile kt + 1 land.  Once every wave is here, tile kt + 1 is
+            if constexpr (MT == 8) {
+                RAZER_LDS_WAIT(8, af[1][1]);
+                RAZER_MFMA(1);
+                RAZER_LDS_WAIT(7, af[1][2]);
+                RAZER_MFMA(2);
+            }
+            // everything issued so far has returned -- this wave is done reading tile kt's stage, and it
+            // has seen its own copies of tile kt + 1 land.  Once every wave is here, tile kt + 1 is
             // complete in LDS and tile kt's stage can be overwritten.  A bare barrier: __syncthreads()
             // would add a fence that waits for every outstanding copy, i.e. also for the tiles that are
             // meant to stay in flight.
-            RAZER_LDS_WAIT3(0, af[1][3], cn, sn);
+            RAZER_LDS_WAIT3(0, af[1][E], cn, sn);
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
@@ -750,31 +773,37 @@ __device__ __forceinline__ void gemm_rb_body(
             flip_and_mask(kt + 1, cn, sn);
             RAZER_LDS_READ64(l0n, lut_lds + (sn & 255u) * 8u);
             RAZER_LDS_READ64(l1n, lut_lds + ((sn >> 8) & 255u) * 8u);
-            // slices 3..5: request step 0 of tile kt + 1, so that the next iteration starts with its
-            // fragments on the way instead of with an empty LDS queue
+            // request step 0 of tile kt + 1 between the remaining MFMAs, so that the next iteration starts
+            // with its fragments on the way instead of with an empty LDS queue
             const uint32_t a0n = aoff[0] + st_next * A_STAGE;
-            RAZER_LDS_READ128(af[0][0], a0n, 4096 * 0);
-            RAZER_LDS_READ128(af[0][1], a0n, 4096 * 1);
-            RAZER_MFMA(3);
-            RAZER_LDS_READ128(af[0][2], a0n, 4096 * 2);
-            RAZER_LDS_READ128(af[0][3], a0n, 4096 * 3);
-            RAZER_LDS_READ128(af[0][4], a0n, 4096 * 4);
-            RAZER_MFMA(4);
-            RAZER_LDS_READ128(af[0][5], a0n, 4096 * 5);
-            RAZER_LDS_READ128(af[0][6], a0n, 4096 * 6);
-            RAZER_LDS_READ128(af[0][7], a0n, 4096 * 7);
-            RAZER_MFMA(5);
-            // slices 6, 7: decode step 0 of the next tile (the two table entries were requested before the
-            // 8 fragment reads)
-            RAZER_LDS_WAIT3(8, l0n, l1n, af[1][6]);
+            if constexpr (MT == 8) {
+                RAZER_LDS_READ128(af[0][0], a0n, 4096 * 0);
+                RAZER_LDS_READ128(af[0][1], a0n, 4096 * 1);
+                RAZER_MFMA(3);
+                RAZER_LDS_READ128(af[0][2], a0n, 4096 * 2);
+                RAZER_LDS_READ128(af[0][3], a0n, 4096 * 3);
+                RAZER_LDS_READ128(af[0][4], a0n, 4096 * 4);
+                RAZER_MFMA(4);
+                RAZER_LDS_READ128(af[0][5], a0n, 4096 * 5);
+                RAZER_LDS_READ128(af[0][6], a0n, 4096 * 6);
+                RAZER_LDS_READ128(af[0][7], a0n, 4096 * 7);
+                RAZER_MFMA(5);
+            } else {
+#pragma unroll
+                for (int mi = 0; mi < MT; ++mi) RAZER_LDS_READ128(af[0][mi], a0n, 4096 * mi);
+                if constexpr (MT == 4) { RAZER_MFMA(1); }
+            }
+            // decode step 0 of the next tile (the two table entries were requested before the MT
+            // fragment reads)
+            asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(l0n), "+v"(l1n), "+v"(af[1][MT - 1]) : "n"(MT));
             le0 = l0n;
             le1 = l1n;
             wq0[0] = cvt_scaled_pair<0>(xw[0], u2f(le0.x), le0.y);
             wq0[1] = cvt_scaled_pair<1>(xw[0], u2f(le0.x), le0.y);
-            RAZER_MFMA(6);
+            if constexpr (MT >= 4) { RAZER_MFMA(MT - 2); }
             wq0[2] = cvt_scaled_pair<2>(xw[0], u2f(le0.x), le0.y);
             wq0[3] = cvt_scaled_pair<3>(xw[0], u2f(le0.x), le0.y);
-            RAZER_MFMA(7);
+            RAZER_MFMA(MT - 1);
 #undef RAZER_MFMA
         }
     };
@@ -818,7 +847,10 @@ __device__ __forceinline__ void gemm_rb_body(
 #undef RAZER_LDS_WAIT
 #undef RAZER_LDS_WAIT3
     if constexpr (KG == 1) {
-        store_tile<MT, 1, false>(acc, w_ts, nullptr, m0, n0 + 32 * wave, m, n, y, ld_y, lane);
+        if (partial)                                    // K-slices of one output meet in the workspace [slice][m][n]
+            store_tile_partial<MT, 1>(acc, m0, n0 + 32 * wave, m, n, partial + (int64_t)kslice * m * n, lane);
+        else
+            store_tile<MT, 1, false>(acc, w_ts, nullptr, m0, n0 + 32 * wave, m, n, y, ld_y, lane);
     } else {
         // The two K groups hold partial sums of the same 256 x 32 outputs.  Once every wave's copies have
         // landed and its fragment reads have returned (the wait above, then this barrier) the activation
@@ -862,14 +894,21 @@ __device__ __forceinline__ void gemm_rb_body(
     }
 }
 
-template <int NW, int S, int KG = 1>
-__global__ __launch_bounds__(64 * NW, KG == 1 ? 8 / NW : 1) void gemm_rb_kernel(
+// Resident waves per SIMD the register budget is set for: 2 with the full 256-row tile (the accumulators
+// alone are 128 registers), 3 / 4 with 128 / 64 rows.
+template <int NW, int KG, int MT>
+constexpr int rb_waves_per_simd() { return KG != 1 ? 1 : MT == 8 ? 8 / NW : MT == 4 ? 3 : 4; }
+
+// grid = (output tiles, K-slices).  partial == nullptr: one slice, bf16 results to y; else slice
+// blockIdx.y covers kt_per_slice K-tiles and leaves fp32 sums in partial[slice][m][n].
+template <int NW, int S, int KG = 1, int MT = 8>
+__global__ __launch_bounds__(64 * NW, (rb_waves_per_simd<NW, KG, MT>())) void gemm_rb_kernel(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
-    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m)
+    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m, float* __restrict__ partial, int kt_per_slice)
 {
-    gemm_rb_body<NW, S, KG>(w_codes, w_scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, (int)(blockIdx.x % tiles_m),
-                        (int)(blockIdx.x / tiles_m));
+    gemm_rb_body<NW, S, KG, MT>(w_codes, w_scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, (int)(blockIdx.x % tiles_m),
+                                (int)(blockIdx.x / tiles_m), partial, (int)blockIdx.y, kt_per_slice);
 }
 
 // Up to four weight matrices against the same activations in one launch (fused q/k/v, gate/up): the
@@ -897,14 +936,16 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 8 / NW : 1) void gemm_rb_grouped
     gemm_rb_body<NW, S, KG>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, tile_m, t - first);
 }
 
-template <int NW, int S, int KG = 1>
+// split > 1 (KG == 1 only, workspace of slices * m * n floats): K in slices of whole K-tiles, summed by
+// launch_slice_reduce.
+template <int NW, int S, int KG = 1, int MT = 8>
 static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                             int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
-                            hipStream_t st)
+                            hipStream_t st, int split = 1, float* workspace = nullptr)
 {
-    constexpr int BM = 256, BN = 32 * NW / KG;
+    constexpr int BM = 32 * MT, BN = 32 * NW / KG;
     constexpr size_t smem = S * (KG * BM * 128 + NW * 1280) + 256 * sizeof(uint2);
-    auto kern = gemm_rb_kernel<NW, S, KG>;
+    auto kern = gemm_rb_kernel<NW, S, KG, MT>;
     static bool attr_set = false;                      // one GPU per process
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -912,10 +953,17 @@ static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, con
         if (e != hipSuccess) return e;
         attr_set = true;
     }
+    if (KG != 1 || !workspace) split = 1;
     const int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
-    kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * NW), smem, st>>>(w_codes, w_scales, w_ts, wcfg.sv0,
-                                                                           wcfg.sv1, n, k, a, m, y, ld_y, tiles_m);
-    return hipGetLastError();
+    // every K-slice must hold at least one K-tile: slices = ceil(KT / ceil(KT / split))
+    const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + split - 1) / split;
+    const int slices = (kt_all + kt_per - 1) / kt_per;
+    kern<<<dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(64 * NW), smem, st>>>(
+        w_codes, w_scales, w_ts, wcfg.sv0, wcfg.sv1, n, k, a, m, y, ld_y, tiles_m, slices > 1 ? workspace : nullptr,
+        slices > 1 ? kt_per : 0x7FFFFFFF);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || slices == 1) return e;
+    return launch_slice_reduce(workspace, w_ts, nullptr, m, n, slices, y, ld_y, st);
 }
 
 template <int BM, int BN, int WGM, int WGN, bool AQ, bool PP = false, bool GB = false>
@@ -951,17 +999,30 @@ static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, co
 // Which kernel and how many K-slices.  Tiles: 0 = 32x256, 1 = 64x256, 2 = 128x128 (one stage pair, all
 // waves alike), 3 = 256x256 and 4 = 256x128 (two wave groups out of phase), 5 / 6 = register-decode
 // kernel with 256x256 / 256x128 tiles, 7 = register-decode kernel, 256x128 tiles, K halved inside
-// the workgroup.  A K-tile costs about 1 us of latency however small the tile, so
+// the workgroup, 8 / 9 = register-decode kernel with 64x128 / 128x128 tiles and K-slices (33..64 /
+// 65..128 activation rows: measured 1.3-2.1x faster than tiles 1 / 2 on 4096^2, 11008 x 4096 and
+// 4096 x 11008).  A K-tile costs about 1 us of latency however small the tile, so
 // when the output tiles cannot occupy the 256 compute units K is split until they do (at most 8 ways,
 // at least 8 K-tiles per slice); the slices meet in the workspace.
 struct GemmPlan {
     int tile;
     int split;
 };
+// K-slices of the register-decode kernel with small activation tiles: about one workgroup per compute
+// unit (best or within 5 % of it at 32 and 86 tiles, K = 4096 and 11008), at least 8 K-tiles per slice.
+static int rb_split(int64_t tiles, int64_t kt_all)
+{
+    int64_t split = (256 + tiles / 2) / tiles;
+    if (split > 16) split = 16;
+    if (split > kt_all / 8) split = kt_all / 8;
+    return split >= 2 ? (int)split : 1;
+}
 static GemmPlan gemm_plan(int64_t m, int64_t n, int64_t k, bool register_decode_ok)
 {
     GemmPlan p{0, 1};
     int64_t tiles;
+    if (m > 32 && m <= 128 && register_decode_ok)
+        return GemmPlan{m <= 64 ? 8 : 9, rb_split((n + 127) / 128, (k + kBK - 1) / kBK)};
     if (m <= 32) { p.tile = 0; tiles = (n + 255) / 256; }
     else if (m <= 64) { p.tile = 1; tiles = (n + 255) / 256; }
     else if (m <= 128) { p.tile = 2; tiles = ((m + 127) / 128) * ((n + 127) / 128); }
@@ -995,11 +1056,18 @@ static GemmPlan gemm_plan(int64_t m, int64_t n, int64_t k, bool register_decode_
 size_t gemm_workspace_bytes(int64_t n, int64_t k, int64_t m)
 {
     if (m <= kSkinnyMaxM || n == 0 || k == 0) return 0;          // (W4A4 with m <= 32 is planned below too)
-    const GemmPlan p = gemm_plan(m, n, k, false);                // the register-decode kernel never splits
-    if (p.split == 1) return 0;
-    const int64_t kt_all = (k + kBK - 1) / kBK, kt_per = (kt_all + p.split - 1) / p.split;
-    const int64_t slices = (kt_all + kt_per - 1) / kt_per;
-    return (size_t)(slices * m * n) * sizeof(float);
+    // the caller of this query does not say which operand formats it will pass: the larger of the
+    // two plans (register-decode kernel allowed or not)
+    size_t need = 0;
+    for (int rd = 0; rd < 2; ++rd) {
+        const GemmPlan p = gemm_plan(m, n, k, rd != 0);
+        if (p.split == 1) continue;
+        const int64_t kt_all = (k + kBK - 1) / kBK, kt_per = (kt_all + p.split - 1) / p.split;
+        const int64_t slices = (kt_all + kt_per - 1) / kt_per;
+        const size_t b = (size_t)(slices * m * n) * sizeof(float);
+        need = b > need ? b : need;
+    }
+    return need;
 }
 
 template <bool AQ, bool GB>
@@ -1022,6 +1090,8 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
     }
 #undef RAZER_GEMM
     if constexpr (!AQ && !GB) {
+        if (p.tile == 8) return launch_rb<4, 2, 1, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, p.split, workspace);
+        if (p.tile == 9) return launch_rb<4, 2, 1, 4>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, p.split, workspace);
         if (p.tile == 5) return launch_rb<8, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
         if (p.tile == 7) return launch_rb<8, 2, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
         return launch_rb<4, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);

@@ -177,6 +177,28 @@ def test_linear_gemm_matches_oracle(oracle, m, n, k):
     assert err <= TOL, err
 
 
+@pytest.mark.parametrize("m,n,k", [(33, 100, 96), (48, 130, 1024), (64, 513, 4096 + 32), (64, 64, 11008), (65, 100, 544),
+                                   (96, 260, 2048), (128, 513, 4096 + 32), (128, 32, 11008), (100, 1, 4096),
+                                   (128, 300, 64)])
+def test_linear_mid_batch_matches_oracle(oracle, m, n, k):
+    """33..128 activation rows: the register-decode kernel with 64- and 128-row tiles; one to sixteen
+    K-slices (the slices meet in the workspace), ragged last K-tile, ragged rows on both sides."""
+    print("gemm mid batch", m, n, k, flush=True)
+    err = _linear_case(oracle, m, n, k, seed=900 + m)
+    assert err <= TOL, err
+
+
+def test_linear_mid_batch_random_codes_all_scale_bytes(oracle):
+    rng = np.random.default_rng(78)
+    n, k = 200, 2048
+    codes, scales, ts = _rand_tensor(rng, W, n, k)
+    for m in (40, 128):
+        a = synth.activation(m, k, seed=70 + m)
+        y64, _ = oracle.linear((codes, scales, ts), a_bf16=a, w_sv=(5.0, 7.0))
+        wt = razer.RazerTensor.from_host(codes, scales, ts, W, (5.0, 7.0))
+        assert max_rel_err(dev_to_bf16_bits(razer.razer_linear(wt, bf16_bits_to_dev(a))), y64) <= TOL
+
+
 def test_linear_special_values_matter(oracle):
     """Decoding the remapped code as a plain zero must show up as an error: guards
     against a kernel that silently drops the special values."""
