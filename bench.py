@@ -268,6 +268,10 @@ def main():
         for m in (4, 16):
             ms, b, _ = linear_leg(m, max(10, args.steps // 4), 5, graph=use_graph, grouped=True)
             legs["linear_m%d" % m] = {"GB/s": b / ms / 1e6, "frac_hbm": b / ms / 1e6 / HBM_PEAK_GBS, "ms_per_step": ms}
+        # the batch curve between the decode regime and the large GEMMs: four prepared calls per step
+        for m in (64, 128, 256):
+            ms, _, fl = linear_leg(m, 10, 3, prepared=True)
+            legs["linear_m%d" % m] = {"TFLOP/s": fl / ms / 1e9, "ms_per_step": ms, "us_per_row": ms * 1e3 / m}
         for m in (512, 2048):
             ms, fl = gemm_leg(m)
             ms7, _, _ = linear_leg(m, 5, 2, prepared_single=True)

@@ -137,7 +137,8 @@ razer_status razer_dequant(const razer_tensor *t, void *out, int32_t dtype, int6
  * tensor scale(s) and rounded to bf16:  y_bf16 device [m][ld_y], ld_y >= N.
  * workspace: device, 16-byte aligned, >= razer_workspace_bytes(RAZER_OP_LINEAR, N, K, m) bytes
  * (non-zero where K is split over workgroups and the slices meet in fp32: W4A16 with 5 <= m <= 32,
- * and m > 32 with fewer than 128 output tiles; else may be NULL); too small -> RAZER_ERR_WORKSPACE. */
+ * and m > 32 with too few output tiles to occupy the GPU -- ask razer_workspace_bytes; else may be
+ * NULL); too small -> RAZER_ERR_WORKSPACE. */
 razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer_tensor *a_q,
                           int64_t m, void *y_bf16, int64_t ld_y,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
@@ -153,8 +154,11 @@ razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer
  *     aligned, and the workspace holds the SUM over i of
  *     razer_workspace_bytes(RAZER_OP_LINEAR, rows[i], cols, m) (plus one launch that adds the
  *     K-slices up);
- *   16-element blocks, m > 128 and the matrices together have >= 512 output tiles of 256 x 128, or
- *     192..256 of them with cols >= 1024 (no workspace).
+ *   16-element blocks, m >= 33: without a workspace when m > 128 and the matrices together have
+ *     >= 512 output tiles of 256 x 128, or 192..256 of them with cols >= 1024; otherwise K is cut into
+ *     slices (plus one launch that adds them up) under the conditions of the 5 <= m <= 32 case --
+ *     rows, ld_y, alignment of y_bf16, and a workspace that holds the SUM over i of the per-matrix
+ *     razer_workspace_bytes.
  * Otherwise it is the sequence of razer_linear calls with the same workspace (which then must
  * satisfy each call).  y_bf16[i] is device [m][ld_y[i]].  The pointer arrays are HOST arrays. */
 #define RAZER_MAX_GROUP 4

@@ -241,14 +241,23 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
             }
             if (ok && (need == 0 || (workspace && workspace_bytes >= need && aligned16(workspace)))) path = SKINNY;
         } else if (gemm_grouped_fits(count, p, m, k)) {
-            path = GEMM;
+            // 33..128 rows with few tiles: K-slices of all matrices in the workspace, summed by the grouped
+            // reduction (which stores four columns at a time)
+            const size_t need = gemm_grouped_workspace_bytes(count, p, m, k);
+            bool ok = true;
+            if (need > 0) {
+                ok = workspace && workspace_bytes >= need && aligned16(workspace);
+                for (int i = 0; i < count; ++i)
+                    if (p[i].n % 4 != 0 || (reinterpret_cast<uintptr_t>(p[i].y) & 7u) != 0 || p[i].ld_y % 4 != 0) ok = false;
+            }
+            if (ok) path = GEMM;
         }
     }
     hipError_t e = hipSuccess;
     switch (path) {
         case GEMV: e = launch_gemv_grouped(sv0, count, p, k, (const uint16_t*)a_bf16, m, st); break;
         case SKINNY: e = launch_skinny_grouped(sv0, count, p, k, (const uint16_t*)a_bf16, m, (float*)workspace, st); break;
-        case GEMM: e = launch_gemm_grouped(sv0, count, p, k, (const uint16_t*)a_bf16, m, st); break;
+        case GEMM: e = launch_gemm_grouped(sv0, count, p, k, (const uint16_t*)a_bf16, m, (float*)workspace, st); break;
         case SEQUENCE:
             for (int i = 0; i < count; ++i) {
                 razer_status s = razer_linear(w[i], a_bf16, nullptr, m, y_bf16[i], ld_y[i], workspace, workspace_bytes,

@@ -915,8 +915,8 @@ __global__ __launch_bounds__(64 * NW, (rb_waves_per_simd<NW, KG, MT>())) void ge
 // column tiles of the matrices are numbered one after another, t1..t3 are the first tile of matrices
 // 1..3 (equal to the total for matrices that are absent).  One launch fills the last round of
 // workgroups better than one launch per matrix.
-template <int NW, int S, int KG = 1>
-__global__ __launch_bounds__(64 * NW, KG == 1 ? 8 / NW : 1) void gemm_rb_grouped_kernel(
+template <int NW, int S, int KG = 1, int MT = 8>
+__global__ __launch_bounds__(64 * NW, (rb_waves_per_simd<NW, KG, MT>())) void gemm_rb_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
     const float* f0, const float* f1, const float* f2, const float* f3,
@@ -924,16 +924,20 @@ __global__ __launch_bounds__(64 * NW, KG == 1 ? 8 / NW : 1) void gemm_rb_grouped
     int64_t n0, int64_t n1, int64_t n2, int64_t n3,
     int64_t l0, int64_t l1, int64_t l2, int64_t l3,
     int t1, int t2, int t3,
-    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int64_t m, int tiles_m)
+    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int64_t m, int tiles_m,
+    float* __restrict__ partial, int kt_per_slice)
 {
     const int tile_m = (int)(blockIdx.x % tiles_m), t = (int)(blockIdx.x / tiles_m);
     const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = f0; uint16_t* y = y0;
-    int64_t n = n0, ld = l0;
+    int64_t n = n0, ld = l0, before = 0;
     int first = 0;
-    if (t >= t1) { codes = c1; scales = s1; ts = f1; y = y1; n = n1; ld = l1; first = t1; }
-    if (t >= t2) { codes = c2; scales = s2; ts = f2; y = y2; n = n2; ld = l2; first = t2; }
-    if (t >= t3) { codes = c3; scales = s3; ts = f3; y = y3; n = n3; ld = l3; first = t3; }
-    gemm_rb_body<NW, S, KG>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, tile_m, t - first);
+    if (t >= t1) { codes = c1; scales = s1; ts = f1; y = y1; n = n1; ld = l1; first = t1; before = n0; }
+    if (t >= t2) { codes = c2; scales = s2; ts = f2; y = y2; n = n2; ld = l2; first = t2; before = n0 + n1; }
+    if (t >= t3) { codes = c3; scales = s3; ts = f3; y = y3; n = n3; ld = l3; first = t3; before = n0 + n1 + n2; }
+    // with K-slices (partial != nullptr) matrix i keeps its [slices][m][n_i] sums behind those of matrices 0 .. i-1
+    gemm_rb_body<NW, S, KG, MT>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, tile_m, t - first,
+                                partial ? partial + (int64_t)gridDim.y * m * before : nullptr, (int)blockIdx.y,
+                                kt_per_slice);
 }
 
 // split > 1 (KG == 1 only, workspace of slices * m * n floats): K in slices of whole K-tiles, summed by
@@ -1008,11 +1012,12 @@ struct GemmPlan {
     int tile;
     int split;
 };
-// K-slices of the register-decode kernel with small activation tiles: about one workgroup per compute
-// unit (best or within 5 % of it at 32 and 86 tiles, K = 4096 and 11008), at least 8 K-tiles per slice.
+// K-slices of the register-decode kernel with small activation tiles: about one and a half workgroups
+// per compute unit (best or within 5 % of it at 32, 86 and 172 tiles, K = 4096 and 11008), at least 8
+// K-tiles per slice.
 static int rb_split(int64_t tiles, int64_t kt_all)
 {
-    int64_t split = (256 + tiles / 2) / tiles;
+    int64_t split = (384 + tiles / 2) / tiles;
     if (split > 16) split = 16;
     if (split > kt_all / 8) split = kt_all / 8;
     return split >= 2 ? (int)split : 1;
@@ -1099,14 +1104,17 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
     return hipErrorInvalidValue;
 }
 
-// The grouped launch uses the register-decode kernel only, so the matrices together must offer the
-// tile counts that kernel is chosen at (see gemm_plan); a weight-tile width that does not divide a
-// matrix's rows just leaves its last tile partly empty.
+// The grouped launch uses the register-decode kernel only.  Above 128 activation rows the matrices
+// together must offer the tile counts that kernel is chosen at (see gemm_plan); a weight-tile width that
+// does not divide a matrix's rows just leaves its last tile partly empty.  From 33 to 128 rows it is the
+// kernel of the single calls too, and the K-slices are chosen for the tiles of all matrices together.
 // Returns 256 / 128 (tile width of the plain kernel), 129 (128-wide tiles, two K groups: one round of
-// tiles on at least three quarters of the compute units) or 0 (no grouped launch).
+// tiles on at least three quarters of the compute units), 2 / 4 / 8 (64 / 128 / 256 activation rows per
+// tile, 128-wide, K-slices when the tiles are few) or 0 (no grouped launch).
 static int grouped_tile_width(int count, const GemvProblem* p, int64_t m, int64_t k)
 {
-    if (m <= 128) return 0;                             // fewer rows take the smaller tiles of the single calls
+    if (m <= 32) return 0;
+    if (m <= 128) return m <= 64 ? 2 : 4;
     const int64_t tm = (m + 255) / 256;
     int64_t t256 = 0, t128 = 0;
     for (int i = 0; i < count; ++i) {
@@ -1116,20 +1124,38 @@ static int grouped_tile_width(int count, const GemvProblem* p, int64_t m, int64_
     if (t256 >= 1024 || (t256 >= 512 && t256 % 256 == 0)) return 256;
     if (t128 >= 512) return 128;
     if (t128 >= 192 && t128 <= 256 && k >= 16 * kBK) return 129;
-    return 0;
+    return 8;                                           // fewer tiles, or between one and two rounds: K-slices
+}
+static int grouped_split(int count, const GemvProblem* p, int64_t m, int64_t k)
+{
+    const int w = grouped_tile_width(count, p, m, k);
+    if (w != 2 && w != 4 && w != 8) return 1;
+    int64_t tiles = 0;
+    for (int i = 0; i < count; ++i) tiles += (p[i].n + 127) / 128;
+    return rb_split(tiles * ((m + 32 * w - 1) / (32 * w)), (k + kBK - 1) / kBK);
 }
 bool gemm_grouped_fits(int count, const GemvProblem* p, int64_t m, int64_t k)
 {
     return count >= 1 && count <= 4 && grouped_tile_width(count, p, m, k) != 0;
 }
-
-template <int NW, int S, int KG = 1>
-static hipError_t launch_rb_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
-                                    int64_t m, hipStream_t st)
+size_t gemm_grouped_workspace_bytes(int count, const GemvProblem* p, int64_t m, int64_t k)
 {
-    constexpr int BM = 256, BN = 32 * NW / KG;
+    const int split = grouped_split(count, p, m, k);
+    if (split == 1) return 0;
+    const int64_t kt_all = (k + kBK - 1) / kBK, kt_per = (kt_all + split - 1) / split;
+    const int64_t slices = (kt_all + kt_per - 1) / kt_per;
+    int64_t n_all = 0;
+    for (int i = 0; i < count; ++i) n_all += p[i].n;
+    return (size_t)(slices * m * n_all) * sizeof(float);
+}
+
+template <int NW, int S, int KG = 1, int MT = 8>
+static hipError_t launch_rb_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
+                                    int64_t m, hipStream_t st, int split = 1, float* workspace = nullptr)
+{
+    constexpr int BM = 32 * MT, BN = 32 * NW / KG;
     constexpr size_t smem = S * (KG * BM * 128 + NW * 1280) + 256 * sizeof(uint2);
-    auto kern = gemm_rb_grouped_kernel<NW, S, KG>;
+    auto kern = gemm_rb_grouped_kernel<NW, S, KG, MT>;
     static bool attr_set = false;                      // one GPU per process
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1137,28 +1163,41 @@ static hipError_t launch_rb_grouped(SvConfig cfg, int count, const GemvProblem* 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
+    if (KG != 1 || !workspace) split = 1;
     const int tiles_m = (int)((m + BM - 1) / BM);
+    const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + split - 1) / split;
+    const int slices = (kt_all + kt_per - 1) / kt_per;
     GemvProblem q[4];
     int t[5] = {0, 0, 0, 0, 0};
     for (int i = 0; i < 4; ++i) {
         q[i] = p[i < count ? i : count - 1];
         t[i + 1] = t[i] + (i < count ? (int)((q[i].n + BN - 1) / BN) : 0);
     }
-    kern<<<dim3((unsigned)(tiles_m * t[4])), dim3(64 * NW), smem, st>>>(
+    kern<<<dim3((unsigned)(tiles_m * t[4]), (unsigned)slices), dim3(64 * NW), smem, st>>>(
         q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts,
         q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,
-        q[1].ld_y, q[2].ld_y, q[3].ld_y, t[1], t[2], t[3], cfg.sv0, cfg.sv1, k, a, m, tiles_m);
-    return hipGetLastError();
+        q[1].ld_y, q[2].ld_y, q[3].ld_y, t[1], t[2], t[3], cfg.sv0, cfg.sv1, k, a, m, tiles_m,
+        slices > 1 ? workspace : nullptr, slices > 1 ? kt_per : 0x7FFFFFFF);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || slices == 1) return e;
+    return launch_slice_reduce_grouped(workspace, count, p, m, slices, st);
 }
 
 hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
-                               int64_t m, hipStream_t st)
+                               int64_t m, float* workspace, hipStream_t st)
 {
     if (count < 1 || count > 4 || cfg.lb != 4) return hipErrorInvalidValue;
     const int w = grouped_tile_width(count, p, m, k);
     if (w == 256) return launch_rb_grouped<8, 2>(cfg, count, p, k, a, m, st);
     if (w == 128) return launch_rb_grouped<4, 2>(cfg, count, p, k, a, m, st);
     if (w == 129) return launch_rb_grouped<8, 2, 2>(cfg, count, p, k, a, m, st);
+    if (w == 2 || w == 4 || w == 8) {
+        const int split = grouped_split(count, p, m, k);
+        if (split > 1 && !workspace) return hipErrorInvalidValue;
+        if (w == 2) return launch_rb_grouped<4, 2, 1, 2>(cfg, count, p, k, a, m, st, split, workspace);
+        if (w == 4) return launch_rb_grouped<4, 2, 1, 4>(cfg, count, p, k, a, m, st, split, workspace);
+        return launch_rb_grouped<4, 2, 1, 8>(cfg, count, p, k, a, m, st, split, workspace);
+    }
     return hipErrorInvalidValue;
 }
 

@@ -62,11 +62,19 @@ hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_s
 hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
                                  int64_t m, float* workspace, hipStream_t st);
 
+// Sum of the K-slices of a grouped launch: partial holds matrix i's [nslices][m][n_i] fp32 slices
+// behind those of matrices 0 .. i-1 (every n a positive multiple of 4, y 8-byte aligned, ld_y % 4 == 0).
+hipError_t launch_slice_reduce_grouped(const float* partial, int count, const GemvProblem* p, int64_t m, int nslices,
+                                       hipStream_t st);
+
 // Up to 4 weight matrices (16-element blocks, equal special values, every n > 0, k > 0) against the
 // same bf16 activations in one launch of the register-decode GEMM kernel; possible when
-// gemm_grouped_fits() says the matrices together have enough output tiles for it.
+// gemm_grouped_fits() says so (m >= 33).  gemm_grouped_workspace_bytes() > 0 (few output tiles: K is
+// sliced): the launch needs that many bytes of workspace and the conditions of
+// launch_slice_reduce_grouped.
 bool gemm_grouped_fits(int count, const GemvProblem* p, int64_t m, int64_t k);
+size_t gemm_grouped_workspace_bytes(int count, const GemvProblem* p, int64_t m, int64_t k);
 hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
-                               int64_t m, hipStream_t st);
+                               int64_t m, float* workspace, hipStream_t st);
 
 }  // namespace razer

@@ -267,6 +267,23 @@ __global__ __launch_bounds__(256) void slice_reduce_grouped_kernel(
     *reinterpret_cast<uint2*>(y + r * ld + c) = make_uint2(lo, hi);      // y 8-byte aligned, ld a multiple of 4
 }
 
+// partial: matrix i's [nslices][m][n_i] fp32 slices behind those of matrices 0 .. i-1.  Every n a
+// positive multiple of 4, every y 8-byte aligned, every ld_y a multiple of 4.
+hipError_t launch_slice_reduce_grouped(const float* partial, int count, const GemvProblem* p, int64_t m, int nslices,
+                                       hipStream_t st)
+{
+    GemvProblem q[4];
+    int64_t e[5] = {0, 0, 0, 0, 0};
+    for (int i = 0; i < 4; ++i) {
+        q[i] = p[i < count ? i : count - 1];
+        e[i + 1] = e[i] + (i < count ? m * q[i].n / 4 : 0);
+    }
+    slice_reduce_grouped_kernel<<<(unsigned)((e[4] + 255) / 256), 256, 0, st>>>(
+        partial, q[0].ts, q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n,
+        q[0].ld_y, q[1].ld_y, q[2].ld_y, q[3].ld_y, e[1], e[2], e[3], e[4], m, nslices);
+    return hipGetLastError();
+}
+
 static int skinny_steps(int64_t k, int64_t m)
 {
     // 512-element K-slices; 1024 for long rows at M <= 16 to bound the number of slices
@@ -328,7 +345,6 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
     const int nslices = (int)((k + kc - 1) / kc);
     GemvProblem q[4];
     unsigned g[5] = {0, 0, 0, 0, 0};
-    int64_t e[5] = {0, 0, 0, 0, 0};
     int64_t row_blocks = 0;
     for (int i = 0; i < count; ++i) row_blocks += (p[i].n + kSkRows - 1) / kSkRows;
     const int nrb = skinny_row_blocks(row_blocks, nslices);
@@ -337,7 +353,6 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
         if (q[i].n % 4 != 0 || q[i].n <= 0) return hipErrorInvalidValue;
         const int64_t rbi = (q[i].n + kSkRows - 1) / kSkRows;
         g[i + 1] = g[i] + (i < count ? (unsigned)((rbi + nrb - 1) / nrb) * nslices : 0u);
-        e[i + 1] = e[i] + (i < count ? m * q[i].n / 4 : 0);
     }
     float* partial = nslices > 1 ? workspace : nullptr;
 #define RAZER_SKG(NB, ST) skinny_grouped_kernel<NB, ST><<<g[4], 256, 0, st>>>(                                      \
@@ -349,10 +364,7 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
 #undef RAZER_SKG
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || nslices == 1) return err;
-    slice_reduce_grouped_kernel<<<(unsigned)((e[4] + 255) / 256), 256, 0, st>>>(
-        partial, q[0].ts, q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n,
-        q[0].ld_y, q[1].ld_y, q[2].ld_y, q[3].ld_y, e[1], e[2], e[3], e[4], m, nslices);
-    return hipGetLastError();
+    return launch_slice_reduce_grouped(partial, count, p, m, nslices, st);
 }
 
 }  // namespace razer

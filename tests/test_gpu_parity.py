@@ -342,6 +342,27 @@ def test_linear_grouped_gemm_one_launch(oracle, m, ns, k):
         assert torch.all(b[:, n:] == 2.0)
 
 
+@pytest.mark.parametrize("m,k,ns", [(33, 512 + 64, [132, 64, 200]), (64, 4096, [132, 64, 200]), (100, 11008, [132, 64]),
+                                    (128, 2048 + 32, [132, 64, 200, 4]), (48, 1024, [130, 61])])
+def test_linear_grouped_mid_batch_one_launch(oracle, m, k, ns):
+    """33 <= m <= 128: one launch of the register-decode GEMM over all matrices, K-slices of all of
+    them in one workspace and one reduction launch (one slice in the first case, eight and more in the
+    others); the last case (row counts that are not multiples of 4) runs matrix by matrix."""
+    print("grouped mid batch", m, k, ns, flush=True)
+    rng = np.random.default_rng(2200 + m)
+    a = synth.activation(m, k, seed=2201 + m)
+    a_dev = bf16_bits_to_dev(a)
+    wqs = [_rand_tensor(rng, W, n, k) for n in ns]
+    wts = [razer.RazerTensor.from_host(*wq, W, (5.0, 8.0)) for wq in wqs]
+    bufs = [torch.full((m, n + (8 if n % 4 == 0 else 3)), 2.0, dtype=torch.bfloat16, device="cuda") for n in ns]
+    razer.razer_linear_grouped(wts, a_dev, outs=[b[:, :n] for b, n in zip(bufs, ns)])
+    torch.cuda.synchronize()
+    for wq, b, n in zip(wqs, bufs, ns):
+        y64, _ = oracle.linear(wq, a_bf16=a)
+        assert max_rel_err(dev_to_bf16_bits(b[:, :n]), y64) <= TOL
+        assert torch.all(b[:, n:] == 2.0)
+
+
 # ------------------------------------------------------------------ block sizes 32, 64, 128 (Sec. 5.4)
 BLOCKS = [32, 64, 128]
 
