@@ -259,7 +259,7 @@ def main():
     def gemm_roofline(ms, fl):
         return {"bound": "mfma", "achieved": fl / ms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                "kernel": "gemm_rb_grouped_kernel<4,2,1> ({q,k,v}, {gate,up}) + gemm_rb_kernel<8,2,2> (o, down), "
+                "kernel": "gemm_rb_grouped_kernel<4,2,1,8> ({q,k,v}, {gate,up}) + gemm_rb_kernel<8,2,2,8> (o, down), "
                           "M=2048, Llama-7B layer set as 4 calls, flops = 2MNK, whole-leg time"}
 
     if args.legs == "gemm":                                  # profiler runs: only the M=2048 GEMM leg

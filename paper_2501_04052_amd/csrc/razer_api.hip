@@ -177,7 +177,7 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
         if (a_q) return RAZER_ERR_CONFIG;
         e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
                         (uint16_t*)y_bf16, ld_y, st);
-    } else if (!a_q && m > kGemvDirectMaxM && m <= kSkinnyMaxM) {
+    } else if (!a_q && m > kGemvDirectMaxM && m <= kSkinnyMaxM && k <= kSkinnyMaxK) {
         const size_t need = skinny_workspace_bytes(n, k, m);
         if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return RAZER_ERR_WORKSPACE;
         e = launch_skinny(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
@@ -231,6 +231,8 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
             path = GEMV;                                 // every block size and both weight formats
         } else if (sv0.lb != 4 || sv0.f16) {
             path = SEQUENCE;                             // the grouped MFMA kernels read one scale byte per 16 elements
+        } else if (m <= kSkinnyMaxM && k > kSkinnyMaxK) {
+            path = SEQUENCE;
         } else if (m <= kSkinnyMaxM) {
             // the K-slices of all matrices live in the workspace side by side
             size_t need = 0;

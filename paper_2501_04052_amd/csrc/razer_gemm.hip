@@ -1060,12 +1060,13 @@ static GemmPlan gemm_plan(int64_t m, int64_t n, int64_t k, bool register_decode_
 
 size_t gemm_workspace_bytes(int64_t n, int64_t k, int64_t m)
 {
-    if (m <= kSkinnyMaxM || n == 0 || k == 0) return 0;          // (W4A4 with m <= 32 is planned below too)
+    if (n == 0 || k == 0) return 0;
+    if (m <= kSkinnyMaxM && k <= kSkinnyMaxK) return 0;          // the small-batch kernel's range (W4A4 there runs unsplit)
     // the caller of this query does not say which operand formats it will pass: the larger of the
     // two plans (register-decode kernel allowed or not)
     size_t need = 0;
     for (int rd = 0; rd < 2; ++rd) {
-        const GemmPlan p = gemm_plan(m, n, k, rd != 0);
+        const GemmPlan p = gemm_plan(m, n, k, rd != 0 && k <= kRbMaxK);
         if (p.split == 1) continue;
         const int64_t kt_all = (k + kBK - 1) / kBK, kt_per = (kt_all + p.split - 1) / p.split;
         const int64_t slices = (kt_all + kt_per - 1) / kt_per;
@@ -1081,8 +1082,8 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
                                 const uint8_t* a_scales, const float* a_ts, SvConfig acfg, int64_t m, uint16_t* y,
                                 int64_t ld_y, float* workspace, hipStream_t st)
 {
-    GemmPlan p = gemm_plan(m, n, k, !AQ && !GB);
-    if (m <= kSkinnyMaxM || !workspace) p.split = 1;             // small m is not sized a workspace
+    GemmPlan p = gemm_plan(m, n, k, !AQ && !GB && k <= kRbMaxK);
+    if ((m <= kSkinnyMaxM && k <= kSkinnyMaxK) || !workspace) p.split = 1;   // not sized a workspace
 #define RAZER_GEMM(BM, BN, WGM, WGN, PP) \
     launch_cfg<BM, BN, WGM, WGN, AQ, PP, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, p.split, workspace, st)
     switch (p.tile) {
@@ -1113,7 +1114,7 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
 // tile, 128-wide, K-slices when the tiles are few) or 0 (no grouped launch).
 static int grouped_tile_width(int count, const GemvProblem* p, int64_t m, int64_t k)
 {
-    if (m <= 32) return 0;
+    if (m <= 32 || k > kRbMaxK) return 0;
     if (m <= 128) return m <= 64 ? 2 : 4;
     const int64_t tm = (m + 255) / 256;
     int64_t t256 = 0, t128 = 0;

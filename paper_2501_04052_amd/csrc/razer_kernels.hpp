@@ -20,6 +20,10 @@ hipError_t launch_dequant(int fmt, SvConfig cfg, const uint8_t* codes, const uin
 constexpr int kGemvMaxM = 16;
 constexpr int kGemvDirectMaxM = 4;     // rows the GEMV kernel takes in one pass
 constexpr int kSkinnyMaxM = 32;        // above this the tiled GEMM takes over
+// The small-batch kernel and the register-decode GEMM address inside a row block / tile with 32-bit
+// offsets (up to 31 rows x 2 K bytes, resp. 255 rows x 2 K bytes); longer rows take the LDS-staged GEMM.
+constexpr int64_t kSkinnyMaxK = (int64_t)1 << 24;
+constexpr int64_t kRbMaxK = (int64_t)1 << 22;
 
 // 5 <= m <= kSkinnyMaxM: decode-once MFMA kernel; K-slices meet in an fp32 workspace of
 // skinny_workspace_bytes(n, k, m) bytes (0 when a single slice covers K).

@@ -52,42 +52,76 @@ __device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, c
     __shared__ __align__(16) uint8_t atile[NB * 16 * ROWB];
     __shared__ uint2 lut[256];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the wave index is uniform: read as a scalar it keeps the row arithmetic off the vector unit
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tid = wave * 64 + lane;
     const int slice = block % nslices;
     const int64_t nfirst = (int64_t)(block / nslices) * nrb * kSkRows;   // nrb consecutive 64-row blocks
     const int64_t k0 = (int64_t)slice * KC;
     const float ts = *w_ts;
 
     // this lane's weights of the row block at n0: row n0 + 16 wave + (lane % 16),
-    // k = k0 + 128 s + 32 (lane / 16) .. +31.  Rows past N re-read the last row (never stored).
+    // k = k0 + 128 s + 32 (lane / 16) .. +31.  Rows past N re-read the last row (never stored).  Steps past
+    // K re-read step 0 and get their scale bytes cleared: scale code 0 is 0.0, so whatever the codes are,
+    // the weights (special values included) decode to 0.
+    // Addresses: a uniform 64-bit base per row block (scalar unit) plus 32-bit lane offsets -- the host
+    // sends rows longer than kSkinnyMaxK elsewhere.
+    const uint32_t code_ld = (uint32_t)(k >> 1), scale_ld = (uint32_t)(k >> lb);
+    const uint32_t krem = (uint32_t)((k - k0 < KC) ? k - k0 : KC);       // elements of this slice inside K
+    const uint32_t kl = 32u * (lane >> 4);
     auto load_weights = [&](int64_t n0, uint4 (&cw)[STEPS], uint32_t (&sw)[STEPS]) {
-        const int64_t wrow_raw = n0 + 16 * wave + (lane & 15);
-        const int64_t wrow = wrow_raw < n ? wrow_raw : n - 1;
+        int64_t r0 = n0 + 16 * wave;                               // uniform: first row of this wave
+        r0 = r0 < n ? r0 : n - 1;
+        const uint32_t left = (uint32_t)((n - 1 - r0 < 15) ? n - 1 - r0 : 15);
+        const uint32_t dl = ((uint32_t)lane & 15u) < left ? ((uint32_t)lane & 15u) : left;
+        const uint8_t* cbase = codes + r0 * (int64_t)code_ld + (k0 >> 1);
+        const uint8_t* sbase = scales + r0 * (int64_t)scale_ld + (k0 >> (GB ? lb : 4));   // k0 holds whole blocks
+        const uint32_t crow = dl * code_ld, srow = dl * scale_ld;
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
-            const int64_t kk = k0 + 128 * s + 32 * (lane >> 4);
-            const bool in = kk < k;
-            const int64_t kc = in ? kk : 0;
-            const uint4 c = *reinterpret_cast<const uint4*>(codes + wrow * (k / 2) + kc / 2);
-            const uint32_t sc = load_scale_pair<GB>(scales + wrow * (k >> lb), kc, lb);
-            const uint32_t msk = in ? 0xFFFFFFFFu : 0u;           // beyond K: code 0, scale 0 -> weight 0
-            cw[s] = make_uint4(c.x & msk, c.y & msk, c.z & msk, c.w & msk);
-            sw[s] = sc & msk;
+            const uint32_t kin = 128u * s + kl;                    // offset inside the slice
+            const bool in = kin < krem;
+            const uint32_t kc = in ? kin : 0u;
+            cw[s] = *reinterpret_cast<const uint4*>(cbase + (crow + (kc >> 1)));
+            uint32_t sc;
+            if (GB) {
+                const uint32_t b = sbase[srow + (kc >> lb)];
+                sc = b | (b << 8);
+            } else {
+                sc = *reinterpret_cast<const uint16_t*>(sbase + (srow + (kc >> 4)));
+            }
+            sw[s] = in ? sc : 0u;
         }
     };
     uint4 cw[STEPS];
     uint32_t sw[STEPS];
     load_weights(nfirst, cw, sw);
-    // activations [NB*16][KC] -> LDS, 16-byte chunks swizzled with the row (shared by all row blocks)
-    constexpr int UNITS = NB * 16 * (KC / 8);
+    // activations [NB*16][KC] -> LDS, 16-byte chunks swizzled with the row (shared by all row blocks).
+    // Fragment rows past M copy row M - 1: their product columns are never stored.  Chunks past K must be
+    // zero -- the weights there are zero, but 0 x Inf would not be.
+    constexpr int CH = KC / 8;                                     // 16-byte chunks per row
+    constexpr int UNITS = NB * 16 * CH;
+    const uint8_t* abase = reinterpret_cast<const uint8_t*>(a + k0);
+    const uint32_t a_ld = (uint32_t)k * 2u;
 #pragma unroll
     for (int i = 0; i < UNITS / 256; ++i) {
-        const int u = tid + i * 256, row = u / (KC / 8), c = u % (KC / 8);
-        const int64_t kk = k0 + c * 8;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (row < m && kk < k) v = *reinterpret_cast<const uint4*>(a + (int64_t)row * k + kk);
-        *reinterpret_cast<uint4*>(atile + row * ROWB + ((c ^ (row & 15)) << 4)) = v;
+        const uint32_t u = (uint32_t)tid + i * 256u, row = u / CH, c = u % CH;
+        const uint32_t src_row = row < (uint32_t)m ? row : (uint32_t)m - 1u;
+        uint4 v;
+        if (krem == KC) {                                          // uniform: the whole slice lies inside K
+            v = *reinterpret_cast<const uint4*>(abase + (src_row * a_ld + c * 16u));
+        } else {
+            v = make_uint4(0, 0, 0, 0);
+            if (c * 8u < krem) v = *reinterpret_cast<const uint4*>(abase + (src_row * a_ld + c * 16u));
+        }
+        *reinterpret_cast<uint4*>(atile + row * ROWB + ((c ^ (row & 15u)) << 4)) = v;
     }
+    // LDS address of this lane's activation fragment for instruction j of step 0, fragment 0: row lane % 16,
+    // logical chunk 4 (lane / 16) + j, swizzled; step s adds 256 bytes, fragment b adds 16 rows
+    uint32_t afrag[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        afrag[j] = ((uint32_t)lane & 15u) * ROWB + (((4u * (lane >> 4) + j) ^ ((uint32_t)lane & 15u)) << 4);
     for (uint32_t sb = tid; sb < 256u; sb += 256) {
         float s, sv;
         decode_scale_byte<0>(sb, sv0, sv1, s, sv);
@@ -102,12 +136,8 @@ __device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, c
         // the next row block's weights are in flight while this one is decoded and multiplied
         uint4 cwn[STEPS];
         uint32_t swn[STEPS];
-#pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            cwn[s] = make_uint4(0, 0, 0, 0);
-            swn[s] = 0;
-        }
-        if (rb + 1 < nrb && n0 + kSkRows < n) load_weights(n0 + kSkRows, cwn, swn);
+        const bool has_next = rb + 1 < nrb && n0 + kSkRows < n;    // uniform over the workgroup
+        if (has_next) load_weights(n0 + kSkRows, cwn, swn);
 
         v4f acc[NB];
 #pragma unroll
@@ -119,11 +149,9 @@ __device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, c
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const v8bf wf = sk_decode_dword(xw[j], j < 2 ? le0 : le1);
-                const int c = 16 * s + 4 * (lane >> 4) + j;
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
-                    const int row = 16 * b + (lane & 15);
-                    const v8bf af = *reinterpret_cast<const v8bf*>(atile + row * ROWB + ((c ^ (row & 15)) << 4));
+                    const v8bf af = *reinterpret_cast<const v8bf*>(atile + afrag[j] + (256 * s + 16 * ROWB * b));
                     acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, af, acc[b], 0, 0, 0);
                 }
             }
@@ -151,6 +179,7 @@ __device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, c
                 }
             }
         }
+        if (!has_next) break;
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
             cw[s] = cwn[s];
@@ -303,7 +332,7 @@ static int skinny_row_blocks(int64_t row_blocks, int64_t nslices)
 
 size_t skinny_workspace_bytes(int64_t n, int64_t k, int64_t m)
 {
-    if (m <= kGemvDirectMaxM || m > kSkinnyMaxM || k == 0) return 0;
+    if (m <= kGemvDirectMaxM || m > kSkinnyMaxM || k == 0 || k > kSkinnyMaxK) return 0;
     const int64_t kc = 128 * skinny_steps(k, m);
     const int64_t nslices = (k + kc - 1) / kc;
     return nslices > 1 ? (size_t)(nslices * m * n) * sizeof(float) : 0;
@@ -339,7 +368,8 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
 hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
                                  int64_t m, float* workspace, hipStream_t st)
 {
-    if (count < 1 || count > 4 || cfg.lb != 4 || m <= kGemvDirectMaxM || m > kSkinnyMaxM) return hipErrorInvalidValue;
+    if (count < 1 || count > 4 || cfg.lb != 4 || m <= kGemvDirectMaxM || m > kSkinnyMaxM || k > kSkinnyMaxK)
+        return hipErrorInvalidValue;
     const int steps = skinny_steps(k, m);
     const int64_t kc = 128 * steps;
     const int nslices = (int)((k + kc - 1) / kc);

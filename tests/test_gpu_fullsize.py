@@ -155,12 +155,31 @@ def test_linear_many_tiles_register_decode_kernel(oracle, m, n, k):
     assert err <= TOL, err
 
 
-@pytest.mark.parametrize("m", [1, 4, 16, 512, 2048])
+@pytest.mark.parametrize("m,n,k", [(64, 4096, 4096), (128, 4096, 11008), (256, 4096, 4096), (100, 11008, 4096)])
+def test_config2_3_mid_batch_single_calls(oracle, m, n, k):
+    """o- and down-shaped projections (and a gate-shaped one) at the batch sizes between decode and large
+    GEMMs: register-decode kernel with 64 / 128-row tiles and K-slices, the LDS-staged split-K kernel at 256."""
+    _say("mid batch at full size, m=%d n=%d k=%d" % (m, n, k))
+    wq = _rand_packed(n, k, seed=8300 + m)
+    wt = razer.RazerTensor.from_host(*wq, W, SV)
+    a = synth.activation(m, k, seed=2300 + m)
+    y = razer.razer_linear(wt, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([synth.sample_indices(m, 32, 9400), [0, m - 1]]))
+    cols = np.unique(np.concatenate([synth.sample_indices(n, 160, 9401), [0, n - 1]]))
+    y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=cols)
+    got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+    err = max_rel_err(got, y64)
+    _say("   %d x %d outputs, max rel err %.2e" % (len(rows), len(cols), err))
+    assert err <= TOL, err
+
+
+@pytest.mark.parametrize("m", [1, 4, 16, 64, 128, 256, 512, 2048])
 def test_config2_3_grouped_launches_as_benchmarked(oracle, m):
     """The launch configuration bench.py times: {q,k,v} and {gate,up} of the Llama-7B-shaped layer each
     as ONE razer_linear_grouped call (grouped GEMV, matrix-instruction GEMV, grouped small-batch kernel
-    with its grouped reduction, grouped register-decode GEMM).  Whole outputs up to M = 16, sampled
-    rows x columns beyond."""
+    with its grouped reduction, grouped register-decode GEMM -- with K-slices and the grouped reduction
+    at M = 64, 128, 256).  Whole outputs up to M = 16, sampled rows x columns beyond."""
     _say("grouped launches at full size, m=%d" % m)
     a = synth.activation(m, 4096, seed=2100 + m)
     a_dev = bf16_bits_to_dev(a)

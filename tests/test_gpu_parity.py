@@ -179,7 +179,7 @@ def test_linear_gemm_matches_oracle(oracle, m, n, k):
 
 @pytest.mark.parametrize("m,n,k", [(33, 100, 96), (48, 130, 1024), (64, 513, 4096 + 32), (64, 64, 11008), (65, 100, 544),
                                    (96, 260, 2048), (128, 513, 4096 + 32), (128, 32, 11008), (100, 1, 4096),
-                                   (128, 300, 64)])
+                                   (128, 300, 64), (40, 70, 32)])
 def test_linear_mid_batch_matches_oracle(oracle, m, n, k):
     """33..128 activation rows: the register-decode kernel with 64- and 128-row tiles; one to sixteen
     K-slices (the slices meet in the workspace), ragged last K-tile, ragged rows on both sides."""
