@@ -62,8 +62,10 @@ __device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, c
 
     // this lane's weights of the row block at n0: row n0 + 16 wave + (lane % 16),
     // k = k0 + 128 s + 32 (lane / 16) .. +31.  Rows past N re-read the last row (never stored).  Steps past
-    // K re-read step 0 and get their scale bytes cleared: scale code 0 is 0.0, so whatever the codes are,
-    // the weights (special values included) decode to 0.
+    // K re-read step 0; where they are used their scale bytes are cleared: scale code 0 is 0.0, so whatever
+    // the codes are, the weights (special values included) decode to 0.  Nothing here touches a loaded
+    // value: an operation on one would make the wave wait for the load right where it was issued, and the
+    // loads for the next row block are meant to stay in flight while the current one is decoded.
     // Addresses: a uniform 64-bit base per row block (scalar unit) plus 32-bit lane offsets -- the host
     // sends rows longer than kSkinnyMaxK elsewhere.
     const uint32_t code_ld = (uint32_t)(k >> 1), scale_ld = (uint32_t)(k >> lb);
@@ -90,12 +92,11 @@ __device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, c
             } else {
                 sc = *reinterpret_cast<const uint16_t*>(sbase + (srow + (kc >> 4)));
             }
-            sw[s] = in ? sc : 0u;
+            sw[s] = sc;
         }
     };
     uint4 cw[STEPS];
     uint32_t sw[STEPS];
-    load_weights(nfirst, cw, sw);
     // activations [NB*16][KC] -> LDS, 16-byte chunks swizzled with the row (shared by all row blocks).
     // Fragment rows past M copy row M - 1: their product columns are never stored.  Chunks past K must be
     // zero -- the weights there are zero, but 0 x Inf would not be.
@@ -103,18 +104,29 @@ __device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, c
     constexpr int UNITS = NB * 16 * CH;
     const uint8_t* abase = reinterpret_cast<const uint8_t*>(a + k0);
     const uint32_t a_ld = (uint32_t)k * 2u;
+    // (loads in batches of four, from clamped addresses and without a branch around any of them: a load
+    // under a branch is waited for before the next one is issued)
+    // The first row block's weights are requested right behind the first batch: loads return in order, so
+    // the staging (L2 hits) is not held up behind them (HBM), and they are under way while LDS is filled.
+    constexpr int NU = UNITS / 256, BATCH = NU < 4 ? NU : 4;
 #pragma unroll
-    for (int i = 0; i < UNITS / 256; ++i) {
-        const uint32_t u = (uint32_t)tid + i * 256u, row = u / CH, c = u % CH;
-        const uint32_t src_row = row < (uint32_t)m ? row : (uint32_t)m - 1u;
-        uint4 v;
-        if (krem == KC) {                                          // uniform: the whole slice lies inside K
-            v = *reinterpret_cast<const uint4*>(abase + (src_row * a_ld + c * 16u));
-        } else {
-            v = make_uint4(0, 0, 0, 0);
-            if (c * 8u < krem) v = *reinterpret_cast<const uint4*>(abase + (src_row * a_ld + c * 16u));
+    for (int i0 = 0; i0 < NU; i0 += BATCH) {
+        uint4 stage[BATCH];
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+            const uint32_t u = (uint32_t)tid + (i0 + i) * 256u, row = u / CH, c = u % CH;
+            const uint32_t src_row = row < (uint32_t)m ? row : (uint32_t)m - 1u;
+            const uint32_t src_c = c * 8u < krem ? c : 0u;
+            stage[i] = *reinterpret_cast<const uint4*>(abase + (src_row * a_ld + src_c * 16u));
         }
-        *reinterpret_cast<uint4*>(atile + row * ROWB + ((c ^ (row & 15u)) << 4)) = v;
+        if (i0 == 0) load_weights(nfirst, cw, sw);
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+            const uint32_t u = (uint32_t)tid + (i0 + i) * 256u, row = u / CH, c = u % CH;
+            const uint32_t keep = c * 8u < krem ? 0xFFFFFFFFu : 0u;
+            const uint4 v = make_uint4(stage[i].x & keep, stage[i].y & keep, stage[i].z & keep, stage[i].w & keep);
+            *reinterpret_cast<uint4*>(atile + row * ROWB + ((c ^ (row & 15u)) << 4)) = v;
+        }
     }
     // LDS address of this lane's activation fragment for instruction j of step 0, fragment 0: row lane % 16,
     // logical chunk 4 (lane / 16) + j, swizzled; step s adds 256 bytes, fragment b adds 16 rows
@@ -144,7 +156,8 @@ __device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, c
         for (int b = 0; b < NB; ++b) acc[b] = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
-            const uint2 le0 = lut[sw[s] & 255u], le1 = lut[(sw[s] >> 8) & 255u];
+            const uint32_t sws = (128u * s + kl < krem) ? sw[s] : 0u;       // steps past K: scale 0
+            const uint2 le0 = lut[sws & 255u], le1 = lut[(sws >> 8) & 255u];
             const uint32_t xw[4] = {cw[s].x, cw[s].y, cw[s].z, cw[s].w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -320,13 +333,14 @@ static int skinny_steps(int64_t k, int64_t m)
 }
 
 // Consecutive 64-row blocks one workgroup walks through (staging its activation slice once and
-// keeping the next block's weights in flight): 2 or 4 when that still leaves kSkTargetWgs workgroups.
-// Measured over 4096^2 .. 57344 x 8192: 5-12 % faster on the large matrices, slower on small ones.
-constexpr int64_t kSkTargetWgs = 1024;
-static int skinny_row_blocks(int64_t row_blocks, int64_t nslices)
+// keeping the next block's weights in flight): 2 or 4 when that still leaves 2048 workgroups (up to
+// 16 activation rows) or 1024 (17..32).  Measured over 4096^2 .. 57344 x 8192: 5-12 % faster on the
+// large matrices, slower on small ones.
+static int skinny_row_blocks(int64_t row_blocks, int64_t nslices, int64_t m)
 {
+    const int64_t target = m <= 16 ? 2048 : 1024;
     int nrb = 1;
-    while (nrb < 4 && (row_blocks / (2 * nrb)) * nslices >= kSkTargetWgs) nrb *= 2;
+    while (nrb < 4 && (row_blocks / (2 * nrb)) * nslices >= target) nrb *= 2;
     return nrb;
 }
 
@@ -346,7 +360,7 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
     const int64_t kc = 128 * steps;
     const int nslices = (int)((k + kc - 1) / kc);
     const int64_t row_blocks = (n + kSkRows - 1) / kSkRows;
-    const int nrb = skinny_row_blocks(row_blocks, nslices);
+    const int nrb = skinny_row_blocks(row_blocks, nslices, m);
     const unsigned grid = (unsigned)(((row_blocks + nrb - 1) / nrb) * nslices);
 #define RAZER_SK(NB, ST, GB) skinny_kernel<NB, ST, GB><<<grid, 256, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, workspace, nslices, cfg.lb, nrb)
     if (cfg.lb == 4) {
@@ -377,7 +391,7 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
     unsigned g[5] = {0, 0, 0, 0, 0};
     int64_t row_blocks = 0;
     for (int i = 0; i < count; ++i) row_blocks += (p[i].n + kSkRows - 1) / kSkRows;
-    const int nrb = skinny_row_blocks(row_blocks, nslices);
+    const int nrb = skinny_row_blocks(row_blocks, nslices, m);
     for (int i = 0; i < 4; ++i) {
         q[i] = p[i < count ? i : count - 1];
         if (q[i].n % 4 != 0 || q[i].n <= 0) return hipErrorInvalidValue;
