@@ -40,13 +40,17 @@ __device__ __forceinline__ v8bf sk_decode_dword(uint32_t x, uint2 le)
 constexpr int kSkRows = 64;            // weight rows per workgroup (4 waves x 16)
 
 // NB: activation fragments of 16 rows (M <= 16 NB); STEPS: 128-k steps per workgroup (KC = 128 STEPS).
-template <int NB, int STEPS, bool GB>
+// NRB: consecutive 64-row blocks per workgroup, a template parameter so that the walk is straight-line
+// code -- with the prefetch under a run-time branch the compiler has to assume at every use of the
+// current block's registers that the prefetch did not happen, and waits for most of it.
+template <int NB, int STEPS, bool GB, int NRB>
 __device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                             const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
                                             int64_t k, const uint16_t* __restrict__ a, int64_t m,
                                             uint16_t* __restrict__ y, int64_t ld_y, float* __restrict__ partial,
-                                            int nslices, int lb, unsigned block, int nrb)
+                                            int nslices, int lb, unsigned block)
 {
+    constexpr int nrb = NRB;
     constexpr int KC = 128 * STEPS;
     constexpr int ROWB = KC * 2;                                   // bytes per activation row in LDS
     __shared__ __align__(16) uint8_t atile[NB * 16 * ROWB];
@@ -142,23 +146,29 @@ __device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, c
     }
     __syncthreads();
 
-    for (int rb = 0; rb < nrb; ++rb) {
+    // two register buffers in turn; the next row block's weights are in flight while this one is decoded
+    // and multiplied.  Blocks past N (last workgroup of a matrix) load clamped rows and store nothing.
+    uint4 cwn[STEPS];
+    uint32_t swn[STEPS];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
         const int64_t n0 = nfirst + (int64_t)rb * kSkRows;
-        if (n0 >= n) break;                                        // uniform over the workgroup
-        // the next row block's weights are in flight while this one is decoded and multiplied
-        uint4 cwn[STEPS];
-        uint32_t swn[STEPS];
-        const bool has_next = rb + 1 < nrb && n0 + kSkRows < n;    // uniform over the workgroup
-        if (has_next) load_weights(n0 + kSkRows, cwn, swn);
+        uint4 (&cwc)[STEPS] = (rb & 1) ? cwn : cw;
+        uint32_t (&swc)[STEPS] = (rb & 1) ? swn : sw;
+        if (rb + 1 < NRB) {
+            if (rb & 1) load_weights(n0 + kSkRows, cw, sw);
+            else load_weights(n0 + kSkRows, cwn, swn);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 
         v4f acc[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) acc[b] = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
-            const uint32_t sws = (128u * s + kl < krem) ? sw[s] : 0u;       // steps past K: scale 0
+            const uint32_t sws = (128u * s + kl < krem) ? swc[s] : 0u;      // steps past K: scale 0
             const uint2 le0 = lut[sws & 255u], le1 = lut[(sws >> 8) & 255u];
-            const uint32_t xw[4] = {cw[s].x, cw[s].y, cw[s].z, cw[s].w};
+            const uint32_t xw[4] = {cwc[s].x, cwc[s].y, cwc[s].z, cwc[s].w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const v8bf wf = sk_decode_dword(xw[j], j < 2 ? le0 : le1);
@@ -192,31 +202,24 @@ __device__ __forceinline__ void skinny_body(const uint8_t* __restrict__ codes, c
                 }
             }
         }
-        if (!has_next) break;
-#pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            cw[s] = cwn[s];
-            sw[s] = swn[s];
-        }
     }
 }
 
-template <int NB, int STEPS, bool GB>
+template <int NB, int STEPS, bool GB, int NRB>
 __global__ __launch_bounds__(256) void skinny_kernel(const uint8_t* __restrict__ codes,
                                                      const uint8_t* __restrict__ scales,
                                                      const float* __restrict__ w_ts, float sv0, float sv1,
                                                      int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
                                                      uint16_t* __restrict__ y, int64_t ld_y,
-                                                     float* __restrict__ partial, int nslices, int lb, int nrb)
+                                                     float* __restrict__ partial, int nslices, int lb)
 {
-    skinny_body<NB, STEPS, GB>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, partial, nslices, lb, blockIdx.x,
-                               nrb);
+    skinny_body<NB, STEPS, GB, NRB>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, partial, nslices, lb, blockIdx.x);
 }
 
 // Up to four weight matrices against the same activations in one launch: workgroups are numbered
 // through the matrices one after another (g1..g3 = first workgroup of matrices 1..3); matrix i keeps
 // its K-slices in the workspace behind those of matrices 0 .. i-1.
-template <int NB, int STEPS>
+template <int NB, int STEPS, int NRB>
 __global__ __launch_bounds__(256) void skinny_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
@@ -226,7 +229,7 @@ __global__ __launch_bounds__(256) void skinny_grouped_kernel(
     int64_t l0, int64_t l1, int64_t l2, int64_t l3,
     unsigned g1, unsigned g2, unsigned g3,
     float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int64_t m, float* __restrict__ partial,
-    int nslices, int nrb)
+    int nslices)
 {
     const unsigned b = blockIdx.x;
     const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = f0; uint16_t* y = y0;
@@ -235,9 +238,8 @@ __global__ __launch_bounds__(256) void skinny_grouped_kernel(
     if (b >= g1) { codes = c1; scales = s1; ts = f1; y = y1; n = n1; ld = l1; first = g1; before = n0; }
     if (b >= g2) { codes = c2; scales = s2; ts = f2; y = y2; n = n2; ld = l2; first = g2; before = n0 + n1; }
     if (b >= g3) { codes = c3; scales = s3; ts = f3; y = y3; n = n3; ld = l3; first = g3; before = n0 + n1 + n2; }
-    skinny_body<NB, STEPS, false>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld,
-                                  partial ? partial + (int64_t)nslices * m * before : nullptr, nslices, 4, b - first,
-                                  nrb);
+    skinny_body<NB, STEPS, false, NRB>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld,
+                                       partial ? partial + (int64_t)nslices * m * before : nullptr, nslices, 4, b - first);
 }
 
 // y[m][n] = bf16(scale * sum over slices, in slice order, of partial[slice][m][n]); scale = -ts_w
@@ -362,7 +364,13 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
     const int64_t row_blocks = (n + kSkRows - 1) / kSkRows;
     const int nrb = skinny_row_blocks(row_blocks, nslices, m);
     const unsigned grid = (unsigned)(((row_blocks + nrb - 1) / nrb) * nslices);
-#define RAZER_SK(NB, ST, GB) skinny_kernel<NB, ST, GB><<<grid, 256, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, workspace, nslices, cfg.lb, nrb)
+#define RAZER_SK_ARGS codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, workspace, nslices, cfg.lb
+#define RAZER_SK(NB, ST, GB)                                                                  \
+    do {                                                                                      \
+        if (nrb == 1) skinny_kernel<NB, ST, GB, 1><<<grid, 256, 0, st>>>(RAZER_SK_ARGS);      \
+        else if (nrb == 2) skinny_kernel<NB, ST, GB, 2><<<grid, 256, 0, st>>>(RAZER_SK_ARGS); \
+        else skinny_kernel<NB, ST, GB, 4><<<grid, 256, 0, st>>>(RAZER_SK_ARGS);               \
+    } while (0)
     if (cfg.lb == 4) {
         if (m <= 16) { if (steps == 8) RAZER_SK(1, 8, false); else RAZER_SK(1, 4, false); }
         else RAZER_SK(2, 4, false);
@@ -371,6 +379,7 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
         else RAZER_SK(2, 4, true);
     }
 #undef RAZER_SK
+#undef RAZER_SK_ARGS
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nslices == 1) return e;
     return launch_slice_reduce(workspace, ts, nullptr, m, n, nslices, y, ld_y, st);
@@ -399,13 +408,20 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
         g[i + 1] = g[i] + (i < count ? (unsigned)((rbi + nrb - 1) / nrb) * nslices : 0u);
     }
     float* partial = nslices > 1 ? workspace : nullptr;
-#define RAZER_SKG(NB, ST) skinny_grouped_kernel<NB, ST><<<g[4], 256, 0, st>>>(                                      \
-        q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts, \
+#define RAZER_SKG_ARGS                                                                                               \
+    q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts,     \
         q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,        \
-        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m, partial, nslices, nrb)
+        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m, partial, nslices
+#define RAZER_SKG(NB, ST)                                                                            \
+    do {                                                                                             \
+        if (nrb == 1) skinny_grouped_kernel<NB, ST, 1><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);        \
+        else if (nrb == 2) skinny_grouped_kernel<NB, ST, 2><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);   \
+        else skinny_grouped_kernel<NB, ST, 4><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);                 \
+    } while (0)
     if (m <= 16) { if (steps == 8) RAZER_SKG(1, 8); else RAZER_SKG(1, 4); }
     else RAZER_SKG(2, 4);
 #undef RAZER_SKG
+#undef RAZER_SKG_ARGS
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || nslices == 1) return err;
     return launch_slice_reduce_grouped(partial, count, p, m, nslices, st);
