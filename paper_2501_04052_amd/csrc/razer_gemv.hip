@@ -267,18 +267,11 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
             row = row < n ? row : n - 1;                                  // tail rows re-read the last row
             const uint8_t* crow = codes + row * code_ld;
             g.cw[r] = *reinterpret_cast<const uint4*>(crow + cc * 16u);
-            // (the mask for idle lanes is applied where the bits are used: an operation on a loaded value
-            // here would make the wave wait for the load before the table barrier, and only then could
-            // the next group's loads go out)
-            g.sw[r] = load_scale_bits<GB, SF>(scales, row, k, (int64_t)cc * 32, lb);
+            g.sw[r] = load_scale_bits<GB, SF>(scales, row, k, (int64_t)cc * 32, lb) & smask;
         }
     };
-    // All D buffers are requested before the table is built: whatever the compiler does to a loaded value
-    // (a zero extension is enough) it does in the block that holds the load, i.e. ahead of the barrier, so
-    // loads issued behind the barrier would leave only after the first ones have returned -- two memory
-    // latencies in a row.  A buffer is refilled as soon as its group has been multiplied.
 #pragma unroll
-    for (int d = 0; d < D; ++d)
+    for (int d = 0; d < D - 1; ++d)
         if (d < G) load(buf[d], d);
     if (SF == 0) {
         fill_weight_lut(lut, sv0, sv1);
@@ -287,11 +280,9 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
 
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+        if (g + D - 1 < G) load(buf[(g + D - 1) % D], g + D - 1);
         float acc[R][M];
-#pragma unroll
-        for (int r = 0; r < R; ++r) buf[g % D].sw[r] &= smask;
         dot_group<M, R, SF, GB || SF == 1>(buf[g % D], av, lut, acc, sv0, sv1);
-        if (g + D < G) load(buf[g % D], g + D);
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -454,26 +445,24 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
 #pragma unroll
             for (int c = 0; c < C; ++c) {
                 g.cw[c] = *reinterpret_cast<const uint4*>(crow + (koff[c] >> 1));
-                g.sw[c] = *reinterpret_cast<const uint16_t*>(srow + (koff[c] >> 4));     // masked where used
+                g.sw[c] = *reinterpret_cast<const uint16_t*>(srow + (koff[c] >> 4)) & smask[c];
             }
         };
-        // all D buffers are requested ahead of the table barrier (see gemv_stream_body)
-#pragma unroll
-        for (int d = 0; d < D; ++d)
-            if (d < G) load(buf[d], d);
+        load(buf[0], 0);
         if (ps == 0) {                                                    // the first loads are in flight meanwhile
             fill_weight_lut(lut, sv0, sv1);
             __syncthreads();                                              // LUT ready
         }
 #pragma unroll
         for (int g = 0; g < G; ++g) {
+            if (g + 1 < G) load(buf[(g + 1) % D], g + 1);
             const Quad& cur = buf[g % D];
 #pragma unroll
             for (int c = 0; c < C; ++c) {
                 const uint32_t xw[4] = {cur.cw[c].x, cur.cw[c].y, cur.cw[c].z, cur.cw[c].w};
 #pragma unroll
                 for (int blk = 0; blk < 2; ++blk) {
-                    const uint2 le = lut[((cur.sw[c] & smask[c]) >> (8 * blk)) & 255u];
+                    const uint2 le = lut[(cur.sw[c] >> (8 * blk)) & 255u];
                     v4f tmp[MS];
 #pragma unroll
                     for (int s = 0; s < MS; ++s) tmp[s] = v4f{0.f, 0.f, 0.f, 0.f};
@@ -508,7 +497,6 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
                     }
                 }
             }
-            if (g + D < G) load(buf[g % D], g + D);                        // the buffer just consumed is refilled
             if (ps == PS - 1) {
                 // sum over the 16 runs of the wavefront: within each row of 16 lanes by DPP, across the rows by shuffles
 #pragma unroll
