@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 LLC_BYTES = 256 << 20          # Infinity Cache
 # HBM bytes per {gate,up} launch from the FETCH_SIZE / WRITE_SIZE counters (profiles/): not measurable live
-GATE_UP_TRAFFIC_BYTES = 24840 * 2 * 1024 + 86 * 1024
+GATE_UP_TRAFFIC_BYTES = 24847 * 2 * 1024 + 86 * 1024
 
 
 def parse():
