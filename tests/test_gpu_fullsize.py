@@ -174,6 +174,25 @@ def test_config2_3_mid_batch_single_calls(oracle, m, n, k):
     assert err <= TOL, err
 
 
+@pytest.mark.parametrize("m,k", [(8, (1 << 24) + 64), (40, (1 << 22) + 64), (300, (1 << 22) + 64)])
+def test_rows_longer_than_the_32_bit_offset_kernels_take(oracle, m, k):
+    """The small-batch kernel and the register-decode GEMM address inside a tile with 32-bit offsets; rows
+    beyond their limits must go to the kernels with 64-bit addressing, not overflow."""
+    _say("very long rows, m=%d k=%d" % (m, k))
+    n = 3
+    wq = _rand_packed(n, k, seed=8400 + m)
+    wt = razer.RazerTensor.from_host(*wq, W, SV)
+    a = synth.activation(m, k, seed=2400 + m)
+    y = razer.razer_linear(wt, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([synth.sample_indices(m, 6, 9500), [0, m - 1]]))
+    y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=np.arange(n))
+    got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()])
+    err = max_rel_err(got, y64)
+    _say("   max rel err %.2e" % err)
+    assert err <= TOL, err
+
+
 @pytest.mark.parametrize("m", [1, 4, 16, 64, 128, 256, 512, 2048])
 def test_config2_3_grouped_launches_as_benchmarked(oracle, m):
     """The launch configuration bench.py times: {q,k,v} and {gate,up} of the Llama-7B-shaped layer each
