@@ -199,6 +199,37 @@ def test_linear_mid_batch_random_codes_all_scale_bytes(oracle):
         assert max_rel_err(dev_to_bf16_bits(razer.razer_linear(wt, bf16_bits_to_dev(a))), y64) <= TOL
 
 
+def test_linear_shapes_around_every_dispatch_boundary(oracle):
+    """Seeded random (n, k) at every activation-row count where the dispatch changes kernels (4|5, 32|33,
+    64|65, 128|129, 256|257) plus a few in between; single calls and grouped calls on the same operands."""
+    rng = np.random.default_rng(4242)
+    ms = [1, 4, 5, 17, 32, 33, 64, 65, 100, 128, 129, 200, 256, 257, 300]
+    for i, m in enumerate(ms):
+        for rep in range(2):
+            n = int(rng.integers(1, 160)) * int(rng.choice([1, 1, 4]))
+            k = 32 * int(rng.integers(1, 70)) if rep == 0 else 32 * int(rng.integers(64, 200))
+            print("boundary shapes", m, n, k, flush=True)
+            codes, scales, ts = _rand_tensor(rng, W, n, k)
+            scales = (scales & 0xC0) | (16 + (scales & 15))        # moderate scales: well-conditioned sums
+            a = synth.activation(m, k, seed=5000 + 2 * i + rep)
+            a_dev = bf16_bits_to_dev(a)
+            y64, _ = oracle.linear((codes, scales, ts), a_bf16=a)
+            wt = razer.RazerTensor.from_host(codes, scales, ts, W, (5.0, 8.0))
+            y = razer.razer_linear(wt, a_dev)
+            torch.cuda.synchronize()
+            assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL, (m, n, k)
+            # the same matrix twice and a second one in a grouped call
+            n2 = int(rng.integers(1, 100)) * 4
+            c2, s2, t2 = _rand_tensor(rng, W, n2, k)
+            s2 = (s2 & 0xC0) | (16 + (s2 & 15))
+            wt2 = razer.RazerTensor.from_host(c2, s2, t2, W, (5.0, 8.0))
+            ys = razer.razer_linear_grouped([wt, wt2, wt], a_dev)
+            torch.cuda.synchronize()
+            assert max_rel_err(dev_to_bf16_bits(ys[0]), y64) <= TOL, ("grouped", m, n, k)
+            assert torch.equal(ys[0], ys[2])
+            assert max_rel_err(dev_to_bf16_bits(ys[1]), oracle.linear((c2, s2, t2), a_bf16=a)[0]) <= TOL, ("grouped 2", m, n2, k)
+
+
 def test_linear_special_values_matter(oracle):
     """Decoding the remapped code as a plain zero must show up as an error: guards
     against a kernel that silently drops the special values."""
