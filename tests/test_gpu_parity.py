@@ -285,6 +285,26 @@ def test_linear_w4a4_matches_oracle(oracle, m, n, k):
     assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
 
 
+def test_linear_w4a4_shapes_around_every_dispatch_boundary(oracle):
+    """W4A4 (both operands decoded): seeded random (n, k) at the activation-row counts where the tile
+    shape changes (32|33, 64|65, 128|129, 256|257), with and without K-slices."""
+    rng = np.random.default_rng(4343)
+    for i, m in enumerate([1, 5, 32, 33, 64, 65, 128, 129, 256, 257]):
+        n = int(rng.integers(1, 300))
+        k = 32 * int(rng.integers(1, 40)) if i % 2 == 0 else 32 * int(rng.integers(100, 180))
+        print("w4a4 boundary shapes", m, n, k, flush=True)
+        wc, ws, wts = _rand_tensor(rng, W, n, k)
+        ws = (ws & 0xC0) | (16 + (ws & 15))
+        ac, asc, ats = _rand_tensor(rng, A, m, k)
+        asc = (asc & 0x80) | (48 + (asc & 15))                      # E4M3 codes 48..63: values 0.5..1.875
+        y64, _ = oracle.linear((wc, ws, wts), a_q=(ac, asc, ats))
+        wt = razer.RazerTensor.from_host(wc, ws, wts, W, (5.0, 8.0))
+        at = razer.RazerTensor.from_host(ac, asc, ats, A, (5.0, 0.0))
+        y = razer.razer_linear(wt, at)
+        torch.cuda.synchronize()
+        assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL, (m, n, k)
+
+
 def test_linear_strided_output_and_empty(oracle):
     n, k = 40, 256
     w = synth.weight(n, k, seed=70)
