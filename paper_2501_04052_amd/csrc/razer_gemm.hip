@@ -14,12 +14,14 @@
 // consecutive n of one output row; two lanes swap halves and store 16 bytes.
 //
 // Kernels, chosen by gemm_plan() from M and the number of output tiles:
-//   gemm_kernel      both operands decoded into LDS, all waves alike (M <= 128; W4A4; blocks 32..128)
+//   gemm_kernel      both operands decoded into LDS, all waves alike (M <= 128 for W4A4 and for
+//                    blocks of 32..128)
 //   gemm_pp_kernel   256-row tiles, two wave groups half a step out of phase (decode | MFMA)
-//   gemm_rb_kernel   W4A16 with many tiles: weights decoded in registers by the wave that uses them,
-//                    global -> LDS copies by the load unit; KG = 2 halves K inside the workgroup when
-//                    there is about one tile per compute unit; the grouped form runs up to four
-//                    matrices (fused q/k/v, gate/up) as one launch
+//   gemm_rb_kernel   W4A16, 16-element blocks: weights decoded in registers by the wave that uses them,
+//                    global -> LDS copies by the load unit; 256-row activation tiles when there are
+//                    many output tiles, 64- / 128-row tiles for 33..128 activation rows; KG = 2 halves
+//                    K inside the workgroup when there is about one tile per compute unit; the grouped
+//                    form runs up to four matrices (fused q/k/v, gate/up) as one launch
 // Problems with too few tiles split K over workgroups (fp32 slices in the caller's workspace).
 #include <type_traits>
 
