@@ -174,6 +174,27 @@ def test_config2_3_mid_batch_single_calls(oracle, m, n, k):
     assert err <= TOL, err
 
 
+def test_kv_cache_shaped_activation_tensors(oracle):
+    """The joint weight / activation / KV-cache setting (App. on W-A-KV results) stores K and V in the
+    activation format: a [tokens x heads][head_dim = 128] bf16 tensor with a calibrated (given) tensor
+    scale, encoded and decoded through the same entry points.  Sampled rows against the oracle, bit for bit."""
+    tokens, heads, hd = 4096, 32, 128
+    _say("KV-cache-shaped tensor %d x %d" % (tokens * heads, hd))
+    x = synth.activation(tokens * heads, hd, seed=7700, outlier_frac=0.002)
+    given = np.float32(np.abs(synth.bf16_bits_to_f32(x[:4096])).max() / (448.0 * 6.0))   # "calibration" on a prefix
+    ts = torch.tensor([given], dtype=torch.float32, device="cuda")
+    t = razer.razer_quantize(bf16_bits_to_dev(x), A, (5.0, 0.0), tensor_scale=ts)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([synth.sample_indices(tokens * heads, 4096, 9600), [0, tokens * heads - 1]]))
+    rc, rs, rts = oracle.quantize(A, x[rows], sv=(5.0, 0.0), given_tensor_scale=given)
+    idx = torch.from_numpy(rows).cuda()
+    assert np.array_equal(t.codes[idx].cpu().numpy(), rc) and np.array_equal(t.scales[idx].cpu().numpy(), rs)
+    assert np.float32(t.tensor_scale.cpu().numpy()[0]) == rts == given
+    deq = razer.razer_dequant(t, torch.bfloat16)
+    ref = oracle.dequant(A, rc, rs, rts, sv=(5.0, 0.0), want=("bf16",))["bf16"]
+    assert np.array_equal(dev_to_bf16_bits(deq[idx]), ref)
+
+
 @pytest.mark.parametrize("m,k", [(8, (1 << 24) + 64), (40, (1 << 22) + 64), (300, (1 << 22) + 64)])
 def test_rows_longer_than_the_32_bit_offset_kernels_take(oracle, m, k):
     """The small-batch kernel and the register-decode GEMM address inside a tile with 32-bit offsets; rows
