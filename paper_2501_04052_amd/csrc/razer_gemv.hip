@@ -278,6 +278,13 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
         __syncthreads();                                                  // LUT ready
     }
 
+    // Slice totals of a wave: with two wave sets per workgroup (the short launches of 7B-sized layers) they
+    // go to scalar registers and lane i stores total i -- one masked LDS write per wave instead of one per
+    // total (1.5-6 % on those launches; measured slower on the one-set kernels of longer rows, which keep
+    // the write per total).
+    constexpr int NV = G * R * M;
+    constexpr bool ONE_WRITE = P == 2 && NV <= 8;
+    float tot[ONE_WRITE ? NV : 1];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         if (g + D - 1 < G) load(buf[(g + D - 1) % D], g + D - 1);
@@ -288,8 +295,17 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
 #pragma unroll
             for (int m = 0; m < M; ++m) {
                 const float t = wave_sum_to_lane63(acc[r][m]);
-                if (lane == 63) part[((par * G + g) * R + r) * M + m][wave] = t;
+                if (ONE_WRITE)                         // totals to scalar registers, one LDS write for all of them below
+                    tot[(g * R + r) * M + m] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, t), 63));
+                else if (lane == 63)
+                    part[((par * G + g) * R + r) * M + m][wave] = t;
             }
+    }
+    if (ONE_WRITE) {                                   // lane i writes total i: one masked store instead of NV
+        float v = tot[0];
+#pragma unroll
+        for (int i = 1; i < NV; ++i) v = (lane == (uint32_t)i) ? tot[i] : v;
+        if (lane < (uint32_t)NV) part[par * NV + lane][wave] = v;
     }
     __syncthreads();
     if (threadIdx.x < P * G * R * M) {
