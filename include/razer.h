@@ -149,12 +149,12 @@ razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer
  * have the same cols; W4A16 only.  With equal format, block size and special values and no empty
  * matrix this is ONE kernel launch (short kernels are launch-latency-bound, and one launch fills the
  * last round of workgroups of a GEMM better than one per matrix) when
- *   m <= 4 (any block size, RAZER_FMT_WEIGHT or RAZER_FMT_WEIGHT_F16);
- *   16-element blocks, 5 <= m <= 32, every rows[i] and ld_y[i] a multiple of 4, y_bf16[i] 8-byte
+ *   m <= 4 (RAZER_FMT_WEIGHT or RAZER_FMT_WEIGHT_F16);
+ *   RAZER_FMT_WEIGHT, 5 <= m <= 32, every rows[i] and ld_y[i] a multiple of 4, y_bf16[i] 8-byte
  *     aligned, and the workspace holds the SUM over i of
  *     razer_workspace_bytes(RAZER_OP_LINEAR, rows[i], cols, m) (plus one launch that adds the
  *     K-slices up);
- *   16-element blocks, m >= 33: without a workspace when m > 128 and the matrices together have
+ *   RAZER_FMT_WEIGHT, m >= 33: without a workspace when m > 128 and the matrices together have
  *     >= 512 output tiles of 256 x 128, or 192..256 of them with cols >= 1024; otherwise K is cut into
  *     slices (plus one launch that adds them up) under the conditions of the 5 <= m <= 32 case --
  *     rows, ld_y, alignment of y_bf16, and a workspace that holds the SUM over i of the per-matrix

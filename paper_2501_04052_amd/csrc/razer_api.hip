@@ -229,8 +229,8 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
     if (one_launch) {
         if (m <= kGemvDirectMaxM) {
             path = GEMV;                                 // every block size and both weight formats
-        } else if (sv0.lb != 4 || sv0.f16) {
-            path = SEQUENCE;                             // the grouped MFMA kernels read one scale byte per 16 elements
+        } else if (sv0.f16) {
+            path = SEQUENCE;                             // FP16 scale words: GEMV kernels only
         } else if (m <= kSkinnyMaxM && k > kSkinnyMaxK) {
             path = SEQUENCE;
         } else if (m <= kSkinnyMaxM) {

@@ -554,12 +554,15 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
 // stages apart, so before any LDS load it knows of it would wait for ALL outstanding copies, which
 // would serialise the prefetch.  Each wait is tied to the registers it guards so that their consumers
 // cannot be scheduled above it; sched_barrier keeps the hand-laid slices (one MFMA each) in order.
-template <int NW, int S, int KG = 1, int MT = 8>
+// GB: blocks of 2^lb = 32, 64 or 128 elements -- the lane's 32 codes of a K-tile share ONE scale byte, at
+// byte (64 t + 32 h) >> lb = ((64 t) >> lb) + ((32 h) >> lb) of the row; it is copied with a 1-byte
+// global -> LDS copy (lands zero-extended at base + 4 lane, measured) and used for both halves.
+template <int NW, int S, int KG = 1, int MT = 8, bool GB = false>
 __device__ __forceinline__ void gemm_rb_body(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
     uint16_t* __restrict__ y, int64_t ld_y, int tile_m, int tile_n, float* __restrict__ partial = nullptr,
-    int kslice = 0, int kt_per_slice = 0x7FFFFFFF)
+    int kslice = 0, int kt_per_slice = 0x7FFFFFFF, int lb = 4)
 {
     // MT: 32-row activation groups per tile (8, or 4 / 2 for at most 128 / 64 activation rows)
     static_assert(MT == 8 || ((MT == 4 || MT == 2) && KG == 1), "activation tile height");
@@ -596,15 +599,17 @@ __device__ __forceinline__ void gemm_rb_body(
     int64_t wrow = n0 + 32 * wn + r;
     wrow = wrow < n ? wrow : n - 1;                     // rows past N re-read the last row, never stored
     const uint8_t* crow = w_codes + wrow * (k / 2) + 16 * h;
-    const uint8_t* srow = w_scales + wrow * (k / 16) + 2 * h;
+    const int64_t scale_ld = GB ? (k >> lb) : (k / 16);
+    const uint32_t s_lane = GB ? ((32u * h) >> lb) : 2u * h;          // this lane's byte inside a K-tile's scale bytes
+    const uint8_t* srow = w_scales + wrow * scale_ld + s_lane;
     // the same addresses as a uniform base (first row of the wave, advanced per K-tile on the scalar
     // unit) plus a 32-bit lane offset that never changes: a full K-tile's copies need no vector
     // address arithmetic at all
     const int64_t wrow_first = (n0 + 32 * wn < n) ? n0 + 32 * wn : n - 1;
     const uint8_t* cfirst = w_codes + wrow_first * (k / 2);
-    const uint8_t* sfirst = w_scales + wrow_first * (k / 16);
+    const uint8_t* sfirst = w_scales + wrow_first * scale_ld;
     const uint32_t c_off = (uint32_t)(wrow - wrow_first) * (uint32_t)(k / 2) + 16u * h;
-    const uint32_t s_off = (uint32_t)(wrow - wrow_first) * (uint32_t)(k / 16) + 2u * h;
+    const uint32_t s_off = (uint32_t)(wrow - wrow_first) * (uint32_t)scale_ld + s_lane;
 
     // Activation copy i of this wave fills LDS rows 8 (wave NU_A + i) .. + 7 of a stage: lane l writes
     // physical chunk l % 8 of row 8 (..) + l / 8, which must hold logical chunk (l % 8) ^ swizzle(row).
@@ -633,9 +638,14 @@ __device__ __forceinline__ void gemm_rb_body(
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(cfirst + (size_t)kt * 32 + c_off),
                                              (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + wave * 1024),
                                              16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(sfirst + (size_t)kt * 4 + s_off),
-                                             (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + B_CODES + wave * 256),
-                                             2, 0, 0);
+            if (GB)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(sfirst + (((size_t)kt * kBK) >> lb) + s_off),
+                    (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + B_CODES + wave * 256), 1, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(sfirst + (size_t)kt * 4 + s_off),
+                    (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + B_CODES + wave * 256), 2, 0, 0);
             return;
         }
 #pragma unroll
@@ -650,9 +660,14 @@ __device__ __forceinline__ void gemm_rb_body(
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(crow + 32 * kc),
                                          (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + wave * 1024),
                                          16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srow + 4 * kc),
-                                         (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + B_CODES + wave * 256),
-                                         2, 0, 0);
+        if (GB)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(srow + (((size_t)kc * kBK) >> lb)),
+                (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + B_CODES + wave * 256), 1, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srow + 4 * kc),
+                                             (__attribute__((address_space(3))) void*)(Bs + st * B_STAGE + B_CODES + wave * 256),
+                                             2, 0, 0);
     };
 
     v16f acc[1][MT];
@@ -702,6 +717,7 @@ __device__ __forceinline__ void gemm_rb_body(
         xw[1] = (c.y & msk) ^ kRemapXor;
         xw[2] = (c.z & msk) ^ kRemapXor;
         xw[3] = (c.w & msk) ^ kRemapXor;
+        if (GB) sc = (sc & 255u) * 0x101u;              // one scale byte for both halves
         sc &= msk;
     };
 
@@ -903,21 +919,22 @@ constexpr int rb_waves_per_simd() { return KG != 1 ? 1 : MT == 8 ? 8 / NW : MT =
 
 // grid = (output tiles, K-slices).  partial == nullptr: one slice, bf16 results to y; else slice
 // blockIdx.y covers kt_per_slice K-tiles and leaves fp32 sums in partial[slice][m][n].
-template <int NW, int S, int KG = 1, int MT = 8>
+template <int NW, int S, int KG = 1, int MT = 8, bool GB = false>
 __global__ __launch_bounds__(64 * NW, (rb_waves_per_simd<NW, KG, MT>())) void gemm_rb_kernel(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
-    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m, float* __restrict__ partial, int kt_per_slice)
+    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m, float* __restrict__ partial, int kt_per_slice, int lb)
 {
-    gemm_rb_body<NW, S, KG, MT>(w_codes, w_scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, (int)(blockIdx.x % tiles_m),
-                                (int)(blockIdx.x / tiles_m), partial, (int)blockIdx.y, kt_per_slice);
+    gemm_rb_body<NW, S, KG, MT, GB>(w_codes, w_scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y,
+                                    (int)(blockIdx.x % tiles_m), (int)(blockIdx.x / tiles_m), partial,
+                                    (int)blockIdx.y, kt_per_slice, lb);
 }
 
 // Up to four weight matrices against the same activations in one launch (fused q/k/v, gate/up): the
 // column tiles of the matrices are numbered one after another, t1..t3 are the first tile of matrices
 // 1..3 (equal to the total for matrices that are absent).  One launch fills the last round of
 // workgroups better than one launch per matrix.
-template <int NW, int S, int KG = 1, int MT = 8>
+template <int NW, int S, int KG = 1, int MT = 8, bool GB = false>
 __global__ __launch_bounds__(64 * NW, (rb_waves_per_simd<NW, KG, MT>())) void gemm_rb_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
@@ -927,7 +944,7 @@ __global__ __launch_bounds__(64 * NW, (rb_waves_per_simd<NW, KG, MT>())) void ge
     int64_t l0, int64_t l1, int64_t l2, int64_t l3,
     int t1, int t2, int t3,
     float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int64_t m, int tiles_m,
-    float* __restrict__ partial, int kt_per_slice)
+    float* __restrict__ partial, int kt_per_slice, int lb)
 {
     const int tile_m = (int)(blockIdx.x % tiles_m), t = (int)(blockIdx.x / tiles_m);
     const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = f0; uint16_t* y = y0;
@@ -937,21 +954,21 @@ __global__ __launch_bounds__(64 * NW, (rb_waves_per_simd<NW, KG, MT>())) void ge
     if (t >= t2) { codes = c2; scales = s2; ts = f2; y = y2; n = n2; ld = l2; first = t2; before = n0 + n1; }
     if (t >= t3) { codes = c3; scales = s3; ts = f3; y = y3; n = n3; ld = l3; first = t3; before = n0 + n1 + n2; }
     // with K-slices (partial != nullptr) matrix i keeps its [slices][m][n_i] sums behind those of matrices 0 .. i-1
-    gemm_rb_body<NW, S, KG, MT>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, tile_m, t - first,
-                                partial ? partial + (int64_t)gridDim.y * m * before : nullptr, (int)blockIdx.y,
-                                kt_per_slice);
+    gemm_rb_body<NW, S, KG, MT, GB>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, tile_m, t - first,
+                                    partial ? partial + (int64_t)gridDim.y * m * before : nullptr, (int)blockIdx.y,
+                                    kt_per_slice, lb);
 }
 
 // split > 1 (KG == 1 only, workspace of slices * m * n floats): K in slices of whole K-tiles, summed by
 // launch_slice_reduce.
-template <int NW, int S, int KG = 1, int MT = 8>
+template <int NW, int S, int KG = 1, int MT = 8, bool GB = false>
 static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                             int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
                             hipStream_t st, int split = 1, float* workspace = nullptr)
 {
     constexpr int BM = 32 * MT, BN = 32 * NW / KG;
     constexpr size_t smem = S * (KG * BM * 128 + NW * 1280) + 256 * sizeof(uint2);
-    auto kern = gemm_rb_kernel<NW, S, KG, MT>;
+    auto kern = gemm_rb_kernel<NW, S, KG, MT, GB>;
     static bool attr_set = false;                      // one GPU per process
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -966,7 +983,7 @@ static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, con
     const int slices = (kt_all + kt_per - 1) / kt_per;
     kern<<<dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(64 * NW), smem, st>>>(
         w_codes, w_scales, w_ts, wcfg.sv0, wcfg.sv1, n, k, a, m, y, ld_y, tiles_m, slices > 1 ? workspace : nullptr,
-        slices > 1 ? kt_per : 0x7FFFFFFF);
+        slices > 1 ? kt_per : 0x7FFFFFFF, wcfg.lb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || slices == 1) return e;
     return launch_slice_reduce(workspace, w_ts, nullptr, m, n, slices, y, ld_y, st);
@@ -1084,7 +1101,9 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
                                 const uint8_t* a_scales, const float* a_ts, SvConfig acfg, int64_t m, uint16_t* y,
                                 int64_t ld_y, float* workspace, hipStream_t st)
 {
-    GemmPlan p = gemm_plan(m, n, k, !AQ && !GB && k <= kRbMaxK);
+    // (the register-decode kernel takes every weight block size; GB here also covers the activation
+    // operand of W4A4, which that kernel does not decode)
+    GemmPlan p = gemm_plan(m, n, k, !AQ && k <= kRbMaxK);
     if ((m <= kSkinnyMaxM && k <= kSkinnyMaxK) || !workspace) p.split = 1;   // not sized a workspace
 #define RAZER_GEMM(BM, BN, WGM, WGN, PP) \
     launch_cfg<BM, BN, WGM, WGN, AQ, PP, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, p.split, workspace, st)
@@ -1097,12 +1116,12 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
         default: break;
     }
 #undef RAZER_GEMM
-    if constexpr (!AQ && !GB) {
-        if (p.tile == 8) return launch_rb<4, 2, 1, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, p.split, workspace);
-        if (p.tile == 9) return launch_rb<4, 2, 1, 4>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, p.split, workspace);
-        if (p.tile == 5) return launch_rb<8, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
-        if (p.tile == 7) return launch_rb<8, 2, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
-        return launch_rb<4, 2>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+    if constexpr (!AQ) {
+        if (p.tile == 8) return launch_rb<4, 2, 1, 2, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, p.split, workspace);
+        if (p.tile == 9) return launch_rb<4, 2, 1, 4, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, p.split, workspace);
+        if (p.tile == 5) return launch_rb<8, 2, 1, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+        if (p.tile == 7) return launch_rb<8, 2, 2, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+        return launch_rb<4, 2, 1, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
     }
     return hipErrorInvalidValue;
 }
@@ -1152,13 +1171,13 @@ size_t gemm_grouped_workspace_bytes(int count, const GemvProblem* p, int64_t m, 
     return (size_t)(slices * m * n_all) * sizeof(float);
 }
 
-template <int NW, int S, int KG = 1, int MT = 8>
+template <int NW, int S, int KG = 1, int MT = 8, bool GB = false>
 static hipError_t launch_rb_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
                                     int64_t m, hipStream_t st, int split = 1, float* workspace = nullptr)
 {
     constexpr int BM = 32 * MT, BN = 32 * NW / KG;
     constexpr size_t smem = S * (KG * BM * 128 + NW * 1280) + 256 * sizeof(uint2);
-    auto kern = gemm_rb_grouped_kernel<NW, S, KG, MT>;
+    auto kern = gemm_rb_grouped_kernel<NW, S, KG, MT, GB>;
     static bool attr_set = false;                      // one GPU per process
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1180,28 +1199,36 @@ static hipError_t launch_rb_grouped(SvConfig cfg, int count, const GemvProblem* 
         q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts,
         q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,
         q[1].ld_y, q[2].ld_y, q[3].ld_y, t[1], t[2], t[3], cfg.sv0, cfg.sv1, k, a, m, tiles_m,
-        slices > 1 ? workspace : nullptr, slices > 1 ? kt_per : 0x7FFFFFFF);
+        slices > 1 ? workspace : nullptr, slices > 1 ? kt_per : 0x7FFFFFFF, cfg.lb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || slices == 1) return e;
     return launch_slice_reduce_grouped(workspace, count, p, m, slices, st);
 }
 
-hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
-                               int64_t m, float* workspace, hipStream_t st)
+template <bool GB>
+static hipError_t launch_gemm_grouped_t(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
+                                        int64_t m, float* workspace, hipStream_t st)
 {
-    if (count < 1 || count > 4 || cfg.lb != 4) return hipErrorInvalidValue;
     const int w = grouped_tile_width(count, p, m, k);
-    if (w == 256) return launch_rb_grouped<8, 2>(cfg, count, p, k, a, m, st);
-    if (w == 128) return launch_rb_grouped<4, 2>(cfg, count, p, k, a, m, st);
-    if (w == 129) return launch_rb_grouped<8, 2, 2>(cfg, count, p, k, a, m, st);
+    if (w == 256) return launch_rb_grouped<8, 2, 1, 8, GB>(cfg, count, p, k, a, m, st);
+    if (w == 128) return launch_rb_grouped<4, 2, 1, 8, GB>(cfg, count, p, k, a, m, st);
+    if (w == 129) return launch_rb_grouped<8, 2, 2, 8, GB>(cfg, count, p, k, a, m, st);
     if (w == 2 || w == 4 || w == 8) {
         const int split = grouped_split(count, p, m, k);
         if (split > 1 && !workspace) return hipErrorInvalidValue;
-        if (w == 2) return launch_rb_grouped<4, 2, 1, 2>(cfg, count, p, k, a, m, st, split, workspace);
-        if (w == 4) return launch_rb_grouped<4, 2, 1, 4>(cfg, count, p, k, a, m, st, split, workspace);
-        return launch_rb_grouped<4, 2, 1, 8>(cfg, count, p, k, a, m, st, split, workspace);
+        if (w == 2) return launch_rb_grouped<4, 2, 1, 2, GB>(cfg, count, p, k, a, m, st, split, workspace);
+        if (w == 4) return launch_rb_grouped<4, 2, 1, 4, GB>(cfg, count, p, k, a, m, st, split, workspace);
+        return launch_rb_grouped<4, 2, 1, 8, GB>(cfg, count, p, k, a, m, st, split, workspace);
     }
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
+                               int64_t m, float* workspace, hipStream_t st)
+{
+    if (count < 1 || count > 4 || cfg.f16) return hipErrorInvalidValue;
+    return cfg.lb == 4 ? launch_gemm_grouped_t<false>(cfg, count, p, k, a, m, workspace, st)
+                       : launch_gemm_grouped_t<true>(cfg, count, p, k, a, m, workspace, st);
 }
 
 hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,

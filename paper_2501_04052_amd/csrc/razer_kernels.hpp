@@ -61,7 +61,7 @@ hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_s
                        const uint8_t* a_scales, const float* a_ts, int64_t m, uint16_t* y, int64_t ld_y,
                        float* workspace, hipStream_t st);
 
-// Grouped form of launch_skinny (5 <= m <= 32, 16-element blocks, every n a positive multiple of 4);
+// Grouped form of launch_skinny (5 <= m <= 32, any block size, every n a positive multiple of 4);
 // workspace = the matrices' skinny_workspace_bytes added up, matrix after matrix.
 hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
                                  int64_t m, float* workspace, hipStream_t st);
@@ -71,7 +71,7 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
 hipError_t launch_slice_reduce_grouped(const float* partial, int count, const GemvProblem* p, int64_t m, int nslices,
                                        hipStream_t st);
 
-// Up to 4 weight matrices (16-element blocks, equal special values, every n > 0, k > 0) against the
+// Up to 4 weight matrices (equal block size and special values, every n > 0, k > 0) against the
 // same bf16 activations in one launch of the register-decode GEMM kernel; possible when
 // gemm_grouped_fits() says so (m >= 33).  gemm_grouped_workspace_bytes() > 0 (few output tiles: K is
 // sliced): the launch needs that many bytes of workspace and the conditions of

@@ -219,7 +219,7 @@ __global__ __launch_bounds__(256) void skinny_kernel(const uint8_t* __restrict__
 // Up to four weight matrices against the same activations in one launch: workgroups are numbered
 // through the matrices one after another (g1..g3 = first workgroup of matrices 1..3); matrix i keeps
 // its K-slices in the workspace behind those of matrices 0 .. i-1.
-template <int NB, int STEPS, int NRB>
+template <int NB, int STEPS, int NRB, bool GB = false>
 __global__ __launch_bounds__(256) void skinny_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256) void skinny_grouped_kernel(
     int64_t l0, int64_t l1, int64_t l2, int64_t l3,
     unsigned g1, unsigned g2, unsigned g3,
     float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int64_t m, float* __restrict__ partial,
-    int nslices)
+    int nslices, int lb)
 {
     const unsigned b = blockIdx.x;
     const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = f0; uint16_t* y = y0;
@@ -238,8 +238,8 @@ __global__ __launch_bounds__(256) void skinny_grouped_kernel(
     if (b >= g1) { codes = c1; scales = s1; ts = f1; y = y1; n = n1; ld = l1; first = g1; before = n0; }
     if (b >= g2) { codes = c2; scales = s2; ts = f2; y = y2; n = n2; ld = l2; first = g2; before = n0 + n1; }
     if (b >= g3) { codes = c3; scales = s3; ts = f3; y = y3; n = n3; ld = l3; first = g3; before = n0 + n1 + n2; }
-    skinny_body<NB, STEPS, false, NRB>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld,
-                                       partial ? partial + (int64_t)nslices * m * before : nullptr, nslices, 4, b - first);
+    skinny_body<NB, STEPS, GB, NRB>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld,
+                                    partial ? partial + (int64_t)nslices * m * before : nullptr, nslices, lb, b - first);
 }
 
 // y[m][n] = bf16(scale * sum over slices, in slice order, of partial[slice][m][n]); scale = -ts_w
@@ -391,7 +391,7 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
 hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
                                  int64_t m, float* workspace, hipStream_t st)
 {
-    if (count < 1 || count > 4 || cfg.lb != 4 || m <= kGemvDirectMaxM || m > kSkinnyMaxM || k > kSkinnyMaxK)
+    if (count < 1 || count > 4 || cfg.f16 || m <= kGemvDirectMaxM || m > kSkinnyMaxM || k > kSkinnyMaxK)
         return hipErrorInvalidValue;
     const int steps = skinny_steps(k, m);
     const int64_t kc = 128 * steps;
@@ -411,15 +411,20 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
 #define RAZER_SKG_ARGS                                                                                               \
     q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts,     \
         q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,        \
-        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m, partial, nslices
-#define RAZER_SKG(NB, ST)                                                                            \
-    do {                                                                                             \
-        if (nrb == 1) skinny_grouped_kernel<NB, ST, 1><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);        \
-        else if (nrb == 2) skinny_grouped_kernel<NB, ST, 2><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);   \
-        else skinny_grouped_kernel<NB, ST, 4><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);                 \
+        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m, partial, nslices, cfg.lb
+#define RAZER_SKG(NB, ST, GB)                                                                            \
+    do {                                                                                                 \
+        if (nrb == 1) skinny_grouped_kernel<NB, ST, 1, GB><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);        \
+        else if (nrb == 2) skinny_grouped_kernel<NB, ST, 2, GB><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);   \
+        else skinny_grouped_kernel<NB, ST, 4, GB><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);                 \
     } while (0)
-    if (m <= 16) { if (steps == 8) RAZER_SKG(1, 8); else RAZER_SKG(1, 4); }
-    else RAZER_SKG(2, 4);
+    if (cfg.lb == 4) {
+        if (m <= 16) { if (steps == 8) RAZER_SKG(1, 8, false); else RAZER_SKG(1, 4, false); }
+        else RAZER_SKG(2, 4, false);
+    } else {                                                            // blocks of 32, 64, 128
+        if (m <= 16) { if (steps == 8) RAZER_SKG(1, 8, true); else RAZER_SKG(1, 4, true); }
+        else RAZER_SKG(2, 4, true);
+    }
 #undef RAZER_SKG
 #undef RAZER_SKG_ARGS
     hipError_t err = hipGetLastError();

@@ -155,6 +155,33 @@ def test_linear_many_tiles_register_decode_kernel(oracle, m, n, k):
     assert err <= TOL, err
 
 
+@pytest.mark.parametrize("block", [32, 64, 128])
+@pytest.mark.parametrize("m,n,k", [(4100, 4096 + 8, 128 + 32 * 4), (2048, 4096, 4096 + 128), (8192, 4096 + 40, 384),
+                                   (100, 4096, 4096), (64, 11008, 1024 + 128), (2048, 11008, 1152)])
+def test_block_sizes_register_decode_kernel(oracle, block, m, n, k):
+    """32-, 64- and 128-element blocks through the register-decode GEMM (one scale byte per lane and
+    K-tile, copied with a 1-byte global->LDS copy): 128- and 256-wide tiles, the two-K-group round, 64- and
+    128-row tiles with K-slices, ragged K-tiles (K a multiple of the block size only).  Sampled outputs."""
+    if k % block:
+        pytest.skip("K must hold whole blocks")
+    _say("block %d register-decode GEMM m=%d n=%d k=%d" % (block, m, n, k))
+    rng = np.random.default_rng(7100 + m + n + k + block)
+    codes = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
+    scales = rng.integers(0, 256, size=(n, k // block), dtype=np.uint8)
+    wq = (codes, scales, np.float32(2.0 ** -9))
+    wt = razer.RazerTensor.from_host(*wq, W, SV)
+    a = synth.activation(m, k, seed=7101 + m, outlier_frac=0.005, outlier_gain=50.0)
+    y = razer.razer_linear(wt, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([synth.sample_indices(m, 48, 9100), np.arange(max(m - 8, 0), m), np.arange(0, 4)]))
+    cols = np.unique(np.concatenate([synth.sample_indices(n, 192, 9101), np.arange(n - 40, n), np.arange(0, 8)]))
+    y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=cols)
+    got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+    err = max_rel_err(got, y64)
+    _say("   max rel err %.2e over %d x %d sampled outputs" % (err, len(rows), len(cols)))
+    assert err <= TOL, err
+
+
 @pytest.mark.parametrize("m,n,k", [(64, 4096, 4096), (128, 4096, 11008), (256, 4096, 4096), (100, 11008, 4096)])
 def test_config2_3_mid_batch_single_calls(oracle, m, n, k):
     """o- and down-shaped projections (and a gate-shaped one) at the batch sizes between decode and large

@@ -510,6 +510,32 @@ def test_block_sizes_grouped_small_batch_one_launch(oracle, block, m, k, ns):
         assert torch.equal(y, razer.razer_linear(wt, bf16_bits_to_dev(a)))
 
 
+@pytest.mark.parametrize("block", [32, 64, 128])
+@pytest.mark.parametrize("m,k,ns", [(8, 1024, (132, 64, 200)), (32, 4096 + 128, (64, 260)), (16, 11008, (132, 64)),
+                                    (64, 4096, (132, 64, 200)), (100, 2048 + 128, (132, 64)), (300, 1152, (4100, 4096, 4200))])
+def test_block_sizes_grouped_larger_batches_one_launch(oracle, block, m, k, ns):
+    """5 <= m: the grouped small-batch kernel and the grouped register-decode GEMM (with and without
+    K-slices, two-K-group round) take 32-, 64- and 128-element blocks as well."""
+    print("block grouped batch", block, m, k, ns, flush=True)
+    rng = np.random.default_rng(1700 + block + m)
+    a = synth.activation(m, k, seed=1701 + m)
+    a_dev = bf16_bits_to_dev(a)
+    wqs = [_rand_tensor_b(rng, W, n, k, block) for n in ns]
+    wts = [razer.RazerTensor.from_host(*wq, W, (5.0, 8.0)) for wq in wqs]
+    ys = razer.razer_linear_grouped(wts, a_dev)
+    torch.cuda.synchronize()
+    if m * max(ns) * k > 3e9:                                       # large case: sampled outputs
+        rows = np.unique(np.concatenate([synth.sample_indices(m, 24, 9700), [0, m - 1]]))
+        for wq, y, n in zip(wqs, ys, ns):
+            cols = np.unique(np.concatenate([synth.sample_indices(n, 96, 9701), [0, n - 1]]))
+            y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=cols)
+            got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+            assert max_rel_err(got, y64) <= TOL
+    else:
+        for wq, y in zip(wqs, ys):
+            assert max_rel_err(dev_to_bf16_bits(y), oracle.linear(wq, a_bf16=a)[0]) <= TOL
+
+
 def test_block_sizes_grouped_mixed_geometry_is_a_sequence(oracle):
     k = 512
     a = synth.activation(2, k, seed=1520)
