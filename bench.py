@@ -234,7 +234,7 @@ def main():
     legs["gemv_m1_unprepared_calls"] = {"GB/s": bytes1 / ms1e / 1e6, "ms_per_step": ms1e,
                                         "note": "same step with the Python binding marshalling every call (host-bound)"}
 
-    # dominant kernel of the step: the {gate, up} launch (gemv_stream_grouped_kernel<1,2,2,2,2>, 44 % of
+    # dominant kernel of the step: the {gate, up} launch (gemv_stream_grouped_kernel<1,2,2,2,2,false,0>, 44 % of
     # the step's bytes).  Average launch duration from HIP events around a region of back-to-back
     # launches of that kernel alone, rotating the packed copies, on the stream it is launched on.
     # (An event pair around every single launch is reported too, with the reading of an empty pair:
@@ -259,7 +259,7 @@ def main():
     def gemm_roofline(ms, fl):
         return {"bound": "mfma", "achieved": fl / ms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                "kernel": "gemm_rb_grouped_kernel<4,2,1,8> ({q,k,v}, {gate,up}) + gemm_rb_kernel<8,2,2,8> (o, down), "
+                "kernel": "gemm_rb_grouped_kernel<4,2,1,8,false> ({q,k,v}, {gate,up}) + gemm_rb_kernel<8,2,2,8,false> (o, down), "
                           "M=2048, Llama-7B layer set as 4 calls, flops = 2MNK, whole-leg time"}
 
     if args.legs == "gemm":                                  # profiler runs: only the M=2048 GEMM leg
@@ -432,7 +432,7 @@ def main():
                    "m": 1, "bytes_per_step": bytes1},
         "roofline": {"bound": "hbm", "achieved": dom_bytes / dom_stream_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": dom_bytes / dom_stream_ms / 1e6 / HBM_PEAK_GBS, "traffic": GATE_UP_TRAFFIC_BYTES,
-                     "kernel": "gemv_stream_grouped_kernel<1,2,2,2,2> on {gate,up} 2 x 11008x4096 (the step's largest launch)",
+                     "kernel": "gemv_stream_grouped_kernel<1,2,2,2,2,false,0> on {gate,up} 2 x 11008x4096 (the step's largest launch)",
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": dom_stream_ms * 1e3,
                      "timing": "HIP events around a region of back-to-back launches of this kernel alone on its stream, "
                                "packed copies rotated; region time / launches",
