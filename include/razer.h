@@ -28,9 +28,12 @@
  * 4 + 8 / block bits in general.
  *
  * Every entry point only enqueues kernels on the HIP stream passed in
- * (hipStream_t cast to void*, NULL = default stream); nothing allocates,
- * synchronizes or keeps state.  Errors are returned as status codes; no
- * exceptions, no aborts.  Non-finite inputs give unspecified values, no faults.
+ * (hipStream_t cast to void*, NULL = default stream); nothing allocates or
+ * synchronizes, and no state is kept from one call to the next (the one
+ * exception: the first launch of a large-tile kernel on a device raises that
+ * kernel's dynamic-LDS limit, once, thread-safely -- make a first call outside
+ * stream capture).  Errors are returned as status codes; no exceptions, no
+ * aborts.  Non-finite inputs give unspecified values, no faults.
  */
 #ifndef RAZER_H
 #define RAZER_H
@@ -97,19 +100,28 @@ enum { RAZER_OP_QUANTIZE = 0, RAZER_OP_DEQUANT = 1, RAZER_OP_LINEAR = 2 };
 
 /* Bytes of device workspace the given operation needs for these sizes
  * (rows x cols operand; m = activation rows for RAZER_OP_LINEAR, else 0).
- * At most 8 * m * rows floats (problems too small to occupy the GPU split K and
- * add the slices in a fixed order); 0 means the workspace may be NULL.       */
+ * Non-zero for RAZER_OP_LINEAR where K is cut into slices whose fp32 partial
+ * sums [slices][m][rows] meet in the workspace and are added in slice order
+ * (the number of slices depends on the shape: always ask, do not estimate);
+ * 0 means the workspace may be NULL.                                        */
 size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m);
+
+/* The same for razer_linear_grouped with `count` weight matrices of rows[i] x cols (rows is a HOST
+ * array): a workspace of this size lets the group run as ONE launch wherever the other conditions
+ * listed at razer_linear_grouped hold (the K-slices are then chosen for all matrices together,
+ * which can take more than the per-matrix sizes added up), and is also enough for the sequence of
+ * razer_linear calls it falls back to.  0 for an invalid count or shape.                        */
+size_t razer_workspace_bytes_grouped(int32_t count, const int64_t *rows, int64_t cols, int64_t m);
 
 /* Encoder: Eq. 1 (tensor scale), Eq. 2 (block scale, round-to-nearest-even on
  * the format's scale grid, saturating), Eq. 4 (per block, the special value
- * with the smallest squared error in the scaled domain, fp64 sum over the 16
+ * with the smallest squared error in the scaled domain, fp64 sum over the block's
  * elements in index order, ties to the smallest metadata index) and Eq. 5
  * (round-to-nearest on Q_FP4 U {special}; ties between FP4 values go to the
  * even code, an FP4 value beats the special value on a tie, zero is always
  * code 0).  A block whose scale rounds to 0 is written as all-zero codes.
- * For blocks longer than 16 the fp64 error sum of Eq. 4 runs over each 16 consecutive
- * elements in index order and adds those sums in order.
+ * For blocks longer than 16 the fp64 error sum of Eq. 4 likewise runs over the block's elements
+ * in index order.
  *   x       device, [rows][ld] elements of dtype (fp32 or bf16), cols used per row
  *   codes, scales, tensor_scale   device outputs (tensor_scale input with the flag)
  *   workspace  device, >= razer_workspace_bytes(RAZER_OP_QUANTIZE, ...) bytes, 16-aligned
@@ -151,14 +163,12 @@ razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer
  * last round of workgroups of a GEMM better than one per matrix) when
  *   m <= 4 (RAZER_FMT_WEIGHT or RAZER_FMT_WEIGHT_F16);
  *   RAZER_FMT_WEIGHT, 5 <= m <= 32, every rows[i] and ld_y[i] a multiple of 4, y_bf16[i] 8-byte
- *     aligned, and the workspace holds the SUM over i of
- *     razer_workspace_bytes(RAZER_OP_LINEAR, rows[i], cols, m) (plus one launch that adds the
- *     K-slices up);
+ *     aligned, and the workspace holds razer_workspace_bytes_grouped(count, rows, cols, m) bytes
+ *     (plus one launch that adds the K-slices up);
  *   RAZER_FMT_WEIGHT, m >= 33: without a workspace when m > 128 and the matrices together have
  *     >= 512 output tiles of 256 x 128, or 192..256 of them with cols >= 1024; otherwise K is cut into
  *     slices (plus one launch that adds them up) under the conditions of the 5 <= m <= 32 case --
- *     rows, ld_y, alignment of y_bf16, and a workspace that holds the SUM over i of the per-matrix
- *     razer_workspace_bytes.
+ *     rows, ld_y, alignment of y_bf16, and a workspace of razer_workspace_bytes_grouped bytes.
  * Otherwise it is the sequence of razer_linear calls with the same workspace (which then must
  * satisfy each call).  y_bf16[i] is device [m][ld_y[i]].  The pointer arrays are HOST arrays. */
 #define RAZER_MAX_GROUP 4

@@ -252,18 +252,14 @@ float oracle_tensor_scale(int fmt, const void *x, int x_is_bf16, int64_t n)
  *   delta32 : the tensor scale.   nsv: number of candidates searched
  *   (0 = plain NVFP4 under the same scale).
  * Outputs: the codes, the 6/7-bit scale code, the metadata index, and the
- * block's squared error in the scaled domain.  Reading taken for the order of
- * the fp64 error sum (the paper is silent): the squared errors of each run of
- * 16 consecutive elements are summed in index order, and the runs' sums are
- * added in run order -- for a block of 16 that is the plain sum k = 0..15.   */
-static double sse_in_runs(const double *e2, int block)
+ * block's squared error in the scaled domain.  Eq. 4's squared-error norm is
+ * the plain sum over the block's elements in index order k = 0 .. block-1, in
+ * fp64 (the paper does not give an order; index order is the one the formula
+ * is written in).                                                           */
+static double sse_in_order(const double *e2, int block)
 {
     double total = 0.0;
-    for (int r0 = 0; r0 < block; r0 += RAZER_BLOCK) {
-        double run = 0.0;
-        for (int k = 0; k < RAZER_BLOCK; ++k) run += e2[r0 + k];
-        total = (r0 == 0) ? run : total + run;
-    }
+    for (int k = 0; k < block; ++k) total += e2[k];
     return total;
 }
 
@@ -296,7 +292,7 @@ static void encode_block(int fmt, const double cand[4], int nsv, float delta32, 
         for (int k = 0; k < block; ++k) {
             double e; codes[k] = (uint8_t)round_elem(xs[k], 0, 0.0, &e); e2[k] = e * e;
         }
-        *sse_out = sse_in_runs(e2, block);
+        *sse_out = sse_in_order(e2, block);
         return;
     }
     /* Eq. 4: try every allowed special value, keep the smallest squared
@@ -306,7 +302,7 @@ static void encode_block(int fmt, const double cand[4], int nsv, float delta32, 
         for (int k = 0; k < block; ++k) {
             double e; (void)round_elem(xs[k], 1, cand[m], &e); e2[k] = e * e;
         }
-        double sse = sse_in_runs(e2, block);
+        double sse = sse_in_order(e2, block);
         if (best_m < 0 || sse < best_sse) { best_sse = sse; best_m = m; }
     }
     /* Eq. 5: quantize the block with the chosen special value. */

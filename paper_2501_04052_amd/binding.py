@@ -16,7 +16,7 @@ F32, BF16 = 0, 1
 OP_QUANTIZE, OP_DEQUANT, OP_LINEAR = 0, 1, 2
 GIVEN_TENSOR_SCALE = 1
 
-EXPORTS = ["razer_workspace_bytes", "razer_quantize", "razer_dequant", "razer_linear",
+EXPORTS = ["razer_workspace_bytes", "razer_workspace_bytes_grouped", "razer_quantize", "razer_dequant", "razer_linear",
            "razer_linear_grouped", "razer_status_string"]
 
 
@@ -56,6 +56,8 @@ def load_library():
                              ctypes.c_size_t)
     L.razer_workspace_bytes.restype = sz
     L.razer_workspace_bytes.argtypes = [ctypes.c_int, i64, i64, i64]
+    L.razer_workspace_bytes_grouped.restype = sz
+    L.razer_workspace_bytes_grouped.argtypes = [i32, ctypes.POINTER(i64), i64, i64]
     L.razer_quantize.restype = ctypes.c_int
     L.razer_quantize.argtypes = [ctypes.POINTER(_Config), vp, i32, i64, i64, i64, vp, vp, vp, u32,
                                  vp, sz, vp]
@@ -79,6 +81,11 @@ def razer_status_string(status):
 
 def razer_workspace_bytes(op, rows, cols, m=0):
     return int(load_library().razer_workspace_bytes(int(op), int(rows), int(cols), int(m)))
+
+
+def razer_workspace_bytes_grouped(rows, cols, m):
+    arr = (ctypes.c_int64 * len(rows))(*[int(r) for r in rows])
+    return int(load_library().razer_workspace_bytes_grouped(len(rows), arr, int(cols), int(m)))
 
 
 def _stream():
@@ -226,7 +233,7 @@ def razer_linear_grouped(ws, a, outs=None):
     yptrs = (ctypes.c_void_p * count)(*[o.data_ptr() for o in outs])
     lds = (ctypes.c_int64 * count)(*[(o.stride(0) if m > 1 else max(o.stride(0), w.rows))
                                      for o, w in zip(outs, ws)])
-    need = sum(razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m) for w in ws)
+    need = razer_workspace_bytes_grouped([w.rows for w in ws], ws[0].cols, m)
     workspace = torch.empty(need, dtype=torch.uint8, device=a.device) if need else None
     st = L.razer_linear_grouped(wptrs, count, _ptr(a), m, yptrs, lds, _ptr(workspace), need, _stream())
     if st != 0:
@@ -275,7 +282,7 @@ def prepare_linear_grouped(ws, a, outs):
     yptrs = (ctypes.c_void_p * count)(*[o.data_ptr() for o in outs])
     lds = (ctypes.c_int64 * count)(*[(o.stride(0) if m > 1 else max(o.stride(0), w.rows))
                                      for o, w in zip(outs, ws)])
-    need = sum(razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m) for w in ws)
+    need = razer_workspace_bytes_grouped([w.rows for w in ws], ws[0].cols, m)
     workspace = torch.empty(need, dtype=torch.uint8, device=a.device) if need else None
     args = (wptrs, count, _ptr(a), m, yptrs, lds, _ptr(workspace), need)
     return PreparedCall(L.razer_linear_grouped, args, (structs, ws, a, outs, workspace), "razer_linear_grouped")

@@ -1,6 +1,8 @@
 // C ABI of the gfx950 RaZeR library: argument validation and kernel dispatch.
 // Every entry point enqueues on the caller's stream and returns; nothing here
 // allocates, synchronizes or keeps per-call state.
+#include <mutex>
+
 #include "../../include/razer.h"
 #include "razer_kernels.hpp"
 
@@ -99,6 +101,27 @@ size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m)
         }
         default: return 0;
     }
+}
+
+size_t razer_workspace_bytes_grouped(int32_t count, const int64_t* rows, int64_t cols, int64_t m)
+{
+    if (!rows || count < 1 || count > RAZER_MAX_GROUP || cols <= 0 || m <= kGemvDirectMaxM) return 0;
+    // what the single launch needs (K-slices of all matrices side by side) ...
+    size_t one = 0, each = 0;
+    GemvProblem p[RAZER_MAX_GROUP];
+    for (int i = 0; i < count; ++i) {
+        if (rows[i] < 0) return 0;
+        p[i] = GemvProblem{nullptr, nullptr, nullptr, rows[i], nullptr, rows[i]};
+        // ... and what the sequence of single calls needs, should the group not qualify for one launch
+        const size_t b = razer_workspace_bytes(RAZER_OP_LINEAR, rows[i], cols, m);
+        each = b > each ? b : each;
+    }
+    if (m <= kSkinnyMaxM) {
+        for (int i = 0; i < count; ++i) one += skinny_workspace_bytes(rows[i], cols, m);
+    } else if (gemm_grouped_fits(count, p, m, cols)) {
+        one = gemm_grouped_workspace_bytes(count, p, m, cols);
+    }
+    return one > each ? one : each;
 }
 
 razer_status razer_quantize(const razer_config* cfg, const void* x, int32_t dtype, int64_t rows, int64_t cols,

@@ -23,6 +23,7 @@
 //                    K inside the workgroup when there is about one tile per compute unit; the grouped
 //                    form runs up to four matrices (fused q/k/v, gate/up) as one launch
 // Problems with too few tiles split K over workgroups (fp32 slices in the caller's workspace).
+#include <mutex>
 #include <type_traits>
 
 #include "razer_device.hpp"
@@ -31,6 +32,24 @@
 namespace razer {
 
 constexpr int kBK = 64;
+
+// The large-tile kernels need more dynamic LDS than the default limit; the limit is raised once per
+// kernel and device, on first use.  RAZER_RAISE_LDS_LIMIT expands inside a launch helper that is
+// instantiated once per kernel configuration, so its flags are per kernel; std::call_once makes the
+// first use safe when several host threads launch at once.
+constexpr int kMaxDevices = 16;
+#define RAZER_RAISE_LDS_LIMIT(kern, smem)                                                                  \
+    do {                                                                                                   \
+        static std::once_flag once[kMaxDevices];                                                           \
+        static hipError_t result[kMaxDevices];                                                             \
+        int dev = 0;                                                                                       \
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice; \
+        std::call_once(once[dev], [&] {                                                                    \
+            result[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                         \
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)(smem));    \
+        });                                                                                                \
+        if (result[dev] != hipSuccess) return result[dev];                                                 \
+    } while (0)
 
 // LUT entry per scale byte: { block scale (fp32 bits), -(special * scale) as a bf16 pair }.
 template <int FMT>
@@ -969,13 +988,7 @@ static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, con
     constexpr int BM = 32 * MT, BN = 32 * NW / KG;
     constexpr size_t smem = S * (KG * BM * 128 + NW * 1280) + 256 * sizeof(uint2);
     auto kern = gemm_rb_kernel<NW, S, KG, MT, GB>;
-    static bool attr_set = false;                      // one GPU per process
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    RAZER_RAISE_LDS_LIMIT(kern, smem);
     if (KG != 1 || !workspace) split = 1;
     const int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
     // every K-slice must hold at least one K-tile: slices = ceil(KT / ceil(KT / split))
@@ -1000,13 +1013,7 @@ static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, co
                  const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, uint16_t*, int64_t, int, float*);
     if constexpr (PP) kern = gemm_pp_kernel<BM, BN, WGM, WGN, AQ, GB>;
     else kern = gemm_kernel<BM, BN, WGM, WGN, AQ, GB>;
-    static bool attr_set = false;                      // one GPU per process
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    RAZER_RAISE_LDS_LIMIT(kern, smem);
     const int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
     // every K-slice must hold at least one K-tile: slices = ceil(KT / ceil(KT / split))
     const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + split - 1) / split;
@@ -1178,13 +1185,7 @@ static hipError_t launch_rb_grouped(SvConfig cfg, int count, const GemvProblem* 
     constexpr int BM = 32 * MT, BN = 32 * NW / KG;
     constexpr size_t smem = S * (KG * BM * 128 + NW * 1280) + 256 * sizeof(uint2);
     auto kern = gemm_rb_grouped_kernel<NW, S, KG, MT, GB>;
-    static bool attr_set = false;                      // one GPU per process
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    RAZER_RAISE_LDS_LIMIT(kern, smem);
     if (KG != 1 || !workspace) split = 1;
     const int tiles_m = (int)((m + BM - 1) / BM);
     const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + split - 1) / split;

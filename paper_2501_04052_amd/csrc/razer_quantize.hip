@@ -3,9 +3,10 @@
 //
 // Bit-exactness contract: every fp32 operation below is a single IEEE operation
 // (true division, no reciprocal, no contraction), squared errors are summed in
-// fp64 over the 16 elements in index order (for blocks of 32, 64, 128 -- the
-// block-size study of Sec. 5.4 -- over each run of 16 in index order, the runs'
-// sums then added in run order), and ties are broken as documented in razer.h.
+// fp64 over the block's elements in index order (also for blocks of 32, 64, 128
+// -- the block-size study of Sec. 5.4 -- where the lanes that share a block
+// hand the running sum from one to the next), and ties are broken as documented
+// in razer.h.
 // Compile without fast-math.
 #include "razer_device.hpp"
 #include "razer_kernels.hpp"
@@ -96,8 +97,10 @@ __device__ __forceinline__ uint32_t round_scale(float t)
 
 // ---------------------------------------------------------------- block encoder
 // One thread encodes one run of 16 elements; G = block / 16 consecutive lanes share a block: they
-// agree on the block maximum (hence on the scale) and on the special value by exchanging their
-// run's maximum and squared-error sums within the wavefront.
+// agree on the block maximum (hence on the scale) by exchanging their run's maximum, and on the
+// special value by forming Eq. 4's error sum as ONE chain over the block's elements in index order:
+// lane j of the block continues the sum where lane j - 1 ended (G rounds of 16 additions, of which
+// each lane keeps the one round that started from its predecessor's total).
 template <typename T, int FMT, int G>
 __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, int64_t rows, int64_t cols,
                                                      int64_t ld, SvConfig cfg,
@@ -163,6 +166,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, in
         if (FMT != 1) { cand[0] = cfg.sv0; cand[1] = cfg.sv1; cand[2] = -cfg.sv0; cand[3] = -cfg.sv1; }
         else { cand[0] = cfg.sv0; cand[1] = -cfg.sv0; }
         double sse[NC];
+        double e2[G > 1 ? NC : 1][kBlock];                                // G > 1: the squared errors, summed as a chain below
         uint32_t take[NC];                                                // bit k: element k takes the special value
 #pragma unroll
         for (int m = 0; m < NC; ++m) { sse[m] = 0.0; take[m] = 0u; }
@@ -191,21 +195,28 @@ __global__ __launch_bounds__(256) void encode_kernel(const T* __restrict__ x, in
                     const double ev = xd - cand[m];
                     const bool sp = fabs(ev) < fabs(eb);
                     const double e = sp ? ev : eb;
-                    sse[m] = __builtin_fma(e, e, sse[m]);                 // e*e is exact in fp64: same as sse + e*e
+                    if (G > 1) e2[m][k + j] = e * e;                      // exact in fp64
+                    else sse[m] = __builtin_fma(e, e, sse[m]);            // e*e is exact in fp64: same as sse + e*e
                     take[m] |= (uint32_t)sp << (k + j);
                 }
             }
         }
         if (G > 1) {
-            // block error = run sums added in run order; every lane of the block forms the same sum
-            const int base = (int)(threadIdx.x & 63u) & ~(G - 1);
+            // block error = sum over all 16 G elements in index order.  Round p is the one in which lane
+            // base + p of the block holds the right starting value (its predecessor's total of round p - 1).
+            const int sub = (int)(threadIdx.x & 63u) & (G - 1), base = (int)(threadIdx.x & 63u) & ~(G - 1);
 #pragma unroll
-            for (int m = 0; m < NC; ++m) {
-                double tot = __shfl(sse[m], base);
+            for (int p = 0; p < G; ++p) {
 #pragma unroll
-                for (int c = 1; c < G; ++c) tot += __shfl(sse[m], base + c);
-                sse[m] = tot;
+                for (int m = 0; m < NC; ++m) {
+                    double a = (p == 0) ? 0.0 : __shfl(sse[m], base + p - 1);
+#pragma unroll
+                    for (int k = 0; k < kBlock; ++k) a += e2[m][k];
+                    sse[m] = (sub == p) ? a : sse[m];
+                }
             }
+#pragma unroll
+            for (int m = 0; m < NC; ++m) sse[m] = __shfl(sse[m], base + G - 1);   // every lane of the block: the block's sum
         }
         // Eq. 4: smallest error, ties to the smallest metadata index
         double best = sse[0];

@@ -47,6 +47,21 @@ def test_workspace_sizes(razer):
     assert razer.razer_workspace_bytes(2, 4096, 512, 16) == 0
 
 
+def test_grouped_workspace_query_covers_single_launch_and_fallback(razer):
+    """The grouped query is never smaller than any per-matrix size (the fallback sequence of calls
+    must fit) and, where K-slices are chosen for all matrices together, can exceed their sum."""
+    q = razer.razer_workspace_bytes_grouped
+    one = lambda n, k, m: razer.razer_workspace_bytes(2, n, k, m)
+    assert q([4096, 4096, 4096], 4096, 1) == 0 and q([], 4096, 16) == 0 and q([4096] * 5, 4096, 16) == 0
+    # small batch: K-slices of the matrices side by side
+    assert q([11008, 11008], 4096, 16) == 2 * one(11008, 4096, 16) > 0
+    for rows, k, m in (([4096, 4096, 4096], 4096, 64), ([11008, 11008], 4096, 128), ([1024, 23040], 4096, 256),
+                       ([4096, 4096, 4096], 4096, 2048)):
+        assert q(rows, k, m) >= max(one(n, k, m) for n in rows)
+    # one small and one large matrix at m > 128: slices chosen over the group, more than the sum
+    assert q([1024, 23040], 4096, 256) >= one(1024, 4096, 256) + one(23040, 4096, 256)
+
+
 def test_bad_arguments_return_status_codes_without_gpu(razer):
     from paper_2501_04052_amd.binding import _Config, _Tensor, load_library
     L = load_library()

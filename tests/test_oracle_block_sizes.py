@@ -18,17 +18,13 @@ def unpack(codes):
     return np.stack([codes & 15, codes >> 4], axis=-1).reshape(codes.shape[0], -1)
 
 
-def _sum_in_runs(e):
-    """The reading taken for the error norm of Eq. 4 on blocks longer than 16: sums over runs of
-    16 consecutive elements in index order, run sums added in run order."""
-    n, b = e.shape
-    total = None
-    for r0 in range(0, b, 16):
-        run = np.zeros(n)
-        for k in range(16):
-            run = run + e[:, r0 + k]
-        total = run if total is None else total + run
-    return total
+def _sum_in_index_order(e):
+    """Eq. 4's squared-error norm written out: the plain sum over the block's elements in index
+    order k = 0 .. block-1 (every term is exact in fp64; only the order of the additions rounds)."""
+    acc = np.zeros(e.shape[0])
+    for k in range(e.shape[1]):
+        acc = acc + e[:, k]
+    return acc
 
 
 @pytest.mark.parametrize("block", BLOCKS)
@@ -52,12 +48,12 @@ def test_search_is_brute_force_optimal(oracle, block, fmt, sv):
     errs = []
     for v in cand:
         vals = np.concatenate([BASE, [v]])
-        errs.append(_sum_in_runs(np.min((xs[:, :, None] - vals[None, None, :]) ** 2, axis=2)))
+        errs.append(_sum_in_index_order(np.min((xs[:, :, None] - vals[None, None, :]) ** 2, axis=2)))
     errs = np.stack(errs, axis=1)
     assert np.array_equal(scales[:, 0] >> sh, np.argmin(errs, axis=1))
     assert np.array_equal(sse[:, 0], errs.min(axis=1))
     dq = oracle.dequant(fmt, codes, scales, ts, sv=sv, want=("sq",))["sq"]
-    assert np.array_equal(_sum_in_runs((xs - dq) ** 2), errs.min(axis=1))
+    assert np.array_equal(_sum_in_index_order((xs - dq) ** 2), errs.min(axis=1))
     assert len(set((scales[:, 0] >> sh).tolist())) > 1   # more than one special value gets chosen
 
 
