@@ -155,6 +155,17 @@ razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer
                           int64_t m, void *y_bf16, int64_t ld_y,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* razer_linear for callers that cannot allocate device memory or pass a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the
+ * workspace, same kernels, same results; the K-slices meet in a static device array of
+ * RAZER_STATIC_WORKSPACE_BYTES that each GPU the library runs on holds until the process ends.
+ * Allocates nothing.  Sizes for which razer_workspace_bytes(RAZER_OP_LINEAR, rows, cols, m) exceeds
+ * RAZER_STATIC_WORKSPACE_BYTES are refused with RAZER_ERR_WORKSPACE.  All calls on one GPU share that
+ * array: calls that overlap in time on one GPU (different streams) race; calls on one stream do not. */
+#define RAZER_STATIC_WORKSPACE_BYTES (32u << 20)
+razer_status razer_linear_static(const razer_tensor *w, const void *a_bf16, const razer_tensor *a_q,
+                                 int64_t m, void *y_bf16, int64_t ld_y, void *hip_stream);
+
 /* The same layer for several weight matrices that consume the SAME activation rows (fused q/k/v,
  * gate/up projections; the paper's stripe partition likewise lets one launch span several N
  * ranges, Sec. 4.3): y_bf16[i] = A w[i]^T for i < count, count <= RAZER_MAX_GROUP.  All w[i] must

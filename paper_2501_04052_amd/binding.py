@@ -17,7 +17,7 @@ OP_QUANTIZE, OP_DEQUANT, OP_LINEAR = 0, 1, 2
 GIVEN_TENSOR_SCALE = 1
 
 EXPORTS = ["razer_workspace_bytes", "razer_workspace_bytes_grouped", "razer_quantize", "razer_dequant", "razer_linear",
-           "razer_linear_grouped", "razer_status_string"]
+           "razer_linear_grouped", "razer_linear_static", "razer_status_string"]
 
 
 class RazerError(RuntimeError):
@@ -66,6 +66,8 @@ def load_library():
     L.razer_linear.restype = ctypes.c_int
     L.razer_linear.argtypes = [ctypes.POINTER(_Tensor), vp, ctypes.POINTER(_Tensor), i64, vp, i64,
                                vp, sz, vp]
+    L.razer_linear_static.restype = ctypes.c_int
+    L.razer_linear_static.argtypes = [ctypes.POINTER(_Tensor), vp, ctypes.POINTER(_Tensor), i64, vp, i64, vp]
     L.razer_linear_grouped.restype = ctypes.c_int
     L.razer_linear_grouped.argtypes = [ctypes.POINTER(ctypes.POINTER(_Tensor)), i32, vp, i64,
                                        ctypes.POINTER(vp), ctypes.POINTER(i64), vp, sz, vp]
@@ -217,6 +219,28 @@ def razer_linear(w, a, out=None, workspace=None):
                         0 if workspace is None else workspace.numel(), _stream())
     if st != 0:
         raise RazerError(st, "razer_linear")
+    return out
+
+
+def razer_linear_static(w, a, out):
+    """razer_linear without a workspace argument and without any allocation: `out` must be given
+    (bfloat16 [M][N]); the library's static scratch array holds the K-slices."""
+    L = load_library()
+    if isinstance(a, RazerTensor):
+        m = a.rows
+        a_struct = a.c_struct()
+        a_ptr, aq_ptr = None, ctypes.byref(a_struct)
+    else:
+        assert a.is_cuda and a.dtype == torch.bfloat16 and a.dim() == 2 and a.is_contiguous()
+        assert a.shape[1] == w.cols
+        m = a.shape[0]
+        a_ptr, aq_ptr = _ptr(a), None
+    assert out.shape == (m, w.rows) and out.dtype == torch.bfloat16
+    ws = w.c_struct()
+    ld_y = out.stride(0) if m > 1 else max(out.stride(0), w.rows)
+    st = L.razer_linear_static(ctypes.byref(ws), a_ptr, aq_ptr, m, _ptr(out), ld_y, _stream())
+    if st != 0:
+        raise RazerError(st, "razer_linear_static")
     return out
 
 

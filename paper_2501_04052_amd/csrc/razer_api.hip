@@ -8,7 +8,31 @@
 
 using namespace razer;
 
+// Scratch of razer_linear_static: the K-slice workspace of the linear layer as a static device array,
+// for callers that cannot allocate.  In host code the array's name is only a handle: its device address
+// is looked up once per device (hipGetSymbolAddress with that device current) and kept.
+constexpr size_t kStaticScratchBytes = (size_t)RAZER_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxScratchDevices = 16;
+std::once_flag scratch_once[kMaxScratchDevices];
+void* scratch_ptr[kMaxScratchDevices];
+hipError_t scratch_err[kMaxScratchDevices];
+
+// device address of `scratch` on the current device, or nullptr
+void* static_scratch()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxScratchDevices) return nullptr;
+    std::call_once(scratch_once[dev], [dev] {
+        void* p = nullptr;
+        scratch_err[dev] = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        scratch_ptr[dev] = scratch_err[dev] == hipSuccess ? p : nullptr;
+    });
+    return scratch_ptr[dev];
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -217,6 +241,19 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
                         need > 0 ? (float*)workspace : nullptr, st);
     }
     return e == hipSuccess ? RAZER_OK : RAZER_ERR_HIP;
+}
+
+razer_status razer_linear_static(const razer_tensor* w, const void* a_bf16, const razer_tensor* a_q, int64_t m,
+                                 void* y_bf16, int64_t ld_y, void* hip_stream)
+{
+    if (!w) return RAZER_ERR_NULL;
+    if (w->rows < 0 || w->cols < 0 || m < 0) return RAZER_ERR_SHAPE;
+    // sizes whose K-slices do not fit the static array are refused, never truncated
+    if (razer_workspace_bytes(RAZER_OP_LINEAR, w->rows, w->cols, m) > kStaticScratchBytes) return RAZER_ERR_WORKSPACE;
+    void* ws = static_scratch();
+    if (!ws) return RAZER_ERR_HIP;
+    // every K-slice is written by the main kernel before the reduction reads it: nothing to clear
+    return razer_linear(w, a_bf16, a_q, m, y_bf16, ld_y, ws, kStaticScratchBytes, hip_stream);
 }
 
 razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, const void* a_bf16, int64_t m,
