@@ -22,8 +22,19 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 LLC_BYTES = 256 << 20          # Infinity Cache
-# HBM bytes per {gate,up} launch from the FETCH_SIZE / WRITE_SIZE counters (profiles/): not measurable live
-GATE_UP_TRAFFIC_BYTES = 24847 * 2 * 1024 + 86 * 1024
+# HBM bytes per {gate,up} launch come from the FETCH_SIZE / WRITE_SIZE counter runs summarised in this file
+# (counters cannot be read live); bench.py only parses the figure out of it
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "gemv_m1_llama7b_hbm_traffic.txt")
+
+
+def profiled_traffic_bytes():
+    """`gate_up_hbm_bytes_per_launch = N` from the committed counter summary, or None."""
+    import re
+    try:
+        m = re.search(r"gate_up_hbm_bytes_per_launch\s*=\s*([0-9,]+)", open(TRAFFIC_PROFILE).read())
+        return int(m.group(1).replace(",", "")) if m else None
+    except OSError:
+        return None
 
 
 def parse():
@@ -103,29 +114,36 @@ def time_region(fn, steps, warmup, graph_period=0):
     return e0.elapsed_time(e1) / steps
 
 
-def time_launches(fn, n, warmup):
-    """Average duration (ms) of single launches: one HIP event pair around EACH call of fn(i), on the
-    stream fn launches on, so consecutive launches cannot overlap their ramp-up and drain (this is the
-    figure a kernel trace reports per dispatch); all pairs are read after one final synchronize.
-    Returns (duration net of the markers' own cost, raw pair reading, empty pair reading)."""
+def time_dispatches(fn, n, warmup):
+    """Average duration (ms) of single dispatches of the ONE kernel fn(i) launches: the library records
+    the begin and end time stamps of the dispatch itself into a HIP event pair handed to it through
+    razer_probe_dispatch_events -- the per-dispatch duration a kernel trace (rocprofv3 --kernel-trace)
+    reports, measured live on the stream the kernel runs on.  Every launch has its own pair; all pairs
+    are read after one final synchronize.  Returns (mean, median)."""
     import torch
+    import paper_2501_04052_amd as razer
+    t0, j = time.perf_counter(), 0
+    while time.perf_counter() - t0 < RAMP_S:
+        for _ in range(8):
+            fn(j)
+            j += 1
+        torch.cuda.synchronize()
     for i in range(warmup):
         fn(i)
-    torch.cuda.synchronize()
     pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-    for i, (e0, e1) in enumerate(pairs):
-        e0.record()
-        fn(warmup + i)
-        e1.record()
-    torch.cuda.synchronize()
-    raw = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / n
-    # what an event pair reads with nothing between the two records: the markers' own cost
-    for e0, e1 in pairs:
+    for e0, e1 in pairs:                              # a first record creates the HIP event handles
         e0.record()
         e1.record()
     torch.cuda.synchronize()
-    empty = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / n
-    return raw - empty, raw, empty
+    try:
+        for i, (e0, e1) in enumerate(pairs):
+            razer.razer_probe_dispatch_events(e0, e1)
+            fn(warmup + i)
+    finally:
+        razer.razer_probe_dispatch_events(None, None)
+    torch.cuda.synchronize()
+    d = sorted(e0.elapsed_time(e1) for e0, e1 in pairs)
+    return sum(d) / n, d[n // 2]
 
 
 def main():
@@ -235,17 +253,63 @@ def main():
                                         "note": "same step with the Python binding marshalling every call (host-bound)"}
 
     # dominant kernel of the step: the {gate, up} launch (gemv_stream_grouped_kernel<1,2,2,2,2,false,0>, 44 % of
-    # the step's bytes).  Average launch duration from HIP events around a region of back-to-back
-    # launches of that kernel alone, rotating the packed copies, on the stream it is launched on.
-    # (An event pair around every single launch is reported too, with the reading of an empty pair:
-    # the markers cost several microseconds themselves, so that figure only bounds the duration.)
+    # the step's bytes).  Two live figures, both with HIP events on the stream it runs on:
+    #   per dispatch  -- begin/end time stamps of each single dispatch (what a kernel trace reports; the
+    #                    `roofline` entry uses this one, so it can be recomputed from profiles/)
+    #   back to back  -- a region of launches of that kernel alone, region time / launches (in a stream the
+    #                    drain of one launch overlaps the ramp-up of the next, so this reads lower)
     a1 = make_act(1, 4096, 2101)
     o2 = [torch.empty((1, 11008), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
     dom = [razer.prepare_linear_grouped(cp[4:6], a1, o2) for cp in copies]
     dstream = torch.cuda.current_stream().cuda_stream
     dom_stream_ms = time_region(lambda i: dom[i % n_copies](dstream), max(100, args.steps), 20)
-    dom_ms, dom_raw_ms, dom_empty_ms = time_launches(lambda i: dom[i % n_copies](dstream), max(100, args.steps), 20)
+    dom_ms, dom_median_ms = time_dispatches(lambda i: dom[i % n_copies](dstream), max(200, args.steps), 20)
     dom_bytes = 2 * (11008 * 4096 * 9 // 16 + 2 * 11008 + 4) + 2 * 4096
+    # per-dispatch durations of the step's four launches, measured the same way
+    acts1 = {k: make_act(1, k, 2101) for k in (4096, 11008)}
+    outs1 = [torch.empty((1, n), dtype=torch.bfloat16, device="cuda") for _, n, _ in layers]
+    per_launch = {}
+    for label, mk, byts in (
+            ("qkv", lambda cp: razer.prepare_linear_grouped(cp[0:3], acts1[4096], outs1[0:3]),
+             3 * (4096 * 4096 * 9 // 16 + 2 * 4096 + 4) + 2 * 4096),
+            ("o", lambda cp: razer.prepare_linear(cp[3], acts1[4096], outs1[3]), 4096 * 4096 * 9 // 16 + 4 * 4096 + 4),
+            ("down", lambda cp: razer.prepare_linear(cp[6], acts1[11008], outs1[6]),
+             4096 * 11008 * 9 // 16 + 2 * 11008 + 2 * 4096 + 4)):
+        calls = [mk(cp) for cp in copies]
+        mean_ms, _ = time_dispatches(lambda i: calls[i % n_copies](dstream), 100, 10)
+        per_launch[label] = {"us": mean_ms * 1e3, "GB/s": byts / mean_ms / 1e6}
+    per_launch["gate_up"] = {"us": dom_ms * 1e3, "GB/s": dom_bytes / dom_ms / 1e6}
+    legs["gemv_m1_per_dispatch"] = per_launch
+
+    # measured ceilings, timed in this run: a kernel that only streams a buffer of the size of a launch's
+    # weights (rotated through a pool larger than the last-level cache), per dispatch and back to back
+    pool = torch.empty(3 * LLC_BYTES, dtype=torch.uint8, device="cuda")
+    pool.random_(0, 256, generator=gen)
+    sink = torch.zeros(64, dtype=torch.int32, device="cuda")
+    ceil = {}
+    for label, size in (("9.4MB", 4096 * 4096 * 9 // 16), ("50.8MB", dom_bytes), ("264MB", 2 * 28672 * 8192 * 9 // 16)):
+        size = size // 4096 * 4096
+        slots = [pool[o:o + size] for o in range(0, pool.numel() - size + 1, size)]
+        best = None
+        for wgs in (1024, 2048, 4096, 8192, 16384):
+            fn = lambda i: razer.razer_probe_stream_read(slots[i % len(slots)], wgs, sink)
+            b2b = time_region(fn, 60, 10)
+            if best is None or b2b < best[1]:
+                best = (wgs, b2b)
+        wgs = best[0]
+        fn = lambda i: razer.razer_probe_stream_read(slots[i % len(slots)], wgs, sink)
+        disp, _ = time_dispatches(fn, 100, 10)
+        ceil[label] = {"bytes": size, "workgroups": wgs, "per_dispatch_us": disp * 1e3, "per_dispatch_GB/s": size / disp / 1e6,
+                       "back_to_back_us": best[1] * 1e3, "back_to_back_GB/s": size / best[1] / 1e6}
+    del pool, slots
+    legs["ceiling_stream_read"] = ceil
+    fl_box = [0.0]
+
+    def mfma_fn(i):
+        fl_box[0] = razer.razer_probe_mfma_bf16(4000, 512, sink)
+    mfma_ms = time_region(mfma_fn, 10, 2)
+    legs["ceiling_mfma_bf16_loop"] = {"TFLOP/s": fl_box[0] / mfma_ms / 1e9, "ms": mfma_ms,
+                                      "note": "register-resident v_mfma_f32_32x32x16_bf16 loop, 2 wavefronts per SIMD, no memory traffic"}
 
     gemm_roof = None
 
@@ -257,10 +321,22 @@ def main():
         return ms, fl
 
     def gemm_roofline(ms, fl):
-        return {"bound": "mfma", "achieved": fl / ms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                "kernel": "gemm_rb_grouped_kernel<4,2,1,8,false> ({q,k,v}, {gate,up}) + gemm_rb_kernel<8,2,2,8,false> (o, down), "
-                          "M=2048, Llama-7B layer set as 4 calls, flops = 2MNK, whole-leg time"}
+        # dominant kernel of the M=2048 layer: the {gate,up} launch (gemm_rb_grouped_kernel), per dispatch
+        m = 2048
+        a2k = make_act(m, 4096, 2100 + m)
+        o2k = [torch.empty((m, 11008), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+        calls = [razer.prepare_linear_grouped(cp[4:6], a2k, o2k) for cp in copies]
+        st = torch.cuda.current_stream().cuda_stream
+        dms, _ = time_dispatches(lambda i: calls[i % n_copies](st), 20, 3)
+        dfl = 2.0 * m * 2 * 11008 * 4096
+        return {"bound": "mfma", "achieved": dfl / dms / 1e9, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": dfl / dms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "kernel": "gemm_rb_grouped_kernel<4,2,1,8,false> on {gate,up} 2 x 11008x4096 at M=2048 (44 % of the layer's flops), "
+                          "flops = 2MNK, per-dispatch duration from the dispatch's own time stamps",
+                "avg_dispatch_us": dms * 1e3, "flops_per_launch": dfl,
+                "layer_TFLOP/s": fl / ms / 1e9, "layer_frac": fl / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                "layer_note": "Llama-7B layer set at M=2048 as 4 calls, whole-leg time",
+                "measured_ceiling_TFLOP/s": legs.get("ceiling_mfma_bf16_loop", {}).get("TFLOP/s")}
 
     if args.legs == "gemm":                                  # profiler runs: only the M=2048 GEMM leg
         gemm_roof = gemm_roofline(*gemm_leg(2048))
@@ -408,16 +484,25 @@ def main():
               np.float32(t.tensor_scale.cpu().numpy()[0]))
         a_bits = make_act(1, k, 2101).view(torch.int16).cpu().numpy().view(np.uint16)
         oracle.linear(wq, a_bf16=a_bits, rows=None, cols=np.arange(8, dtype=np.int64))   # page in
-        t0 = time.perf_counter()
-        reps = 0
-        while time.perf_counter() - t0 < 10.0:
-            oracle.linear(wq, a_bf16=a_bits)
-            reps += 1
-        dt = (time.perf_counter() - t0) / reps
-        cpu = {"value": (rows * k * 9 // 16 + 2 * k + 2 * rows) / dt / 1e9, "unit": "GB/s",
-               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())), "kind": "oracle",
-               "sample": "oracle_linear, M=1, first %d of %d output rows of the %dx%d q projection, %d repeats in ~10 s"
-                         % (rows, n, n, k, reps)}
+        nthreads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count()))
+        sample_bytes = rows * k * 9 // 16 + 2 * k + 2 * rows
+
+        def timed(threads, seconds):
+            oracle.set_threads(threads)
+            t0 = time.perf_counter()
+            reps = 0
+            while time.perf_counter() - t0 < seconds:
+                oracle.linear(wq, a_bf16=a_bits)
+                reps += 1
+            return (time.perf_counter() - t0) / reps, reps
+        dt_omp, reps_omp = timed(nthreads, 8.0)
+        dt_one, reps_one = timed(1, 8.0)
+        oracle.set_threads(nthreads)
+        cpu = {"value": sample_bytes / dt_omp / 1e9, "unit": "GB/s", "cores": nthreads, "kind": "oracle",
+               "sample": "oracle_linear, M=1, first %d of %d output rows of the %dx%d q projection, %d repeats in ~8 s "
+                         "with OpenMP over the output rows" % (rows, n, n, k, reps_omp),
+               "single_thread": {"value": sample_bytes / dt_one / 1e9, "unit": "GB/s", "cores": 1,
+                                 "sample": "the same sample on one thread, %d repeats in ~8 s" % reps_one}}
 
     out = {
         "metric": "RaZeR W4A16 GEMV HBM GB/s at M=1 (Llama-7B-shaped layer set)",
@@ -430,15 +515,20 @@ def main():
                                "razer_linear_grouped; plain stream launches through the C ABI; %d packed copies rotated (%.0f MB > 2x LLC); "
                                "fp4 codes x bf16 activations, fp32 accumulate" % (n_copies, n_copies * layer_bytes / 1e6),
                    "m": 1, "bytes_per_step": bytes1},
-        "roofline": {"bound": "hbm", "achieved": dom_bytes / dom_stream_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": dom_bytes / dom_stream_ms / 1e6 / HBM_PEAK_GBS, "traffic": GATE_UP_TRAFFIC_BYTES,
+        "roofline": {"bound": "hbm", "achieved": dom_bytes / dom_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": dom_bytes / dom_ms / 1e6 / HBM_PEAK_GBS, "traffic": profiled_traffic_bytes(),
                      "kernel": "gemv_stream_grouped_kernel<1,2,2,2,2,false,0> on {gate,up} 2 x 11008x4096 (the step's largest launch)",
-                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": dom_stream_ms * 1e3,
-                     "timing": "HIP events around a region of back-to-back launches of this kernel alone on its stream, "
-                               "packed copies rotated; region time / launches",
-                     "single_launch_event_pair_us": dom_raw_ms * 1e3, "empty_event_pair_us": dom_empty_ms * 1e3,
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": dom_ms * 1e3, "median_launch_us": dom_median_ms * 1e3,
+                     "timing": "average over single dispatches of this kernel, each timed by the begin/end time stamps of its own "
+                               "dispatch (HIP events handed to the launch), packed copies rotated -- the per-dispatch duration a "
+                               "kernel trace reports",
+                     "back_to_back_us": dom_stream_ms * 1e3, "back_to_back_GB/s": dom_bytes / dom_stream_ms / 1e6,
+                     "back_to_back_note": "region of launches of this kernel alone / launches: drain and ramp-up of neighbours overlap",
+                     "measured_ceiling_GB/s": ceil["50.8MB"]["per_dispatch_GB/s"],
+                     "frac_of_measured_ceiling": ceil["50.8MB"]["per_dispatch_us"] / (dom_ms * 1e3),
                      "step_frac": gbs / HBM_PEAK_GBS,
-                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, scaled by a plain copy (profiles/)"},
+                     "traffic_source": "profiles/gemv_m1_llama7b_hbm_traffic.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
+                                       "command, scaled by a plain copy; parsed from that file, not measured in this run"},
         "cpu_baseline": cpu,
         "legs": legs,
     }

@@ -74,6 +74,12 @@ def lib():
     return _lib
 
 
+def set_threads(n):
+    """Number of OpenMP threads the oracle's row loops use from now on (timing only)."""
+    lib()
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
 def _p(a):
     return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
 

@@ -18,6 +18,8 @@ GIVEN_TENSOR_SCALE = 1
 
 EXPORTS = ["razer_workspace_bytes", "razer_workspace_bytes_grouped", "razer_quantize", "razer_dequant", "razer_linear",
            "razer_linear_grouped", "razer_linear_static", "razer_status_string"]
+# measurement utilities (include/razer_probe.h)
+PROBE_EXPORTS = ["razer_probe_dispatch_events", "razer_probe_stream_read", "razer_probe_mfma_bf16"]
 
 
 class RazerError(RuntimeError):
@@ -71,6 +73,12 @@ def load_library():
     L.razer_linear_grouped.restype = ctypes.c_int
     L.razer_linear_grouped.argtypes = [ctypes.POINTER(ctypes.POINTER(_Tensor)), i32, vp, i64,
                                        ctypes.POINTER(vp), ctypes.POINTER(i64), vp, sz, vp]
+    L.razer_probe_dispatch_events.restype = None
+    L.razer_probe_dispatch_events.argtypes = [vp, vp]
+    L.razer_probe_stream_read.restype = ctypes.c_int
+    L.razer_probe_stream_read.argtypes = [vp, sz, ctypes.c_int, vp, vp]
+    L.razer_probe_mfma_bf16.restype = ctypes.c_int
+    L.razer_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, ctypes.POINTER(ctypes.c_double)]
     L.razer_status_string.restype = ctypes.c_char_p
     L.razer_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -88,6 +96,29 @@ def razer_workspace_bytes(op, rows, cols, m=0):
 def razer_workspace_bytes_grouped(rows, cols, m):
     arr = (ctypes.c_int64 * len(rows))(*[int(r) for r in rows])
     return int(load_library().razer_workspace_bytes_grouped(len(rows), arr, int(cols), int(m)))
+
+
+def razer_probe_dispatch_events(start=None, stop=None):
+    """start / stop: torch.cuda.Event(enable_timing=True) that have been recorded once (so that their
+    HIP handles exist), or None to switch the recording off."""
+    h = lambda e: None if e is None else ctypes.c_void_p(e.cuda_event)
+    load_library().razer_probe_dispatch_events(h(start), h(stop))
+
+
+def razer_probe_stream_read(buf, workgroups, sink):
+    st = load_library().razer_probe_stream_read(_ptr(buf), buf.numel() * buf.element_size(), int(workgroups),
+                                                _ptr(sink), _stream())
+    if st != 0:
+        raise RazerError(st, "razer_probe_stream_read")
+
+
+def razer_probe_mfma_bf16(iters, workgroups, sink):
+    """Returns the floating-point operations of the launch."""
+    fl = ctypes.c_double()
+    st = load_library().razer_probe_mfma_bf16(int(iters), int(workgroups), _ptr(sink), _stream(), ctypes.byref(fl))
+    if st != 0:
+        raise RazerError(st, "razer_probe_mfma_bf16")
+    return fl.value
 
 
 def _stream():

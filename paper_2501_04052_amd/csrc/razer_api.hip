@@ -216,7 +216,7 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
     hipError_t e;
     if (k == 0) {                                                        // empty contraction: Y = 0
         const int64_t total = m * n;
-        fill_zero_bf16_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((uint16_t*)y_bf16, m, n, ld_y);
+        launch(fill_zero_bf16_kernel, (unsigned)((total + 255) / 256), 256, 0, st, (uint16_t*)y_bf16, m, n, ld_y);
         e = hipGetLastError();
     } else if (wsv.f16) {
         // FP16-scale format: built for the decode regime; more activation rows go through the same

@@ -67,7 +67,7 @@ hipError_t launch_dequant(int fmt, SvConfig cfg, const uint8_t* codes, const uin
     const int64_t nblk = rows * (cols / kBlock);
     if (nblk == 0) return hipSuccess;
     const unsigned grid = (unsigned)((nblk + 255) / 256);
-#define RAZER_DQ(F, B) dequant_kernel<F, B><<<grid, 256, 0, st>>>(codes, scales, tensor_scale, cfg, rows, cols, out, ld)
+#define RAZER_DQ(F, B) launch(dequant_kernel<F, B>, grid, 256, 0, st, codes, scales, tensor_scale, cfg, rows, cols, out, ld)
     if (fmt == 0)      { if (dtype_bf16) RAZER_DQ(0, true); else RAZER_DQ(0, false); }
     else if (fmt == 1) { if (dtype_bf16) RAZER_DQ(1, true); else RAZER_DQ(1, false); }
     else               { if (dtype_bf16) RAZER_DQ(2, true); else RAZER_DQ(2, false); }

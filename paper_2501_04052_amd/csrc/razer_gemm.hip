@@ -994,8 +994,7 @@ static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, con
     // every K-slice must hold at least one K-tile: slices = ceil(KT / ceil(KT / split))
     const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + split - 1) / split;
     const int slices = (kt_all + kt_per - 1) / kt_per;
-    kern<<<dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(64 * NW), smem, st>>>(
-        w_codes, w_scales, w_ts, wcfg.sv0, wcfg.sv1, n, k, a, m, y, ld_y, tiles_m, slices > 1 ? workspace : nullptr,
+    launch(kern, dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(64 * NW), smem, st, w_codes, w_scales, w_ts, wcfg.sv0, wcfg.sv1, n, k, a, m, y, ld_y, tiles_m, slices > 1 ? workspace : nullptr,
         slices > 1 ? kt_per : 0x7FFFFFFF, wcfg.lb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || slices == 1) return e;
@@ -1018,8 +1017,7 @@ static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, co
     // every K-slice must hold at least one K-tile: slices = ceil(KT / ceil(KT / split))
     const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + split - 1) / split;
     const int slices = (kt_all + kt_per - 1) / kt_per;
-    kern<<<dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(64 * WGM * WGN), smem, st>>>(
-        w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, tiles_m,
+    launch(kern, dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(64 * WGM * WGN), smem, st, w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, tiles_m,
         slices > 1 ? workspace : nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || slices == 1) return e;
@@ -1196,8 +1194,7 @@ static hipError_t launch_rb_grouped(SvConfig cfg, int count, const GemvProblem* 
         q[i] = p[i < count ? i : count - 1];
         t[i + 1] = t[i] + (i < count ? (int)((q[i].n + BN - 1) / BN) : 0);
     }
-    kern<<<dim3((unsigned)(tiles_m * t[4]), (unsigned)slices), dim3(64 * NW), smem, st>>>(
-        q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts,
+    launch(kern, dim3((unsigned)(tiles_m * t[4]), (unsigned)slices), dim3(64 * NW), smem, st, q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts,
         q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,
         q[1].ld_y, q[2].ld_y, q[3].ld_y, t[1], t[2], t[3], cfg.sv0, cfg.sv1, k, a, m, tiles_m,
         slices > 1 ? workspace : nullptr, slices > 1 ? kt_per : 0x7FFFFFFF, cfg.lb);

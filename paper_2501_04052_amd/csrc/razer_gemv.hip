@@ -594,7 +594,7 @@ static hipError_t launch_gemv_quad(SvConfig cfg, const uint8_t* codes, const uin
     const int groups = passes == 2 ? 4 : quad_groups(n);         // two passes keep G running sums: 8 groups would spill
     const int nwaves = (int)((k + 512 * runs * passes - 1) / (512 * runs * passes));
     const unsigned grid = (unsigned)((n + 4 * groups - 1) / (4 * groups));
-#define RAZER_QUAD(C, G, PS) gemv_quad_kernel<C, G, 2, 1, 1, PS><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y)
+#define RAZER_QUAD(C, G, PS) launch(gemv_quad_kernel<C, G, 2, 1, 1, PS>, grid, 64 * nwaves, 0, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y)
     if (passes == 2)    { RAZER_QUAD(2, 4, 2); }
     else if (runs == 1) { if (groups == 8) RAZER_QUAD(1, 8, 1); else RAZER_QUAD(1, 4, 1); }
     else                { if (groups == 8) RAZER_QUAD(2, 8, 1); else RAZER_QUAD(2, 4, 1); }
@@ -617,7 +617,7 @@ static hipError_t launch_gemv_quad_grouped(SvConfig cfg, int count, const GemvPr
         q[i] = p[i < count ? i : count - 1];
         g[i + 1] = g[i] + (i < count ? (unsigned)((q[i].n + rows_per_wg - 1) / rows_per_wg) : 0u);
     }
-#define RAZER_QUADG(C, G, PS) gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS><<<g[4], 64 * nwaves, 0, st>>>(                      \
+#define RAZER_QUADG(C, G, PS) launch(gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS>, g[4], 64 * nwaves, 0, st, \
         q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts, \
         q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,        \
         q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m)
@@ -647,9 +647,9 @@ static hipError_t launch_gemv_mr(SvConfig cfg, const uint8_t* codes, const uint8
     const int64_t nslices = (k + kSliceK - 1) / kSliceK;
     const int nwaves = (int)(nslices < kMaxWaves ? nslices : kMaxWaves);
     const unsigned grid = (unsigned)((n + R - 1) / R);
-    if (cfg.f16) gemv_kernel<M, R, true, 1><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, 7);
-    else if (cfg.lb == 4) gemv_kernel<M, R, false><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, 4);
-    else gemv_kernel<M, R, true><<<grid, 64 * nwaves, 0, st>>>(codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, cfg.lb);
+    if (cfg.f16) launch(gemv_kernel<M, R, true, 1>, grid, 64 * nwaves, 0, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, 7);
+    else if (cfg.lb == 4) launch(gemv_kernel<M, R, false>, grid, 64 * nwaves, 0, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, 4);
+    else launch(gemv_kernel<M, R, true>, grid, 64 * nwaves, 0, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, cfg.lb);
     return hipGetLastError();
 }
 template <int M>
@@ -667,9 +667,9 @@ static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_
 #define RAZER_GEMV_ARGS codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, cfg.lb
 #define RAZER_GEMV_SHAPES(GB, SF)                                                                              \
     do {                                                                                                       \
-        if (groups == 8) gemv_stream_kernel<M, R, 8, 2, 1, GB, SF><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);  \
-        else if (sets == 2) gemv_stream_kernel<M, R, 2, 2, 2, GB, SF><<<grid, 128 * nwaves, 0, st>>>(RAZER_GEMV_ARGS); \
-        else gemv_stream_kernel<M, R, 2, 2, 1, GB, SF><<<grid, 64 * nwaves, 0, st>>>(RAZER_GEMV_ARGS);              \
+        if (groups == 8) launch(gemv_stream_kernel<M, R, 8, 2, 1, GB, SF>, grid, 64 * nwaves, 0, st, RAZER_GEMV_ARGS);  \
+        else if (sets == 2) launch(gemv_stream_kernel<M, R, 2, 2, 2, GB, SF>, grid, 128 * nwaves, 0, st, RAZER_GEMV_ARGS); \
+        else launch(gemv_stream_kernel<M, R, 2, 2, 1, GB, SF>, grid, 64 * nwaves, 0, st, RAZER_GEMV_ARGS);              \
     } while (0)
     if (cfg.f16) RAZER_GEMV_SHAPES(true, 1);
     else if (cfg.lb != 4) RAZER_GEMV_SHAPES(true, 0);
@@ -702,13 +702,13 @@ static hipError_t launch_gemv_grouped_m(SvConfig cfg, int count, const GemvProbl
 #define RAZER_GROUPED_SHAPES(GB, SF)                                                                                      \
     do {                                                                                                                  \
         if (!stream)                                                                                                      \
-            gemv_grouped_kernel<M, 4, GB, SF><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);                          \
+            launch(gemv_grouped_kernel<M, 4, GB, SF>, g[4], 64 * nwaves, 0, st, RAZER_GROUPED_ARGS);                          \
         else if (groups == 8)                                                                                             \
-            gemv_stream_grouped_kernel<M, kStreamR, 8, 2, 1, GB, SF><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);   \
+            launch(gemv_stream_grouped_kernel<M, kStreamR, 8, 2, 1, GB, SF>, g[4], 64 * nwaves, 0, st, RAZER_GROUPED_ARGS);   \
         else if (sets == 2)                                                                                               \
-            gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 2, GB, SF><<<g[4], 128 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);  \
+            launch(gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 2, GB, SF>, g[4], 128 * nwaves, 0, st, RAZER_GROUPED_ARGS);  \
         else                                                                                                              \
-            gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 1, GB, SF><<<g[4], 64 * nwaves, 0, st>>>(RAZER_GROUPED_ARGS);   \
+            launch(gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 1, GB, SF>, g[4], 64 * nwaves, 0, st, RAZER_GROUPED_ARGS);   \
     } while (0)
     if (cfg.f16) RAZER_GROUPED_SHAPES(true, 1);
     else if (cfg.lb != 4) RAZER_GROUPED_SHAPES(true, 0);

@@ -1,10 +1,29 @@
 // Host-side launchers of the gfx950 RaZeR kernels (internal to the library).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include "razer_device.hpp"
 
 namespace razer {
+
+// Every kernel of the library is launched through launch().  Measurement hook: a host thread may
+// hand the library a pair of HIP events (razer_probe_dispatch_events); while they are set, each launch
+// made by that thread records the begin and end time stamps of its own dispatch into them -- the
+// duration a kernel trace reports per dispatch, without a profiler attached.  Both are null otherwise,
+// and the launch is then an ordinary one.
+struct ProbeEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+ProbeEvents& probe_events();          // this thread's pair (razer_probe.hip)
+
+template <typename... KArgs, typename... Args>
+inline void launch(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t smem, hipStream_t st, Args... args)
+{
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "kernel argument count");
+    const ProbeEvents& ev = probe_events();
+    hipExtLaunchKernelGGL(kern, grid, block, (uint32_t)smem, st, ev.start, ev.stop, 0u, static_cast<KArgs>(args)...);
+}
 
 // Encoder (absmax pass + block encoder).  ws: >= 16 bytes of device scratch.
 hipError_t launch_quantize(int fmt, SvConfig cfg, const void* x, int dtype_bf16, int64_t rows, int64_t cols,

@@ -1,0 +1,101 @@
+// Measurement utilities of the gfx950 RaZeR library (include/razer_probe.h): nothing here computes any
+// part of the method.  Two ceiling kernels -- a pure streaming read and a register-resident bf16 MFMA
+// loop -- so that a benchmark can time, in its own run and on its own GPU, what the memory system and
+// the matrix cores give a kernel that does nothing else; and the per-thread event pair through which
+// launch() reports the duration of single dispatches.
+#include "../../include/razer_probe.h"
+#include "razer_kernels.hpp"
+
+namespace razer {
+
+ProbeEvents& probe_events()
+{
+    static thread_local ProbeEvents ev;
+    return ev;
+}
+
+// Every workgroup walks the buffer grid-stride in 16-byte loads (one 1 KiB wavefront row per load
+// instruction, UNROLL loads in flight per lane) and folds what it read with xor; one dword per
+// workgroup goes to `sink` so that the loads cannot be dropped.
+template <int UNROLL>
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ buf, size_t n16,
+                                                          uint32_t* __restrict__ sink)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    uint32_t acc = 0;
+    for (; i + (UNROLL - 1) * stride < n16; i += UNROLL * stride) {
+        uint4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) v[u] = buf[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 v = buf[i];
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc ^= (uint32_t)__shfl_xor((int)acc, off);
+    if ((threadIdx.x & 63) == 0) atomicXor(sink + (blockIdx.x & 63u), acc);
+}
+
+// iters x 8 independent v_mfma_f32_32x32x16_bf16 per wavefront, operands and accumulators in
+// registers the whole time: 2 * 32 * 32 * 16 flops per instruction.
+__global__ __launch_bounds__(256, 2) void mfma_loop_kernel(int iters, float* __restrict__ sink)
+{
+    v8bf a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)(float)((threadIdx.x + i) & 3);
+        b[i] = (__bf16)(float)((threadIdx.x * 3 + i) & 1);
+    }
+    v16f acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    }
+    float t = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) t += acc[j][v];
+    if (t == -1.0f) sink[0] = t;                       // never true: keeps the loop alive
+}
+
+}  // namespace razer
+
+using namespace razer;
+
+extern "C" {
+
+void razer_probe_dispatch_events(void* start_event, void* stop_event)
+{
+    ProbeEvents& ev = probe_events();
+    ev.start = (hipEvent_t)start_event;
+    ev.stop = (hipEvent_t)stop_event;
+}
+
+int razer_probe_stream_read(const void* buf, size_t bytes, int workgroups, void* sink, void* hip_stream)
+{
+    if (!buf || !sink) return 1;
+    if ((reinterpret_cast<uintptr_t>(buf) & 15u) != 0 || bytes % 16 != 0 || workgroups < 1 || workgroups > (1 << 20)) return 2;
+    launch(stream_read_kernel<4>, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream,
+           (const uint4*)buf, bytes / 16, (uint32_t*)sink);
+    return hipGetLastError() == hipSuccess ? 0 : 6;
+}
+
+int razer_probe_mfma_bf16(int iters, int workgroups, void* sink, void* hip_stream, double* flops)
+{
+    if (!sink) return 1;
+    if (iters < 1 || workgroups < 1 || workgroups > (1 << 20)) return 2;
+    launch(mfma_loop_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink);
+    if (flops) *flops = 2.0 * 32 * 32 * 16 * 8.0 * iters * 4.0 * workgroups;   // 4 wavefronts per workgroup
+    return hipGetLastError() == hipSuccess ? 0 : 6;
+}
+
+}  // extern "C"

@@ -256,7 +256,7 @@ static void launch_encode(int lb, unsigned grid, unsigned threads, hipStream_t s
                           int64_t cols, int64_t ld, SvConfig cfg, const uint32_t* ws, float* tensor_scale, int given,
                           uint8_t* codes, uint8_t* scales)
 {
-#define RAZER_ENC(G) encode_kernel<T, FMT, G><<<grid, threads, 0, st>>>(x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales)
+#define RAZER_ENC(G) launch(encode_kernel<T, FMT, G>, grid, threads, 0, st, x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales)
     switch (lb) {
         case 4: RAZER_ENC(1); break;
         case 5: RAZER_ENC(2); break;
@@ -273,25 +273,25 @@ static hipError_t launch_quantize_t(int fmt, SvConfig cfg, const T* x, int64_t r
 {
     if (rows == 0 || cols == 0) {
         if (!given) {                       // an empty tensor gets the all-zero tensor's scale of 1
-            absmax_init_kernel<<<1, kAbsmaxCells, 0, st>>>(ws);
+            launch(absmax_init_kernel, 1, kAbsmaxCells, 0, st, ws);
             if (fmt == 0) launch_encode<T, 0>(4, 1, 64, st, x, 0, 16, 16, cfg, ws, tensor_scale, 0, codes, scales);
             else launch_encode<T, 1>(4, 1, 64, st, x, 0, 16, 16, cfg, ws, tensor_scale, 0, codes, scales);
         }
         return hipGetLastError();
     }
     if (!given) {
-        absmax_init_kernel<<<1, kAbsmaxCells, 0, st>>>(ws);
+        launch(absmax_init_kernel, 1, kAbsmaxCells, 0, st, ws);
         constexpr int VEC = 16 / sizeof(T);
         int64_t total = rows * (cols / VEC);
         int64_t blocks = (total + 255) / 256;
         if (blocks > kAbsmaxBlocks) blocks = kAbsmaxBlocks;
-        absmax_kernel<T><<<(unsigned)blocks, 256, 0, st>>>(x, rows, cols, ld, ws);
+        launch(absmax_kernel<T>, (unsigned)blocks, 256, 0, st, x, rows, cols, ld, ws);
     }
     int64_t nblk = rows * (cols / kBlock);
     unsigned grid = (unsigned)((nblk + 255) / 256);
     if (fmt == 0) launch_encode<T, 0>(cfg.lb, grid, 256, st, x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
     else if (fmt == 1) launch_encode<T, 1>(cfg.lb, grid, 256, st, x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
-    else encode_kernel<T, 2, 8><<<grid, 256, 0, st>>>(x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
+    else launch(encode_kernel<T, 2, 8>, grid, 256, 0, st, x, rows, cols, ld, cfg, ws, tensor_scale, given, codes, scales);
     return hipGetLastError();
 }
 

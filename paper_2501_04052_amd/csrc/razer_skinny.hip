@@ -276,9 +276,9 @@ hipError_t launch_slice_reduce(const float* partial, const float* w_ts, const fl
 {
     const int64_t total = m * n;
     if (n % 4 == 0 && ld_y % 4 == 0 && (reinterpret_cast<uintptr_t>(y) & 7u) == 0)
-        slice_reduce_kernel<4><<<(unsigned)((total / 4 + 255) / 256), 256, 0, st>>>(partial, w_ts, a_ts, m, n, nslices, y, ld_y);
+        launch(slice_reduce_kernel<4>, (unsigned)((total / 4 + 255) / 256), 256, 0, st, partial, w_ts, a_ts, m, n, nslices, y, ld_y);
     else
-        slice_reduce_kernel<1><<<(unsigned)((total + 255) / 256), 256, 0, st>>>(partial, w_ts, a_ts, m, n, nslices, y, ld_y);
+        launch(slice_reduce_kernel<1>, (unsigned)((total + 255) / 256), 256, 0, st, partial, w_ts, a_ts, m, n, nslices, y, ld_y);
     return hipGetLastError();
 }
 
@@ -322,8 +322,7 @@ hipError_t launch_slice_reduce_grouped(const float* partial, int count, const Ge
         q[i] = p[i < count ? i : count - 1];
         e[i + 1] = e[i] + (i < count ? m * q[i].n / 4 : 0);
     }
-    slice_reduce_grouped_kernel<<<(unsigned)((e[4] + 255) / 256), 256, 0, st>>>(
-        partial, q[0].ts, q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n,
+    launch(slice_reduce_grouped_kernel, (unsigned)((e[4] + 255) / 256), 256, 0, st, partial, q[0].ts, q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n,
         q[0].ld_y, q[1].ld_y, q[2].ld_y, q[3].ld_y, e[1], e[2], e[3], e[4], m, nslices);
     return hipGetLastError();
 }
@@ -367,9 +366,9 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
 #define RAZER_SK_ARGS codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, workspace, nslices, cfg.lb
 #define RAZER_SK(NB, ST, GB)                                                                  \
     do {                                                                                      \
-        if (nrb == 1) skinny_kernel<NB, ST, GB, 1><<<grid, 256, 0, st>>>(RAZER_SK_ARGS);      \
-        else if (nrb == 2) skinny_kernel<NB, ST, GB, 2><<<grid, 256, 0, st>>>(RAZER_SK_ARGS); \
-        else skinny_kernel<NB, ST, GB, 4><<<grid, 256, 0, st>>>(RAZER_SK_ARGS);               \
+        if (nrb == 1) launch(skinny_kernel<NB, ST, GB, 1>, grid, 256, 0, st, RAZER_SK_ARGS);      \
+        else if (nrb == 2) launch(skinny_kernel<NB, ST, GB, 2>, grid, 256, 0, st, RAZER_SK_ARGS); \
+        else launch(skinny_kernel<NB, ST, GB, 4>, grid, 256, 0, st, RAZER_SK_ARGS);               \
     } while (0)
     if (cfg.lb == 4) {
         if (m <= 16) { if (steps == 8) RAZER_SK(1, 8, false); else RAZER_SK(1, 4, false); }
@@ -414,9 +413,9 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
         q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m, partial, nslices, cfg.lb
 #define RAZER_SKG(NB, ST, GB)                                                                            \
     do {                                                                                                 \
-        if (nrb == 1) skinny_grouped_kernel<NB, ST, 1, GB><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);        \
-        else if (nrb == 2) skinny_grouped_kernel<NB, ST, 2, GB><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);   \
-        else skinny_grouped_kernel<NB, ST, 4, GB><<<g[4], 256, 0, st>>>(RAZER_SKG_ARGS);                 \
+        if (nrb == 1) launch(skinny_grouped_kernel<NB, ST, 1, GB>, g[4], 256, 0, st, RAZER_SKG_ARGS);        \
+        else if (nrb == 2) launch(skinny_grouped_kernel<NB, ST, 2, GB>, g[4], 256, 0, st, RAZER_SKG_ARGS);   \
+        else launch(skinny_grouped_kernel<NB, ST, 4, GB>, g[4], 256, 0, st, RAZER_SKG_ARGS);                 \
     } while (0)
     if (cfg.lb == 4) {
         if (m <= 16) { if (steps == 8) RAZER_SKG(1, 8, false); else RAZER_SKG(1, 4, false); }

@@ -29,6 +29,11 @@ def test_header_symbols_are_exported(razer):
         assert hasattr(lib, n), n
     from paper_2501_04052_amd import binding
     assert set(binding.EXPORTS) == names
+    probe = open(os.path.join(ROOT, "include", "razer_probe.h")).read()
+    pnames = set(re.findall(r"\b(razer_probe_[a-z_0-9]+)\s*\(", probe))
+    assert pnames == set(binding.PROBE_EXPORTS)
+    for n in pnames:
+        assert hasattr(lib, n), n
 
 
 def test_status_strings(razer):
