@@ -15,8 +15,8 @@ ProbeEvents& probe_events()
 }
 
 // Every workgroup walks the buffer grid-stride in 16-byte loads (one 1 KiB wavefront row per load
-// instruction, UNROLL loads in flight per lane) and folds what it read with xor; one dword per
-// workgroup goes to `sink` so that the loads cannot be dropped.
+// instruction, UNROLL loads in flight per lane) and folds what it read with xor; the fold decides a
+// store that (almost) never happens, so the loads cannot be dropped and nothing is written.
 template <int UNROLL>
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ buf, size_t n16,
                                                           uint32_t* __restrict__ sink)
@@ -35,20 +35,23 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
         const uint4 v = buf[i];
         acc ^= v.x ^ v.y ^ v.z ^ v.w;
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) acc ^= (uint32_t)__shfl_xor((int)acc, off);
-    if ((threadIdx.x & 63) == 0) atomicXor(sink + (blockIdx.x & 63u), acc);
+    if (acc == 0x9E3779B9u) sink[threadIdx.x & 63u] = acc;     // one chance in 2^32 per lane
 }
 
 // iters x 8 independent v_mfma_f32_32x32x16_bf16 per wavefront, operands and accumulators in
 // registers the whole time: 2 * 32 * 32 * 16 flops per instruction.
 __global__ __launch_bounds__(256, 2) void mfma_loop_kernel(int iters, float* __restrict__ sink)
 {
+    // operands with well-mixed bits (values of magnitude 0.5 .. 2, both signs): the power a matrix
+    // instruction draws, and with it the clock the GPU sustains, depends on how many bits toggle
     v8bf a, b;
+    uint32_t h = (threadIdx.x + 1u) * 2654435761u + blockIdx.x * 40503u;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        a[i] = (__bf16)(float)((threadIdx.x + i) & 3);
-        b[i] = (__bf16)(float)((threadIdx.x * 3 + i) & 1);
+        h = h * 1664525u + 1013904223u;
+        a[i] = __builtin_bit_cast(__bf16, (uint16_t)(0x3F00u | ((h >> 9) & 0x00FFu) | ((h >> 2) & 0x8000u)));
+        h = h * 1664525u + 1013904223u;
+        b[i] = __builtin_bit_cast(__bf16, (uint16_t)(0x3F00u | ((h >> 9) & 0x00FFu) | ((h >> 2) & 0x8000u)));
     }
     v16f acc[8];
 #pragma unroll

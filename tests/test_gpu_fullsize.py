@@ -19,10 +19,11 @@ def _say(*a):
 
 
 def _rand_packed(n, k, seed):
+    """Random packed bytes: every code, every scale byte (all 64 scale codes, zero and subnormal scales
+    included, all four metadata values)."""
     rng = np.random.default_rng(seed)
     codes = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
     scales = rng.integers(0, 256, size=(n, k // 16), dtype=np.uint8)
-    scales = (scales & 0xC0) | (16 + (scales & 31))              # E3M3 codes 16..47: values 0.5..7.5
     return codes, scales, np.float32(2.0 ** -10)
 
 
@@ -80,43 +81,32 @@ def test_config2_3_llama7b_layer(oracle, name, n, k, idx):
         _check_linear(oracle, wq, wt, m, 2100 + m, sampled=True)
 
 
-@pytest.mark.parametrize("n,k", [(8192, 8192), (1024, 8192), (28672, 8192), (8192, 28672)])
-def test_config4_llama70b_shapes(oracle, n, k):
-    _say("config 4: %dx%d random packed tensor, M in {1,8} whole-ish, M=4096 sampled" % (n, k))
-    wq = _rand_packed(n, k, seed=4000 + n // 1024 + k)
-    wt = razer.RazerTensor.from_host(*wq, W, SV)
+@pytest.mark.parametrize("name,n,k,idx", [(name, n, k, i) for i, (name, n, k) in enumerate(synth.LLAMA_70B_LAYER)])
+def test_config4_llama70b_layer(oracle, name, n, k, idx):
+    """Every tensor of the 70B-shaped layer from the seeded Student-t generator (seed 4000 + index): encoded
+    on the GPU and by the oracle, bit for bit, one tensor at a time; then the linear layer on those ENCODED
+    weights -- M = 1 whole output for every tensor; M = 8 and M = 4096 for one tensor of each shape (whole
+    output where the oracle finishes in seconds, else 64 sampled rows x 256 sampled columns)."""
+    _say("config 4: %s %dx%d seed %d, encode + linear on the encoded weights" % (name, n, k, 4000 + idx))
+    w = synth.weight(n, k, seed=4000 + idx, outlier_frac=0.001)
+    wt, wq = _encode_and_check(oracle, w, W, SV)
+    del w
     _check_linear(oracle, wq, wt, 1, 4101, sampled=False)
-    for m, sampled in ((8, n * k > 2 ** 27), (4096, True)):
-        a = synth.activation(m, k, seed=4100 + m)
-        y = razer.razer_linear(wt, bf16_bits_to_dev(a))
-        torch.cuda.synchronize()
-        rows = synth.sample_indices(m, 64, 9000)
-        cols = synth.sample_indices(n, 256 if sampled else n, 9001)
-        y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=cols)
-        got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
-        err = max_rel_err(got, y64)
-        _say("   linear m=%d n=%d k=%d: %d x %d outputs checked, max rel err %.2e" % (m, n, k, len(rows), len(cols), err))
-        assert err <= TOL, err
-        del y, a
-
-
-def test_config4_llama70b_encoder(oracle):
-    _say("config 4: encoder on 70B-shaped tensors (k 1024x8192 whole, a 2048-row slab of gate 28672x8192)")
-    w = synth.weight(1024, 8192, seed=4001, outlier_frac=0.001)
-    _encode_and_check(oracle, w, W, SV)
-    w = synth.weight(2048, 8192, seed=4004, outlier_frac=0.001)
-    _encode_and_check(oracle, w, W, SV)
+    if name in ("q", "k", "gate", "down"):
+        _check_linear(oracle, wq, wt, 8, 4108, sampled=n * k > 2 ** 24)
+        _check_linear(oracle, wq, wt, 4096, 4100 + 4096, sampled=True)
 
 
 def test_config5_w4a4(oracle):
-    _say("config 5: activation 4096x4096 encode (E4M3 + 1 bit, +-5) and W4A4 linear vs gate 11008x4096")
+    _say("config 5: activation 4096x4096 encode (E4M3 + 1 bit, +-5) and W4A4 linear vs the encoded gate-shaped weight 11008x4096 (seed 5001)")
     a = synth.activation(4096, 4096, seed=5000, outlier_frac=0.005, outlier_gain=50.0)
     at, aq = _encode_and_check(oracle, a, A, (5.0, 0.0))
     frac = np.mean(((aq[0] & 15) == 8) | ((aq[0] >> 4) == 8))
     _say("   activation elements on the special value: %.4f" % frac)
     assert frac > 0.005
-    wq = _rand_packed(11008, 4096, seed=5001)
-    wt = razer.RazerTensor.from_host(*wq, W, SV)
+    w = synth.weight(11008, 4096, seed=5001, outlier_frac=0.001)   # the gate-shaped weight, encoded here too
+    wt, wq = _encode_and_check(oracle, w, W, SV)
+    del w
     y = razer.razer_linear(wt, at)
     torch.cuda.synchronize()
     rows = synth.sample_indices(4096, 64, 9000)
@@ -155,15 +145,15 @@ def test_linear_many_tiles_register_decode_kernel(oracle, m, n, k):
     assert err <= TOL, err
 
 
-@pytest.mark.parametrize("block", [32, 64, 128])
-@pytest.mark.parametrize("m,n,k", [(4100, 4096 + 8, 128 + 32 * 4), (2048, 4096, 4096 + 128), (8192, 4096 + 40, 384),
-                                   (100, 4096, 4096), (64, 11008, 1024 + 128), (2048, 11008, 1152)])
+_BLOCK_SHAPES = [(4100, 4096 + 8, 128 + 32 * 4), (2048, 4096, 4096 + 128), (8192, 4096 + 40, 384),
+                 (100, 4096, 4096), (64, 11008, 1024 + 128), (2048, 11008, 1152)]
+
+
+@pytest.mark.parametrize("block,m,n,k", [(b, m, n, k) for b in (32, 64, 128) for m, n, k in _BLOCK_SHAPES if k % b == 0])
 def test_block_sizes_register_decode_kernel(oracle, block, m, n, k):
     """32-, 64- and 128-element blocks through the register-decode GEMM (one scale byte per lane and
     K-tile, copied with a 1-byte global->LDS copy): 128- and 256-wide tiles, the two-K-group round, 64- and
     128-row tiles with K-slices, ragged K-tiles (K a multiple of the block size only).  Sampled outputs."""
-    if k % block:
-        pytest.skip("K must hold whole blocks")
     _say("block %d register-decode GEMM m=%d n=%d k=%d" % (block, m, n, k))
     rng = np.random.default_rng(7100 + m + n + k + block)
     codes = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
