@@ -20,6 +20,9 @@ EXPORTS = ["razer_workspace_bytes", "razer_workspace_bytes_grouped", "razer_quan
            "razer_linear_grouped", "razer_linear_static", "razer_status_string"]
 # measurement utilities (include/razer_probe.h)
 PROBE_EXPORTS = ["razer_probe_dispatch_events", "razer_probe_stream_read", "razer_probe_mfma_bf16"]
+# launch-shape tuning hooks (include/razer_tune.h)
+TUNE_EXPORTS = ["razer_tune_force", "razer_tune_lookup", "razer_tune_table_size"]
+TUNE_GEMV, TUNE_GEMV_QUAD, TUNE_SMALL_BATCH, TUNE_GEMM_SLICES = 0, 1, 2, 3
 
 
 class RazerError(RuntimeError):
@@ -79,6 +82,12 @@ def load_library():
     L.razer_probe_stream_read.argtypes = [vp, sz, ctypes.c_int, vp, vp]
     L.razer_probe_mfma_bf16.restype = ctypes.c_int
     L.razer_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    L.razer_tune_force.restype = ctypes.c_int
+    L.razer_tune_force.argtypes = [ctypes.c_int, ctypes.POINTER(i32)]
+    L.razer_tune_lookup.restype = ctypes.c_int
+    L.razer_tune_lookup.argtypes = [ctypes.c_int, i64, i64, i64, ctypes.POINTER(i32)]
+    L.razer_tune_table_size.restype = ctypes.c_int
+    L.razer_tune_table_size.argtypes = []
     L.razer_status_string.restype = ctypes.c_char_p
     L.razer_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -96,6 +105,29 @@ def razer_workspace_bytes(op, rows, cols, m=0):
 def razer_workspace_bytes_grouped(rows, cols, m):
     arr = (ctypes.c_int64 * len(rows))(*[int(r) for r in rows])
     return int(load_library().razer_workspace_bytes_grouped(len(rows), arr, int(cols), int(m)))
+
+
+def razer_tune_force(family, shape=None):
+    """Force the launch shape of a kernel family for this host thread (shape: up to 4 ints), or clear
+    it (shape None; family -1 clears all).  For the tuner and for tests."""
+    arr = None
+    if shape is not None:
+        vals = list(shape) + [0] * (4 - len(shape))
+        arr = (ctypes.c_int32 * 4)(*vals)
+    st = load_library().razer_tune_force(int(family), arr)
+    if st != 0:
+        raise RazerError(st, "razer_tune_force")
+
+
+def razer_tune_lookup(family, m, rows, cols):
+    """(source, shape): source 0 = heuristic (shape None), 1 = forced, 2 = built-in table."""
+    arr = (ctypes.c_int32 * 4)()
+    src = load_library().razer_tune_lookup(int(family), int(m), int(rows), int(cols), arr)
+    return src, (tuple(arr) if src else None)
+
+
+def razer_tune_table_size():
+    return int(load_library().razer_tune_table_size())
 
 
 def razer_probe_dispatch_events(start=None, stop=None):

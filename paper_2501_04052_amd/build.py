@@ -6,7 +6,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_PKG, "csrc")
 LIB_PATH = os.path.join(_PKG, "librazer_hip.so")
 SOURCES = ["razer_api.hip", "razer_quantize.hip", "razer_dequant.hip", "razer_gemv.hip", "razer_skinny.hip",
-           "razer_gemm.hip", "razer_probe.hip"]
+           "razer_gemm.hip", "razer_probe.hip", "razer_tune.hip"]
 # No fast-math anywhere: the encoder must reproduce IEEE division and fp64 sums bit for bit.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

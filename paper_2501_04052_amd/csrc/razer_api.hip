@@ -141,7 +141,7 @@ size_t razer_workspace_bytes_grouped(int32_t count, const int64_t* rows, int64_t
         each = b > each ? b : each;
     }
     if (m <= kSkinnyMaxM) {
-        for (int i = 0; i < count; ++i) one += skinny_workspace_bytes(rows[i], cols, m);
+        one = skinny_grouped_workspace_bytes(count, p, cols, m);
     } else if (gemm_grouped_fits(count, p, m, cols)) {
         one = gemm_grouped_workspace_bytes(count, p, m, cols);
     }
@@ -295,10 +295,9 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
             path = SEQUENCE;
         } else if (m <= kSkinnyMaxM) {
             // the K-slices of all matrices live in the workspace side by side
-            size_t need = 0;
+            const size_t need = skinny_grouped_workspace_bytes(count, p, k, m);
             bool ok = true;
             for (int i = 0; i < count; ++i) {
-                need += skinny_workspace_bytes(p[i].n, k, m);
                 if (p[i].n % 4 != 0 || (reinterpret_cast<uintptr_t>(p[i].y) & 7u) != 0 || p[i].ld_y % 4 != 0) ok = false;
             }
             if (ok && (need == 0 || (workspace && workspace_bytes >= need && aligned16(workspace)))) path = SKINNY;

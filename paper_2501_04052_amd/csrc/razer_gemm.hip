@@ -1039,8 +1039,11 @@ struct GemmPlan {
 // K-slices of the register-decode kernel with small activation tiles: about one and a half workgroups
 // per compute unit (best or within 5 % of it at 32, 86 and 172 tiles, K = 4096 and 11008), at least 8
 // K-tiles per slice.
-static int rb_split(int64_t tiles, int64_t kt_all)
+static int rb_split(int64_t tiles, int64_t kt_all, int64_t m = 0, int64_t rows = 0, int64_t k = 0)
 {
+    // the tuner's entry for (m, rows, k), if any: K-slices 1 .. 16, each at least one K-tile
+    const TuneShape t = tuned_shape(kTuneGemmSlices, m, rows, k);
+    if (t.source && t.p[0] >= 1 && t.p[0] <= 16 && t.p[0] <= kt_all) return t.p[0];
     int64_t split = (384 + tiles / 2) / tiles;
     if (split > 16) split = 16;
     if (split > kt_all / 8) split = kt_all / 8;
@@ -1051,7 +1054,7 @@ static GemmPlan gemm_plan(int64_t m, int64_t n, int64_t k, bool register_decode_
     GemmPlan p{0, 1};
     int64_t tiles;
     if (m > 32 && m <= 128 && register_decode_ok)
-        return GemmPlan{m <= 64 ? 8 : 9, rb_split((n + 127) / 128, (k + kBK - 1) / kBK)};
+        return GemmPlan{m <= 64 ? 8 : 9, rb_split((n + 127) / 128, (k + kBK - 1) / kBK, m, n, k)};
     if (m <= 32) { p.tile = 0; tiles = (n + 255) / 256; }
     else if (m <= 64) { p.tile = 1; tiles = (n + 255) / 256; }
     else if (m <= 128) { p.tile = 2; tiles = ((m + 127) / 128) * ((n + 127) / 128); }
@@ -1157,9 +1160,10 @@ static int grouped_split(int count, const GemvProblem* p, int64_t m, int64_t k)
 {
     const int w = grouped_tile_width(count, p, m, k);
     if (w != 2 && w != 4 && w != 8) return 1;
-    int64_t tiles = 0;
-    for (int i = 0; i < count; ++i) tiles += (p[i].n + 127) / 128;
-    return rb_split(tiles * ((m + 32 * w - 1) / (32 * w)), (k + kBK - 1) / kBK);
+    int64_t tiles = 0, rows = 0;
+    for (int i = 0; i < count; ++i) { tiles += (p[i].n + 127) / 128; rows += p[i].n; }
+    if (m > 128) return rb_split(tiles * ((m + 32 * w - 1) / (32 * w)), (k + kBK - 1) / kBK);   // (not a tuned family)
+    return rb_split(tiles * ((m + 32 * w - 1) / (32 * w)), (k + kBK - 1) / kBK, m, rows, k);
 }
 bool gemm_grouped_fits(int count, const GemvProblem* p, int64_t m, int64_t k)
 {

@@ -584,14 +584,19 @@ static inline bool quad_fits(const SvConfig& cfg, int64_t k, int64_t m)
 }
 static inline int quad_runs(int64_t k) { return (k + 511) / 512 <= kMaxWaves ? 1 : 2; }
 static inline int quad_passes(int64_t k) { return k <= 16384 ? 1 : 2; }
-static inline int quad_groups(int64_t rows) { return rows >= 16384 ? 8 : 4; }
+static inline int quad_groups(int64_t rows, int64_t k, int64_t m)
+{
+    const TuneShape t = tuned_shape(kTuneGemvQuad, m, rows, k);          // the tuner's entry, if it names a built shape
+    if (t.source && (t.p[0] == 4 || t.p[0] == 8)) return t.p[0];
+    return rows >= 16384 ? 8 : 4;
+}
 
 static hipError_t launch_gemv_quad(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,
                                    int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
                                    hipStream_t st)
 {
     const int runs = quad_runs(k), passes = quad_passes(k);
-    const int groups = passes == 2 ? 4 : quad_groups(n);         // two passes keep G running sums: 8 groups would spill
+    const int groups = passes == 2 ? 4 : quad_groups(n, k, m);   // two passes keep G running sums: 8 groups would spill
     const int nwaves = (int)((k + 512 * runs * passes - 1) / (512 * runs * passes));
     const unsigned grid = (unsigned)((n + 4 * groups - 1) / (4 * groups));
 #define RAZER_QUAD(C, G, PS) launch(gemv_quad_kernel<C, G, 2, 1, 1, PS>, grid, 64 * nwaves, 0, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y)
@@ -608,7 +613,7 @@ static hipError_t launch_gemv_quad_grouped(SvConfig cfg, int count, const GemvPr
     int64_t rows = 0;
     for (int i = 0; i < count; ++i) rows += p[i].n;
     const int runs = quad_runs(k), passes = quad_passes(k);
-    const int groups = passes == 2 ? 4 : quad_groups(rows);
+    const int groups = passes == 2 ? 4 : quad_groups(rows, k, m);
     const int nwaves = (int)((k + 512 * runs * passes - 1) / (512 * runs * passes));
     const int64_t rows_per_wg = 4 * groups;
     GemvProblem q[4];
@@ -638,6 +643,22 @@ static inline int stream_groups(int nwaves, int m) { return (nwaves > 8 || (m >=
 // 1-3 and 5-8 slices (K = 4096, 11008), slower for 4 slices (K = 8192): dispatching workgroups is part
 // of the cost of these short kernels.
 static inline int stream_sets(int nwaves, int groups) { return (groups == 2 && nwaves <= 8 && nwaves != 4) ? 2 : 1; }
+// (groups, sets) of a launch: the tuner's entry for (m, rows, k) when it names a shape the kernels are
+// built for -- (2, 1), (2, 2) with at most 8 waves per set, (4, 1), (8, 1) -- else the rules above.
+static inline void stream_shape(int nwaves, int64_t m, int64_t rows, int64_t k, int& groups, int& sets)
+{
+    const TuneShape t = tuned_shape(kTuneGemv, m, rows, k);
+    if (t.source) {
+        const int g = t.p[0], s = t.p[1];
+        if (((g == 2 || g == 4 || g == 8) && s == 1) || (g == 2 && s == 2 && nwaves <= 8)) {
+            groups = g;
+            sets = s;
+            return;
+        }
+    }
+    groups = stream_groups(nwaves, (int)m);
+    sets = stream_sets(nwaves, groups);
+}
 
 template <int M, int R>
 static hipError_t launch_gemv_mr(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts,
@@ -661,13 +682,14 @@ static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_
         return launch_gemv_mr<M, 4>(cfg, codes, scales, ts, n, k, a, y, ld_y, st);
     constexpr int R = kStreamR;
     const int nwaves = (int)nslices;
-    const int groups = stream_groups(nwaves, M);
-    const int sets = stream_sets(nwaves, groups);
+    int groups, sets;
+    stream_shape(nwaves, M, n, k, groups, sets);
     const unsigned grid = (unsigned)((n + sets * R * groups - 1) / (sets * R * groups));
 #define RAZER_GEMV_ARGS codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, y, ld_y, cfg.lb
 #define RAZER_GEMV_SHAPES(GB, SF)                                                                              \
     do {                                                                                                       \
         if (groups == 8) launch(gemv_stream_kernel<M, R, 8, 2, 1, GB, SF>, grid, 64 * nwaves, 0, st, RAZER_GEMV_ARGS);  \
+        else if (groups == 4) launch(gemv_stream_kernel<M, R, 4, 2, 1, GB, SF>, grid, 64 * nwaves, 0, st, RAZER_GEMV_ARGS); \
         else if (sets == 2) launch(gemv_stream_kernel<M, R, 2, 2, 2, GB, SF>, grid, 128 * nwaves, 0, st, RAZER_GEMV_ARGS); \
         else launch(gemv_stream_kernel<M, R, 2, 2, 1, GB, SF>, grid, 64 * nwaves, 0, st, RAZER_GEMV_ARGS);              \
     } while (0)
@@ -686,8 +708,12 @@ static hipError_t launch_gemv_grouped_m(SvConfig cfg, int count, const GemvProbl
     const int64_t nslices = (k + kSliceK - 1) / kSliceK;
     const bool stream = nslices <= kMaxWaves;
     const int nwaves = (int)(stream ? nslices : kMaxWaves);
-    const int groups = stream ? stream_groups(nwaves, M) : 1;
-    const int sets = stream ? stream_sets(nwaves, groups) : 1;
+    int groups = 1, sets = 1;
+    if (stream) {
+        int64_t rows = 0;
+        for (int i = 0; i < count; ++i) rows += p[i].n;
+        stream_shape(nwaves, M, rows, k, groups, sets);
+    }
     const int64_t rows_per_wg = stream ? sets * kStreamR * groups : 4;
     GemvProblem q[4];
     unsigned g[5] = {0, 0, 0, 0, 0};
@@ -705,6 +731,8 @@ static hipError_t launch_gemv_grouped_m(SvConfig cfg, int count, const GemvProbl
             launch(gemv_grouped_kernel<M, 4, GB, SF>, g[4], 64 * nwaves, 0, st, RAZER_GROUPED_ARGS);                          \
         else if (groups == 8)                                                                                             \
             launch(gemv_stream_grouped_kernel<M, kStreamR, 8, 2, 1, GB, SF>, g[4], 64 * nwaves, 0, st, RAZER_GROUPED_ARGS);   \
+        else if (groups == 4)                                                                                             \
+            launch(gemv_stream_grouped_kernel<M, kStreamR, 4, 2, 1, GB, SF>, g[4], 64 * nwaves, 0, st, RAZER_GROUPED_ARGS);   \
         else if (sets == 2)                                                                                               \
             launch(gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 2, GB, SF>, g[4], 128 * nwaves, 0, st, RAZER_GROUPED_ARGS);  \
         else                                                                                                              \

@@ -25,6 +25,16 @@ inline void launch(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t smem, h
     hipExtLaunchKernelGGL(kern, grid, block, (uint32_t)smem, st, ev.start, ev.stop, 0u, static_cast<KArgs>(args)...);
 }
 
+// Launch shape of a problem: this thread's forced shape (source 1), else the entry of the built-in table
+// (source 2), else source 0 -- the caller's heuristic applies (razer_tune.hip; families and parameters as in
+// include/razer_tune.h).
+struct TuneShape {
+    int p[4];
+    int source;
+};
+enum { kTuneGemv = 0, kTuneGemvQuad = 1, kTuneSmallBatch = 2, kTuneGemmSlices = 3 };
+TuneShape tuned_shape(int family, int64_t m, int64_t n, int64_t k);
+
 // Encoder (absmax pass + block encoder).  ws: >= 16 bytes of device scratch.
 hipError_t launch_quantize(int fmt, SvConfig cfg, const void* x, int dtype_bf16, int64_t rows, int64_t cols,
                            int64_t ld, uint8_t* codes, uint8_t* scales, float* tensor_scale, int given,
@@ -69,6 +79,8 @@ struct GemvProblem {
 };
 hipError_t launch_gemv_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
                                int64_t m, hipStream_t st);
+// workspace of a grouped small-batch launch (the launch shape is chosen for the rows of all matrices together)
+size_t skinny_grouped_workspace_bytes(int count, const GemvProblem* p, int64_t k, int64_t m);
 
 // Same contraction on bf16 matrix cores with LDS-staged decoded tiles.  Activations are
 // bf16 (a != nullptr) or RaZeR activation-format (a_codes != nullptr).

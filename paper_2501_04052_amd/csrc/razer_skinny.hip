@@ -14,6 +14,12 @@
 // and multiplies the current one.  K-slices of one output tile are summed in fixed order by a second
 // kernel (slice_reduce_kernel) from an fp32 workspace [slices][M][N] (deterministic, no atomics).
 // The kernel is bound by the decode's vector ALU work (about 3 ops per weight), not by HBM.
+//
+// A second kernel for up to 16 activation rows (mv_kernel) keeps K inside the workgroup instead: the
+// structure of the streaming GEMV -- a wave owns a K-slice of every row, its activation fragments stay in
+// registers, it walks over groups of 16 rows with the next group's weights in flight, partial sums of the
+// waves meet in LDS -- with the dot products on the 16x16x32 matrix instruction.  One launch, no workspace.
+// Which of the two serves a shape, and with which launch shape, is the tuner's choice (razer_tune.h).
 #include "razer_device.hpp"
 #include "razer_kernels.hpp"
 
@@ -327,41 +333,293 @@ hipError_t launch_slice_reduce_grouped(const float* partial, int count, const Ge
     return hipGetLastError();
 }
 
-static int skinny_steps(int64_t k, int64_t m)
+// ---------------------------------------------------------------------------------------------
+// NB: 16-row activation fragments (M <= 16 NB); S: 128-k steps per wave and pass; G: groups of 16 weight
+// rows per workgroup.  Wave w of the workgroup owns K-slice w (S steps) of every row, in pass p slice
+// p * waves + w; its activation fragments for that slice stay in registers while it walks the G row
+// groups, the next group's packed weights in flight.  Partial sums of the waves meet in LDS after ONE
+// barrier.
+template <int NB, int S, int G, bool GB>
+__device__ __forceinline__ void mv_body(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+                                        const float* __restrict__ w_ts, float sv0, float sv1, int64_t n, int64_t k,
+                                        const uint16_t* __restrict__ a, int64_t m, uint16_t* __restrict__ y,
+                                        int64_t ld_y, int lb, int64_t group0, int npass)
 {
-    // 512-element K-slices; 1024 for long rows at M <= 16 to bound the number of slices
-    return (m <= 16 && k > 8192) ? 8 : 4;
+    __shared__ uint2 lut[256];
+    extern __shared__ __align__(16) uint8_t dyn_smem[];
+    float4* part = reinterpret_cast<float4*>(dyn_smem);               // [G][waves][NB][64]
+    const float ts = *w_ts;
+    const uint32_t lane = threadIdx.x & 63u, nwaves = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t r = lane & 15u, g = lane >> 4;
+    const uint32_t kk32 = (uint32_t)k;
+    const uint32_t code_ld = (uint32_t)(k >> 1), scale_ld = (uint32_t)(k >> (GB ? lb : 4));
+
+    struct WBuf {
+        uint32_t cw[S][4];
+        uint32_t sw[S];
+    };
+    v4f acc[G][NB];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[gi][b] = v4f{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll 1
+    for (int p = 0; p < npass; ++p) {
+        const uint32_t kw = ((uint32_t)p * nwaves + wave) * (128u * S) + 32u * g;   // this lane's first k of step 0
+        // element offsets of this lane's S steps (clamped to 0 past K) and the matching scale masks
+        uint32_t koff[S], smask[S];
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const uint32_t kk = kw + 128u * s;
+            const bool in = kk < kk32;
+            koff[s] = in ? kk : 0u;
+            smask[s] = in ? 0xFFFFFFFFu : 0u;
+        }
+        // activation fragments of this K-slice: row 16 b + r (rows past M re-read row M - 1, their product
+        // columns are never stored), 64 contiguous bytes per step
+        uint32_t af[NB][S][4][4];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const uint32_t mrow = (16u * b + r < (uint32_t)m) ? 16u * b + r : (uint32_t)m - 1u;
+            const uint8_t* ap = reinterpret_cast<const uint8_t*>(a + (int64_t)mrow * k);
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint4 t = *reinterpret_cast<const uint4*>(ap + (koff[s] * 2u + 16u * j));
+                    af[b][s][j][0] = t.x; af[b][s][j][1] = t.y; af[b][s][j][2] = t.z; af[b][s][j][3] = t.w;
+                }
+        }
+        auto load = [&](WBuf& w, int gi) {
+            int64_t row = (group0 + gi) * 16 + r;
+            row = row < n ? row : n - 1;                                  // rows past N re-read the last row
+            const uint8_t* crow = codes + row * (int64_t)code_ld;
+            const uint8_t* srow = scales + row * (int64_t)scale_ld;
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const uint4 t = *reinterpret_cast<const uint4*>(crow + (koff[s] >> 1));
+                w.cw[s][0] = t.x; w.cw[s][1] = t.y; w.cw[s][2] = t.z; w.cw[s][3] = t.w;
+                if (GB) {
+                    const uint32_t bb = srow[koff[s] >> lb];
+                    w.sw[s] = bb | (bb << 8);
+                } else {
+                    w.sw[s] = *reinterpret_cast<const uint16_t*>(srow + (koff[s] >> 4));
+                }
+            }
+        };
+        WBuf w0, w1;
+        load(w0, 0);
+        if (p == 0) {
+            for (uint32_t sb = threadIdx.x; sb < 256u; sb += blockDim.x) {
+                float s, sv;
+                decode_scale_byte<0>(sb, sv0, sv1, s, sv);
+                const uint32_t pp = (uint32_t)f32_to_bf16_rne(-(sv * s));
+                lut[sb] = make_uint2(f2u(s), pp | (pp << 16));
+            }
+            __syncthreads();
+        }
+        auto mul = [&](const WBuf& w, int gi) {
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const uint32_t sws = w.sw[s] & smask[s];                  // past K: scale 0
+                const uint2 le0 = lut[sws & 255u], le1 = lut[(sws >> 8) & 255u];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const v8bf wf = sk_decode_dword(w.cw[s][j], j < 2 ? le0 : le1);
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) {
+                        const v8bf av = __builtin_bit_cast(v8bf, make_uint4(af[b][s][j][0], af[b][s][j][1], af[b][s][j][2], af[b][s][j][3]));
+                        acc[gi][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, av, acc[gi][b], 0, 0, 0);
+                    }
+                }
+            }
+        };
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            if (gi + 1 < G) load((gi & 1) ? w0 : w1, gi + 1);
+            mul((gi & 1) ? w1 : w0, gi);
+        }
+    }
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+            part[((gi * nwaves + wave) * NB + b) * 64 + lane] = make_float4(acc[gi][b][0], acc[gi][b][1], acc[gi][b][2], acc[gi][b][3]);
+    __syncthreads();
+    // entry e = (group gi, fragment b, lane l): rows 16 (group0 + gi) + 4 (l / 16) + 0..3, column 16 b + l % 16
+    for (uint32_t e = threadIdx.x; e < (uint32_t)(G * NB * 64); e += blockDim.x) {
+        const uint32_t gi = e / (NB * 64), b = (e / 64) % NB, l = e & 63u;
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (uint32_t w = 0; w < nwaves; ++w) {
+            const float4 q = part[((gi * nwaves + w) * NB + b) * 64 + l];
+            t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+        }
+        const int64_t gn = (group0 + gi) * 16 + 4 * (l >> 4);
+        const int64_t gm = 16 * b + (l & 15u);
+        if (gm < m && gn < n) {
+            uint16_t* dst = y + gm * ld_y + gn;
+            const float sc = -ts;
+            if (gn + 3 < n && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {
+                const uint32_t lo = (uint32_t)f32_to_bf16_rne(sc * t.x) | ((uint32_t)f32_to_bf16_rne(sc * t.y) << 16);
+                const uint32_t hi = (uint32_t)f32_to_bf16_rne(sc * t.z) | ((uint32_t)f32_to_bf16_rne(sc * t.w) << 16);
+                *reinterpret_cast<uint2*>(dst) = make_uint2(lo, hi);
+            } else {
+                const float v[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (gn + i < n) dst[i] = f32_to_bf16_rne(sc * v[i]);
+            }
+        }
+    }
 }
 
-// Consecutive 64-row blocks one workgroup walks through (staging its activation slice once and
-// keeping the next block's weights in flight): 2 or 4 when that still leaves 2048 workgroups (up to
-// 16 activation rows) or 1024 (17..32).  Measured over 4096^2 .. 57344 x 8192: 5-12 % faster on the
-// large matrices, slower on small ones.
-static int skinny_row_blocks(int64_t row_blocks, int64_t nslices, int64_t m)
+template <int NB, int S, int G, bool GB, int MAXW>
+__global__ __launch_bounds__(64 * MAXW) void mv_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+                                                       const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
+                                                       int64_t k, const uint16_t* __restrict__ a, int64_t m,
+                                                       uint16_t* __restrict__ y, int64_t ld_y, int lb, int npass)
 {
+    mv_body<NB, S, G, GB>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, lb, (int64_t)blockIdx.x * G, npass);
+}
+
+// Grouped form: workgroups [0, g1) serve matrix 0, [g1, g2) matrix 1, ... (scalar arguments picked by
+// uniform compares, as in the other grouped kernels).
+template <int NB, int S, int G, bool GB, int MAXW>
+__global__ __launch_bounds__(64 * MAXW) void mv_grouped_kernel(
+    const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
+    const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
+    const float* f0, const float* f1, const float* f2, const float* f3,
+    uint16_t* y0, uint16_t* y1, uint16_t* y2, uint16_t* y3,
+    int64_t n0, int64_t n1, int64_t n2, int64_t n3,
+    int64_t l0, int64_t l1, int64_t l2, int64_t l3,
+    unsigned g1, unsigned g2, unsigned g3,
+    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int64_t m, int lb, int npass)
+{
+    const unsigned b = blockIdx.x;
+    const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = f0; uint16_t* y = y0;
+    int64_t n = n0, ld = l0;
+    unsigned first = 0;
+    if (b >= g1) { codes = c1; scales = s1; ts = f1; y = y1; n = n1; ld = l1; first = g1; }
+    if (b >= g2) { codes = c2; scales = s2; ts = f2; y = y2; n = n2; ld = l2; first = g2; }
+    if (b >= g3) { codes = c3; scales = s3; ts = f3; y = y3; n = n3; ld = l3; first = g3; }
+    mv_body<NB, S, G, GB>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, lb, (int64_t)(b - first) * G, npass);
+}
+
+// Launch shapes of the K-in-workgroup kernel: (S steps per wave and pass, G row groups per workgroup,
+// at most MAXW waves).  The partial sums take G x waves KiB of LDS.
+struct MvShape {
+    int s, g, maxw;
+};
+constexpr MvShape kMvShapes[] = {{1, 2, 16}, {1, 4, 16}, {2, 2, 16}, {2, 4, 16}, {2, 8, 8}};
+static bool mv_shape_ok(int s, int g)
+{
+    for (const MvShape& sh : kMvShapes)
+        if (sh.s == s && sh.g == g) return true;
+    return false;
+}
+static int mv_maxw(int s, int g)
+{
+    for (const MvShape& sh : kMvShapes)
+        if (sh.s == s && sh.g == g) return sh.maxw;
+    return 16;
+}
+static void mv_geometry(int s, int g, int64_t k, int& nwaves, int& npass)
+{
+    const int64_t slices = (k + 128 * s - 1) / (128 * s);
+    const int maxw = mv_maxw(s, g);
+    nwaves = (int)(slices < maxw ? slices : maxw);
+    npass = (int)((slices + nwaves - 1) / nwaves);
+}
+
+// The launch plan of a small-batch problem: the tuner's entry for (m, rows, k) when it names shapes the
+// kernels are built for, else the heuristic -- the K-sliced kernel with 512-element slices (1024 for long
+// rows at M <= 16, to bound the number of slices) and 2 or 4 consecutive 64-row blocks per workgroup when
+// that still leaves 2048 workgroups (up to 16 activation rows) or 1024 (17..32); measured over 4096^2 ..
+// 57344 x 8192: 5-12 % faster on the large matrices, slower on small ones.
+struct SkinnyPlan {
+    bool in_workgroup;      // K inside the workgroup (mv_kernel): no workspace
+    int steps, nrb;         // K-sliced kernel
+    int s, g;               // K-in-workgroup kernel
+};
+static SkinnyPlan skinny_plan(int64_t rows, int64_t k, int64_t m)
+{
+    SkinnyPlan p{false, (m <= 16 && k > 8192) ? 8 : 4, 1, 0, 0};
+    const int64_t row_blocks = (rows + kSkRows - 1) / kSkRows;
+    const TuneShape t = tuned_shape(kTuneSmallBatch, m, rows, k);
+    if (t.source && t.p[0] == 1 && m <= 16 && mv_shape_ok(t.p[1], t.p[2])) {
+        p.in_workgroup = true;
+        p.s = t.p[1];
+        p.g = t.p[2];
+        return p;
+    }
+    if (t.source && t.p[0] == 0 && (t.p[1] == 4 || (t.p[1] == 8 && m <= 16)) && (t.p[2] == 1 || t.p[2] == 2 || t.p[2] == 4)) {
+        p.steps = t.p[1];
+        p.nrb = t.p[2];
+        return p;
+    }
+    const int64_t nslices = (k + 128 * p.steps - 1) / (128 * p.steps);
     const int64_t target = m <= 16 ? 2048 : 1024;
-    int nrb = 1;
-    while (nrb < 4 && (row_blocks / (2 * nrb)) * nslices >= target) nrb *= 2;
-    return nrb;
+    while (p.nrb < 4 && (row_blocks / (2 * p.nrb)) * nslices >= target) p.nrb *= 2;
+    return p;
 }
 
 size_t skinny_workspace_bytes(int64_t n, int64_t k, int64_t m)
 {
     if (m <= kGemvDirectMaxM || m > kSkinnyMaxM || k == 0 || k > kSkinnyMaxK) return 0;
-    const int64_t kc = 128 * skinny_steps(k, m);
+    const SkinnyPlan p = skinny_plan(n, k, m);
+    if (p.in_workgroup) return 0;
+    const int64_t kc = 128 * p.steps;
     const int64_t nslices = (k + kc - 1) / kc;
     return nslices > 1 ? (size_t)(nslices * m * n) * sizeof(float) : 0;
 }
+
+size_t skinny_grouped_workspace_bytes(int count, const GemvProblem* p, int64_t k, int64_t m)
+{
+    if (m <= kGemvDirectMaxM || m > kSkinnyMaxM || k == 0 || k > kSkinnyMaxK) return 0;
+    int64_t rows = 0;
+    for (int i = 0; i < count; ++i) rows += p[i].n;
+    const SkinnyPlan pl = skinny_plan(rows, k, m);
+    if (pl.in_workgroup) return 0;
+    const int64_t kc = 128 * pl.steps;
+    const int64_t nslices = (k + kc - 1) / kc;
+    return nslices > 1 ? (size_t)(nslices * m * rows) * sizeof(float) : 0;
+}
+
+#define RAZER_MV_SHAPES(LAUNCH)                       \
+    do {                                              \
+        if (pl.s == 1 && pl.g == 2) LAUNCH(1, 2, 16); \
+        else if (pl.s == 1) LAUNCH(1, 4, 16);         \
+        else if (pl.g == 2) LAUNCH(2, 2, 16);         \
+        else if (pl.g == 4) LAUNCH(2, 4, 16);         \
+        else LAUNCH(2, 8, 8);                         \
+    } while (0)
 
 hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scales, const float* ts, int64_t n,
                          int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y, float* workspace,
                          hipStream_t st)
 {
-    const int steps = skinny_steps(k, m);
+    const SkinnyPlan pl = skinny_plan(n, k, m);
+    if (pl.in_workgroup) {
+        int nwaves, npass;
+        mv_geometry(pl.s, pl.g, k, nwaves, npass);
+        const unsigned grid = (unsigned)(((n + 15) / 16 + pl.g - 1) / pl.g);
+        const size_t smem = (size_t)pl.g * nwaves * 1024;
+#define RAZER_MV(S, G, MW)                                                                                           \
+        do {                                                                                                         \
+            if (cfg.lb == 4) launch(mv_kernel<1, S, G, false, MW>, grid, 64 * nwaves, smem, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, cfg.lb, npass); \
+            else launch(mv_kernel<1, S, G, true, MW>, grid, 64 * nwaves, smem, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, cfg.lb, npass);             \
+        } while (0)
+        RAZER_MV_SHAPES(RAZER_MV);
+#undef RAZER_MV
+        return hipGetLastError();
+    }
+    const int steps = pl.steps;
     const int64_t kc = 128 * steps;
     const int nslices = (int)((k + kc - 1) / kc);
     const int64_t row_blocks = (n + kSkRows - 1) / kSkRows;
-    const int nrb = skinny_row_blocks(row_blocks, nslices, m);
+    const int nrb = pl.nrb;
     const unsigned grid = (unsigned)(((row_blocks + nrb - 1) / nrb) * nslices);
 #define RAZER_SK_ARGS codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, workspace, nslices, cfg.lb
 #define RAZER_SK(NB, ST, GB)                                                                  \
@@ -384,33 +642,52 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
     return launch_slice_reduce(workspace, ts, nullptr, m, n, nslices, y, ld_y, st);
 }
 
-// One launch (plus one reduction launch when K is sliced) for up to 4 matrices sharing K, the
-// activation rows (5..32), 16-element blocks and the special values; every n a positive multiple of 4.
-// Workspace: skinny_workspace_bytes of the matrices, added up.
+// One launch (plus one reduction launch when K is sliced over workgroups) for up to 4 matrices sharing K,
+// the activation rows (5..32), the block size and the special values; every n a positive multiple of 4.
+// Workspace: skinny_grouped_workspace_bytes.
 hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
                                  int64_t m, float* workspace, hipStream_t st)
 {
     if (count < 1 || count > 4 || cfg.f16 || m <= kGemvDirectMaxM || m > kSkinnyMaxM || k > kSkinnyMaxK)
         return hipErrorInvalidValue;
-    const int steps = skinny_steps(k, m);
-    const int64_t kc = 128 * steps;
-    const int nslices = (int)((k + kc - 1) / kc);
+    int64_t rows = 0;
+    for (int i = 0; i < count; ++i) rows += p[i].n;
+    const SkinnyPlan pl = skinny_plan(rows, k, m);
     GemvProblem q[4];
     unsigned g[5] = {0, 0, 0, 0, 0};
-    int64_t row_blocks = 0;
-    for (int i = 0; i < count; ++i) row_blocks += (p[i].n + kSkRows - 1) / kSkRows;
-    const int nrb = skinny_row_blocks(row_blocks, nslices, m);
     for (int i = 0; i < 4; ++i) {
         q[i] = p[i < count ? i : count - 1];
         if (q[i].n % 4 != 0 || q[i].n <= 0) return hipErrorInvalidValue;
+    }
+#define RAZER_SKG_COMMON                                                                                             \
+    q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts,     \
+        q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,        \
+        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m
+    if (pl.in_workgroup) {
+        int nwaves, npass;
+        mv_geometry(pl.s, pl.g, k, nwaves, npass);
+        for (int i = 0; i < 4; ++i)
+            g[i + 1] = g[i] + (i < count ? (unsigned)(((q[i].n + 15) / 16 + pl.g - 1) / pl.g) : 0u);
+        const size_t smem = (size_t)pl.g * nwaves * 1024;
+#define RAZER_MVG(S, G, MW)                                                                                                   \
+        do {                                                                                                                  \
+            if (cfg.lb == 4) launch(mv_grouped_kernel<1, S, G, false, MW>, g[4], 64 * nwaves, smem, st, RAZER_SKG_COMMON, cfg.lb, npass); \
+            else launch(mv_grouped_kernel<1, S, G, true, MW>, g[4], 64 * nwaves, smem, st, RAZER_SKG_COMMON, cfg.lb, npass);             \
+        } while (0)
+        RAZER_MV_SHAPES(RAZER_MVG);
+#undef RAZER_MVG
+        return hipGetLastError();
+    }
+    const int steps = pl.steps;
+    const int64_t kc = 128 * steps;
+    const int nslices = (int)((k + kc - 1) / kc);
+    const int nrb = pl.nrb;
+    for (int i = 0; i < 4; ++i) {
         const int64_t rbi = (q[i].n + kSkRows - 1) / kSkRows;
         g[i + 1] = g[i] + (i < count ? (unsigned)((rbi + nrb - 1) / nrb) * nslices : 0u);
     }
     float* partial = nslices > 1 ? workspace : nullptr;
-#define RAZER_SKG_ARGS                                                                                               \
-    q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts,     \
-        q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,        \
-        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m, partial, nslices, cfg.lb
+#define RAZER_SKG_ARGS RAZER_SKG_COMMON, partial, nslices, cfg.lb
 #define RAZER_SKG(NB, ST, GB)                                                                            \
     do {                                                                                                 \
         if (nrb == 1) launch(skinny_grouped_kernel<NB, ST, 1, GB>, g[4], 256, 0, st, RAZER_SKG_ARGS);        \
@@ -426,6 +703,7 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
     }
 #undef RAZER_SKG
 #undef RAZER_SKG_ARGS
+#undef RAZER_SKG_COMMON
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || nslices == 1) return err;
     return launch_slice_reduce_grouped(partial, count, p, m, nslices, st);

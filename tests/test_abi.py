@@ -34,6 +34,37 @@ def test_header_symbols_are_exported(razer):
     assert pnames == set(binding.PROBE_EXPORTS)
     for n in pnames:
         assert hasattr(lib, n), n
+    tune = open(os.path.join(ROOT, "include", "razer_tune.h")).read()
+    tnames = set(re.findall(r"\b(razer_tune_[a-z_0-9]+)\s*\(", tune))
+    assert tnames == set(binding.TUNE_EXPORTS)
+    for n in tnames:
+        assert hasattr(lib, n), n
+
+
+def test_tuning_hooks_force_lookup_and_workspace(razer):
+    """Forcing a launch shape is visible through the lookup and through the workspace query (the
+    K-in-workgroup small-batch kernel needs none); clearing restores the table / heuristic; a forced
+    shape the kernels are not built for falls back to the heuristic."""
+    from paper_2501_04052_amd import binding as b
+    fam = b.TUNE_SMALL_BATCH
+    base = razer.razer_workspace_bytes(2, 4100, 4096, 16)
+    src0, shape0 = razer.razer_tune_lookup(fam, 16, 4100, 4096)
+    assert src0 == 0 and shape0 is None and base == 8 * 16 * 4100 * 4      # no table entry for this odd shape
+    razer.razer_tune_force(fam, (1, 1, 2))
+    assert razer.razer_tune_lookup(fam, 16, 4100, 4096) == (1, (1, 1, 2, 0))
+    assert razer.razer_workspace_bytes(2, 4100, 4096, 16) == 0
+    assert razer.razer_workspace_bytes(2, 4100, 4096, 20) == 8 * 20 * 4100 * 4   # more than 16 rows: K-sliced kernel
+    razer.razer_tune_force(fam, (0, 8, 1))
+    assert razer.razer_workspace_bytes(2, 4100, 4096, 16) == 4 * 16 * 4100 * 4
+    razer.razer_tune_force(fam, (1, 3, 5))                                        # not a built shape
+    assert razer.razer_workspace_bytes(2, 4100, 4096, 16) == base
+    razer.razer_tune_force(fam, None)
+    assert razer.razer_tune_lookup(fam, 16, 4100, 4096)[0] == 0
+    assert razer.razer_workspace_bytes(2, 4100, 4096, 16) == base
+    razer.razer_tune_force(-1, None)
+    with pytest.raises(razer.RazerError):
+        razer.razer_tune_force(9, (1, 2))
+    assert razer.razer_tune_table_size() >= 0
 
 
 def test_status_strings(razer):
