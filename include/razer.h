@@ -81,7 +81,11 @@ typedef struct {
     float sv[2];
     int32_t block;             /* elements per scale byte: 16, 32, 64 or 128; 0 means 16.  cols must be
                                   a multiple of max(32, block).                                         */
+    int32_t layout;            /* RAZER_LAYOUT_CANONICAL (0: the storage described above) or
+                                  RAZER_LAYOUT_INTERLEAVED (a razer_prepack result, see there)          */
 } razer_config;
+
+enum { RAZER_LAYOUT_CANONICAL = 0, RAZER_LAYOUT_INTERLEAVED = 1 };
 
 /* A quantized tensor: device pointers + shape + configuration. */
 typedef struct {
@@ -154,6 +158,20 @@ razer_status razer_dequant(const razer_tensor *t, void *out, int32_t dtype, int6
 razer_status razer_linear(const razer_tensor *w, const void *a_bf16, const razer_tensor *a_q,
                           int64_t m, void *y_bf16, int64_t ld_y,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Private pre-packed weight layout (the paper shuffles its weights offline so that a thread's loads are
+ * contiguous, Sec. 4.3).  Here: per row, every run of 2048 elements is stored as its 1024 bytes of codes
+ * followed by its 128 scale bytes (a last, shorter run is padded to the same 1152 bytes), so that the
+ * scale bytes a wavefront needs travel in the same stream as its codes instead of coming from a second
+ * array.  razer_prepack copies a canonical RAZER_FMT_WEIGHT tensor with 16-element blocks into `packed`
+ * (device, 16-byte aligned, razer_prepack_bytes(t) bytes = rows * ceil(cols / 2048) * 1152); the result is
+ * used as a razer_tensor with codes = packed, scales = NULL, the same tensor_scale, rows, cols and cfg
+ * with cfg.layout = RAZER_LAYOUT_INTERLEAVED.  Such a tensor is accepted by razer_linear and
+ * razer_linear_grouped (all matrices of a group in the same layout) for the decode regime they are meant
+ * for -- bf16 activations, m <= 4, cols <= 32768 -- with results bit-identical to the canonical tensor's;
+ * every other use returns RAZER_ERR_CONFIG (keep the canonical tensor for prefill, razer_dequant and W4A4). */
+size_t razer_prepack_bytes(const razer_tensor *t);
+razer_status razer_prepack(const razer_tensor *t, void *packed, size_t packed_bytes, void *hip_stream);
 
 /* razer_linear for callers that cannot allocate device memory or pass a workspace (code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the

@@ -16,7 +16,8 @@ F32, BF16 = 0, 1
 OP_QUANTIZE, OP_DEQUANT, OP_LINEAR = 0, 1, 2
 GIVEN_TENSOR_SCALE = 1
 
-EXPORTS = ["razer_workspace_bytes", "razer_workspace_bytes_grouped", "razer_quantize", "razer_dequant", "razer_linear",
+LAYOUT_CANONICAL, LAYOUT_INTERLEAVED = 0, 1
+EXPORTS = ["razer_workspace_bytes", "razer_workspace_bytes_grouped", "razer_prepack_bytes", "razer_prepack", "razer_quantize", "razer_dequant", "razer_linear",
            "razer_linear_grouped", "razer_linear_static", "razer_status_string"]
 # measurement utilities (include/razer_probe.h)
 PROBE_EXPORTS = ["razer_probe_dispatch_events", "razer_probe_stream_read", "razer_probe_mfma_bf16"]
@@ -32,7 +33,8 @@ class RazerError(RuntimeError):
 
 
 class _Config(ctypes.Structure):
-    _fields_ = [("format", ctypes.c_int32), ("sv", ctypes.c_float * 2), ("block", ctypes.c_int32)]
+    _fields_ = [("format", ctypes.c_int32), ("sv", ctypes.c_float * 2), ("block", ctypes.c_int32),
+                ("layout", ctypes.c_int32)]
 
 
 class _Tensor(ctypes.Structure):
@@ -63,6 +65,10 @@ def load_library():
     L.razer_workspace_bytes.argtypes = [ctypes.c_int, i64, i64, i64]
     L.razer_workspace_bytes_grouped.restype = sz
     L.razer_workspace_bytes_grouped.argtypes = [i32, ctypes.POINTER(i64), i64, i64]
+    L.razer_prepack_bytes.restype = sz
+    L.razer_prepack_bytes.argtypes = [ctypes.POINTER(_Tensor)]
+    L.razer_prepack.restype = ctypes.c_int
+    L.razer_prepack.argtypes = [ctypes.POINTER(_Tensor), vp, sz, vp]
     L.razer_quantize.restype = ctypes.c_int
     L.razer_quantize.argtypes = [ctypes.POINTER(_Config), vp, i32, i64, i64, i64, vp, vp, vp, u32,
                                  vp, sz, vp]
@@ -161,29 +167,31 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-def _cfg(fmt, sv, block=16):
+def _cfg(fmt, sv, block=16, layout=LAYOUT_CANONICAL):
     c = _Config()
     c.format = fmt
     c.sv[0] = float(sv[0])
     c.sv[1] = float(sv[1]) if len(sv) > 1 else 0.0
     c.block = int(block)
+    c.layout = int(layout)
     return c
 
 
 class RazerTensor:
     """A quantized tensor: device buffers + shape + configuration (razer_tensor in the ABI)."""
 
-    def __init__(self, codes, scales, tensor_scale, rows, cols, fmt, sv, block=16):
+    def __init__(self, codes, scales, tensor_scale, rows, cols, fmt, sv, block=16, layout=LAYOUT_CANONICAL):
         self.codes, self.scales, self.tensor_scale = codes, scales, tensor_scale
         self.rows, self.cols, self.fmt, self.sv, self.block = int(rows), int(cols), fmt, tuple(sv), int(block)
+        self.layout = int(layout)                      # LAYOUT_INTERLEAVED: codes is the packed buffer, scales None
 
     def c_struct(self):
         t = _Tensor()
         t.codes = self.codes.data_ptr()
-        t.scales = self.scales.data_ptr()
+        t.scales = None if self.scales is None else self.scales.data_ptr()
         t.tensor_scale = self.tensor_scale.data_ptr()
         t.rows, t.cols = self.rows, self.cols
-        t.cfg = _cfg(self.fmt, self.sv, self.block)
+        t.cfg = _cfg(self.fmt, self.sv, self.block, self.layout)
         return t
 
     @staticmethod
@@ -239,6 +247,19 @@ def razer_quantize(x, fmt=WEIGHT, sv=(5.0, 8.0), tensor_scale=None, out=None, wo
     if st != 0:
         raise RazerError(st, "razer_quantize")
     return RazerTensor(codes, scales, ts, rows, cols, fmt, sv, block)
+
+
+def razer_prepack(t):
+    """The weight tensor t (canonical layout, scale bytes, 16-element blocks) in the library's private
+    interleaved layout: a RazerTensor whose `codes` is the packed buffer (it shares t's tensor scale)."""
+    L = load_library()
+    cs = t.c_struct()
+    nbytes = int(L.razer_prepack_bytes(ctypes.byref(cs)))
+    packed = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=t.codes.device)
+    st = L.razer_prepack(ctypes.byref(cs), _ptr(packed), nbytes, _stream())
+    if st != 0:
+        raise RazerError(st, "razer_prepack")
+    return RazerTensor(packed, None, t.tensor_scale, t.rows, t.cols, t.fmt, t.sv, t.block, LAYOUT_INTERLEAVED)
 
 
 def razer_dequant(t, dtype=torch.float32, out=None):

@@ -55,6 +55,12 @@ razer_status check_cfg(const razer_config& c, SvConfig& out)
     out.sv0 = c.sv[0];
     out.sv1 = (c.format != RAZER_FMT_ACT) ? c.sv[1] : c.sv[0];
     out.f16 = 0;
+    out.il = 0;
+    if (c.layout != RAZER_LAYOUT_CANONICAL && c.layout != RAZER_LAYOUT_INTERLEAVED) return RAZER_ERR_CONFIG;
+    if (c.layout == RAZER_LAYOUT_INTERLEAVED) {                 // scale-byte weights with 16-element blocks only
+        if (c.format != RAZER_FMT_WEIGHT || (c.block != 0 && c.block != 16)) return RAZER_ERR_CONFIG;
+        out.il = 1;
+    }
     if (c.format == RAZER_FMT_WEIGHT_F16) {                     // blocks of 128 only, 16-bit scale words
         if (c.block != 0 && c.block != 128) return RAZER_ERR_CONFIG;
         out.lb = 7;
@@ -85,10 +91,37 @@ razer_status check_tensor(const razer_tensor* t, int want_fmt, SvConfig& cfg)
     if (want_fmt >= 0 && fmt_class != want_fmt) return RAZER_ERR_CONFIG;
     if (!t->tensor_scale) return RAZER_ERR_NULL;
     if (t->rows > 0 && t->cols > 0) {
-        if (!t->codes || !t->scales) return RAZER_ERR_NULL;
-        if (!aligned16(t->codes) || !aligned16(t->scales)) return RAZER_ERR_ALIGN;
+        if (!t->codes || (!cfg.il && !t->scales)) return RAZER_ERR_NULL;      // interleaved: one buffer
+        if (!aligned16(t->codes) || (!cfg.il && !aligned16(t->scales))) return RAZER_ERR_ALIGN;
     }
     return RAZER_OK;
+}
+
+// one thread per 16 bytes of the packed buffer: code chunks and scale chunks of the interleaved runs
+__global__ __launch_bounds__(256) void prepack_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+                                                      int64_t rows, int64_t cols, uint8_t* __restrict__ packed)
+{
+    const int64_t row_bytes = il_row_bytes(cols), units_per_row = row_bytes / 16;
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= rows * units_per_row) return;
+    const int64_t r = u / units_per_row;
+    const uint32_t off = (uint32_t)(u - r * units_per_row) * 16u, run = off / kIlRun, in = off - run * kIlRun;
+    uint4 v = make_uint4(0, 0, 0, 0);                                         // padding of a short last run
+    if (in < 1024u) {
+        const int64_t cb = (int64_t)run * 1024 + in;                          // byte of the row's codes
+        if (cb < cols / 2) v = *reinterpret_cast<const uint4*>(codes + r * (cols / 2) + cb);
+    } else {
+        const int64_t sb = (int64_t)run * 128 + (in - 1024u);                 // byte of the row's scales
+        if (sb < cols / 16) {
+            // (cols % 32 == 0 only guarantees pairs of scale bytes: copy byte-wise at the row's end)
+            const uint8_t* src = scales + r * (cols / 16) + sb;
+            uint8_t b[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) b[i] = (sb + i < cols / 16) ? src[i] : (uint8_t)0;
+            v = *reinterpret_cast<const uint4*>(b);
+        }
+    }
+    *reinterpret_cast<uint4*>(packed + r * row_bytes + off) = v;
 }
 
 __global__ void fill_zero_bf16_kernel(uint16_t* y, int64_t m, int64_t n, int64_t ld)
@@ -182,6 +215,7 @@ razer_status razer_dequant(const razer_tensor* t, void* out, int32_t dtype, int6
     razer_status s = check_tensor(t, -1, sv);
     if (s != RAZER_OK) return s;
     if (dtype != RAZER_F32 && dtype != RAZER_BF16) return RAZER_ERR_CONFIG;
+    if (sv.il) return RAZER_ERR_CONFIG;                                  // the decoder takes the canonical layout
     if (ld < t->cols) return RAZER_ERR_SHAPE;
     const size_t esz = (dtype == RAZER_F32) ? 4 : 2;
     if (t->rows > 0 && t->cols > 0) {
@@ -203,6 +237,8 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
     if (m == 0 && !a_q) return RAZER_OK;                                  // nothing to compute, operands may be NULL
     if ((a_bf16 == nullptr) == (a_q == nullptr)) return RAZER_ERR_NULL;   // exactly one activation operand
     const int64_t n = w->rows, k = w->cols;
+    // the interleaved layout serves the decode regime only: bf16 activations, m <= 4, rows of at most 32768
+    if (wsv.il && (a_q || m > kGemvDirectMaxM || k > 32768)) return RAZER_ERR_CONFIG;
     if (a_q) {
         s = check_tensor(a_q, RAZER_FMT_ACT, asv);
         if (s != RAZER_OK) return s;
@@ -243,6 +279,29 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
     return e == hipSuccess ? RAZER_OK : RAZER_ERR_HIP;
 }
 
+size_t razer_prepack_bytes(const razer_tensor* t)
+{
+    if (!t || t->rows < 0 || t->cols < 0) return 0;
+    return (size_t)(t->rows * il_row_bytes(t->cols));
+}
+
+razer_status razer_prepack(const razer_tensor* t, void* packed, size_t packed_bytes, void* hip_stream)
+{
+    SvConfig sv;
+    razer_status s = check_tensor(t, RAZER_FMT_WEIGHT, sv);
+    if (s != RAZER_OK) return s;
+    if (sv.il || sv.f16 || sv.lb != 4) return RAZER_ERR_CONFIG;          // a canonical scale-byte tensor, blocks of 16
+    const size_t need = razer_prepack_bytes(t);
+    if (need == 0) return RAZER_OK;
+    if (!packed) return RAZER_ERR_NULL;
+    if (!aligned16(packed)) return RAZER_ERR_ALIGN;
+    if (packed_bytes < need) return RAZER_ERR_WORKSPACE;
+    const int64_t units = (int64_t)(need / 16);
+    launch(prepack_kernel, (unsigned)((units + 255) / 256), 256, 0, (hipStream_t)hip_stream, t->codes, t->scales, t->rows,
+           t->cols, (uint8_t*)packed);
+    return hipGetLastError() == hipSuccess ? RAZER_OK : RAZER_ERR_HIP;
+}
+
 razer_status razer_linear_static(const razer_tensor* w, const void* a_bf16, const razer_tensor* a_q, int64_t m,
                                  void* y_bf16, int64_t ld_y, void* hip_stream)
 {
@@ -273,6 +332,8 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
         if (m > 0 && w[i]->rows > 0 && !y_bf16[i]) return RAZER_ERR_NULL;
         if (i == 0) sv0 = sv;
         else if (sv.sv0 != sv0.sv0 || sv.sv1 != sv0.sv1 || sv.lb != sv0.lb || sv.f16 != sv0.f16) one_launch = false;
+        if (sv.il != sv0.il && i > 0) return RAZER_ERR_CONFIG;           // one layout per group
+        if (sv.il && (m > kGemvDirectMaxM || w[i]->cols > 32768)) return RAZER_ERR_CONFIG;
         if (w[i]->rows == 0) one_launch = false;
     }
     if (m == 0) return RAZER_OK;

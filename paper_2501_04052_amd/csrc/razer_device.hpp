@@ -26,7 +26,16 @@ struct SvConfig {          // special-value magnitudes and log2(block size), alr
     float sv0, sv1;
     int lb = 4;
     int f16 = 0;           // 1: one 16-bit scale word per block of 128 (sign | selector | 14 low bits of an IEEE half)
+    int il = 0;            // 1: interleaved layout (below); 16-element blocks, scale-byte format only
 };
+
+// Interleaved layout of a weight row: runs of 2048 elements, each stored as 1024 bytes of codes followed
+// by its 128 scale bytes (1152 bytes per run, also for a shorter last run).  Byte offsets inside a row of
+// the code byte / scale byte of element k, and the bytes of a row of `cols` elements.
+constexpr uint32_t kIlRun = 1152;
+__host__ __device__ __forceinline__ uint32_t il_code_off(uint32_t k) { return (k >> 11) * kIlRun + ((k & 2047u) >> 1); }
+__host__ __device__ __forceinline__ uint32_t il_scale_off(uint32_t k) { return (k >> 11) * kIlRun + 1024u + ((k & 2047u) >> 4); }
+__host__ __device__ __forceinline__ int64_t il_row_bytes(int64_t cols) { return ((cols + 2047) >> 11) * (int64_t)kIlRun; }
 
 // The two scale bytes (low byte first) that govern the 32 consecutive elements starting at element
 // k0 (a multiple of 32) of a row whose scale bytes start at srow.  GB = false: blocks of 16, one

@@ -222,7 +222,9 @@ __device__ __forceinline__ void gemv_body(const uint8_t* __restrict__ codes, con
 // are always in flight while one is decoded.  Wave w owns K-slice w of every row; its 32
 // activations per lane stay in registers for the whole walk.  Slice totals of all G * R rows meet
 // in LDS after ONE barrier.  Row addresses are uniform (scalar) and lane offsets 32-bit.
-template <int M, int R, int G, int D, int P = 1, bool GB = false, int SF = 0>
+// IL: the interleaved layout (razer_device.hpp): `codes` is the packed buffer, a wave's 2048-element run is
+// 1152 contiguous bytes -- its 1 KiB of codes, then its 128 scale bytes.
+template <int M, int R, int G, int D, int P = 1, bool GB = false, int SF = 0, bool IL = false>
 __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ codes,
                                                  const uint8_t* __restrict__ scales,
                                                  const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
@@ -250,7 +252,8 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     // cleared: scale code 0 decodes to 0.0, so whatever they accumulate is multiplied by zero.
     const uint32_t cc = active ? c : 0u;
     const uint32_t smask = active ? 0xFFFFFFFFu : 0u;
-    const int64_t code_ld = k >> 1;
+    const int64_t code_ld = IL ? il_row_bytes(k) : (k >> 1);
+    static_assert(!IL || (!GB && SF == 0), "interleaved layout: 16-element blocks, scale bytes");
 
     uint4 av[M][4];
 #pragma unroll
@@ -266,8 +269,14 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
             int64_t row = wrow0 + gi * R + r;
             row = row < n ? row : n - 1;                                  // tail rows re-read the last row
             const uint8_t* crow = codes + row * code_ld;
-            g.cw[r] = *reinterpret_cast<const uint4*>(crow + cc * 16u);
-            g.sw[r] = load_scale_bits<GB, SF>(scales, row, k, (int64_t)cc * 32, lb) & smask;
+            if (IL) {
+                const uint8_t* run = crow + (cc >> 6) * kIlRun;           // this wave's run (idle lanes: run 0)
+                g.cw[r] = *reinterpret_cast<const uint4*>(run + (cc & 63u) * 16u);
+                g.sw[r] = *reinterpret_cast<const uint16_t*>(run + 1024u + (cc & 63u) * 2u) & smask;
+            } else {
+                g.cw[r] = *reinterpret_cast<const uint4*>(crow + cc * 16u);
+                g.sw[r] = load_scale_bits<GB, SF>(scales, row, k, (int64_t)cc * 32, lb) & smask;
+            }
         }
     };
 #pragma unroll
@@ -318,7 +327,7 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     }
 }
 
-template <int M, int R, int G, int D, int P = 1, bool GB = false, int SF = 0>
+template <int M, int R, int G, int D, int P = 1, bool GB = false, int SF = 0, bool IL = false>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_kernel(const uint8_t* __restrict__ codes,
                                                                      const uint8_t* __restrict__ scales,
                                                                      const float* __restrict__ w_ts, float sv0,
@@ -326,8 +335,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_kernel(const uint8
                                                                      const uint16_t* __restrict__ a,
                                                                      uint16_t* __restrict__ y, int64_t ld_y, int lb)
 {
-    gemv_stream_body<M, R, G, D, P, GB, SF>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y,
-                                            (int64_t)blockIdx.x * (P * R * G), lb);
+    gemv_stream_body<M, R, G, D, P, GB, SF, IL>(codes, scales, w_ts, sv0, sv1, n, k, a, y, ld_y,
+                                                (int64_t)blockIdx.x * (P * R * G), lb);
 }
 
 template <int M, int R, bool GB = false, int SF = 0>
@@ -366,7 +375,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_grouped_kernel(
     gemv_body<M, R, GB, SF>(codes, scales, ts, sv0, sv1, n, k, a, y, ld, (int64_t)(b - first) * R, lb);
 }
 
-template <int M, int R, int G, int D, int P = 1, bool GB = false, int SF = 0>
+template <int M, int R, int G, int D, int P = 1, bool GB = false, int SF = 0, bool IL = false>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
@@ -384,8 +393,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
     if (b >= g1) { codes = c1; scales = s1; ts = t1; y = y1; n = n1; ld = l1; first = g1; }
     if (b >= g2) { codes = c2; scales = s2; ts = t2; y = y2; n = n2; ld = l2; first = g2; }
     if (b >= g3) { codes = c3; scales = s3; ts = t3; y = y3; n = n3; ld = l3; first = g3; }
-    gemv_stream_body<M, R, G, D, P, GB, SF>(codes, scales, ts, sv0, sv1, n, k, a, y, ld,
-                                            (int64_t)(b - first) * (P * R * G), lb);
+    gemv_stream_body<M, R, G, D, P, GB, SF, IL>(codes, scales, ts, sv0, sv1, n, k, a, y, ld,
+                                                (int64_t)(b - first) * (P * R * G), lb);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -403,7 +412,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
 // of 512 elements), walks G groups of four rows with the next group's loads in flight, partial sums
 // of the waves meet in LDS.  Idle lanes (K tail) are silenced through their scale bits; activation
 // rows past M are never masked, their product columns are simply not stored.
-template <int C, int G, int D, int P, int MS, int PS = 1>
+template <int C, int G, int D, int P, int MS, int PS = 1, bool IL = false>
 __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                                const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
                                                int64_t k, const uint16_t* __restrict__ a, int64_t m,
@@ -419,7 +428,7 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
     const uint32_t wave = wid % nwaves, par = wid / nwaves;
     const uint32_t b = lane >> 2, q = lane & 3u;
     const int64_t wrow0 = row0 + (int64_t)par * (R * G);
-    const int64_t code_ld = k >> 1, scale_ld = k >> 4;
+    const int64_t code_ld = IL ? il_row_bytes(k) : (k >> 1), scale_ld = IL ? il_row_bytes(k) : (k >> 4);
 
     struct Quad {
         uint4 cw[C];
@@ -457,11 +466,11 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
             int64_t row = wrow0 + gi * R + q;
             row = row < n ? row : n - 1;                                  // tail rows re-read the last row
             const uint8_t* crow = codes + row * code_ld;
-            const uint8_t* srow = scales + row * scale_ld;
+            const uint8_t* srow = (IL ? codes : scales) + row * scale_ld;
 #pragma unroll
             for (int c = 0; c < C; ++c) {
-                g.cw[c] = *reinterpret_cast<const uint4*>(crow + (koff[c] >> 1));
-                g.sw[c] = *reinterpret_cast<const uint16_t*>(srow + (koff[c] >> 4)) & smask[c];
+                g.cw[c] = *reinterpret_cast<const uint4*>(crow + (IL ? il_code_off(koff[c]) : (koff[c] >> 1)));
+                g.sw[c] = *reinterpret_cast<const uint16_t*>(srow + (IL ? il_scale_off(koff[c]) : (koff[c] >> 4))) & smask[c];
             }
         };
         load(buf[0], 0);
@@ -540,18 +549,18 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
     }
 }
 
-template <int C, int G, int D, int P, int MS, int PS = 1>
+template <int C, int G, int D, int P, int MS, int PS = 1, bool IL = false>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_kernel(const uint8_t* __restrict__ codes,
                                                                    const uint8_t* __restrict__ scales,
                                                                    const float* __restrict__ w_ts, float sv0, float sv1,
                                                                    int64_t n, int64_t k, const uint16_t* __restrict__ a,
                                                                    int64_t m, uint16_t* __restrict__ y, int64_t ld_y)
 {
-    gemv_quad_body<C, G, D, P, MS, PS>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y,
-                                       (int64_t)blockIdx.x * (P * 4 * G));
+    gemv_quad_body<C, G, D, P, MS, PS, IL>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y,
+                                           (int64_t)blockIdx.x * (P * 4 * G));
 }
 
-template <int C, int G, int D, int P, int MS, int PS = 1>
+template <int C, int G, int D, int P, int MS, int PS = 1, bool IL = false>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
@@ -569,7 +578,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_grouped_kernel(
     if (b >= g1) { codes = c1; scales = s1; ts = t1; y = y1; n = n1; ld = l1; first = g1; }
     if (b >= g2) { codes = c2; scales = s2; ts = t2; y = y2; n = n2; ld = l2; first = g2; }
     if (b >= g3) { codes = c3; scales = s3; ts = t3; y = y3; n = n3; ld = l3; first = g3; }
-    gemv_quad_body<C, G, D, P, MS, PS>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, (int64_t)(b - first) * (P * 4 * G));
+    gemv_quad_body<C, G, D, P, MS, PS, IL>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, (int64_t)(b - first) * (P * 4 * G));
 }
 
 // The matrix-instruction kernel serves 3 and 4 activation rows (at 1-2 the dot-product kernel is as
@@ -599,7 +608,11 @@ static hipError_t launch_gemv_quad(SvConfig cfg, const uint8_t* codes, const uin
     const int groups = passes == 2 ? 4 : quad_groups(n, k, m);   // two passes keep G running sums: 8 groups would spill
     const int nwaves = (int)((k + 512 * runs * passes - 1) / (512 * runs * passes));
     const unsigned grid = (unsigned)((n + 4 * groups - 1) / (4 * groups));
-#define RAZER_QUAD(C, G, PS) launch(gemv_quad_kernel<C, G, 2, 1, 1, PS>, grid, 64 * nwaves, 0, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y)
+#define RAZER_QUAD(C, G, PS)                                                                                                          \
+    do {                                                                                                                              \
+        if (cfg.il) launch(gemv_quad_kernel<C, G, 2, 1, 1, PS, true>, grid, 64 * nwaves, 0, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y); \
+        else launch(gemv_quad_kernel<C, G, 2, 1, 1, PS>, grid, 64 * nwaves, 0, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y);              \
+    } while (0)
     if (passes == 2)    { RAZER_QUAD(2, 4, 2); }
     else if (runs == 1) { if (groups == 8) RAZER_QUAD(1, 8, 1); else RAZER_QUAD(1, 4, 1); }
     else                { if (groups == 8) RAZER_QUAD(2, 8, 1); else RAZER_QUAD(2, 4, 1); }
@@ -622,14 +635,20 @@ static hipError_t launch_gemv_quad_grouped(SvConfig cfg, int count, const GemvPr
         q[i] = p[i < count ? i : count - 1];
         g[i + 1] = g[i] + (i < count ? (unsigned)((q[i].n + rows_per_wg - 1) / rows_per_wg) : 0u);
     }
-#define RAZER_QUADG(C, G, PS) launch(gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS>, g[4], 64 * nwaves, 0, st, \
-        q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts, \
+#define RAZER_QUADG_ARGS                                                                                             \
+    q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts,     \
         q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,        \
-        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m)
+        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m
+#define RAZER_QUADG(C, G, PS)                                                                                                   \
+    do {                                                                                                                        \
+        if (cfg.il) launch(gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS, true>, g[4], 64 * nwaves, 0, st, RAZER_QUADG_ARGS);      \
+        else launch(gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS>, g[4], 64 * nwaves, 0, st, RAZER_QUADG_ARGS);                   \
+    } while (0)
     if (passes == 2)    { RAZER_QUADG(2, 4, 2); }
     else if (runs == 1) { if (groups == 8) RAZER_QUADG(1, 8, 1); else RAZER_QUADG(1, 4, 1); }
     else                { if (groups == 8) RAZER_QUADG(2, 8, 1); else RAZER_QUADG(2, 4, 1); }
 #undef RAZER_QUADG
+#undef RAZER_QUADG_ARGS
     return hipGetLastError();
 }
 
@@ -678,8 +697,10 @@ static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_
                                 int64_t n, int64_t k, const uint16_t* a, uint16_t* y, int64_t ld_y, hipStream_t st)
 {
     const int64_t nslices = (k + kSliceK - 1) / kSliceK;
-    if (nslices > kMaxWaves)                                              // K > 32768: several passes per wave
+    if (nslices > kMaxWaves) {                                            // K > 32768: several passes per wave
+        if (cfg.il) return hipErrorInvalidValue;                          // (the host admits K <= 32768 only)
         return launch_gemv_mr<M, 4>(cfg, codes, scales, ts, n, k, a, y, ld_y, st);
+    }
     constexpr int R = kStreamR;
     const int nwaves = (int)nslices;
     int groups, sets;
@@ -693,7 +714,13 @@ static hipError_t launch_gemv_m(SvConfig cfg, const uint8_t* codes, const uint8_
         else if (sets == 2) launch(gemv_stream_kernel<M, R, 2, 2, 2, GB, SF>, grid, 128 * nwaves, 0, st, RAZER_GEMV_ARGS); \
         else launch(gemv_stream_kernel<M, R, 2, 2, 1, GB, SF>, grid, 64 * nwaves, 0, st, RAZER_GEMV_ARGS);              \
     } while (0)
-    if (cfg.f16) RAZER_GEMV_SHAPES(true, 1);
+    if (cfg.il) {
+        if (groups == 8) launch(gemv_stream_kernel<M, R, 8, 2, 1, false, 0, true>, grid, 64 * nwaves, 0, st, RAZER_GEMV_ARGS);
+        else if (groups == 4) launch(gemv_stream_kernel<M, R, 4, 2, 1, false, 0, true>, grid, 64 * nwaves, 0, st, RAZER_GEMV_ARGS);
+        else if (sets == 2) launch(gemv_stream_kernel<M, R, 2, 2, 2, false, 0, true>, grid, 128 * nwaves, 0, st, RAZER_GEMV_ARGS);
+        else launch(gemv_stream_kernel<M, R, 2, 2, 1, false, 0, true>, grid, 64 * nwaves, 0, st, RAZER_GEMV_ARGS);
+    }
+    else if (cfg.f16) RAZER_GEMV_SHAPES(true, 1);
     else if (cfg.lb != 4) RAZER_GEMV_SHAPES(true, 0);
     else RAZER_GEMV_SHAPES(false, 0);
 #undef RAZER_GEMV_SHAPES
@@ -738,7 +765,14 @@ static hipError_t launch_gemv_grouped_m(SvConfig cfg, int count, const GemvProbl
         else                                                                                                              \
             launch(gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 1, GB, SF>, g[4], 64 * nwaves, 0, st, RAZER_GROUPED_ARGS);   \
     } while (0)
-    if (cfg.f16) RAZER_GROUPED_SHAPES(true, 1);
+    if (cfg.il) {
+        if (!stream) return hipErrorInvalidValue;                          // (the host admits K <= 32768 only)
+        if (groups == 8) launch(gemv_stream_grouped_kernel<M, kStreamR, 8, 2, 1, false, 0, true>, g[4], 64 * nwaves, 0, st, RAZER_GROUPED_ARGS);
+        else if (groups == 4) launch(gemv_stream_grouped_kernel<M, kStreamR, 4, 2, 1, false, 0, true>, g[4], 64 * nwaves, 0, st, RAZER_GROUPED_ARGS);
+        else if (sets == 2) launch(gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 2, false, 0, true>, g[4], 128 * nwaves, 0, st, RAZER_GROUPED_ARGS);
+        else launch(gemv_stream_grouped_kernel<M, kStreamR, 2, 2, 1, false, 0, true>, g[4], 64 * nwaves, 0, st, RAZER_GROUPED_ARGS);
+    }
+    else if (cfg.f16) RAZER_GROUPED_SHAPES(true, 1);
     else if (cfg.lb != 4) RAZER_GROUPED_SHAPES(true, 0);
     else RAZER_GROUPED_SHAPES(false, 0);
 #undef RAZER_GROUPED_SHAPES
