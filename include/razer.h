@@ -64,8 +64,9 @@ typedef enum {
      * bit 15 = special-value sign, bit 14 = selector, bits 13..0 = the low 14 bits of an IEEE half
      * (exponent below 16: values up to 2 - 2^-10; the tensor scale of Eq. 1 uses that maximum).
      * block must be 0 or 128; cols a multiple of 128.  A weight format: accepted wherever
-     * RAZER_FMT_WEIGHT is, except that razer_linear takes bf16 activations only and runs every m
-     * through the kernels built for m <= 4 (passes of 4 activation rows, no workspace). */
+     * RAZER_FMT_WEIGHT is, except that razer_linear takes bf16 activations only (no workspace at any m:
+     * wavefront dot products up to 4 activation rows, from 5 rows up a matrix-core kernel that folds each
+     * block's partial sums with the block's scale in fp32). */
     RAZER_FMT_WEIGHT_F16 = 2
 } razer_format;
 

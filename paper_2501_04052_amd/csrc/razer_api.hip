@@ -255,11 +255,15 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
         launch(fill_zero_bf16_kernel, (unsigned)((total + 255) / 256), 256, 0, st, (uint16_t*)y_bf16, m, n, ld_y);
         e = hipGetLastError();
     } else if (wsv.f16) {
-        // FP16-scale format: built for the decode regime; more activation rows go through the same
-        // kernels in passes of 4
+        // FP16-scale format: the GEMV kernels up to 4 activation rows, from 5 rows up the matrix-core kernel
+        // that folds each block's partial sums with its scale (no workspace either way)
         if (a_q) return RAZER_ERR_CONFIG;
-        e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
-                        (uint16_t*)y_bf16, ld_y, st);
+        if (m <= kGemvDirectMaxM)
+            e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
+                            (uint16_t*)y_bf16, ld_y, st);
+        else
+            e = launch_gemm(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, asv, nullptr,
+                            nullptr, nullptr, m, (uint16_t*)y_bf16, ld_y, nullptr, st);
     } else if (!a_q && m > kGemvDirectMaxM && m <= kSkinnyMaxM && k <= kSkinnyMaxK) {
         const size_t need = skinny_workspace_bytes(n, k, m);
         if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return RAZER_ERR_WORKSPACE;

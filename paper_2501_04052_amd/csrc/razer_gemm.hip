@@ -81,6 +81,21 @@ __device__ __forceinline__ uint4 decode_dword(uint32_t x, uint2 lut_entry)
                       cvt_scaled_pair<2>(xf, s, lut_entry.y), cvt_scaled_pair<3>(xf, s, lut_entry.y));
 }
 
+// 8 codes -> 8 bare, negated FP4 values as bf16 (exact), remapped codes patched with `patch` (the negated
+// special value as a bf16 pair): the decode of the FP16-scale format, whose scale multiplies partial sums.
+template <int BYTE>
+__device__ __forceinline__ uint32_t cvt_bare_pair(uint32_t xflip, uint32_t patch)
+{
+    v2bf p = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(xflip, 1.0f, BYTE);
+    return patch_zero_halves(__builtin_bit_cast(uint32_t, p), patch);
+}
+__device__ __forceinline__ uint4 decode_dword_bare(uint32_t x, uint32_t patch)
+{
+    const uint32_t xf = x ^ kRemapXor;
+    return make_uint4(cvt_bare_pair<0>(xf, patch), cvt_bare_pair<1>(xf, patch), cvt_bare_pair<2>(xf, patch),
+                      cvt_bare_pair<3>(xf, patch));
+}
+
 // gfx950 LDS: 64 banks x 4 B; a 128-bit access is served 16 lanes per clock, so 16 consecutive rows
 // (256-byte period = 2 rows) must land on 16 distinct 16-byte slots: swizzle with bits 1..3 of the row.
 __device__ __forceinline__ uint32_t lds_off(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
@@ -166,7 +181,11 @@ __device__ __forceinline__ void store_tile_partial(const v16f (&acc)[TN][TM], in
         }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AQ, bool GB>
+// SF: the FP16-scale weight format (blocks of 128, one scale word; bf16 activations only).  A half scale
+// times an FP4 value does not fit a bf16 operand, so the weights go to LDS as bare FP4 values and the
+// matrix instructions accumulate one block (two K-tiles) into a second set of accumulators, which the
+// block's scale -- per weight row, fp32 in LDS next to the tile -- then folds into the running sums.
+template <int BM, int BN, int WGM, int WGN, bool AQ, bool GB, bool SF = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     SvConfig wcfg, int64_t n, int64_t k, const uint16_t* __restrict__ a, const uint8_t* __restrict__ a_codes,
@@ -185,6 +204,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
     uint8_t* Bs = smem + 2 * BM * 128;               // 2 stages x BN x 128 B
     uint2* wlut = reinterpret_cast<uint2*>(smem + 2 * (BM + BN) * 128);
     uint2* alut = wlut + 256;
+    float* wsc = reinterpret_cast<float*>(wlut);      // SF: 2 stages x BN block scales in place of the tables
+    static_assert(!SF || (!AQ && !GB && 2 * BN * 4 <= 2 * 256 * 8), "FP16-scale variant");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WGM, wn = wave / WGM;
@@ -195,7 +216,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
     const int kt0 = (int)blockIdx.y * kt_per;
     const int KT = kt_all - kt0 < kt_per ? kt_all - kt0 : kt_per;
 
-    fill_scaled_lut<0>(wlut, wcfg.sv0, wcfg.sv1, tid, NT);
+    if (!SF) fill_scaled_lut<0>(wlut, wcfg.sv0, wcfg.sv1, tid, NT);
     if (AQ) fill_scaled_lut<1>(alut, acfg.sv0, acfg.sv1, tid, NT);
 
     v16f acc[TN][TM];
@@ -242,7 +263,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
             rsb[i] = 0;
             if (u < BN * 2 && gr < n && kk < k) {
                 rb[i] = *reinterpret_cast<const uint4*>(w_codes + gr * (k / 2) + kk / 2);
-                rsb[i] = load_scale_pair<GB>(w_scales + gr * (k >> wcfg.lb), kk, wcfg.lb);
+                if (SF) rsb[i] = reinterpret_cast<const uint16_t*>(w_scales)[gr * (k >> 7) + (kk >> 7)];
+                else rsb[i] = load_scale_pair<GB>(w_scales + gr * (k >> wcfg.lb), kk, wcfg.lb);
             }
         }
     };
@@ -274,11 +296,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
             const int u = tid + i * NT, row = u >> 1, half = u & 1;
             if (u < BN * 2) {
                 const uint32_t x = (q == 0) ? rb[i].x : (q == 1) ? rb[i].y : (q == 2) ? rb[i].z : rb[i].w;
-                const uint2 le = wlut[(rsb[i] >> (8 * (q >> 1))) & 255u];
-                *reinterpret_cast<uint4*>(bs + lds_off(row, half * 4 + q)) = decode_dword(x, le);
+                if (SF) {
+                    float sc, sv;
+                    decode_scale_word(rsb[i], wcfg.sv0, wcfg.sv1, sc, sv);          // (rows past N: word 0, scale 0)
+                    const uint32_t nsv = (uint32_t)f32_to_bf16_rne(-sv);
+                    *reinterpret_cast<uint4*>(bs + lds_off(row, half * 4 + q)) = decode_dword_bare(x, nsv | (nsv << 16));
+                    if (q == 0 && half == 0) wsc[st * BN + row] = sc;               // the block's scale, for the fold
+                } else {
+                    const uint2 le = wlut[(rsb[i] >> (8 * (q >> 1))) & 255u];
+                    *reinterpret_cast<uint4*>(bs + lds_off(row, half * 4 + q)) = decode_dword(x, le);
+                }
             }
         }
     };
+    // SF: sums of the current block of 128 elements (two K-tiles), folded into acc with the block scales
+    v16f blk[SF ? TN : 1][SF ? TM : 1];
 
     load_tiles(0);
     __syncthreads();                                   // LUTs ready
@@ -292,6 +324,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
         if (more) load_tiles(kt + 1);
         const uint8_t* as = As + st * BM * 128;
         const uint8_t* bs = Bs + st * BN * 128;
+        // SF: a block starts with every even K-tile of the matrix (K is a multiple of 128 and K-slices hold
+        // whole blocks): its first matrix instruction starts from zero instead of from the previous block
+        const bool block_start = SF && ((kt0 + kt) & 1) == 0;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             v8bf fw[TN], fa[TM];
@@ -305,9 +340,38 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
-                for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TM; ++j) {
+                    if (SF) {
+                        if (ks == 0 && block_start) {
+                            v16f zero;
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+                            blk[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], zero, 0, 0, 0);
+                        } else {
+                            blk[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], blk[i][j], 0, 0, 0);
+                        }
+                    } else {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+                    }
+                }
             if (more) store_part(st ^ 1, ks);
+        }
+        if (SF && (((kt0 + kt) & 1) == 1 || !more)) {
+            // fold the finished block: register v of a 32x32 accumulator belongs to weight row
+            // 8 (v / 4) + 4 (lane / 32) + v % 4 of the fragment (the layout store_tile documents)
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+                float sc[16];
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const float4 t = *reinterpret_cast<const float4*>(wsc + st * BN + wn * WTN + i * 32 + 8 * g4 + 4 * (lane >> 5));
+                    sc[4 * g4] = t.x; sc[4 * g4 + 1] = t.y; sc[4 * g4 + 2] = t.z; sc[4 * g4 + 3] = t.w;
+                }
+#pragma unroll
+                for (int j = 0; j < TM; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] = __builtin_fmaf(sc[v], blk[i][j][v], acc[i][j][v]);
+            }
         }
         __syncthreads();
     }
@@ -1001,7 +1065,7 @@ static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, con
     return launch_slice_reduce(workspace, w_ts, nullptr, m, n, slices, y, ld_y, st);
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AQ, bool PP = false, bool GB = false>
+template <int BM, int BN, int WGM, int WGN, bool AQ, bool PP = false, bool GB = false, bool SF = false>
 static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                              int64_t n, int64_t k, const uint16_t* a, const uint8_t* a_codes,
                              const uint8_t* a_scales, const float* a_ts, SvConfig acfg, int64_t m, uint16_t* y,
@@ -1010,8 +1074,9 @@ static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, co
     constexpr size_t smem = 2 * (BM + BN) * 128 + 2 * 256 * sizeof(uint2);
     void (*kern)(const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, int64_t, const uint16_t*,
                  const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, uint16_t*, int64_t, int, float*);
+    static_assert(!(PP && SF), "the FP16-scale format runs on the single-group kernel");
     if constexpr (PP) kern = gemm_pp_kernel<BM, BN, WGM, WGN, AQ, GB>;
-    else kern = gemm_kernel<BM, BN, WGM, WGN, AQ, GB>;
+    else kern = gemm_kernel<BM, BN, WGM, WGN, AQ, GB, SF>;
     RAZER_RAISE_LDS_LIMIT(kern, smem);
     const int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
     // every K-slice must hold at least one K-tile: slices = ceil(KT / ceil(KT / split))
@@ -1233,12 +1298,31 @@ hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, in
                        : launch_gemm_grouped_t<true>(cfg, count, p, k, a, m, workspace, st);
 }
 
+// The FP16-scale weight format from 5 activation rows up (bf16 activations): the single-group kernel with
+// bare FP4 operands and per-block folds; 32-, 64- or 128-row activation tiles, K never split.
+static hipError_t launch_gemm_f16(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
+                                  int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
+                                  hipStream_t st)
+{
+    const SvConfig none{5.0f, 5.0f};
+#define RAZER_GEMM_F16(BM, BN, WGM, WGN) \
+    launch_cfg<BM, BN, WGM, WGN, false, false, false, true>(w_codes, w_scales, w_ts, wcfg, n, k, a, nullptr, nullptr, nullptr, none, m, y, ld_y, 1, nullptr, st)
+    if (m <= 32) return RAZER_GEMM_F16(32, 256, 1, 4);
+    if (m <= 64) return RAZER_GEMM_F16(64, 256, 1, 4);
+    return RAZER_GEMM_F16(128, 128, 2, 2);
+#undef RAZER_GEMM_F16
+}
+
 hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
                        int64_t n, int64_t k, const uint16_t* a, SvConfig acfg, const uint8_t* a_codes,
                        const uint8_t* a_scales, const float* a_ts, int64_t m, uint16_t* y, int64_t ld_y,
                        float* workspace, hipStream_t st)
 {
     if (n == 0 || m == 0) return hipSuccess;
+    if (wcfg.f16) {
+        if (a_codes || !a) return hipErrorInvalidValue;
+        return launch_gemm_f16(wcfg, w_codes, w_scales, w_ts, n, k, a, m, y, ld_y, st);
+    }
     // blocks of 32, 64, 128 (either operand) take the variants whose scale-byte loads index by block
     const bool generic = wcfg.lb != 4 || (a_codes && acfg.lb != 4);
 #define RAZER_GEMM_ARGS w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, workspace, st

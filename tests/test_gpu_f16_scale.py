@@ -90,20 +90,51 @@ def test_linear_matches_oracle(oracle, m, n, k):
     assert torch.all(buf[:, n:] == 2.0)
 
 
+@pytest.mark.parametrize("m,n,k", [(5, 40, 128), (16, 300, 1024 + 128), (33, 257, 2048), (64, 100, 4096), (100, 640, 1152),
+                                   (300, 200, 2048 + 384), (129, 8, 128 * 9)])
+def test_linear_matrix_core_path_matches_oracle(oracle, m, n, k):
+    """From 5 activation rows up the format runs on the matrix cores with bare FP4 operands and a per-block
+    fold in fp32: 32-, 64- and 128-row tiles, ragged M and N, odd and even numbers of blocks, every scale word
+    field (zero, subnormal and saturated scales included)."""
+    print("f16-scale matrix-core linear", m, n, k, flush=True)
+    rng = np.random.default_rng(3700 + m + n)
+    wq = _rand_tensor(rng, n, k)
+    wq[1][0, 0] = 0x0000
+    wq[1][-1, -1] = 0xFFFF
+    wt = razer.RazerTensor.from_host(*wq, F16, (5.0, 8.0))
+    a = synth.activation(m, k, seed=3701 + m + k, outlier_frac=0.01)
+    buf = torch.full((m, n + 8), 2.0, dtype=torch.bfloat16, device="cuda")
+    razer.razer_linear(wt, bf16_bits_to_dev(a), out=buf[:, :n])
+    torch.cuda.synchronize()
+    y64, _ = oracle.linear(wq, a_bf16=a)
+    assert max_rel_err(dev_to_bf16_bits(buf[:, :n]), y64) <= TOL
+    assert torch.all(buf[:, n:] == 2.0)
+
+
 def test_linear_on_encoded_weights_full_layer_shape(oracle):
-    """The Llama-7B q projection, encoded on the GPU in this format, M = 1 and 4, whole output."""
+    """The Llama-7B q projection, encoded on the GPU in this format: M = 1, 4, 16 whole output, M = 512 and
+    2048 on sampled outputs."""
     w = synth.weight(4096, 4096, seed=3400, outlier_frac=0.001)
     t = razer.razer_quantize(torch.from_numpy(w).cuda(), F16, (5.0, 8.0))
     torch.cuda.synchronize()
     wq = tensor_to_host(t)
     rq = oracle.quantize(F16, w)
     assert np.array_equal(wq[0], rq[0]) and np.array_equal(wq[1], rq[1]) and wq[2] == rq[2]
-    for m in (1, 4):
+    for m in (1, 4, 16):
         a = synth.activation(m, 4096, seed=3401 + m)
         y = razer.razer_linear(t, bf16_bits_to_dev(a))
         torch.cuda.synchronize()
         y64, _ = oracle.linear(rq, a_bf16=a)
         assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
+    for m in (512, 2048):                                                # prefill-shaped: sampled rows x columns
+        a = synth.activation(m, 4096, seed=3401 + m)
+        y = razer.razer_linear(t, bf16_bits_to_dev(a))
+        torch.cuda.synchronize()
+        rows = synth.sample_indices(m, 64, 9000)
+        cols = synth.sample_indices(4096, 256, 9001)
+        y64, _ = oracle.linear(rq, a_bf16=a, rows=rows, cols=cols)
+        got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+        assert max_rel_err(got, y64) <= TOL
 
 
 @pytest.mark.parametrize("m,k,ns", [(1, 4096, (40, 9, 64)), (1, 11008, (70, 35)), (4, 8192, (24, 24, 24, 5)), (2, 34816, (10, 7))])
