@@ -322,7 +322,16 @@ def main():
         fl_box[0] = razer.razer_probe_mfma_bf16(4000, 512, sink)
     mfma_ms = time_region(mfma_fn, 10, 2)
     legs["ceiling_mfma_bf16_loop"] = {"TFLOP/s": fl_box[0] / mfma_ms / 1e9, "ms": mfma_ms,
-                                      "note": "register-resident v_mfma_f32_32x32x16_bf16 loop, 2 wavefronts per SIMD, no memory traffic"}
+                                      "note": "register-resident v_mfma_f32_32x32x16_bf16 loop, 2 wavefronts per SIMD, no memory "
+                                              "traffic, operands with well-mixed bits (the sustained clock depends on them)"}
+
+    def fp4_fn(i):
+        fl_box[0] = razer.razer_probe_mfma_fp4(2000, 512, sink)
+    fp4_ms = time_region(fp4_fn, 10, 2)
+    legs["ceiling_mfma_fp4_scaled_loop"] = {
+        "TFLOP/s": fl_box[0] / fp4_ms / 1e9, "ms": fp4_ms,
+        "note": "register-resident v_mfma_scale_f32_32x32x64_f8f6f4 loop, FP4 x FP4 with E8M0 scales: context for the two-pass "
+                "FP4 realisation of W4A4 (App. D.3), which this GPU's power-of-two scales per 32 elements cannot carry exactly"}
 
     gemm_roof = None
 
@@ -486,6 +495,23 @@ def main():
                 "GB/s": b / ms / 1e6, "ms_per_step": ms, "bits_per_weight": 4 + 8.0 * sbytes / block,
                 "note": "same layer shapes with %d-element blocks%s, random packed bytes, 4 launches"
                         % (block, " and one FP16 scale word per block (the format of the paper's own kernel)" if f16 else "")}
+            if f16:
+                # the same format beyond the decode regime: matrix-core kernel with per-block folds
+                for mm in (16, 64, 2048):
+                    actm = {k: make_act(mm, k, 2100 + mm) for k in {k for _, _, k in layers}}
+                    outm = [torch.empty((mm, n), dtype=torch.bfloat16, device="cuda") for _, n, _ in layers]
+                    plansm = [[razer.prepare_linear(t, actm[t.cols], outm[j]) for j, t in enumerate(cp)] for cp in sets]
+
+                    def stepm(i):
+                        for call in plansm[i % n_copies]:
+                            call(stream)
+                    msm = time_region(stepm, 5, 2)
+                    flm = sum(2.0 * mm * n * k for _, n, k in layers)
+                    legs["linear_m%d_block128_fp16_scale" % mm] = {
+                        "TFLOP/s": flm / msm / 1e9, "ms_per_step": msm,
+                        "note": "7 razer_linear calls; up to 32 rows passes of the GEMV kernels, beyond that bare FP4 operands on the "
+                                "matrix cores, each 128-element block's partial sums folded with its FP16 scale in fp32"}
+                    del plansm, actm, outm
             del sets, plans
             torch.cuda.empty_cache()
 

@@ -65,8 +65,8 @@ typedef enum {
      * (exponent below 16: values up to 2 - 2^-10; the tensor scale of Eq. 1 uses that maximum).
      * block must be 0 or 128; cols a multiple of 128.  A weight format: accepted wherever
      * RAZER_FMT_WEIGHT is, except that razer_linear takes bf16 activations only (no workspace at any m:
-     * wavefront dot products up to 4 activation rows, from 5 rows up a matrix-core kernel that folds each
-     * block's partial sums with the block's scale in fp32). */
+     * wavefront dot products up to 32 activation rows, in passes of 4 rows; beyond that a matrix-core kernel
+     * that folds each block's partial sums with the block's scale in fp32). */
     RAZER_FMT_WEIGHT_F16 = 2
 } razer_format;
 

@@ -36,6 +36,11 @@ int razer_probe_stream_read(const void *buf, size_t bytes, int workgroups, void 
  * floating-point operations of the launch, 2 * 32 * 32 * 16 per instruction. */
 int razer_probe_mfma_bf16(int iters, int workgroups, void *sink, void *hip_stream, double *flops);
 
+/* The same loop on the block-scaled FP4 x FP4 matrix instruction (v_mfma_scale_f32_32x32x64_f8f6f4, E8M0
+ * scales of 2^0): the rate a two-pass FP4 realisation of the weight-activation mode (App. D.3) could at
+ * most run at on this GPU.  2 * 32 * 32 * 64 flops per instruction. */
+int razer_probe_mfma_fp4(int iters, int workgroups, void *sink, void *hip_stream, double *flops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ LAYOUT_CANONICAL, LAYOUT_INTERLEAVED = 0, 1
 EXPORTS = ["razer_workspace_bytes", "razer_workspace_bytes_grouped", "razer_prepack_bytes", "razer_prepack", "razer_quantize", "razer_dequant", "razer_linear",
            "razer_linear_grouped", "razer_linear_static", "razer_status_string"]
 # measurement utilities (include/razer_probe.h)
-PROBE_EXPORTS = ["razer_probe_dispatch_events", "razer_probe_stream_read", "razer_probe_mfma_bf16"]
+PROBE_EXPORTS = ["razer_probe_dispatch_events", "razer_probe_stream_read", "razer_probe_mfma_bf16", "razer_probe_mfma_fp4"]
 # launch-shape tuning hooks (include/razer_tune.h)
 TUNE_EXPORTS = ["razer_tune_force", "razer_tune_lookup", "razer_tune_table_size"]
 TUNE_GEMV, TUNE_GEMV_QUAD, TUNE_SMALL_BATCH, TUNE_GEMM_SLICES = 0, 1, 2, 3
@@ -88,6 +88,8 @@ def load_library():
     L.razer_probe_stream_read.argtypes = [vp, sz, ctypes.c_int, vp, vp]
     L.razer_probe_mfma_bf16.restype = ctypes.c_int
     L.razer_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    L.razer_probe_mfma_fp4.restype = ctypes.c_int
+    L.razer_probe_mfma_fp4.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, ctypes.POINTER(ctypes.c_double)]
     L.razer_tune_force.restype = ctypes.c_int
     L.razer_tune_force.argtypes = [ctypes.c_int, ctypes.POINTER(i32)]
     L.razer_tune_lookup.restype = ctypes.c_int
@@ -156,6 +158,15 @@ def razer_probe_mfma_bf16(iters, workgroups, sink):
     st = load_library().razer_probe_mfma_bf16(int(iters), int(workgroups), _ptr(sink), _stream(), ctypes.byref(fl))
     if st != 0:
         raise RazerError(st, "razer_probe_mfma_bf16")
+    return fl.value
+
+
+def razer_probe_mfma_fp4(iters, workgroups, sink):
+    """Returns the floating-point operations of the launch."""
+    fl = ctypes.c_double()
+    st = load_library().razer_probe_mfma_fp4(int(iters), int(workgroups), _ptr(sink), _stream(), ctypes.byref(fl))
+    if st != 0:
+        raise RazerError(st, "razer_probe_mfma_fp4")
     return fl.value
 
 

@@ -255,10 +255,11 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
         launch(fill_zero_bf16_kernel, (unsigned)((total + 255) / 256), 256, 0, st, (uint16_t*)y_bf16, m, n, ld_y);
         e = hipGetLastError();
     } else if (wsv.f16) {
-        // FP16-scale format: the GEMV kernels up to 4 activation rows, from 5 rows up the matrix-core kernel
-        // that folds each block's partial sums with its scale (no workspace either way)
+        // FP16-scale format: the GEMV kernels up to 32 activation rows (in passes of 4 from 5 rows up: measured
+        // faster than the few tiles a matrix-core launch has there), beyond that the matrix-core kernel that
+        // folds each block's partial sums with its scale (no workspace either way)
         if (a_q) return RAZER_ERR_CONFIG;
-        if (m <= kGemvDirectMaxM)
+        if (m <= kSkinnyMaxM)
             e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
                             (uint16_t*)y_bf16, ld_y, st);
         else

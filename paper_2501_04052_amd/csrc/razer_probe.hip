@@ -70,6 +70,39 @@ __global__ __launch_bounds__(256, 2) void mfma_loop_kernel(int iters, float* __r
     if (t == -1.0f) sink[0] = t;                       // never true: keeps the loop alive
 }
 
+// The same loop on the block-scaled FP4 matrix instruction (v_mfma_scale_f32_32x32x64_f8f6f4, both operands
+// FP4-E2M1, one E8M0 scale per 32 elements and operand, here 2^0): 2 * 32 * 32 * 64 flops per instruction.
+// It is what a two-pass FP4 x FP4 realisation of the weight-activation mode would run on.
+typedef int v8i32 __attribute__((ext_vector_type(8)));
+__global__ __launch_bounds__(256, 2) void mfma_fp4_loop_kernel(int iters, float* __restrict__ sink)
+{
+    v8i32 a, b;
+    uint32_t h = (threadIdx.x + 1u) * 2654435761u + blockIdx.x * 40503u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {                      // (only the low four dwords hold FP4 data)
+        h = h * 1664525u + 1013904223u;
+        a[i] = (int)h;
+        h = h * 1664525u + 1013904223u;
+        b[i] = (int)h;
+    }
+    v16f acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[j], 4, 4, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+    }
+    float t = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) t += acc[j][v];
+    if (t == -1.0f) sink[0] = t;                       // never true: keeps the loop alive
+}
+
 }  // namespace razer
 
 using namespace razer;
@@ -98,6 +131,15 @@ int razer_probe_mfma_bf16(int iters, int workgroups, void* sink, void* hip_strea
     if (iters < 1 || workgroups < 1 || workgroups > (1 << 20)) return 2;
     launch(mfma_loop_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink);
     if (flops) *flops = 2.0 * 32 * 32 * 16 * 8.0 * iters * 4.0 * workgroups;   // 4 wavefronts per workgroup
+    return hipGetLastError() == hipSuccess ? 0 : 6;
+}
+
+int razer_probe_mfma_fp4(int iters, int workgroups, void* sink, void* hip_stream, double* flops)
+{
+    if (!sink) return 1;
+    if (iters < 1 || workgroups < 1 || workgroups > (1 << 20)) return 2;
+    launch(mfma_fp4_loop_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, (float*)sink);
+    if (flops) *flops = 2.0 * 32 * 32 * 64 * 8.0 * iters * 4.0 * workgroups;
     return hipGetLastError() == hipSuccess ? 0 : 6;
 }
 

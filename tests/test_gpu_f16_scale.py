@@ -93,9 +93,9 @@ def test_linear_matches_oracle(oracle, m, n, k):
 @pytest.mark.parametrize("m,n,k", [(5, 40, 128), (16, 300, 1024 + 128), (33, 257, 2048), (64, 100, 4096), (100, 640, 1152),
                                    (300, 200, 2048 + 384), (129, 8, 128 * 9)])
 def test_linear_matrix_core_path_matches_oracle(oracle, m, n, k):
-    """From 5 activation rows up the format runs on the matrix cores with bare FP4 operands and a per-block
-    fold in fp32: 32-, 64- and 128-row tiles, ragged M and N, odd and even numbers of blocks, every scale word
-    field (zero, subnormal and saturated scales included)."""
+    """Beyond 32 activation rows the format runs on the matrix cores with bare FP4 operands and a per-block
+    fold in fp32 (64- and 128-row tiles; up to 32 rows: passes of the GEMV kernels): ragged M and N, odd and
+    even numbers of blocks, every scale word field (zero, subnormal and saturated scales included)."""
     print("f16-scale matrix-core linear", m, n, k, flush=True)
     rng = np.random.default_rng(3700 + m + n)
     wq = _rand_tensor(rng, n, k)
