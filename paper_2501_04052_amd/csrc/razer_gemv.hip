@@ -235,16 +235,14 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     __shared__ uint2 lut[256];
     __shared__ float part[P * G * R * M][kMaxWaves / P];
     const float ts = *w_ts;
-    // P sets of waves work side by side on P consecutive blocks of G * R rows (fewer, larger workgroups)
-    // The wave index is uniform over the wavefront: telling the compiler so moves the row arithmetic
-    // (clamps, 64-bit row offsets; ~90 of ~540 vector instructions) to the scalar unit.  Measured 3-7 %
-    // faster on the long launches of a 70B-shaped layer (one wave set) and 5 % slower on the shortest
-    // 7B launch (two wave sets, 4 us: the scalar chain delays the first loads) and 2-3 % slower with 8
-    // groups per workgroup, hence only for P = 1, G = 2.
+    // P sets of waves work side by side on P consecutive blocks of G * R rows (fewer, larger workgroups).
+    // With one set and two groups the wave index is read as a scalar as well (measured 3-7 % faster on the
+    // long launches of a 70B-shaped layer, slower with two sets or eight groups).
+    static_assert(P == 1 || P == 2, "one or two sets of waves");
     const uint32_t lane = threadIdx.x & 63u, nwaves = (blockDim.x >> 6) / P;
     const uint32_t wid = (P == 1 && G == 2) ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) : (threadIdx.x >> 6);
-    const uint32_t wave = wid % nwaves, par = wid / nwaves;
-    const int64_t wrow0 = row0 + (int64_t)par * (R * G);
+    const uint32_t par = (P == 2 && wid >= nwaves) ? 1u : 0u;             // (no division: a reciprocal sits ahead of the first load)
+    const uint32_t wave = wid - par * nwaves;
     const uint32_t chunks = (uint32_t)(k >> 5);                           // 16-byte code chunks per row
     const uint32_t c = wave * 64u + lane;
     const bool active = c < chunks;
@@ -252,8 +250,19 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     // cleared: scale code 0 decodes to 0.0, so whatever they accumulate is multiplied by zero.
     const uint32_t cc = active ? c : 0u;
     const uint32_t smask = active ? 0xFFFFFFFFu : 0u;
-    const int64_t code_ld = IL ? il_row_bytes(k) : (k >> 1);
     static_assert(!IL || (!GB && SF == 0), "interleaved layout: 16-element blocks, scale bytes");
+    // Addresses: the workgroup's first row gives a uniform 64-bit base (scalar unit); a row of the workgroup
+    // and the lane's place in it are a 32-bit offset from there (at most 15 rows of at most 18 KiB).  Rows
+    // past N (last workgroup of a matrix) re-read the last row.
+    const uint32_t code_ld = (uint32_t)(IL ? il_row_bytes(k) : (k >> 1));
+    const uint32_t scale_ld = IL ? code_ld : (SF == 1) ? (uint32_t)(k >> 7) * 2u : GB ? (uint32_t)(k >> lb) : (uint32_t)(k >> 4);
+    const uint32_t last_row = (uint32_t)((n - 1 - row0 < P * R * G - 1) ? n - 1 - row0 : P * R * G - 1);
+    const uint8_t* cbase = codes + row0 * (int64_t)code_ld;
+    const uint8_t* sbase = (IL ? codes : scales) + row0 * (int64_t)scale_ld;
+    // the lane's byte offsets inside a row: its 16 bytes of codes, its scale bits
+    const uint32_t c_lane = IL ? (cc >> 6) * kIlRun + (cc & 63u) * 16u : cc * 16u;
+    const uint32_t s_lane = IL ? (cc >> 6) * kIlRun + 1024u + (cc & 63u) * 2u
+                               : (SF == 1) ? ((cc * 32u) >> 7) * 2u : GB ? ((cc * 32u) >> lb) : cc * 2u;
 
     uint4 av[M][4];
 #pragma unroll
@@ -266,17 +275,15 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     auto load = [&](RowGroup<R>& g, int gi) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            int64_t row = wrow0 + gi * R + r;
-            row = row < n ? row : n - 1;                                  // tail rows re-read the last row
-            const uint8_t* crow = codes + row * code_ld;
-            if (IL) {
-                const uint8_t* run = crow + (cc >> 6) * kIlRun;           // this wave's run (idle lanes: run 0)
-                g.cw[r] = *reinterpret_cast<const uint4*>(run + (cc & 63u) * 16u);
-                g.sw[r] = *reinterpret_cast<const uint16_t*>(run + 1024u + (cc & 63u) * 2u) & smask;
-            } else {
-                g.cw[r] = *reinterpret_cast<const uint4*>(crow + cc * 16u);
-                g.sw[r] = load_scale_bits<GB, SF>(scales, row, k, (int64_t)cc * 32, lb) & smask;
-            }
+            const uint32_t rel = par * (R * G) + gi * R + r;
+            const uint32_t row = rel < last_row ? rel : last_row;
+            // (24-bit multiply-add: one 32-bit instruction.  The generic 32-bit form compiles to a 64-bit
+            // multiply-add whose unused high input half the register allocator overlaps with a load in
+            // flight, and the wave then waits for that load before it requests its weights.)
+            g.cw[r] = *reinterpret_cast<const uint4*>(cbase + (__umul24(row, code_ld) + c_lane));
+            const uint8_t* sp = sbase + (__umul24(row, scale_ld) + s_lane);
+            if (GB && SF == 0) g.sw[r] = *sp & smask;                     // blocks of 32 and more: one scale byte
+            else g.sw[r] = *reinterpret_cast<const uint16_t*>(sp) & smask;
         }
     };
 #pragma unroll
@@ -423,12 +430,18 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
     __shared__ uint2 lut[256];
     __shared__ float part[P * G * R * 4 * MS][kMaxWaves / P];
     const float ts = *w_ts;
+    static_assert(P == 1 || P == 2, "one or two sets of waves");
     const uint32_t lane = threadIdx.x & 63u, nwaves = (blockDim.x >> 6) / P;
     const uint32_t wid = threadIdx.x >> 6;
-    const uint32_t wave = wid % nwaves, par = wid / nwaves;
+    const uint32_t par = (P == 2 && wid >= nwaves) ? 1u : 0u;             // (no division ahead of the first load)
+    const uint32_t wave = wid - par * nwaves;
     const uint32_t b = lane >> 2, q = lane & 3u;
-    const int64_t wrow0 = row0 + (int64_t)par * (R * G);
-    const int64_t code_ld = IL ? il_row_bytes(k) : (k >> 1), scale_ld = IL ? il_row_bytes(k) : (k >> 4);
+    // uniform 64-bit bases (first row of the workgroup) + 32-bit offsets of the lane's row, as in the
+    // streaming kernel; rows past N re-read the last row
+    const uint32_t code_ld = (uint32_t)(IL ? il_row_bytes(k) : (k >> 1)), scale_ld = IL ? code_ld : (uint32_t)(k >> 4);
+    const uint32_t last_row = (uint32_t)((n - 1 - row0 < P * R * G - 1) ? n - 1 - row0 : P * R * G - 1);
+    const uint8_t* cbase = codes + row0 * (int64_t)code_ld;
+    const uint8_t* sbase = (IL ? codes : scales) + row0 * (int64_t)scale_ld;
 
     struct Quad {
         uint4 cw[C];
@@ -463,14 +476,13 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
         }
         Quad buf[D];
         auto load = [&](Quad& g, int gi) {
-            int64_t row = wrow0 + gi * R + q;
-            row = row < n ? row : n - 1;                                  // tail rows re-read the last row
-            const uint8_t* crow = codes + row * code_ld;
-            const uint8_t* srow = (IL ? codes : scales) + row * scale_ld;
+            const uint32_t rel = par * (R * G) + gi * R + q;
+            const uint32_t row = rel < last_row ? rel : last_row;
+            const uint32_t crow = __umul24(row, code_ld), srow = __umul24(row, scale_ld);
 #pragma unroll
             for (int c = 0; c < C; ++c) {
-                g.cw[c] = *reinterpret_cast<const uint4*>(crow + (IL ? il_code_off(koff[c]) : (koff[c] >> 1)));
-                g.sw[c] = *reinterpret_cast<const uint16_t*>(srow + (IL ? il_scale_off(koff[c]) : (koff[c] >> 4))) & smask[c];
+                g.cw[c] = *reinterpret_cast<const uint4*>(cbase + (crow + (IL ? il_code_off(koff[c]) : (koff[c] >> 1))));
+                g.sw[c] = *reinterpret_cast<const uint16_t*>(sbase + (srow + (IL ? il_scale_off(koff[c]) : (koff[c] >> 4)))) & smask[c];
             }
         };
         load(buf[0], 0);
