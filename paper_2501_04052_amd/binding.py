@@ -13,7 +13,7 @@ _LIB_PATH = os.path.join(_PKG, "librazer_hip.so")
 
 WEIGHT, ACT, WEIGHT_F16 = 0, 1, 2
 F32, BF16 = 0, 1
-OP_QUANTIZE, OP_DEQUANT, OP_LINEAR = 0, 1, 2
+OP_QUANTIZE, OP_DEQUANT, OP_LINEAR, OP_LINEAR_W4A4 = 0, 1, 2, 3
 GIVEN_TENSOR_SCALE = 1
 
 LAYOUT_CANONICAL, LAYOUT_INTERLEAVED = 0, 1
@@ -307,7 +307,7 @@ def razer_linear(w, a, out=None, workspace=None):
     ws = w.c_struct()
     ld_y = out.stride(0) if m > 1 else max(out.stride(0), w.rows)
     if workspace is None:
-        need = razer_workspace_bytes(OP_LINEAR, w.rows, w.cols, m)
+        need = razer_workspace_bytes(OP_LINEAR_W4A4 if aq_ptr is not None else OP_LINEAR, w.rows, w.cols, m)
         if need:
             workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     st = L.razer_linear(ctypes.byref(ws), a_ptr, aq_ptr, m, _ptr(out), ld_y, _ptr(workspace),

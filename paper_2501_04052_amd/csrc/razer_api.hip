@@ -156,6 +156,11 @@ size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m)
             const size_t a = skinny_workspace_bytes(rows, cols, m), b = gemm_workspace_bytes(rows, cols, m);
             return a > b ? a : b;
         }
+        case RAZER_OP_LINEAR_W4A4: {           // room for the activations decoded to bf16, where that path is taken
+            const size_t base = razer_workspace_bytes(RAZER_OP_LINEAR, rows, cols, m);
+            const size_t staged = gemm_w4a4_staged(rows, cols, m) ? (size_t)m * (size_t)cols * 2u : 0u;
+            return staged > base ? staged : base;
+        }
         default: return 0;
     }
 }
@@ -257,14 +262,17 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
     } else if (wsv.f16) {
         // FP16-scale format: the GEMV kernels up to 32 activation rows (in passes of 4 from 5 rows up: measured
         // faster than the few tiles a matrix-core launch has there), beyond that the matrix-core kernel that
-        // folds each block's partial sums with its scale (no workspace either way)
+        // folds each block's partial sums with its scale
         if (a_q) return RAZER_ERR_CONFIG;
         if (m <= kSkinnyMaxM)
             e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
                             (uint16_t*)y_bf16, ld_y, st);
-        else
+        else {
+            const size_t need = gemm_workspace_bytes(n, k, m);       // K-slices while the tiles are few
+            if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return RAZER_ERR_WORKSPACE;
             e = launch_gemm(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, asv, nullptr,
-                            nullptr, nullptr, m, (uint16_t*)y_bf16, ld_y, nullptr, st);
+                            nullptr, nullptr, m, (uint16_t*)y_bf16, ld_y, need > 0 ? (float*)workspace : nullptr, st);
+        }
     } else if (!a_q && m > kGemvDirectMaxM && m <= kSkinnyMaxM && k <= kSkinnyMaxK) {
         const size_t need = skinny_workspace_bytes(n, k, m);
         if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return RAZER_ERR_WORKSPACE;
@@ -273,6 +281,14 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
     } else if (!a_q && m <= kGemvDirectMaxM) {
         e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
                         (uint16_t*)y_bf16, ld_y, st);
+    } else if (a_q && gemm_w4a4_staged(n, k, m) && workspace && aligned16(workspace) &&
+               workspace_bytes >= (size_t)m * (size_t)k * 2u) {
+        // W4A4 with room for the decoded activations: block scale x element of the whole activation tensor as
+        // bf16 (exact), then the W4A16 register-decode kernel with both tensor scales in its epilogue
+        e = launch_dequant(RAZER_FMT_ACT, asv, a_q->codes, a_q->scales, nullptr, m, k, workspace, 1, k, st);
+        if (e == hipSuccess)
+            e = launch_gemm(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)workspace, asv, nullptr,
+                            nullptr, a_q->tensor_scale, m, (uint16_t*)y_bf16, ld_y, nullptr, st);
     } else {
         const size_t need = gemm_workspace_bytes(n, k, m);
         if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return RAZER_ERR_WORKSPACE;

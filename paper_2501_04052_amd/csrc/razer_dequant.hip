@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict_
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= rows * nb) return;
     const int64_t r = gid / nb, b = gid - r * nb;
-    const float ts = *tensor_scale;
+    const float ts = tensor_scale ? *tensor_scale : 1.0f;
     const uint2 cw = *reinterpret_cast<const uint2*>(codes + r * (cols / 2) + b * 8);
     float s, sv;
     if (FMT == 2)                                               // one 16-bit scale word per 128 elements

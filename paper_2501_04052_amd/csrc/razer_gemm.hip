@@ -111,7 +111,10 @@ __device__ __forceinline__ void store_tile(const v16f (&acc)[TN][TM], const floa
                                            int64_t wm0, int64_t wn0, int64_t m, int64_t n, uint16_t* y,
                                            int64_t ld_y, int lane)
 {
-    const float scale = AQ ? (*w_ts) * (*a_ts) : -(*w_ts);
+    // W4A4 with both operands decoded in the flipped domain: the two negations cancel; bf16 activations
+    // (true sign) against flipped weights: negate -- with the activations' tensor scale when they are a
+    // decoded RaZeR tensor (a_ts given)
+    const float scale = AQ ? (*w_ts) * (*a_ts) : (a_ts ? -((*w_ts) * (*a_ts)) : -(*w_ts));
     const int hi = lane >> 5;
 #pragma unroll
     for (int i = 0; i < TN; ++i)
@@ -212,7 +215,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
     const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     // blockIdx.y = K-slice (split-K for problems with few output tiles): K-tiles [kt0, kt0 + KT)
-    const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + (int)gridDim.y - 1) / (int)gridDim.y;
+    // (SF: slices of whole 128-element blocks, i.e. an even number of K-tiles)
+    const int kt_all = (int)((k + kBK - 1) / kBK);
+    const int kt_even = (kt_all + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int kt_per = SF ? ((kt_even + 1) & ~1) : kt_even;
     const int kt0 = (int)blockIdx.y * kt_per;
     const int KT = kt_all - kt0 < kt_per ? kt_all - kt0 : kt_per;
 
@@ -645,7 +651,7 @@ __device__ __forceinline__ void gemm_rb_body(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
     uint16_t* __restrict__ y, int64_t ld_y, int tile_m, int tile_n, float* __restrict__ partial = nullptr,
-    int kslice = 0, int kt_per_slice = 0x7FFFFFFF, int lb = 4)
+    int kslice = 0, int kt_per_slice = 0x7FFFFFFF, int lb = 4, const float* __restrict__ a_ts = nullptr)
 {
     // MT: 32-row activation groups per tile (8, or 4 / 2 for at most 128 / 64 activation rows)
     static_assert(MT == 8 || ((MT == 4 || MT == 2) && KG == 1), "activation tile height");
@@ -951,7 +957,7 @@ __device__ __forceinline__ void gemm_rb_body(
         if (partial)                                    // K-slices of one output meet in the workspace [slice][m][n]
             store_tile_partial<MT, 1>(acc, m0, n0 + 32 * wave, m, n, partial + (int64_t)kslice * m * n, lane);
         else
-            store_tile<MT, 1, false>(acc, w_ts, nullptr, m0, n0 + 32 * wave, m, n, y, ld_y, lane);
+            store_tile<MT, 1, false>(acc, w_ts, a_ts, m0, n0 + 32 * wave, m, n, y, ld_y, lane);
     } else {
         // The two K groups hold partial sums of the same 256 x 32 outputs.  Once every wave's copies have
         // landed and its fragment reads have returned (the wait above, then this barrier) the activation
@@ -991,7 +997,7 @@ __device__ __forceinline__ void gemm_rb_body(
                 keep[0][j][4 * q + 2] += t.z;
                 keep[0][j][4 * q + 3] += t.w;
             }
-        store_tile<MT / 2, 1, false>(keep, w_ts, nullptr, m0 + 128 * kg, n0 + 32 * wn, m, n, y, ld_y, lane);
+        store_tile<MT / 2, 1, false>(keep, w_ts, a_ts, m0 + 128 * kg, n0 + 32 * wn, m, n, y, ld_y, lane);
     }
 }
 
@@ -1006,11 +1012,12 @@ template <int NW, int S, int KG = 1, int MT = 8, bool GB = false>
 __global__ __launch_bounds__(64 * NW, (rb_waves_per_simd<NW, KG, MT>())) void gemm_rb_kernel(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
-    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m, float* __restrict__ partial, int kt_per_slice, int lb)
+    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m, float* __restrict__ partial, int kt_per_slice, int lb,
+    const float* __restrict__ a_ts)
 {
     gemm_rb_body<NW, S, KG, MT, GB>(w_codes, w_scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y,
                                     (int)(blockIdx.x % tiles_m), (int)(blockIdx.x / tiles_m), partial,
-                                    (int)blockIdx.y, kt_per_slice, lb);
+                                    (int)blockIdx.y, kt_per_slice, lb, a_ts);
 }
 
 // Up to four weight matrices against the same activations in one launch (fused q/k/v, gate/up): the
@@ -1047,7 +1054,7 @@ __global__ __launch_bounds__(64 * NW, (rb_waves_per_simd<NW, KG, MT>())) void ge
 template <int NW, int S, int KG = 1, int MT = 8, bool GB = false>
 static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                             int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
-                            hipStream_t st, int split = 1, float* workspace = nullptr)
+                            hipStream_t st, int split = 1, float* workspace = nullptr, const float* a_ts = nullptr)
 {
     constexpr int BM = 32 * MT, BN = 32 * NW / KG;
     constexpr size_t smem = S * (KG * BM * 128 + NW * 1280) + 256 * sizeof(uint2);
@@ -1059,9 +1066,10 @@ static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, con
     const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + split - 1) / split;
     const int slices = (kt_all + kt_per - 1) / kt_per;
     launch(kern, dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(64 * NW), smem, st, w_codes, w_scales, w_ts, wcfg.sv0, wcfg.sv1, n, k, a, m, y, ld_y, tiles_m, slices > 1 ? workspace : nullptr,
-        slices > 1 ? kt_per : 0x7FFFFFFF, wcfg.lb);
+        slices > 1 ? kt_per : 0x7FFFFFFF, wcfg.lb, a_ts);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || slices == 1) return e;
+    if (a_ts) return hipErrorInvalidValue;                               // (decoded RaZeR activations run unsplit)
     return launch_slice_reduce(workspace, w_ts, nullptr, m, n, slices, y, ld_y, st);
 }
 
@@ -1080,7 +1088,9 @@ static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, co
     RAZER_RAISE_LDS_LIMIT(kern, smem);
     const int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
     // every K-slice must hold at least one K-tile: slices = ceil(KT / ceil(KT / split))
-    const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + split - 1) / split;
+    // (SF: an even number of K-tiles per slice; the kernel rounds its own share of the grid's slices the same way)
+    const int kt_all = (int)((k + kBK - 1) / kBK), kt_raw = (kt_all + split - 1) / split;
+    const int kt_per = SF ? ((kt_raw + 1) & ~1) : kt_raw;
     const int slices = (kt_all + kt_per - 1) / kt_per;
     launch(kern, dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(64 * WGM * WGN), smem, st, w_codes, w_scales, w_ts, wcfg, n, k, a, a_codes, a_scales, a_ts, acfg, m, y, ld_y, tiles_m,
         slices > 1 ? workspace : nullptr);
@@ -1168,6 +1178,16 @@ size_t gemm_workspace_bytes(int64_t n, int64_t k, int64_t m)
     return need;
 }
 
+// W4A4 as two launches -- the activation tensor decoded once into bf16 (m x k, in the caller's workspace), then
+// the register-decode kernel with the activations' tensor scale in its epilogue -- pays where that kernel runs
+// unsplit on many tiles: the fused W4A4 kernel decodes every activation once per 256 weight rows.
+bool gemm_w4a4_staged(int64_t n, int64_t k, int64_t m)
+{
+    if (m <= 128 || k > kRbMaxK) return false;
+    const GemmPlan p = gemm_plan(m, n, k, true);
+    return p.split == 1 && (p.tile == 5 || p.tile == 6 || p.tile == 7);
+}
+
 template <bool AQ, bool GB>
 static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                                 int64_t n, int64_t k, const uint16_t* a, const uint8_t* a_codes,
@@ -1192,9 +1212,9 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
     if constexpr (!AQ) {
         if (p.tile == 8) return launch_rb<4, 2, 1, 2, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, p.split, workspace);
         if (p.tile == 9) return launch_rb<4, 2, 1, 4, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, p.split, workspace);
-        if (p.tile == 5) return launch_rb<8, 2, 1, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
-        if (p.tile == 7) return launch_rb<8, 2, 2, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
-        return launch_rb<4, 2, 1, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+        if (p.tile == 5) return launch_rb<8, 2, 1, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, 1, nullptr, a_ts);
+        if (p.tile == 7) return launch_rb<8, 2, 2, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, 1, nullptr, a_ts);
+        return launch_rb<4, 2, 1, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, 1, nullptr, a_ts);
     }
     return hipErrorInvalidValue;
 }
@@ -1299,14 +1319,26 @@ hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, in
 }
 
 // The FP16-scale weight format from 5 activation rows up (bf16 activations): the single-group kernel with
-// bare FP4 operands and per-block folds; 32-, 64- or 128-row activation tiles, K never split.
+// bare FP4 operands and per-block folds; 32-, 64- or 128-row activation tiles.  With a workspace, K is cut
+// into slices of whole blocks while the tiles are fewer than the compute units (the rule of gemm_plan, whose
+// tiles are never smaller than these, so gemm_workspace_bytes covers it).
+static int f16_split(int64_t m, int64_t n, int64_t k)
+{
+    const int64_t tiles = m <= 64 ? (n + 255) / 256 : ((m + 127) / 128) * ((n + 127) / 128);
+    const int64_t kt_all = (k + kBK - 1) / kBK;
+    int64_t split = 256 / tiles;
+    if (split > 8) split = 8;
+    if (split > kt_all / 8) split = kt_all / 8;
+    return split >= 2 ? (int)split : 1;
+}
 static hipError_t launch_gemm_f16(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
                                   int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
-                                  hipStream_t st)
+                                  float* workspace, hipStream_t st)
 {
     const SvConfig none{5.0f, 5.0f};
+    const int split = workspace ? f16_split(m, n, k) : 1;
 #define RAZER_GEMM_F16(BM, BN, WGM, WGN) \
-    launch_cfg<BM, BN, WGM, WGN, false, false, false, true>(w_codes, w_scales, w_ts, wcfg, n, k, a, nullptr, nullptr, nullptr, none, m, y, ld_y, 1, nullptr, st)
+    launch_cfg<BM, BN, WGM, WGN, false, false, false, true>(w_codes, w_scales, w_ts, wcfg, n, k, a, nullptr, nullptr, nullptr, none, m, y, ld_y, split, workspace, st)
     if (m <= 32) return RAZER_GEMM_F16(32, 256, 1, 4);
     if (m <= 64) return RAZER_GEMM_F16(64, 256, 1, 4);
     return RAZER_GEMM_F16(128, 128, 2, 2);
@@ -1321,7 +1353,7 @@ hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_s
     if (n == 0 || m == 0) return hipSuccess;
     if (wcfg.f16) {
         if (a_codes || !a) return hipErrorInvalidValue;
-        return launch_gemm_f16(wcfg, w_codes, w_scales, w_ts, n, k, a, m, y, ld_y, st);
+        return launch_gemm_f16(wcfg, w_codes, w_scales, w_ts, n, k, a, m, y, ld_y, workspace, st);
     }
     // blocks of 32, 64, 128 (either operand) take the variants whose scale-byte loads index by block
     const bool generic = wcfg.lb != 4 || (a_codes && acfg.lb != 4);

@@ -81,6 +81,12 @@ def test_workspace_sizes(razer):
     assert razer.razer_workspace_bytes(2, 4096, 4096, 2048) == 0
     assert razer.razer_workspace_bytes(2, 4096, 4096, 16) == 8 * 16 * 4096 * 4
     assert razer.razer_workspace_bytes(2, 4096, 512, 16) == 0
+    # W4A4 query: room for the activations decoded to bf16 where the many-tile weight-only kernel serves the
+    # shape, otherwise (few tiles, few rows) the plain linear figure
+    assert razer.razer_workspace_bytes(3, 11008, 4096, 4096) == 4096 * 4096 * 2
+    assert razer.razer_workspace_bytes(3, 4096, 4096, 2048) == 2048 * 4096 * 2
+    for n, k, m in ((4096, 4096, 64), (4096, 4096, 128), (512, 4096, 1024), (4096, 4096, 16)):
+        assert razer.razer_workspace_bytes(3, n, k, m) == razer.razer_workspace_bytes(2, n, k, m)
 
 
 def test_grouped_workspace_query_covers_single_launch_and_fallback(razer):

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import paper_2501_04052_amd as razer
-from paper_2501_04052_amd import synth
+from paper_2501_04052_amd import binding, synth
 from gpu_util import TOL, bf16_bits_to_dev, dev_to_bf16_bits, max_rel_err, tensor_to_host
 
 pytestmark = pytest.mark.gpu
@@ -107,15 +107,50 @@ def test_config5_w4a4(oracle):
     w = synth.weight(11008, 4096, seed=5001, outlier_frac=0.001)   # the gate-shaped weight, encoded here too
     wt, wq = _encode_and_check(oracle, w, W, SV)
     del w
-    y = razer.razer_linear(wt, at)
-    torch.cuda.synchronize()
     rows = synth.sample_indices(4096, 64, 9000)
     cols = synth.sample_indices(11008, 256, 9001)
     y64, _ = oracle.linear(wq, a_q=aq, rows=rows, cols=cols)
-    got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
-    err = max_rel_err(got, y64)
-    _say("   w4a4 max rel err %.2e" % err)
-    assert err <= TOL, err
+    # both forms of the call: with room for the decoded activations (the binding's default), and with a token
+    # workspace, which keeps the single fused kernel
+    assert razer.razer_workspace_bytes(binding.OP_LINEAR_W4A4, 11008, 4096, 4096) == 4096 * 4096 * 2
+    for label, ws in (("decoded activations + weight-only kernel", None),
+                      ("fused kernel", torch.empty(256, dtype=torch.uint8, device="cuda"))):
+        y = razer.razer_linear(wt, at, workspace=ws)
+        torch.cuda.synchronize()
+        got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+        err = max_rel_err(got, y64)
+        _say("   w4a4 (%s) max rel err %.2e" % (label, err))
+        assert err <= TOL, (label, err)
+
+
+@pytest.mark.parametrize("m,n,k,ablock", [(300, 12776, 1088, 16), (2000, 4000, 1056, 16), (4100, 4096 + 8, 160, 16),
+                                          (8192, 2048 + 40, 32, 16), (2048, 11008, 1024 + 64, 32), (1030, 6400 + 64, 4096, 64)])
+def test_w4a4_decoded_activations_then_weight_only_kernel(oracle, m, n, k, ablock):
+    """W4A4 on shapes where the library, given room for them, decodes the activations once into bf16 and
+    runs the register-decode weight-only kernel (128- and 256-wide tiles, the two-K-group round; ragged M, N,
+    K; activation blocks of 16, 32, 64): random code and scale bytes on both operands, sampled outputs
+    against the oracle, and the same call with a token workspace (fused kernel) against the same values."""
+    _say("w4a4 decoded-activation path m=%d n=%d k=%d activation block %d" % (m, n, k, ablock))
+    need = razer.razer_workspace_bytes(binding.OP_LINEAR_W4A4, n, k, m)
+    assert need == m * k * 2, "shape is meant to take the decoded-activation path"
+    rng = np.random.default_rng(7300 + m + n + k)
+    wq = (rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8), rng.integers(0, 256, size=(n, k // 16), dtype=np.uint8),
+          np.float32(2.0 ** -9))
+    asc = rng.integers(0, 256, size=(m, k // ablock), dtype=np.uint8)
+    asc = (asc & 0x80) | (40 + (asc & 31))                             # E4M3 codes 40..71: 2^-2 .. 3.75
+    aq = (rng.integers(0, 256, size=(m, k // 2), dtype=np.uint8), asc.astype(np.uint8), np.float32(2.0 ** -3))
+    wt = razer.RazerTensor.from_host(*wq, W, SV)
+    at = razer.RazerTensor.from_host(*aq, A, (5.0, 0.0))
+    rows = np.unique(np.concatenate([synth.sample_indices(m, 40, 9300), np.arange(m - 6, m), np.arange(0, 3)]))
+    cols = np.unique(np.concatenate([synth.sample_indices(n, 160, 9301), np.arange(n - 36, n), np.arange(0, 6)]))
+    y64, _ = oracle.linear(wq, a_q=aq, rows=rows, cols=cols)
+    for label, ws in (("decoded", None), ("fused", torch.empty(256, dtype=torch.uint8, device="cuda"))):
+        y = razer.razer_linear(wt, at, workspace=ws)
+        torch.cuda.synchronize()
+        got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+        err = max_rel_err(got, y64)
+        _say("   %s: max rel err %.2e over %d x %d sampled outputs" % (label, err, len(rows), len(cols)))
+        assert err <= TOL, (label, err)
 
 
 @pytest.mark.parametrize("m,n,k", [(8192, 2048 + 40, 32), (4100, 4096 + 8, 160), (16384, 4096, 96),
