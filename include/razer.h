@@ -64,9 +64,10 @@ typedef enum {
      * bit 15 = special-value sign, bit 14 = selector, bits 13..0 = the low 14 bits of an IEEE half
      * (exponent below 16: values up to 2 - 2^-10; the tensor scale of Eq. 1 uses that maximum).
      * block must be 0 or 128; cols a multiple of 128.  A weight format: accepted wherever
-     * RAZER_FMT_WEIGHT is, except that razer_linear takes bf16 activations only (no workspace at any m:
-     * wavefront dot products up to 32 activation rows, in passes of 4 rows; beyond that a matrix-core kernel
-     * that folds each block's partial sums with the block's scale in fp32). */
+     * RAZER_FMT_WEIGHT is, except that razer_linear takes bf16 activations only: wavefront dot products
+     * up to 4 activation rows; beyond that matrix-core kernels that multiply bare FP4 operands and fold
+     * each block's partial sums with the block's scale in fp32 (no workspace up to 32 rows; from 33 rows
+     * the usual razer_workspace_bytes rule -- K is cut into slices of whole blocks while tiles are few). */
     RAZER_FMT_WEIGHT_F16 = 2
 } razer_format;
 
@@ -200,7 +201,8 @@ razer_status razer_linear_static(const razer_tensor *w, const void *a_bf16, cons
  *   m <= 4 (RAZER_FMT_WEIGHT or RAZER_FMT_WEIGHT_F16);
  *   RAZER_FMT_WEIGHT, 5 <= m <= 32, every rows[i] and ld_y[i] a multiple of 4, y_bf16[i] 8-byte
  *     aligned, and the workspace holds razer_workspace_bytes_grouped(count, rows, cols, m) bytes
- *     (plus one launch that adds the K-slices up);
+ *     (plus one launch that adds the K-slices up); RAZER_FMT_WEIGHT_F16 under the same conditions on
+ *     rows, ld_y and y_bf16, without a workspace;
  *   RAZER_FMT_WEIGHT, m >= 33: without a workspace when m > 128 and the matrices together have
  *     >= 512 output tiles of 256 x 128, or 192..256 of them with cols >= 1024; otherwise K is cut into
  *     slices (plus one launch that adds them up) under the conditions of the 5 <= m <= 32 case --

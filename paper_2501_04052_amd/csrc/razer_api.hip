@@ -260,13 +260,16 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
         launch(fill_zero_bf16_kernel, (unsigned)((total + 255) / 256), 256, 0, st, (uint16_t*)y_bf16, m, n, ld_y);
         e = hipGetLastError();
     } else if (wsv.f16) {
-        // FP16-scale format: the GEMV kernels up to 32 activation rows (in passes of 4 from 5 rows up: measured
-        // faster than the few tiles a matrix-core launch has there), beyond that the matrix-core kernel that
-        // folds each block's partial sums with its scale
+        // FP16-scale format: the GEMV kernels up to 4 activation rows, the K-in-workgroup small-batch kernel up
+        // to 32, beyond that the tiled matrix-core kernel; both matrix-core kernels multiply bare FP4 operands
+        // and fold each block's partial sums with its scale in fp32
         if (a_q) return RAZER_ERR_CONFIG;
-        if (m <= kSkinnyMaxM)
+        if (m <= kGemvDirectMaxM || (m <= kSkinnyMaxM && k > kSkinnyMaxK))
             e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
                             (uint16_t*)y_bf16, ld_y, st);
+        else if (m <= kSkinnyMaxM)                                   // K inside the workgroup: no workspace
+            e = launch_skinny(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
+                              (uint16_t*)y_bf16, ld_y, nullptr, st);
         else {
             const size_t need = gemm_workspace_bytes(n, k, m);       // K-slices while the tiles are few
             if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return RAZER_ERR_WORKSPACE;
@@ -371,13 +374,13 @@ razer_status razer_linear_grouped(const razer_tensor* const* w, int32_t count, c
     if (one_launch) {
         if (m <= kGemvDirectMaxM) {
             path = GEMV;                                 // every block size and both weight formats
-        } else if (sv0.f16) {
-            path = SEQUENCE;                             // FP16 scale words: GEMV kernels only
+        } else if (sv0.f16 && m > kSkinnyMaxM) {
+            path = SEQUENCE;                             // FP16 scale words: no grouped matrix-core launch
         } else if (m <= kSkinnyMaxM && k > kSkinnyMaxK) {
             path = SEQUENCE;
         } else if (m <= kSkinnyMaxM) {
             // the K-slices of all matrices live in the workspace side by side
-            const size_t need = skinny_grouped_workspace_bytes(count, p, k, m);
+            const size_t need = sv0.f16 ? 0 : skinny_grouped_workspace_bytes(count, p, k, m);
             bool ok = true;
             for (int i = 0; i < count; ++i) {
                 if (p[i].n % 4 != 0 || (reinterpret_cast<uintptr_t>(p[i].y) & 7u) != 0 || p[i].ld_y % 4 != 0) ok = false;

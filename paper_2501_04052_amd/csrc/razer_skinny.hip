@@ -34,6 +34,21 @@ __device__ __forceinline__ uint32_t sk_cvt_scaled_pair(uint32_t xflip, float s, 
     v2bf b = __builtin_convertvector(p, v2bf);
     return patch_zero_halves(__builtin_bit_cast(uint32_t, b), patch);
 }
+// 8 codes -> 8 bare, negated FP4 values as bf16, remapped codes patched with `patch` (the negated special
+// value as a bf16 pair): the FP16-scale format, whose scale multiplies the block's partial sum instead.
+template <int BYTE>
+__device__ __forceinline__ uint32_t sk_cvt_bare_pair(uint32_t xflip, uint32_t patch)
+{
+    v2bf p = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(xflip, 1.0f, BYTE);
+    return patch_zero_halves(__builtin_bit_cast(uint32_t, p), patch);
+}
+__device__ __forceinline__ v8bf sk_decode_dword_bare(uint32_t x, uint32_t patch)
+{
+    const uint32_t xf = x ^ kRemapXor;
+    const uint4 r = make_uint4(sk_cvt_bare_pair<0>(xf, patch), sk_cvt_bare_pair<1>(xf, patch), sk_cvt_bare_pair<2>(xf, patch),
+                               sk_cvt_bare_pair<3>(xf, patch));
+    return __builtin_bit_cast(v8bf, r);
+}
 __device__ __forceinline__ v8bf sk_decode_dword(uint32_t x, uint2 le)
 {
     const uint32_t xf = x ^ kRemapXor;
@@ -339,7 +354,11 @@ hipError_t launch_slice_reduce_grouped(const float* partial, int count, const Ge
 // p * waves + w; its activation fragments for that slice stay in registers while it walks the G row
 // groups, the next group's packed weights in flight.  Partial sums of the waves meet in LDS after ONE
 // barrier.
-template <int NB, int S, int G, bool GB>
+// SF = 1: the FP16-scale weight format (blocks of 128 = one step: one scale word per lane and step).  The
+// operands are bare FP4 values; the roles of the two matrix operands are swapped so that a lane's four
+// results of a step belong to ITS weight row (lane % 16) and activation rows 4 (lane / 16) + 0..3, and the
+// step's sum is folded into the running sums with the lane's own block scale in fp32.
+template <int NB, int S, int G, bool GB, int SF = 0>
 __device__ __forceinline__ void mv_body(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                         const float* __restrict__ w_ts, float sv0, float sv1, int64_t n, int64_t k,
                                         const uint16_t* __restrict__ a, int64_t m, uint16_t* __restrict__ y,
@@ -353,7 +372,7 @@ __device__ __forceinline__ void mv_body(const uint8_t* __restrict__ codes, const
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t r = lane & 15u, g = lane >> 4;
     const uint32_t kk32 = (uint32_t)k;
-    const uint32_t code_ld = (uint32_t)(k >> 1), scale_ld = (uint32_t)(k >> (GB ? lb : 4));
+    const uint32_t code_ld = (uint32_t)(k >> 1), scale_ld = SF ? (uint32_t)(k >> 7) * 2u : (uint32_t)(k >> (GB ? lb : 4));
 
     struct WBuf {
         uint32_t cw[S][4];
@@ -401,7 +420,9 @@ __device__ __forceinline__ void mv_body(const uint8_t* __restrict__ codes, const
             for (int s = 0; s < S; ++s) {
                 const uint4 t = *reinterpret_cast<const uint4*>(crow + (koff[s] >> 1));
                 w.cw[s][0] = t.x; w.cw[s][1] = t.y; w.cw[s][2] = t.z; w.cw[s][3] = t.w;
-                if (GB) {
+                if (SF) {
+                    w.sw[s] = *reinterpret_cast<const uint16_t*>(srow + ((koff[s] >> 7) << 1));
+                } else if (GB) {
                     const uint32_t bb = srow[koff[s] >> lb];
                     w.sw[s] = bb | (bb << 8);
                 } else {
@@ -411,7 +432,7 @@ __device__ __forceinline__ void mv_body(const uint8_t* __restrict__ codes, const
         };
         WBuf w0, w1;
         load(w0, 0);
-        if (p == 0) {
+        if (!SF && p == 0) {
             for (uint32_t sb = threadIdx.x; sb < 256u; sb += blockDim.x) {
                 float s, sv;
                 decode_scale_byte<0>(sb, sv0, sv1, s, sv);
@@ -424,6 +445,26 @@ __device__ __forceinline__ void mv_body(const uint8_t* __restrict__ codes, const
 #pragma unroll
             for (int s = 0; s < S; ++s) {
                 const uint32_t sws = w.sw[s] & smask[s];                  // past K: scale 0
+                if constexpr (SF != 0) {
+                    float bs, sv;
+                    decode_scale_word(sws, sv0, sv1, bs, sv);
+                    const uint32_t nsv = (uint32_t)f32_to_bf16_rne(-sv);
+                    v4f blk[NB];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const v8bf wf = sk_decode_dword_bare(w.cw[s][j], nsv | (nsv << 16));
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) {
+                            const v8bf av = __builtin_bit_cast(v8bf, make_uint4(af[b][s][j][0], af[b][s][j][1], af[b][s][j][2], af[b][s][j][3]));
+                            blk[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, wf, j == 0 ? v4f{0.f, 0.f, 0.f, 0.f} : blk[b], 0, 0, 0);
+                        }
+                    }
+#pragma unroll
+                    for (int b = 0; b < NB; ++b)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[gi][b][i] = __builtin_fmaf(bs, blk[b][i], acc[gi][b][i]);
+                    continue;
+                }
                 const uint2 le0 = lut[sws & 255u], le1 = lut[(sws >> 8) & 255u];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -456,6 +497,19 @@ __device__ __forceinline__ void mv_body(const uint8_t* __restrict__ codes, const
             const float4 q = part[((gi * nwaves + w) * NB + b) * 64 + l];
             t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
         }
+        if constexpr (SF != 0) {
+            // swapped operands: weight row 16 (group0 + gi) + l % 16, activation rows 16 b + 4 (l / 16) + 0..3
+            const int64_t wn = (group0 + gi) * 16 + (l & 15u);
+            const float v[4] = {t.x, t.y, t.z, t.w};
+            if (wn < n) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t am = 16 * b + 4 * (l >> 4) + i;
+                    if (am < m) y[am * ld_y + wn] = f32_to_bf16_rne(-ts * v[i]);
+                }
+            }
+            continue;
+        }
         const int64_t gn = (group0 + gi) * 16 + 4 * (l >> 4);
         const int64_t gm = 16 * b + (l & 15u);
         if (gm < m && gn < n) {
@@ -475,18 +529,18 @@ __device__ __forceinline__ void mv_body(const uint8_t* __restrict__ codes, const
     }
 }
 
-template <int NB, int S, int G, bool GB, int MAXW>
+template <int NB, int S, int G, bool GB, int MAXW, int SF = 0>
 __global__ __launch_bounds__(64 * MAXW) void mv_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                                        const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
                                                        int64_t k, const uint16_t* __restrict__ a, int64_t m,
                                                        uint16_t* __restrict__ y, int64_t ld_y, int lb, int npass)
 {
-    mv_body<NB, S, G, GB>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, lb, (int64_t)blockIdx.x * G, npass);
+    mv_body<NB, S, G, GB, SF>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y, lb, (int64_t)blockIdx.x * G, npass);
 }
 
 // Grouped form: workgroups [0, g1) serve matrix 0, [g1, g2) matrix 1, ... (scalar arguments picked by
 // uniform compares, as in the other grouped kernels).
-template <int NB, int S, int G, bool GB, int MAXW>
+template <int NB, int S, int G, bool GB, int MAXW, int SF = 0>
 __global__ __launch_bounds__(64 * MAXW) void mv_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
@@ -504,7 +558,7 @@ __global__ __launch_bounds__(64 * MAXW) void mv_grouped_kernel(
     if (b >= g1) { codes = c1; scales = s1; ts = f1; y = y1; n = n1; ld = l1; first = g1; }
     if (b >= g2) { codes = c2; scales = s2; ts = f2; y = y2; n = n2; ld = l2; first = g2; }
     if (b >= g3) { codes = c3; scales = s3; ts = f3; y = y3; n = n3; ld = l3; first = g3; }
-    mv_body<NB, S, G, GB>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, lb, (int64_t)(b - first) * G, npass);
+    mv_body<NB, S, G, GB, SF>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, lb, (int64_t)(b - first) * G, npass);
 }
 
 // Launch shapes of the K-in-workgroup kernel: (S steps per wave and pass, G row groups per workgroup,
@@ -525,10 +579,12 @@ static int mv_maxw(int s, int g)
         if (sh.s == s && sh.g == g) return sh.maxw;
     return 16;
 }
-static void mv_geometry(int s, int g, int64_t k, int& nwaves, int& npass)
+// (nb 16-row activation fragments: the partial sums take g x waves x nb KiB of LDS, at most 64)
+static void mv_geometry(int s, int g, int64_t k, int& nwaves, int& npass, int nb = 1)
 {
     const int64_t slices = (k + 128 * s - 1) / (128 * s);
-    const int maxw = mv_maxw(s, g);
+    int maxw = mv_maxw(s, g) / nb;                                  // (two fragments: kernels built for half the waves)
+    if (maxw > 64 / (g * nb)) maxw = 64 / (g * nb);
     nwaves = (int)(slices < maxw ? slices : maxw);
     npass = (int)((slices + nwaves - 1) / nwaves);
 }
@@ -543,11 +599,21 @@ struct SkinnyPlan {
     int steps, nrb;         // K-sliced kernel
     int s, g;               // K-in-workgroup kernel
 };
-static SkinnyPlan skinny_plan(int64_t rows, int64_t k, int64_t m)
+static SkinnyPlan skinny_plan(int64_t rows, int64_t k, int64_t m, bool f16 = false)
 {
     SkinnyPlan p{false, (m <= 16 && k > 8192) ? 8 : 4, 1, 0, 0};
     const int64_t row_blocks = (rows + kSkRows - 1) / kSkRows;
     const TuneShape t = tuned_shape(kTuneSmallBatch, m, rows, k);
+    if (f16) {
+        // the FP16-scale format has the K-in-workgroup kernel only (up to 32 activation rows): a forced shape,
+        // else 1 step per wave and pass and 2 row groups (best of the five shapes on the 7B-class layer at 8,
+        // 16 and 32 rows: 64 / 75 / 105 us against 79-80 / 89-91 / 115 with 4 groups)
+        p.in_workgroup = true;
+        p.s = 1;
+        p.g = 2;
+        if (t.source == 1 && t.p[0] == 1 && mv_shape_ok(t.p[1], t.p[2])) { p.s = t.p[1]; p.g = t.p[2]; }
+        return p;
+    }
     if (t.source && t.p[0] == 1 && m <= 16 && mv_shape_ok(t.p[1], t.p[2])) {
         p.in_workgroup = true;
         p.s = t.p[1];
@@ -600,15 +666,18 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
                          int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y, float* workspace,
                          hipStream_t st)
 {
-    const SkinnyPlan pl = skinny_plan(n, k, m);
+    const SkinnyPlan pl = skinny_plan(n, k, m, cfg.f16 != 0);
     if (pl.in_workgroup) {
+        const int nb = m <= 16 ? 1 : 2;
         int nwaves, npass;
-        mv_geometry(pl.s, pl.g, k, nwaves, npass);
+        mv_geometry(pl.s, pl.g, k, nwaves, npass, nb);
         const unsigned grid = (unsigned)(((n + 15) / 16 + pl.g - 1) / pl.g);
-        const size_t smem = (size_t)pl.g * nwaves * 1024;
+        const size_t smem = (size_t)pl.g * nwaves * nb * 1024;
 #define RAZER_MV(S, G, MW)                                                                                           \
         do {                                                                                                         \
-            if (cfg.lb == 4) launch(mv_kernel<1, S, G, false, MW>, grid, 64 * nwaves, smem, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, cfg.lb, npass); \
+            if (cfg.f16 && nb == 2) launch(mv_kernel<2, S, G, false, MW / 2, 1>, grid, 64 * nwaves, smem, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, cfg.lb, npass); \
+            else if (cfg.f16) launch(mv_kernel<1, S, G, false, MW, 1>, grid, 64 * nwaves, smem, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, cfg.lb, npass); \
+            else if (cfg.lb == 4) launch(mv_kernel<1, S, G, false, MW>, grid, 64 * nwaves, smem, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, cfg.lb, npass); \
             else launch(mv_kernel<1, S, G, true, MW>, grid, 64 * nwaves, smem, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, cfg.lb, npass);             \
         } while (0)
         RAZER_MV_SHAPES(RAZER_MV);
@@ -648,11 +717,11 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
 hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, int64_t k, const uint16_t* a,
                                  int64_t m, float* workspace, hipStream_t st)
 {
-    if (count < 1 || count > 4 || cfg.f16 || m <= kGemvDirectMaxM || m > kSkinnyMaxM || k > kSkinnyMaxK)
+    if (count < 1 || count > 4 || m <= kGemvDirectMaxM || m > kSkinnyMaxM || k > kSkinnyMaxK)
         return hipErrorInvalidValue;
     int64_t rows = 0;
     for (int i = 0; i < count; ++i) rows += p[i].n;
-    const SkinnyPlan pl = skinny_plan(rows, k, m);
+    const SkinnyPlan pl = skinny_plan(rows, k, m, cfg.f16 != 0);
     GemvProblem q[4];
     unsigned g[5] = {0, 0, 0, 0, 0};
     for (int i = 0; i < 4; ++i) {
@@ -664,14 +733,17 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
         q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,        \
         q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m
     if (pl.in_workgroup) {
+        const int nb = m <= 16 ? 1 : 2;
         int nwaves, npass;
-        mv_geometry(pl.s, pl.g, k, nwaves, npass);
+        mv_geometry(pl.s, pl.g, k, nwaves, npass, nb);
         for (int i = 0; i < 4; ++i)
             g[i + 1] = g[i] + (i < count ? (unsigned)(((q[i].n + 15) / 16 + pl.g - 1) / pl.g) : 0u);
-        const size_t smem = (size_t)pl.g * nwaves * 1024;
+        const size_t smem = (size_t)pl.g * nwaves * nb * 1024;
 #define RAZER_MVG(S, G, MW)                                                                                                   \
         do {                                                                                                                  \
-            if (cfg.lb == 4) launch(mv_grouped_kernel<1, S, G, false, MW>, g[4], 64 * nwaves, smem, st, RAZER_SKG_COMMON, cfg.lb, npass); \
+            if (cfg.f16 && nb == 2) launch(mv_grouped_kernel<2, S, G, false, MW / 2, 1>, g[4], 64 * nwaves, smem, st, RAZER_SKG_COMMON, cfg.lb, npass); \
+            else if (cfg.f16) launch(mv_grouped_kernel<1, S, G, false, MW, 1>, g[4], 64 * nwaves, smem, st, RAZER_SKG_COMMON, cfg.lb, npass); \
+            else if (cfg.lb == 4) launch(mv_grouped_kernel<1, S, G, false, MW>, g[4], 64 * nwaves, smem, st, RAZER_SKG_COMMON, cfg.lb, npass); \
             else launch(mv_grouped_kernel<1, S, G, true, MW>, g[4], 64 * nwaves, smem, st, RAZER_SKG_COMMON, cfg.lb, npass);             \
         } while (0)
         RAZER_MV_SHAPES(RAZER_MVG);

@@ -94,7 +94,7 @@ def test_linear_matches_oracle(oracle, m, n, k):
                                    (300, 200, 2048 + 384), (129, 8, 128 * 9)])
 def test_linear_matrix_core_path_matches_oracle(oracle, m, n, k):
     """Beyond 32 activation rows the format runs on the matrix cores with bare FP4 operands and a per-block
-    fold in fp32 (64- and 128-row tiles; up to 32 rows: passes of the GEMV kernels): ragged M and N, odd and
+    fold in fp32 (64- and 128-row tiles; up to 32 rows: the K-in-workgroup small-batch kernel): ragged M and N, odd and
     even numbers of blocks, every scale word field (zero, subnormal and saturated scales included)."""
     print("f16-scale matrix-core linear", m, n, k, flush=True)
     rng = np.random.default_rng(3700 + m + n)
@@ -109,6 +109,43 @@ def test_linear_matrix_core_path_matches_oracle(oracle, m, n, k):
     y64, _ = oracle.linear(wq, a_bf16=a)
     assert max_rel_err(dev_to_bf16_bits(buf[:, :n]), y64) <= TOL
     assert torch.all(buf[:, n:] == 2.0)
+
+
+MV_SHAPES = [None, (1, 1, 2), (1, 1, 4), (1, 2, 2), (1, 2, 4), (1, 2, 8)]
+
+
+@pytest.mark.parametrize("shape", MV_SHAPES)
+@pytest.mark.parametrize("m,ns,k", [(5, (1000,), 4096 + 128), (16, (328, 200), 1152), (9, (72,), 128), (17, (40, 24, 4), 34944),
+                                    (32, (333,), 2048 + 384), (24, (100, 36), 11008)])
+def test_small_batch_kernel_every_launch_shape(oracle, shape, m, ns, k):
+    """5..32 activation rows run on the K-in-workgroup matrix-core kernel with bare FP4 operands and the block
+    scale folded per 128-element step (one and two 16-row activation fragments; single and grouped launches;
+    ragged N; one block to 273 blocks per row, several passes per wave): the default launch shape and every
+    shape the tuner may force, every scale word field."""
+    from paper_2501_04052_amd import binding
+    print("f16-scale small batch", shape, m, ns, k, flush=True)
+    rng = np.random.default_rng(3800 + m + k)
+    wqs = [_rand_tensor(rng, n, k) for n in ns]
+    wqs[0][1][0, 0] = 0x0000
+    wqs[-1][1][-1, -1] = 0xFFFF
+    wts = [razer.RazerTensor.from_host(*wq, F16, (5.0, 8.0)) for wq in wqs]
+    a = synth.activation(m, k, seed=3801 + m + k, outlier_frac=0.01)
+    if shape is not None:
+        razer.razer_tune_force(binding.TUNE_SMALL_BATCH, shape)
+    try:
+        if len(ns) == 1:
+            buf = torch.full((m, ns[0] + 8), 2.0, dtype=torch.bfloat16, device="cuda")
+            razer.razer_linear(wts[0], bf16_bits_to_dev(a), out=buf[:, :ns[0]])
+            ys = [buf[:, :ns[0]]]
+        else:
+            ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a))
+        torch.cuda.synchronize()
+    finally:
+        razer.razer_tune_force(binding.TUNE_SMALL_BATCH, None)
+    for wq, y in zip(wqs, ys):
+        assert max_rel_err(dev_to_bf16_bits(y), oracle.linear(wq, a_bf16=a)[0]) <= TOL
+    if len(ns) == 1:
+        assert torch.all(buf[:, ns[0]:] == 2.0)
 
 
 def test_linear_on_encoded_weights_full_layer_shape(oracle):
@@ -163,7 +200,7 @@ def test_grouped_and_error_paths(oracle):
     for wq, y in zip(wqs, ys):
         assert max_rel_err(dev_to_bf16_bits(y), oracle.linear(wq, a_bf16=a)[0]) <= TOL
     a9 = synth.activation(9, k, seed=3503)
-    ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a9))         # matrix by matrix, passes of 4 rows
+    ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a9))         # matrix by matrix (rows not multiples of 4)
     for wq, y in zip(wqs, ys):
         assert max_rel_err(dev_to_bf16_bits(y), oracle.linear(wq, a_bf16=a9)[0]) <= TOL
     # W4A4 is not built for this weight format
