@@ -79,7 +79,7 @@ def test_workspace_sizes(razer):
     # linear: only the 5..32-row kernel meets its K-slices in a workspace
     assert razer.razer_workspace_bytes(2, 4096, 4096, 1) == 0
     assert razer.razer_workspace_bytes(2, 4096, 4096, 2048) == 0
-    assert razer.razer_workspace_bytes(2, 4096, 4096, 16) == 8 * 16 * 4096 * 4
+    assert razer.razer_workspace_bytes(2, 4100, 4096, 16) == 8 * 16 * 4100 * 4     # (a shape the tuned table does not list)
     assert razer.razer_workspace_bytes(2, 4096, 512, 16) == 0
     # W4A4 query: room for the activations decoded to bf16 where the many-tile weight-only kernel serves the
     # shape, otherwise (few tiles, few rows) the plain linear figure
