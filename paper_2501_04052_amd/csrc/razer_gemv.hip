@@ -14,9 +14,9 @@
 // streaming kernel (groups of 2 rows, next group in flight while one is decoded);
 // longer rows take the multi-pass kernel (4 rows per workgroup).
 //
-// Three and four activation rows take a variant of the streaming kernel that multiplies on the
-// 4x4x4 matrix instruction (gemv_quad_kernel, further down): with v_dot2 every activation row costs
-// another half operation per weight and the kernel turns VALU-bound.
+// Two to four activation rows (16-element blocks) take a variant of the streaming kernel that multiplies
+// on the 4x4x4 matrix instruction (gemv_quad_kernel, further down): with v_dot2 every activation row
+// costs another half operation per weight and the kernel turns VALU-bound.
 //
 // Decode.  The 8 codes of a dword are sign-flipped with one xor, converted to
 // packed bf16 pairs by the hardware FP4 conversion, and the (now all-zero)
@@ -408,17 +408,21 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
 // Several activation rows on the 4x4x4 matrix instruction.  v_mfma_f32_4x4x4_16B_bf16 multiplies 16
 // independent 4x4x4 blocks per wavefront: lane 4b+i supplies row i of block b's left matrix (4 values
 // along k), lane 4b+j column j of its right matrix, and lane 4b+j receives column j of the product in
-// 4 registers (rows i) -- checked on the GPU.  Here block b is a run of 32 k's, i one of four weight
-// rows and j one of four activation rows: a lane decodes the 32 codes of ITS row into bare FP4
-// values (1.5 ops per weight, as in the dot-product kernels), eight MFMAs per run multiply them with
-// its activation row's 32 values, and after each 16-element block the four partial sums a lane holds
-// (one per weight row) take that row's block scale, fetched from the quad lane that owns the row by a
-// DPP broadcast.  Per weight: 1.5 decode + 0.25 MFMA + 0.25 FMA per set of four activation rows,
-// against 1.5 + 0.5 per activation row with v_dot2 -- the dot-product kernels are VALU-bound from two
-// activation rows up.  Workgroup structure as in the streaming kernel: wave w owns K-slice w (C runs
-// of 512 elements), walks G groups of four rows with the next group's loads in flight, partial sums
-// of the waves meet in LDS.  Idle lanes (K tail) are silenced through their scale bits; activation
-// rows past M are never masked, their product columns are simply not stored.
+// 4 registers (rows i) -- checked on the GPU.  Here block b is a run of 32 k's; the LEFT matrix holds
+// four activation rows (lane 4b+i: activation row i) and the RIGHT one four weight rows (lane 4b+j:
+// weight row j), so a lane decodes the 32 codes of ITS weight row into bare FP4 values (1.5 ops per
+// weight, as in the dot-product kernels), eight MFMAs per run multiply them with its activation row's
+// 32 values, and the four sums a lane receives per 16-element block -- its own weight row against the
+// four activation rows -- take the block scale the lane itself looked up: no cross-lane traffic.  (With
+// the roles the other way round a lane held one sum per weight row and needed the scales of its three
+// quad neighbours by DPP: 15 % more vector instructions, 9-12 % slower.)  Per weight: 1.5 decode +
+// 0.25 MFMA + 0.25 FMA per set of four activation rows, against 1.5 + 0.5 per activation row with
+// v_dot2 -- the dot-product kernels are VALU-bound from two activation rows up.  Workgroup structure
+// as in the streaming kernel: wave w owns K-slice w (C runs of 512 elements), walks G groups of four
+// rows with the next group's loads in flight, partial sums of the waves meet in LDS (each wave leaves
+// one sum per row of 16 lanes: the cross-row step of the wave reduction is part of the final sum).
+// Idle lanes (K tail) are silenced through their scale bits; activation rows past M are never masked,
+// their results are simply not stored.
 template <int C, int G, int D, int P, int MS, int PS = 1, bool IL = false>
 __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                                const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
@@ -428,7 +432,7 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
     constexpr int R = 4;
     static_assert(D == 2, "two register buffers");
     __shared__ uint2 lut[256];
-    __shared__ float part[P * G * R * 4 * MS][kMaxWaves / P];
+    __shared__ float part[P * G * R * 4 * MS][4 * kMaxWaves / P];       // per wave: one partial sum per row of 16 lanes
     const float ts = *w_ts;
     static_assert(P == 1 || P == 2, "one or two sets of waves");
     const uint32_t lane = threadIdx.x & 63u, nwaves = (blockDim.x >> 6) / P;
@@ -497,45 +501,47 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
 #pragma unroll
             for (int c = 0; c < C; ++c) {
                 const uint32_t xw[4] = {cur.cw[c].x, cur.cw[c].y, cur.cw[c].z, cur.cw[c].w};
+                const uint2 le0 = lut[cur.sw[c] & 255u], le1 = lut[(cur.sw[c] >> 8) & 255u];
+                // bare FP4 values of the lane's 32 codes: dwords 0, 1 belong to the first block, 2, 3 to the second
+                v4bf wa[4], wb[4];
 #pragma unroll
-                for (int blk = 0; blk < 2; ++blk) {
-                    const uint2 le = lut[(cur.sw[c] >> (8 * blk)) & 255u];
-                    v4f tmp[MS];
+                for (int d = 0; d < 4; ++d) {
+                    const uint32_t x = xw[d] ^ kRemapXor;
+                    const uint32_t patch = d < 2 ? le0.y : le1.y;
+                    const uint32_t w0 = patch_zero_halves(cvt_pair<0>(x), patch);
+                    const uint32_t w1 = patch_zero_halves(cvt_pair<1>(x), patch);
+                    const uint32_t w2 = patch_zero_halves(cvt_pair<2>(x), patch);
+                    const uint32_t w3 = patch_zero_halves(cvt_pair<3>(x), patch);
+                    wa[d] = __builtin_bit_cast(v4bf, make_uint2(w0, w1));
+                    wb[d] = __builtin_bit_cast(v4bf, make_uint2(w2, w3));
+                }
+                // The activations are the LEFT operand (lane 4b+i: activation row i), the weights the right one
+                // (lane 4b+j: weight row j), so a lane receives the four products of ITS weight row with the four
+                // activation rows and folds them with its own row's (negated) block scale -- no cross-lane traffic.
+                // The two blocks' chains of four dependent matrix instructions are interleaved.
+                const float sc0 = u2f(le0.x), sc1 = u2f(le1.x);
 #pragma unroll
-                    for (int s = 0; s < MS; ++s) tmp[s] = v4f{0.f, 0.f, 0.f, 0.f};
+                for (int s = 0; s < MS; ++s) {
+                    const uint4 a0 = av[s][c][0], a1 = av[s][c][1], a2 = av[s][c][2], a3 = av[s][c][3];
+                    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+                    v4f t0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4bf, make_uint2(a0.x, a0.y)), wa[0], zero, 0, 0, 0);
+                    v4f t1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4bf, make_uint2(a2.x, a2.y)), wa[2], zero, 0, 0, 0);
+                    t0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4bf, make_uint2(a0.z, a0.w)), wb[0], t0, 0, 0, 0);
+                    t1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4bf, make_uint2(a2.z, a2.w)), wb[2], t1, 0, 0, 0);
+                    t0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4bf, make_uint2(a1.x, a1.y)), wa[1], t0, 0, 0, 0);
+                    t1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4bf, make_uint2(a3.x, a3.y)), wa[3], t1, 0, 0, 0);
+                    t0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4bf, make_uint2(a1.z, a1.w)), wb[1], t0, 0, 0, 0);
+                    t1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4bf, make_uint2(a3.z, a3.w)), wb[3], t1, 0, 0, 0);
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const uint32_t x = xw[2 * blk + h] ^ kRemapXor;
-                        const uint32_t w0 = patch_zero_halves(cvt_pair<0>(x), le.y);
-                        const uint32_t w1 = patch_zero_halves(cvt_pair<1>(x), le.y);
-                        const uint32_t w2 = patch_zero_halves(cvt_pair<2>(x), le.y);
-                        const uint32_t w3 = patch_zero_halves(cvt_pair<3>(x), le.y);
-                        const v4bf wa = __builtin_bit_cast(v4bf, make_uint2(w0, w1));
-                        const v4bf wb = __builtin_bit_cast(v4bf, make_uint2(w2, w3));
-#pragma unroll
-                        for (int s = 0; s < MS; ++s) {
-                            const uint4 aq = av[s][c][2 * blk + h];
-                            tmp[s] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(wa, __builtin_bit_cast(v4bf, make_uint2(aq.x, aq.y)), tmp[s], 0, 0, 0);
-                            tmp[s] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(wb, __builtin_bit_cast(v4bf, make_uint2(aq.z, aq.w)), tmp[s], 0, 0, 0);
-                        }
-                    }
-                    // register i of tmp belongs to weight row i, whose (negated) block scale sits in quad lane i
-                    const int nsb = (int)le.x;
-                    const float s0 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0x00, 0xF, 0xF, false));
-                    const float s1 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0x55, 0xF, 0xF, false));
-                    const float s2 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0xAA, 0xF, 0xF, false));
-                    const float s3 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, nsb, 0xFF, 0xF, 0xF, false));
-#pragma unroll
-                    for (int s = 0; s < MS; ++s) {
-                        acc[g][s][0] = __builtin_fmaf(s0, tmp[s][0], acc[g][s][0]);
-                        acc[g][s][1] = __builtin_fmaf(s1, tmp[s][1], acc[g][s][1]);
-                        acc[g][s][2] = __builtin_fmaf(s2, tmp[s][2], acc[g][s][2]);
-                        acc[g][s][3] = __builtin_fmaf(s3, tmp[s][3], acc[g][s][3]);
+                    for (int i = 0; i < 4; ++i) {
+                        acc[g][s][i] = __builtin_fmaf(sc0, t0[i], acc[g][s][i]);
+                        acc[g][s][i] = __builtin_fmaf(sc1, t1[i], acc[g][s][i]);
                     }
                 }
             }
             if (ps == PS - 1) {
-                // sum over the 16 runs of the wavefront: within each row of 16 lanes by DPP, across the rows by shuffles
+                // sum over the 16 runs of the wavefront: within each row of 16 lanes by DPP; the four rows' sums go to
+                // LDS side by side and meet in the final sum over the waves (no cross-row shuffles)
 #pragma unroll
                 for (int s = 0; s < MS; ++s)
 #pragma unroll
@@ -543,9 +549,7 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
                         float v = acc[g][s][i];
                         v = dpp_add<0x114>(v);                            // row_shr:4
                         v = dpp_add<0x118>(v);                            // row_shr:8 -> lanes 12..15 of each row
-                        v += __shfl_xor(v, 16);
-                        v += __shfl_xor(v, 32);
-                        if ((lane & 60u) == 12u) part[((par * G + g) * R + i) * (4 * MS) + 4 * s + q][wave] = v;
+                        if ((lane & 12u) == 12u) part[((par * G + g) * R + q) * (4 * MS) + 4 * s + i][4 * wave + (lane >> 4)] = v;   // weight row q, activation row 4 s + i
                     }
             }
         }
@@ -555,7 +559,7 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
         const uint32_t pr = t / (4 * MS), mcol = t - pr * (4 * MS);
         if ((int64_t)mcol < m && row0 + pr < n) {
             float acc = 0.0f;
-            for (uint32_t w = 0; w < nwaves; ++w) acc += part[t][w];
+            for (uint32_t w = 0; w < 4 * nwaves; ++w) acc += part[t][w];
             y[(int64_t)mcol * ld_y + row0 + pr] = f32_to_bf16_rne(acc * ts);
         }
     }
@@ -593,15 +597,16 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_grouped_kernel(
     gemv_quad_body<C, G, D, P, MS, PS, IL>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, (int64_t)(b - first) * (P * 4 * G));
 }
 
-// The matrix-instruction kernel serves 3 and 4 activation rows (at 1-2 the dot-product kernel is as
-// fast): measured 7-32 % faster at M = 4 over the projection shapes of 7B- and 70B-class layers.  One
+// The matrix-instruction kernel serves 2 to 4 activation rows (one row: the dot-product kernel is faster):
+// measured 5-11 % faster than it at M = 2 and 15-40 % at M = 4 over the projection shapes of 7B- and 70B-class
+// layers.  One
 // 512-element run per lane while that needs at most 16 waves (K <= 8192), two up to K = 16384, two
 // passes of two up to K = 32768 (four runs at once do not fit the register budget of a 16-wave
 // workgroup); longer rows stay with the dot-product kernel.  4 groups of 4 rows per workgroup, 8 when
 // the launch has at least 16384 rows.
 static inline bool quad_fits(const SvConfig& cfg, int64_t k, int64_t m)
 {
-    return (m == 3 || m == 4) && cfg.lb == 4 && !cfg.f16 && k <= 32768;
+    return (m >= 2 && m <= 4) && cfg.lb == 4 && !cfg.f16 && k <= 32768;
 }
 static inline int quad_runs(int64_t k) { return (k + 511) / 512 <= kMaxWaves ? 1 : 2; }
 static inline int quad_passes(int64_t k) { return k <= 16384 ? 1 : 2; }

@@ -68,7 +68,7 @@ def test_gemv_shapes(oracle, shape, m, ns, k, block):
 
 
 @pytest.mark.parametrize("shape", [(4,), (8,)])
-@pytest.mark.parametrize("m,ns,k", [(3, (333,), 4096 + 32), (4, (100, 57), 11008), (4, (70,), 16384)])
+@pytest.mark.parametrize("m,ns,k", [(2, (97, 40), 4096), (3, (333,), 4096 + 32), (4, (100, 57), 11008), (4, (70,), 16384)])
 def test_gemv_quad_shapes(oracle, shape, m, ns, k):
     _check(oracle, binding.TUNE_GEMV_QUAD, shape, m, ns, k)
 
