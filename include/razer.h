@@ -66,8 +66,9 @@ typedef enum {
      * block must be 0 or 128; cols a multiple of 128.  A weight format: accepted wherever
      * RAZER_FMT_WEIGHT is, except that razer_linear takes bf16 activations only: wavefront dot products
      * up to 4 activation rows; beyond that matrix-core kernels that multiply bare FP4 operands and fold
-     * each block's partial sums with the block's scale in fp32 (no workspace up to 32 rows; from 33 rows
-     * the usual razer_workspace_bytes rule -- K is cut into slices of whole blocks while tiles are few). */
+     * each block's partial sums with the block's scale in fp32 (no workspace is used up to 64 rows; from
+     * 65 rows the usual razer_workspace_bytes rule -- K is cut into slices of whole blocks while tiles are
+     * few). */
     RAZER_FMT_WEIGHT_F16 = 2
 } razer_format;
 

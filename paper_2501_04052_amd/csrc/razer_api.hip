@@ -261,13 +261,13 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
         e = hipGetLastError();
     } else if (wsv.f16) {
         // FP16-scale format: the GEMV kernels up to 4 activation rows, the K-in-workgroup small-batch kernel up
-        // to 32, beyond that the tiled matrix-core kernel; both matrix-core kernels multiply bare FP4 operands
+        // to 64, beyond that the tiled matrix-core kernels; all matrix-core kernels multiply bare FP4 operands
         // and fold each block's partial sums with its scale in fp32
         if (a_q) return RAZER_ERR_CONFIG;
         if (m <= kGemvDirectMaxM || (m <= kSkinnyMaxM && k > kSkinnyMaxK))
             e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
                             (uint16_t*)y_bf16, ld_y, st);
-        else if (m <= kSkinnyMaxM)                                   // K inside the workgroup: no workspace
+        else if (m <= 64 && k <= kSkinnyMaxK)                        // K inside the workgroup: no workspace
             e = launch_skinny(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
                               (uint16_t*)y_bf16, ld_y, nullptr, st);
         else {

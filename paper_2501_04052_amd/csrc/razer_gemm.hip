@@ -401,7 +401,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(
 // One barrier ends every slot.  Tile i+1 is complete at the end of slot 2i+1 and is first read in
 // slot 2i+2; the stage it overwrites was last read in slot 2i-1.  Global loads for a group's half of
 // tile i+2 are issued right after it stored tile i+1 and land during its next MFMA slot.
-template <int BM, int BN, int WGM, int WGN, bool AQ, bool GB>
+// SF: the FP16-scale weight format, as in gemm_kernel -- bare FP4 weights in LDS, the blocks' scales as fp32
+// beside the tile, a second accumulator set per block of 128 elements (two K-tiles) and a fold after every
+// second K-tile (256 x 128 tiles only: the second set must fit the registers of two waves per SIMD).
+template <int BM, int BN, int WGM, int WGN, bool AQ, bool GB, bool SF = false>
 __global__ __launch_bounds__(512) void gemm_pp_kernel(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     SvConfig wcfg, int64_t n, int64_t k, const uint16_t* __restrict__ a, const uint8_t* __restrict__ a_codes,
@@ -425,17 +428,22 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
     uint8_t* Bs = smem + 2 * BM * 128;
     uint2* wlut = reinterpret_cast<uint2*>(smem + 2 * (BM + BN) * 128);
     uint2* alut = wlut + 256;
+    float* wsc = reinterpret_cast<float*>(wlut);       // SF: 2 stages x BN block scales in place of the tables
+    static_assert(!SF || (!AQ && !GB && TM * TN <= 4 && 2 * BN * 4 <= 2 * 256 * 8), "FP16-scale variant");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int grp = wave >> 2, gt = tid & (GT - 1);
     const int wm = wave % WGM, wn = wave / WGM;
     const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + (int)gridDim.y - 1) / (int)gridDim.y;
+    // (SF: slices of whole 128-element blocks, i.e. an even number of K-tiles)
+    const int kt_all = (int)((k + kBK - 1) / kBK);
+    const int kt_even = (kt_all + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int kt_per = SF ? ((kt_even + 1) & ~1) : kt_even;
     const int kt0 = (int)blockIdx.y * kt_per;                          // K-slice of this workgroup (split-K)
     const int KT = kt_all - kt0 < kt_per ? kt_all - kt0 : kt_per;
 
-    fill_scaled_lut<0>(wlut, wcfg.sv0, wcfg.sv1, tid, 512);
+    if (!SF) fill_scaled_lut<0>(wlut, wcfg.sv0, wcfg.sv1, tid, 512);
     if (AQ) fill_scaled_lut<1>(alut, acfg.sv0, acfg.sv1, tid, 512);
 
     v16f acc[TN][TM];
@@ -489,12 +497,14 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
             if (gr < n && kk < k) {
                 if (UB == 2) {
                     pf.rb[i] = *reinterpret_cast<const uint4*>(w_codes + gr * (k / 2) + kk / 2);
-                    pf.rsb[i] = load_scale_pair<GB>(w_scales + gr * (k >> wcfg.lb), kk, wcfg.lb);
+                    if (SF) pf.rsb[i] = reinterpret_cast<const uint16_t*>(w_scales)[gr * (k >> 7) + (kk >> 7)];
+                    else pf.rsb[i] = load_scale_pair<GB>(w_scales + gr * (k >> wcfg.lb), kk, wcfg.lb);
                 } else {
                     const uint2 t2 = *reinterpret_cast<const uint2*>(w_codes + gr * (k / 2) + kk / 2);
                     pf.rb[i].x = t2.x;
                     pf.rb[i].y = t2.y;
-                    pf.rsb[i] = w_scales[gr * (k >> wcfg.lb) + (kk >> wcfg.lb)];
+                    if (SF) pf.rsb[i] = reinterpret_cast<const uint16_t*>(w_scales)[gr * (k >> 7) + (kk >> 7)];
+                    else pf.rsb[i] = w_scales[gr * (k >> wcfg.lb) + (kk >> wcfg.lb)];
                 }
             }
         }
@@ -520,6 +530,19 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
 #pragma unroll
         for (int i = 0; i < B_PT; ++i) {
             const int u = gt + i * GT, row = grp * (BN / 2) + u / UPR, part = u % UPR;
+            if constexpr (SF) {
+                float sc, sv;
+                decode_scale_word(pf.rsb[i], wcfg.sv0, wcfg.sv1, sc, sv);      // (rows past N, tiles past K: word 0, scale 0)
+                const uint32_t nsv = (uint32_t)f32_to_bf16_rne(-sv), patch = nsv | (nsv << 16);
+                *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * UB * part + 0)) = decode_dword_bare(pf.rb[i].x, patch);
+                *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * UB * part + 1)) = decode_dword_bare(pf.rb[i].y, patch);
+                if (UB == 2) {
+                    *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * UB * part + 2)) = decode_dword_bare(pf.rb[i].z, patch);
+                    *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * UB * part + 3)) = decode_dword_bare(pf.rb[i].w, patch);
+                }
+                if (part == 0) wsc[st * BN + row] = sc;                        // the block's scale, for the fold
+                continue;
+            }
             const uint2 le0 = wlut[pf.rsb[i] & 255u];
             *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * UB * part + 0)) = decode_dword(pf.rb[i].x, le0);
             *reinterpret_cast<uint4*>(bs + lds_off(row, 2 * UB * part + 1)) = decode_dword(pf.rb[i].y, le0);
@@ -530,11 +553,15 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
             }
         }
     };
-    auto mfma_tile = [&](int st) {
+    // SF: sums of the current block of 128 elements (two K-tiles), folded into acc with the block scales
+    v16f blk[SF ? TN : 1][SF ? TM : 1];
+    auto mfma_tile = [&](int st, int t) {
         const uint8_t* as = As + st * BM * 128;
         const uint8_t* bs = Bs + st * BN * 128;
+        // SF: a block starts with every even K-tile of the matrix (K-slices hold whole blocks)
+        const bool block_start = SF && ((kt0 + t) & 1) == 0;
         // operand fragments are fetched DEPTH k-steps ahead of the MFMAs that use them
-        constexpr int DEPTH = (TM + TN <= 4) ? 4 : 2;
+        constexpr int DEPTH = (!SF && TM + TN <= 4) ? 4 : 2;             // (SF: the second accumulator set needs the registers)
         v8bf fw[DEPTH][TN], fa[DEPTH][TM];
         auto frags = [&](int ks, int buf) {
             const int chunk = ks * 2 + (lane >> 5);
@@ -553,8 +580,39 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
-                for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks % DEPTH][i], fa[ks % DEPTH][j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TM; ++j) {
+                    if constexpr (SF) {
+                        if (ks == 0 && block_start) {
+                            v16f zero;
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+                            blk[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks % DEPTH][i], fa[ks % DEPTH][j], zero, 0, 0, 0);
+                        } else {
+                            blk[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks % DEPTH][i], fa[ks % DEPTH][j], blk[i][j], 0, 0, 0);
+                        }
+                    } else {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks % DEPTH][i], fa[ks % DEPTH][j], acc[i][j], 0, 0, 0);
+                    }
+                }
+        }
+        if constexpr (SF) {
+            if (((kt0 + t) & 1) == 1 || t + 1 >= KT) {
+                // fold the finished block: register v of a 32x32 accumulator belongs to weight row
+                // 8 (v / 4) + 4 (lane / 32) + v % 4 of the fragment
+#pragma unroll
+                for (int i = 0; i < TN; ++i) {
+                    float sc[16];
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        const float4 q = *reinterpret_cast<const float4*>(wsc + st * BN + wn * WTN + i * 32 + 8 * g4 + 4 * (lane >> 5));
+                        sc[4 * g4] = q.x; sc[4 * g4 + 1] = q.y; sc[4 * g4 + 2] = q.z; sc[4 * g4 + 3] = q.w;
+                    }
+#pragma unroll
+                    for (int j = 0; j < TM; ++j)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[i][j][v] = __builtin_fmaf(sc[v], blk[i][j][v], acc[i][j][v]);
+                }
+            }
         }
     };
 
@@ -575,7 +633,7 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(
     auto mfma_slot = [&](int t) {
         if (t < KT) {
             __builtin_amdgcn_s_setprio(1);
-            mfma_tile(t & 1);
+            mfma_tile(t & 1, t);
             __builtin_amdgcn_s_setprio(0);
         }
     };
@@ -1082,8 +1140,7 @@ static hipError_t launch_cfg(const uint8_t* w_codes, const uint8_t* w_scales, co
     constexpr size_t smem = 2 * (BM + BN) * 128 + 2 * 256 * sizeof(uint2);
     void (*kern)(const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, int64_t, const uint16_t*,
                  const uint8_t*, const uint8_t*, const float*, SvConfig, int64_t, uint16_t*, int64_t, int, float*);
-    static_assert(!(PP && SF), "the FP16-scale format runs on the single-group kernel");
-    if constexpr (PP) kern = gemm_pp_kernel<BM, BN, WGM, WGN, AQ, GB>;
+    if constexpr (PP) kern = gemm_pp_kernel<BM, BN, WGM, WGN, AQ, GB, SF>;
     else kern = gemm_kernel<BM, BN, WGM, WGN, AQ, GB, SF>;
     RAZER_RAISE_LDS_LIMIT(kern, smem);
     const int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
@@ -1319,12 +1376,12 @@ hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, in
 }
 
 // The FP16-scale weight format from 5 activation rows up (bf16 activations): the single-group kernel with
-// bare FP4 operands and per-block folds; 32-, 64- or 128-row activation tiles.  With a workspace, K is cut
+// bare FP4 operands and per-block folds; 32-, 64-, 128- or 256-row activation tiles.  With a workspace, K is cut
 // into slices of whole blocks while the tiles are fewer than the compute units (the rule of gemm_plan, whose
 // tiles are never smaller than these, so gemm_workspace_bytes covers it).
 static int f16_split(int64_t m, int64_t n, int64_t k)
 {
-    const int64_t tiles = m <= 64 ? (n + 255) / 256 : ((m + 127) / 128) * ((n + 127) / 128);
+    const int64_t tiles = m <= 64 ? (n + 255) / 256 : m <= 128 ? (n + 127) / 128 : ((m + 255) / 256) * ((n + 127) / 128);
     const int64_t kt_all = (k + kBK - 1) / kBK;
     int64_t split = 256 / tiles;
     if (split > 8) split = 8;
@@ -1337,11 +1394,14 @@ static hipError_t launch_gemm_f16(SvConfig wcfg, const uint8_t* w_codes, const u
 {
     const SvConfig none{5.0f, 5.0f};
     const int split = workspace ? f16_split(m, n, k) : 1;
-#define RAZER_GEMM_F16(BM, BN, WGM, WGN) \
-    launch_cfg<BM, BN, WGM, WGN, false, false, false, true>(w_codes, w_scales, w_ts, wcfg, n, k, a, nullptr, nullptr, nullptr, none, m, y, ld_y, split, workspace, st)
-    if (m <= 32) return RAZER_GEMM_F16(32, 256, 1, 4);
-    if (m <= 64) return RAZER_GEMM_F16(64, 256, 1, 4);
-    return RAZER_GEMM_F16(128, 128, 2, 2);
+#define RAZER_GEMM_F16(BM, BN, WGM, WGN, PP) \
+    launch_cfg<BM, BN, WGM, WGN, false, PP, false, true>(w_codes, w_scales, w_ts, wcfg, n, k, a, nullptr, nullptr, nullptr, none, m, y, ld_y, split, workspace, st)
+    if (m <= 32) return RAZER_GEMM_F16(32, 256, 1, 4, false);
+    if (m <= 64) return RAZER_GEMM_F16(64, 256, 1, 4, false);
+    if (m <= 128) return RAZER_GEMM_F16(128, 128, 2, 2, false);
+    // above 128 rows: 256 x 128 tiles on the two-group kernel (decode of one K-tile under the matrix instructions
+    // of the other)
+    return RAZER_GEMM_F16(256, 128, 4, 2, true);
 #undef RAZER_GEMM_F16
 }
 

@@ -583,7 +583,7 @@ static int mv_maxw(int s, int g)
 static void mv_geometry(int s, int g, int64_t k, int& nwaves, int& npass, int nb = 1)
 {
     const int64_t slices = (k + 128 * s - 1) / (128 * s);
-    int maxw = mv_maxw(s, g) / nb;                                  // (two fragments: kernels built for half the waves)
+    int maxw = nb == 4 ? 8 : mv_maxw(s, g) / nb;                    // (two / four fragments: kernels built for 8 waves)
     if (maxw > 64 / (g * nb)) maxw = 64 / (g * nb);
     nwaves = (int)(slices < maxw ? slices : maxw);
     npass = (int)((slices + nwaves - 1) / nwaves);
@@ -667,6 +667,14 @@ hipError_t launch_skinny(SvConfig cfg, const uint8_t* codes, const uint8_t* scal
                          hipStream_t st)
 {
     const SkinnyPlan pl = skinny_plan(n, k, m, cfg.f16 != 0);
+    if (pl.in_workgroup && cfg.f16 && m > 32) {
+        // FP16-scale format, 33..64 activation rows: four 16-row fragments, one step per wave and pass, two row groups
+        int nwaves, npass;
+        mv_geometry(1, 2, k, nwaves, npass, 4);
+        launch(mv_kernel<4, 1, 2, false, 8, 1>, (unsigned)(((n + 15) / 16 + 1) / 2), 64 * nwaves, (size_t)2 * nwaves * 4 * 1024, st,
+               codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, cfg.lb, npass);
+        return hipGetLastError();
+    }
     if (pl.in_workgroup) {
         const int nb = m <= 16 ? 1 : 2;
         int nwaves, npass;

@@ -91,11 +91,12 @@ def test_linear_matches_oracle(oracle, m, n, k):
 
 
 @pytest.mark.parametrize("m,n,k", [(5, 40, 128), (16, 300, 1024 + 128), (33, 257, 2048), (64, 100, 4096), (100, 640, 1152),
-                                   (300, 200, 2048 + 384), (129, 8, 128 * 9)])
+                                   (300, 200, 2048 + 384), (129, 8, 128 * 9), (48, 1000, 34944), (50, 72, 128), (64, 4104, 1152)])
 def test_linear_matrix_core_path_matches_oracle(oracle, m, n, k):
-    """Beyond 32 activation rows the format runs on the matrix cores with bare FP4 operands and a per-block
-    fold in fp32 (64- and 128-row tiles; up to 32 rows: the K-in-workgroup small-batch kernel): ragged M and N, odd and
-    even numbers of blocks, every scale word field (zero, subnormal and saturated scales included)."""
+    """From 5 activation rows up the format runs on the matrix cores with bare FP4 operands and a per-block
+    fold in fp32 (up to 64 rows: the K-in-workgroup kernel with one, two or four 16-row fragments; beyond: tiled
+    kernels with K-slices): ragged M and N, odd and even numbers of blocks, several passes per wave, every scale
+    word field (zero, subnormal and saturated scales included)."""
     print("f16-scale matrix-core linear", m, n, k, flush=True)
     rng = np.random.default_rng(3700 + m + n)
     wq = _rand_tensor(rng, n, k)
@@ -109,6 +110,28 @@ def test_linear_matrix_core_path_matches_oracle(oracle, m, n, k):
     y64, _ = oracle.linear(wq, a_bf16=a)
     assert max_rel_err(dev_to_bf16_bits(buf[:, :n]), y64) <= TOL
     assert torch.all(buf[:, n:] == 2.0)
+
+
+@pytest.mark.parametrize("m,n,k", [(300, 12776, 1152), (2000, 4000, 128 * 9), (1030, 6464, 128), (2048, 11008, 1024 + 128),
+                                   (4100, 4096 + 8, 256)])
+def test_linear_two_group_kernel_many_tiles(oracle, m, n, k):
+    """From about 192 tiles of 256 x 128 up the format runs on the two-group LDS-staged kernel (bare FP4 operands,
+    second accumulator set per block, fold after every second K-tile): ragged M, N; one block, odd and even
+    numbers of blocks; every scale word field.  Sampled outputs plus the last rows and columns."""
+    print("f16-scale two-group kernel", m, n, k, flush=True)
+    rng = np.random.default_rng(3900 + m + n + k)
+    wq = _rand_tensor(rng, n, k)
+    wq[1][0, 0] = 0x0000
+    wq[1][-1, -1] = 0xFFFF
+    wt = razer.RazerTensor.from_host(*wq, F16, (5.0, 8.0))
+    a = synth.activation(m, k, seed=3901 + m + k, outlier_frac=0.01)
+    y = razer.razer_linear(wt, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([synth.sample_indices(m, 40, 9400), np.arange(m - 6, m), np.arange(0, 3)]))
+    cols = np.unique(np.concatenate([synth.sample_indices(n, 160, 9401), np.arange(n - 36, n), np.arange(0, 6)]))
+    y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=cols)
+    got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+    assert max_rel_err(got, y64) <= TOL
 
 
 MV_SHAPES = [None, (1, 1, 2), (1, 1, 4), (1, 2, 2), (1, 2, 4), (1, 2, 8)]
