@@ -507,7 +507,12 @@ def main():
                 for mm in (16, 64, 2048):
                     actm = {k: make_act(mm, k, 2100 + mm) for k in {k for _, _, k in layers}}
                     outm = [torch.empty((mm, n), dtype=torch.bfloat16, device="cuda") for _, n, _ in layers]
-                    plansm = [[razer.prepare_linear(t, actm[t.cols], outm[j]) for j, t in enumerate(cp)] for cp in sets]
+                    # the same 4 calls as every other leg ({q,k,v} and {gate,up} through razer_linear_grouped, which is
+                    # one launch each up to 32 rows and the sequence of single calls beyond)
+                    plansm = [[razer.prepare_linear_grouped(cp[0:3], actm[cp[0].cols], outm[0:3]),
+                               razer.prepare_linear(cp[3], actm[cp[3].cols], outm[3]),
+                               razer.prepare_linear_grouped(cp[4:6], actm[cp[4].cols], outm[4:6]),
+                               razer.prepare_linear(cp[6], actm[cp[6].cols], outm[6])] for cp in sets]
 
                     def stepm(i):
                         for call in plansm[i % n_copies]:
@@ -516,8 +521,8 @@ def main():
                     flm = sum(2.0 * mm * n * k for _, n, k in layers)
                     legs["linear_m%d_block128_fp16_scale" % mm] = {
                         "TFLOP/s": flm / msm / 1e9, "ms_per_step": msm,
-                        "note": "7 razer_linear calls; up to 32 rows passes of the GEMV kernels, beyond that bare FP4 operands on the "
-                                "matrix cores, each 128-element block's partial sums folded with its FP16 scale in fp32"}
+                        "note": "bare FP4 operands on the matrix cores, each 128-element block's partial sums folded with its "
+                                "FP16 scale in fp32: K-in-workgroup kernel up to 64 rows, LDS-staged tiled kernels beyond"}
                     del plansm, actm, outm
             del sets, plans
             torch.cuda.empty_cache()
