@@ -160,6 +160,9 @@ razer_status razer_dequant(const razer_tensor *t, void *out, int32_t dtype, int6
  * is non-NULL.  Products are accumulated in fp32 (bf16 matrix cores for large
  * m, wavefront dot products for m <= 4, a decode-once MFMA kernel in between), scaled by the
  * tensor scale(s) and rounded to bf16:  y_bf16 device [m][ld_y], ld_y >= N.
+ * The first call on a device that reaches one of the large-tile matrix-core kernels raises that kernel's
+ * dynamic-LDS limit (hipFuncSetAttribute, once per kernel and device, race-free): a caller that captures
+ * a stream into a HIP graph makes one ordinary call of each shape first.
  * workspace: device, 16-byte aligned, >= razer_workspace_bytes(RAZER_OP_LINEAR, N, K, m) bytes
  * (non-zero where K is split over workgroups and the slices meet in fp32: W4A16 with 5 <= m <= 32,
  * and m > 32 with too few output tiles to occupy the GPU -- ask razer_workspace_bytes; else may be

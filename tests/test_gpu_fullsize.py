@@ -71,11 +71,11 @@ def test_config1_single_layer_4096(oracle):
 
 @pytest.mark.parametrize("name,n,k,idx", [("q", 4096, 4096, 0), ("gate", 11008, 4096, 4), ("down", 4096, 11008, 6)])
 def test_config2_3_llama7b_layer(oracle, name, n, k, idx):
-    _say("config 2/3: %s %dx%d, encode + M in {1,4,16} whole + M in {512,2048} sampled" % (name, n, k))
+    _say("config 2/3: %s %dx%d, encode + M in {1,2,4,16} whole + M in {512,2048} sampled" % (name, n, k))
     w = synth.weight(n, k, seed=2000 + idx, outlier_frac=0.001)
     wt, wq = _encode_and_check(oracle, w, W, SV)
     del w
-    for m in (1, 4, 16):
+    for m in (1, 2, 4, 16):
         _check_linear(oracle, wq, wt, m, 2100 + m, sampled=False)
     for m in (512, 2048):
         _check_linear(oracle, wq, wt, m, 2100 + m, sampled=True)
