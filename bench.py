@@ -300,7 +300,8 @@ def main():
     pool.random_(0, 256, generator=gen)
     sink = torch.zeros(64, dtype=torch.int32, device="cuda")
     ceil = {}
-    for label, size in (("9.4MB", 4096 * 4096 * 9 // 16), ("50.8MB", dom_bytes), ("264MB", 2 * 28672 * 8192 * 9 // 16)):
+    for label, size in (("9.4MB", 4096 * 4096 * 9 // 16), ("25.4MB", 4096 * 11008 * 9 // 16), ("28.3MB", 3 * 4096 * 4096 * 9 // 16),
+                        ("50.8MB", dom_bytes), ("264MB", 2 * 28672 * 8192 * 9 // 16)):
         size = size // 4096 * 4096
         slots = [pool[o:o + size] for o in range(0, pool.numel() - size + 1, size)]
         best = None
@@ -315,6 +316,11 @@ def main():
         ceil[label] = {"bytes": size, "workgroups": wgs, "per_dispatch_us": disp * 1e3, "per_dispatch_GB/s": size / disp / 1e6,
                        "back_to_back_us": best[1] * 1e3, "back_to_back_GB/s": size / best[1] / 1e6}
     del pool, slots
+    # the M=1 step made of four load-only kernels of the sizes of its four launches ({q,k,v}, o, {gate,up}, down):
+    # what a sequence of four dependent launches that only read their weights would reach
+    step_ceiling_us = sum(ceil[lab]["per_dispatch_us"] for lab in ("28.3MB", "9.4MB", "50.8MB", "25.4MB"))
+    ceil["step_of_four_load_only_kernels"] = {"us": step_ceiling_us, "GB/s": bytes1 / step_ceiling_us / 1e3,
+                                              "frac_hbm": bytes1 / step_ceiling_us / 1e3 / HBM_PEAK_GBS}
     legs["ceiling_stream_read"] = ceil
     fl_box = [0.0]
 
@@ -581,6 +587,7 @@ def main():
                      "measured_ceiling_GB/s": ceil["50.8MB"]["per_dispatch_GB/s"],
                      "frac_of_measured_ceiling": ceil["50.8MB"]["per_dispatch_us"] / (dom_ms * 1e3),
                      "step_frac": gbs / HBM_PEAK_GBS,
+                     "step_frac_of_measured_ceiling": step_ceiling_us / (ms1 * 1e3),
                      "traffic_source": "profiles/gemv_m1_llama7b_hbm_traffic.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
                                        "command, scaled by a plain copy; parsed from that file, not measured in this run"},
         "cpu_baseline": cpu,
