@@ -293,6 +293,63 @@ def test_config2_3_grouped_launches_as_benchmarked(oracle, m):
             assert err <= TOL, err
 
 
+@pytest.mark.parametrize("m", [1, 4])
+def test_prepacked_layout_as_benchmarked(oracle, m):
+    """bench.py's pre-packed legs: the Llama-7B-shaped layer repacked with razer_prepack, {q,k,v} and {gate,up} as
+    grouped calls, o and down as single calls -- every output bit-identical to the canonical layout's, and the down
+    projection (the long-row shape the layout is meant for) against the oracle."""
+    _say("pre-packed layout at full size, m=%d" % m)
+    for name, ns, k, seed in (("qkv", (4096, 4096, 4096), 4096, 8300), ("o", (4096,), 4096, 8310),
+                              ("gate_up", (11008, 11008), 4096, 8320), ("down", (4096,), 11008, 8330)):
+        a = synth.activation(m, k, seed=2100 + m + k)
+        a_dev = bf16_bits_to_dev(a)
+        wqs = [_rand_packed(n, k, seed=seed + i + m) for i, n in enumerate(ns)]
+        wts = [razer.RazerTensor.from_host(*wq, W, SV) for wq in wqs]
+        pks = [razer.razer_prepack(w) for w in wts]
+        if len(ns) == 1:
+            ys_c, ys_p = [razer.razer_linear(wts[0], a_dev)], [razer.razer_linear(pks[0], a_dev)]
+        else:
+            ys_c, ys_p = razer.razer_linear_grouped(wts, a_dev), razer.razer_linear_grouped(pks, a_dev)
+        torch.cuda.synchronize()
+        for yc, yp in zip(ys_c, ys_p):
+            assert torch.equal(yc, yp), name
+        if name == "down":
+            err = max_rel_err(dev_to_bf16_bits(ys_p[0]), oracle.linear(wqs[0], a_bf16=a)[0])
+            _say("   down, pre-packed, m=%d: max rel err %.2e" % (m, err))
+            assert err <= TOL, err
+
+
+@pytest.mark.parametrize("m", [1, 16, 64, 2048])
+def test_fp16_scale_format_as_benchmarked(oracle, m):
+    """bench.py's FP16-scale legs: {gate,up}-shaped tensors (2 x 11008 x 4096, blocks of 128, random scale words) as
+    one razer_linear_grouped call -- grouped GEMV at M = 1, the grouped K-in-workgroup kernel at 16, per matrix the
+    four-fragment kernel at 64 and the two-group tiled kernel at 2048.  Whole outputs up to M = 16, sampled beyond."""
+    from paper_2501_04052_amd import binding
+    _say("FP16-scale format at full size, m=%d" % m)
+    n, k = 11008, 4096
+    rng = np.random.default_rng(8400 + m)
+    wqs = []
+    for i in range(2):
+        codes = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
+        words = rng.integers(0, 65536, size=(n, k // 128), dtype=np.uint16)
+        wqs.append((codes, words, np.float32(2.0 ** -10)))
+    wts = [razer.RazerTensor.from_host(*wq, binding.WEIGHT_F16, SV) for wq in wqs]
+    a = synth.activation(m, k, seed=8401 + m)
+    ys = razer.razer_linear_grouped(wts, bf16_bits_to_dev(a))
+    torch.cuda.synchronize()
+    if m <= 16:
+        rows, cols = np.arange(m), np.arange(n)
+    else:
+        rows = np.unique(np.concatenate([synth.sample_indices(m, 32, 9500), [0, m - 1]]))
+        cols = np.unique(np.concatenate([synth.sample_indices(n, 128, 9501), [0, n - 1]]))
+    for wq, y in zip(wqs, ys):
+        y64, _ = oracle.linear(wq, a_bf16=a, rows=rows, cols=cols)
+        got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+        err = max_rel_err(got, y64)
+        _say("   m=%d: %d x %d outputs, max rel err %.2e" % (m, len(rows), len(cols), err))
+        assert err <= TOL, err
+
+
 def test_config4_grouped_launches_as_benchmarked(oracle):
     """70B-shaped {q,k,v} (8192 + 1024 + 1024 rows) as one grouped call at M = 1, 8 and 4096."""
     wqs = [_rand_packed(n, 8192, seed=8200 + i) for i, n in enumerate((8192, 1024, 1024))]
