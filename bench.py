@@ -413,8 +413,8 @@ def main():
         aq = razer.razer_quantize(a, razer.ACT, (5.0, 0.0))
         ms_e = time_region(lambda i: razer.razer_quantize(a, razer.ACT, (5.0, 0.0), out=aq), 10, 2)
         y = torch.empty((4096, 11008), dtype=torch.bfloat16, device="cuda")
-        # with room for the decoded activations (the library then decodes them once and runs the weight-only
-        # kernel), and with a token workspace (the single fused kernel that decodes both operands per tile)
+        # with the workspace the W4A4 query asks for (the library then decodes the activations once and runs the
+        # weight-only path), and with a token workspace (the single fused kernel that decodes both operands per tile)
         ws_big = torch.empty(razer.razer_workspace_bytes(binding.OP_LINEAR_W4A4, 11008, 4096, 4096), dtype=torch.uint8, device="cuda")
         ws_small = torch.empty(256, dtype=torch.uint8, device="cuda")
         ms_l = time_region(lambda i: razer.razer_linear(packed[4], aq, out=y, workspace=ws_big), 5, 2)

@@ -111,12 +111,12 @@ enum { RAZER_OP_QUANTIZE = 0, RAZER_OP_DEQUANT = 1, RAZER_OP_LINEAR = 2, RAZER_O
  * sums [slices][m][rows] meet in the workspace and are added in slice order
  * (the number of slices depends on the shape: always ask, do not estimate);
  * 0 means the workspace may be NULL.
- * RAZER_OP_LINEAR_W4A4: what lets razer_linear with a RaZeR activation operand (a_q) take its
- * faster form on large problems -- the activation tensor decoded once into the workspace as bf16
- * (m x cols x 2 bytes), then the weight-only kernel; never less than RAZER_OP_LINEAR's figure, with
- * which (or with any smaller workspace that satisfies it) the same call runs the single fused
- * kernel instead.  Both forms multiply the same exactly decoded bf16 operands and accumulate in
- * fp32; only the order of the sum differs.                                    */
+ * RAZER_OP_LINEAR_W4A4: what lets razer_linear with a RaZeR activation operand (a_q) take its faster
+ * form -- the activation tensor decoded once into the workspace as bf16 (m x cols x 2 bytes, rounded
+ * up to 256, plus a 256-byte cell for the product of the two tensor scales), then the weight-only
+ * path for this m, whose own RAZER_OP_LINEAR figure is included.  With any smaller workspace that
+ * satisfies RAZER_OP_LINEAR the same call runs the single fused kernel instead.  Both forms multiply
+ * the same exactly decoded bf16 operands and accumulate in fp32; only the order of the sum differs. */
 size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m);
 
 /* The same for razer_linear_grouped with `count` weight matrices of rows[i] x cols (rows is a HOST

@@ -130,6 +130,10 @@ __global__ void fill_zero_bf16_kernel(uint16_t* y, int64_t m, int64_t n, int64_t
     if (i < m * n) y[(i / n) * ld + (i % n)] = 0;
 }
 
+// W4A4 in two steps: the decoded activations (bf16 [m][cols], rounded up to 256 bytes), one 256-byte cell for the
+// combined tensor scale, then whatever the weight-only path itself needs for these sizes.
+size_t w4a4_staged_bytes(int64_t rows, int64_t cols, int64_t m);
+
 }  // namespace
 
 extern "C" {
@@ -156,14 +160,24 @@ size_t razer_workspace_bytes(int op, int64_t rows, int64_t cols, int64_t m)
             const size_t a = skinny_workspace_bytes(rows, cols, m), b = gemm_workspace_bytes(rows, cols, m);
             return a > b ? a : b;
         }
-        case RAZER_OP_LINEAR_W4A4: {           // room for the activations decoded to bf16, where that path is taken
-            const size_t base = razer_workspace_bytes(RAZER_OP_LINEAR, rows, cols, m);
-            const size_t staged = gemm_w4a4_staged(rows, cols, m) ? (size_t)m * (size_t)cols * 2u : 0u;
-            return staged > base ? staged : base;
-        }
+        case RAZER_OP_LINEAR_W4A4:             // room for the activations decoded to bf16 ahead of the weight-only path
+            return w4a4_staged_bytes(rows, cols, m);
         default: return 0;
     }
 }
+
+}  // extern "C"
+
+namespace {
+size_t w4a4_staged_bytes(int64_t rows, int64_t cols, int64_t m)
+{
+    const size_t base = razer_workspace_bytes(RAZER_OP_LINEAR, rows, cols, m);
+    if (rows <= 0 || cols <= 0 || m <= 0) return base;
+    return (((size_t)m * (size_t)cols * 2u + 255u) & ~(size_t)255u) + 256u + base;
+}
+}  // namespace
+
+extern "C" {
 
 size_t razer_workspace_bytes_grouped(int32_t count, const int64_t* rows, int64_t cols, int64_t m)
 {
@@ -255,6 +269,22 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
     hipStream_t st = (hipStream_t)hip_stream;
     if (m == 0 || n == 0) return RAZER_OK;
     hipError_t e;
+    if (a_q && k > 0 && !wsv.f16 && workspace && aligned16(workspace) && workspace_bytes >= w4a4_staged_bytes(n, k, m)) {
+        // W4A4 with room in the workspace: the activation tensor is decoded ONCE to bf16 (block scale x element:
+        // the values the fused kernel stages, exact for the paper's special values) and the layer runs on the
+        // weight-only path for this m, with the product of the two tensor scales in place of the weights' scale.
+        // Same products, fp32 accumulation; only the order of the sum differs from the fused kernel's.
+        uint8_t* wsb = (uint8_t*)workspace;
+        const size_t a_bytes = ((size_t)m * (size_t)k * 2u + 255u) & ~(size_t)255u;
+        float* prod = (float*)(wsb + a_bytes);
+        e = launch_dequant(RAZER_FMT_ACT, asv, a_q->codes, a_q->scales, nullptr, m, k, wsb, 1, k, st, w->tensor_scale,
+                           a_q->tensor_scale, prod);
+        if (e != hipSuccess) return RAZER_ERR_HIP;
+        razer_tensor w2 = *w;
+        w2.tensor_scale = prod;
+        const size_t rest = workspace_bytes - a_bytes - 256u;
+        return razer_linear(&w2, wsb, nullptr, m, y_bf16, ld_y, rest ? wsb + a_bytes + 256u : nullptr, rest, hip_stream);
+    }
     if (k == 0) {                                                        // empty contraction: Y = 0
         const int64_t total = m * n;
         launch(fill_zero_bf16_kernel, (unsigned)((total + 255) / 256), 256, 0, st, (uint16_t*)y_bf16, m, n, ld_y);
@@ -284,14 +314,6 @@ razer_status razer_linear(const razer_tensor* w, const void* a_bf16, const razer
     } else if (!a_q && m <= kGemvDirectMaxM) {
         e = launch_gemv(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)a_bf16, m,
                         (uint16_t*)y_bf16, ld_y, st);
-    } else if (a_q && gemm_w4a4_staged(n, k, m) && workspace && aligned16(workspace) &&
-               workspace_bytes >= (size_t)m * (size_t)k * 2u) {
-        // W4A4 with room for the decoded activations: block scale x element of the whole activation tensor as
-        // bf16 (exact), then the W4A16 register-decode kernel with both tensor scales in its epilogue
-        e = launch_dequant(RAZER_FMT_ACT, asv, a_q->codes, a_q->scales, nullptr, m, k, workspace, 1, k, st);
-        if (e == hipSuccess)
-            e = launch_gemm(wsv, w->codes, w->scales, w->tensor_scale, n, k, (const uint16_t*)workspace, asv, nullptr,
-                            nullptr, a_q->tensor_scale, m, (uint16_t*)y_bf16, ld_y, nullptr, st);
     } else {
         const size_t need = gemm_workspace_bytes(n, k, m);
         if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return RAZER_ERR_WORKSPACE;

@@ -13,10 +13,12 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict_
                                                       const uint8_t* __restrict__ scales,
                                                       const float* __restrict__ tensor_scale, SvConfig cfg,
                                                       int64_t rows, int64_t cols, void* __restrict__ out,
-                                                      int64_t ld)
+                                                      int64_t ld, const float* __restrict__ prod_a,
+                                                      const float* __restrict__ prod_b, float* __restrict__ prod_out)
 {
     const int64_t nb = cols / kBlock;
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid == 0 && prod_out) *prod_out = (*prod_a) * (*prod_b);
     if (gid >= rows * nb) return;
     const int64_t r = gid / nb, b = gid - r * nb;
     const float ts = tensor_scale ? *tensor_scale : 1.0f;
@@ -62,12 +64,12 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t* __restrict_
 
 hipError_t launch_dequant(int fmt, SvConfig cfg, const uint8_t* codes, const uint8_t* scales,
                           const float* tensor_scale, int64_t rows, int64_t cols, void* out, int dtype_bf16,
-                          int64_t ld, hipStream_t st)
+                          int64_t ld, hipStream_t st, const float* prod_a, const float* prod_b, float* prod_out)
 {
     const int64_t nblk = rows * (cols / kBlock);
     if (nblk == 0) return hipSuccess;
     const unsigned grid = (unsigned)((nblk + 255) / 256);
-#define RAZER_DQ(F, B) launch(dequant_kernel<F, B>, grid, 256, 0, st, codes, scales, tensor_scale, cfg, rows, cols, out, ld)
+#define RAZER_DQ(F, B) launch(dequant_kernel<F, B>, grid, 256, 0, st, codes, scales, tensor_scale, cfg, rows, cols, out, ld, prod_a, prod_b, prod_out)
     if (fmt == 0)      { if (dtype_bf16) RAZER_DQ(0, true); else RAZER_DQ(0, false); }
     else if (fmt == 1) { if (dtype_bf16) RAZER_DQ(1, true); else RAZER_DQ(1, false); }
     else               { if (dtype_bf16) RAZER_DQ(2, true); else RAZER_DQ(2, false); }

@@ -111,10 +111,7 @@ __device__ __forceinline__ void store_tile(const v16f (&acc)[TN][TM], const floa
                                            int64_t wm0, int64_t wn0, int64_t m, int64_t n, uint16_t* y,
                                            int64_t ld_y, int lane)
 {
-    // W4A4 with both operands decoded in the flipped domain: the two negations cancel; bf16 activations
-    // (true sign) against flipped weights: negate -- with the activations' tensor scale when they are a
-    // decoded RaZeR tensor (a_ts given)
-    const float scale = AQ ? (*w_ts) * (*a_ts) : (a_ts ? -((*w_ts) * (*a_ts)) : -(*w_ts));
+    const float scale = AQ ? (*w_ts) * (*a_ts) : -(*w_ts);
     const int hi = lane >> 5;
 #pragma unroll
     for (int i = 0; i < TN; ++i)
@@ -709,7 +706,7 @@ __device__ __forceinline__ void gemm_rb_body(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
     uint16_t* __restrict__ y, int64_t ld_y, int tile_m, int tile_n, float* __restrict__ partial = nullptr,
-    int kslice = 0, int kt_per_slice = 0x7FFFFFFF, int lb = 4, const float* __restrict__ a_ts = nullptr)
+    int kslice = 0, int kt_per_slice = 0x7FFFFFFF, int lb = 4)
 {
     // MT: 32-row activation groups per tile (8, or 4 / 2 for at most 128 / 64 activation rows)
     static_assert(MT == 8 || ((MT == 4 || MT == 2) && KG == 1), "activation tile height");
@@ -1015,7 +1012,7 @@ __device__ __forceinline__ void gemm_rb_body(
         if (partial)                                    // K-slices of one output meet in the workspace [slice][m][n]
             store_tile_partial<MT, 1>(acc, m0, n0 + 32 * wave, m, n, partial + (int64_t)kslice * m * n, lane);
         else
-            store_tile<MT, 1, false>(acc, w_ts, a_ts, m0, n0 + 32 * wave, m, n, y, ld_y, lane);
+            store_tile<MT, 1, false>(acc, w_ts, nullptr, m0, n0 + 32 * wave, m, n, y, ld_y, lane);
     } else {
         // The two K groups hold partial sums of the same 256 x 32 outputs.  Once every wave's copies have
         // landed and its fragment reads have returned (the wait above, then this barrier) the activation
@@ -1055,7 +1052,7 @@ __device__ __forceinline__ void gemm_rb_body(
                 keep[0][j][4 * q + 2] += t.z;
                 keep[0][j][4 * q + 3] += t.w;
             }
-        store_tile<MT / 2, 1, false>(keep, w_ts, a_ts, m0 + 128 * kg, n0 + 32 * wn, m, n, y, ld_y, lane);
+        store_tile<MT / 2, 1, false>(keep, w_ts, nullptr, m0 + 128 * kg, n0 + 32 * wn, m, n, y, ld_y, lane);
     }
 }
 
@@ -1070,12 +1067,11 @@ template <int NW, int S, int KG = 1, int MT = 8, bool GB = false>
 __global__ __launch_bounds__(64 * NW, (rb_waves_per_simd<NW, KG, MT>())) void gemm_rb_kernel(
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, const float* __restrict__ w_ts,
     float sv0, float sv1, int64_t n, int64_t k, const uint16_t* __restrict__ a, int64_t m,
-    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m, float* __restrict__ partial, int kt_per_slice, int lb,
-    const float* __restrict__ a_ts)
+    uint16_t* __restrict__ y, int64_t ld_y, int tiles_m, float* __restrict__ partial, int kt_per_slice, int lb)
 {
     gemm_rb_body<NW, S, KG, MT, GB>(w_codes, w_scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y,
                                     (int)(blockIdx.x % tiles_m), (int)(blockIdx.x / tiles_m), partial,
-                                    (int)blockIdx.y, kt_per_slice, lb, a_ts);
+                                    (int)blockIdx.y, kt_per_slice, lb);
 }
 
 // Up to four weight matrices against the same activations in one launch (fused q/k/v, gate/up): the
@@ -1112,7 +1108,7 @@ __global__ __launch_bounds__(64 * NW, (rb_waves_per_simd<NW, KG, MT>())) void ge
 template <int NW, int S, int KG = 1, int MT = 8, bool GB = false>
 static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                             int64_t n, int64_t k, const uint16_t* a, int64_t m, uint16_t* y, int64_t ld_y,
-                            hipStream_t st, int split = 1, float* workspace = nullptr, const float* a_ts = nullptr)
+                            hipStream_t st, int split = 1, float* workspace = nullptr)
 {
     constexpr int BM = 32 * MT, BN = 32 * NW / KG;
     constexpr size_t smem = S * (KG * BM * 128 + NW * 1280) + 256 * sizeof(uint2);
@@ -1124,10 +1120,9 @@ static hipError_t launch_rb(const uint8_t* w_codes, const uint8_t* w_scales, con
     const int kt_all = (int)((k + kBK - 1) / kBK), kt_per = (kt_all + split - 1) / split;
     const int slices = (kt_all + kt_per - 1) / kt_per;
     launch(kern, dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(64 * NW), smem, st, w_codes, w_scales, w_ts, wcfg.sv0, wcfg.sv1, n, k, a, m, y, ld_y, tiles_m, slices > 1 ? workspace : nullptr,
-        slices > 1 ? kt_per : 0x7FFFFFFF, wcfg.lb, a_ts);
+        slices > 1 ? kt_per : 0x7FFFFFFF, wcfg.lb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || slices == 1) return e;
-    if (a_ts) return hipErrorInvalidValue;                               // (decoded RaZeR activations run unsplit)
     return launch_slice_reduce(workspace, w_ts, nullptr, m, n, slices, y, ld_y, st);
 }
 
@@ -1235,16 +1230,6 @@ size_t gemm_workspace_bytes(int64_t n, int64_t k, int64_t m)
     return need;
 }
 
-// W4A4 as two launches -- the activation tensor decoded once into bf16 (m x k, in the caller's workspace), then
-// the register-decode kernel with the activations' tensor scale in its epilogue -- pays where that kernel runs
-// unsplit on many tiles: the fused W4A4 kernel decodes every activation once per 256 weight rows.
-bool gemm_w4a4_staged(int64_t n, int64_t k, int64_t m)
-{
-    if (m <= 128 || k > kRbMaxK) return false;
-    const GemmPlan p = gemm_plan(m, n, k, true);
-    return p.split == 1 && (p.tile == 5 || p.tile == 6 || p.tile == 7);
-}
-
 template <bool AQ, bool GB>
 static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts, SvConfig wcfg,
                                 int64_t n, int64_t k, const uint16_t* a, const uint8_t* a_codes,
@@ -1269,9 +1254,9 @@ static hipError_t launch_gemm_t(const uint8_t* w_codes, const uint8_t* w_scales,
     if constexpr (!AQ) {
         if (p.tile == 8) return launch_rb<4, 2, 1, 2, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, p.split, workspace);
         if (p.tile == 9) return launch_rb<4, 2, 1, 4, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, p.split, workspace);
-        if (p.tile == 5) return launch_rb<8, 2, 1, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, 1, nullptr, a_ts);
-        if (p.tile == 7) return launch_rb<8, 2, 2, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, 1, nullptr, a_ts);
-        return launch_rb<4, 2, 1, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st, 1, nullptr, a_ts);
+        if (p.tile == 5) return launch_rb<8, 2, 1, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+        if (p.tile == 7) return launch_rb<8, 2, 2, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
+        return launch_rb<4, 2, 1, 8, GB>(w_codes, w_scales, w_ts, wcfg, n, k, a, m, y, ld_y, st);
     }
     return hipErrorInvalidValue;
 }

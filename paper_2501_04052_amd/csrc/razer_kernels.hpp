@@ -40,10 +40,12 @@ hipError_t launch_quantize(int fmt, SvConfig cfg, const void* x, int dtype_bf16,
                            int64_t ld, uint8_t* codes, uint8_t* scales, float* tensor_scale, int given,
                            void* ws, hipStream_t st);
 
-// Decoder to fp32 or bf16 (tensor_scale == nullptr: block scale x element only).
+// Decoder to fp32 or bf16 (tensor_scale == nullptr: block scale x element only).  prod_out != nullptr: the
+// launch also leaves *prod_a x *prod_b there (one fp32 rounding) -- the combined tensor scale of a W4A4 layer.
 hipError_t launch_dequant(int fmt, SvConfig cfg, const uint8_t* codes, const uint8_t* scales,
                           const float* tensor_scale, int64_t rows, int64_t cols, void* out, int dtype_bf16,
-                          int64_t ld, hipStream_t st);
+                          int64_t ld, hipStream_t st, const float* prod_a = nullptr, const float* prod_b = nullptr,
+                          float* prod_out = nullptr);
 
 // Y[m][n] = A[m][:] . W[n][:], m <= kGemvMaxM: wavefront dot products, HBM-bound (4 rows per pass).
 constexpr int kGemvMaxM = 16;
@@ -86,10 +88,7 @@ size_t skinny_grouped_workspace_bytes(int count, const GemvProblem* p, int64_t k
 // bf16 (a != nullptr) or RaZeR activation-format (a_codes != nullptr).
 // Problems with few output tiles split K over workgroups; the slices meet in an fp32 workspace of
 // gemm_workspace_bytes(n, k, m) bytes (0 when K is not split).
-// a with a_ts: bf16 activations that are a decoded RaZeR tensor without its tensor scale (gemm_w4a4_staged()
-// shapes only: many output tiles, K unsplit); a_ts then enters the epilogue.
 size_t gemm_workspace_bytes(int64_t n, int64_t k, int64_t m);
-bool gemm_w4a4_staged(int64_t n, int64_t k, int64_t m);
 hipError_t launch_gemm(SvConfig wcfg, const uint8_t* w_codes, const uint8_t* w_scales, const float* w_ts,
                        int64_t n, int64_t k, const uint16_t* a, SvConfig acfg, const uint8_t* a_codes,
                        const uint8_t* a_scales, const float* a_ts, int64_t m, uint16_t* y, int64_t ld_y,

@@ -81,12 +81,13 @@ def test_workspace_sizes(razer):
     assert razer.razer_workspace_bytes(2, 4096, 4096, 2048) == 0
     assert razer.razer_workspace_bytes(2, 4100, 4096, 16) == 8 * 16 * 4100 * 4     # (a shape the tuned table does not list)
     assert razer.razer_workspace_bytes(2, 4096, 512, 16) == 0
-    # W4A4 query: room for the activations decoded to bf16 where the many-tile weight-only kernel serves the
-    # shape, otherwise (few tiles, few rows) the plain linear figure
-    assert razer.razer_workspace_bytes(3, 11008, 4096, 4096) == 4096 * 4096 * 2
-    assert razer.razer_workspace_bytes(3, 4096, 4096, 2048) == 2048 * 4096 * 2
-    for n, k, m in ((4096, 4096, 64), (4096, 4096, 128), (512, 4096, 1024), (4096, 4096, 16)):
-        assert razer.razer_workspace_bytes(3, n, k, m) == razer.razer_workspace_bytes(2, n, k, m)
+    # W4A4 query: room for the activations decoded to bf16 (rounded up to 256 bytes), one 256-byte cell for the
+    # combined tensor scale, plus what the weight-only path needs for the same sizes
+    for n, k, m in ((11008, 4096, 4096), (4096, 4096, 2048), (4096, 4096, 64), (4100, 4096, 16), (512, 4096, 1024), (4096, 4096, 1),
+                    (40, 96, 3)):
+        a_bytes = (m * k * 2 + 255) // 256 * 256
+        assert razer.razer_workspace_bytes(3, n, k, m) == a_bytes + 256 + razer.razer_workspace_bytes(2, n, k, m)
+    assert razer.razer_workspace_bytes(3, 4096, 4096, 0) == 0
 
 
 def test_grouped_workspace_query_covers_single_launch_and_fallback(razer):

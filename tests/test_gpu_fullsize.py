@@ -112,9 +112,10 @@ def test_config5_w4a4(oracle):
     y64, _ = oracle.linear(wq, a_q=aq, rows=rows, cols=cols)
     # both forms of the call: with room for the decoded activations (the binding's default), and with a token
     # workspace, which keeps the single fused kernel
-    assert razer.razer_workspace_bytes(binding.OP_LINEAR_W4A4, 11008, 4096, 4096) == 4096 * 4096 * 2
+    assert razer.razer_workspace_bytes(binding.OP_LINEAR_W4A4, 11008, 4096, 4096) == 4096 * 4096 * 2 + 256
     for label, ws in (("decoded activations + weight-only kernel", None),
-                      ("fused kernel", torch.empty(256, dtype=torch.uint8, device="cuda"))):
+                      ("fused kernel", torch.empty(max(256, razer.razer_workspace_bytes(binding.OP_LINEAR, 11008, 4096, 4096)),
+                                                   dtype=torch.uint8, device="cuda"))):
         y = razer.razer_linear(wt, at, workspace=ws)
         torch.cuda.synchronize()
         got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
@@ -126,13 +127,13 @@ def test_config5_w4a4(oracle):
 @pytest.mark.parametrize("m,n,k,ablock", [(300, 12776, 1088, 16), (2000, 4000, 1056, 16), (4100, 4096 + 8, 160, 16),
                                           (8192, 2048 + 40, 32, 16), (2048, 11008, 1024 + 64, 32), (1030, 6400 + 64, 4096, 64)])
 def test_w4a4_decoded_activations_then_weight_only_kernel(oracle, m, n, k, ablock):
-    """W4A4 on shapes where the library, given room for them, decodes the activations once into bf16 and
-    runs the register-decode weight-only kernel (128- and 256-wide tiles, the two-K-group round; ragged M, N,
-    K; activation blocks of 16, 32, 64): random code and scale bytes on both operands, sampled outputs
-    against the oracle, and the same call with a token workspace (fused kernel) against the same values."""
+    """W4A4 with room in the workspace: the library decodes the activations once into bf16 and runs the weight-only
+    path (here the register-decode kernel: 128- and 256-wide tiles, the two-K-group round; ragged M, N, K;
+    activation blocks of 16, 32, 64): random code and scale bytes on both operands, sampled outputs against the
+    oracle, and the same call with a token workspace (fused kernel) against the same values."""
     _say("w4a4 decoded-activation path m=%d n=%d k=%d activation block %d" % (m, n, k, ablock))
     need = razer.razer_workspace_bytes(binding.OP_LINEAR_W4A4, n, k, m)
-    assert need == m * k * 2, "shape is meant to take the decoded-activation path"
+    assert need == (m * k * 2 + 255) // 256 * 256 + 256 + razer.razer_workspace_bytes(binding.OP_LINEAR, n, k, m)
     rng = np.random.default_rng(7300 + m + n + k)
     wq = (rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8), rng.integers(0, 256, size=(n, k // 16), dtype=np.uint8),
           np.float32(2.0 ** -9))
@@ -144,7 +145,8 @@ def test_w4a4_decoded_activations_then_weight_only_kernel(oracle, m, n, k, abloc
     rows = np.unique(np.concatenate([synth.sample_indices(m, 40, 9300), np.arange(m - 6, m), np.arange(0, 3)]))
     cols = np.unique(np.concatenate([synth.sample_indices(n, 160, 9301), np.arange(n - 36, n), np.arange(0, 6)]))
     y64, _ = oracle.linear(wq, a_q=aq, rows=rows, cols=cols)
-    for label, ws in (("decoded", None), ("fused", torch.empty(256, dtype=torch.uint8, device="cuda"))):
+    fused_ws = torch.empty(max(256, razer.razer_workspace_bytes(binding.OP_LINEAR, n, k, m)), dtype=torch.uint8, device="cuda")
+    for label, ws in (("decoded", None), ("fused", fused_ws)):
         y = razer.razer_linear(wt, at, workspace=ws)
         torch.cuda.synchronize()
         got = dev_to_bf16_bits(y[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])

@@ -269,6 +269,19 @@ def test_linear_random_codes_all_scale_bytes(oracle):
         assert max_rel_err(dev_to_bf16_bits(razer.razer_linear(wt, bf16_bits_to_dev(a))), y64) <= TOL
 
 
+def _w4a4_both_forms(wt, at, m):
+    """razer_linear with a RaZeR activation operand in its two forms: with the workspace the W4A4 query asks for
+    (activations decoded once, then the weight-only path) and with the plain linear figure (one fused kernel)."""
+    from paper_2501_04052_amd import binding
+    need = max(256, razer.razer_workspace_bytes(binding.OP_LINEAR, wt.rows, wt.cols, m))
+    fused_ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    assert need < razer.razer_workspace_bytes(binding.OP_LINEAR_W4A4, wt.rows, wt.cols, m)
+    ys = [razer.razer_linear(wt, at), razer.razer_linear(wt, at, workspace=fused_ws)]
+    torch.cuda.synchronize()
+    return ys
+
+
+
 @pytest.mark.parametrize("m,n,k", [(4, 64, 256), (130, 260, 512), (257, 128, 1056)])
 def test_linear_w4a4_matches_oracle(oracle, m, n, k):
     print("w4a4", m, n, k, flush=True)
@@ -281,8 +294,8 @@ def test_linear_w4a4_matches_oracle(oracle, m, n, k):
     at = razer.razer_quantize(bf16_bits_to_dev(a), A, (5.0, 0.0))       # on-the-fly activation encode
     ac, asc, ats = tensor_to_host(at)
     assert np.array_equal(ac, aq[0]) and np.array_equal(asc, aq[1]) and ats == aq[2]
-    y = razer.razer_linear(wt, at)
-    assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
+    for y in _w4a4_both_forms(wt, at, m):
+        assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
 
 
 def test_linear_w4a4_shapes_around_every_dispatch_boundary(oracle):
@@ -300,9 +313,8 @@ def test_linear_w4a4_shapes_around_every_dispatch_boundary(oracle):
         y64, _ = oracle.linear((wc, ws, wts), a_q=(ac, asc, ats))
         wt = razer.RazerTensor.from_host(wc, ws, wts, W, (5.0, 8.0))
         at = razer.RazerTensor.from_host(ac, asc, ats, A, (5.0, 0.0))
-        y = razer.razer_linear(wt, at)
-        torch.cuda.synchronize()
-        assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL, (m, n, k)
+        for y in _w4a4_both_forms(wt, at, m):
+            assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL, (m, n, k)
 
 
 def test_linear_strided_output_and_empty(oracle):
@@ -486,10 +498,9 @@ def test_block_sizes_w4a4_matches_oracle(oracle, wb, ab, m, n, k):
     ra = oracle.quantize(A, a_bits, sv=(5.0, 0.0), block=ab)
     assert np.array_equal(aq[0], ra[0]) and np.array_equal(aq[1], ra[1])
     wt = razer.RazerTensor.from_host(*wq, W, (5.0, 8.0))
-    y = razer.razer_linear(wt, at)
-    torch.cuda.synchronize()
     y64, _ = oracle.linear(wq, a_q=ra)
-    assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
+    for y in _w4a4_both_forms(wt, at, m):
+        assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
 
 
 @pytest.mark.parametrize("block", [32, 64, 128])
