@@ -424,6 +424,19 @@ def main():
                                                "end_to_end_TFLOP/s": 2.0 * 4096 * 11008 * 4096 / (ms_l + ms_e) / 1e9,
                                                "fused_kernel_TFLOP/s": 2.0 * 4096 * 11008 * 4096 / ms_f / 1e9}
         del ws_big, ws_small
+        # the same layer in the decode regime: few activation rows, RaZeR activations (both forms as above)
+        for mm in (1, 16):
+            am = make_act(mm, 4096, 5100 + mm)
+            aqm = razer.razer_quantize(am, razer.ACT, (5.0, 0.0))
+            ym = torch.empty((mm, 11008), dtype=torch.bfloat16, device="cuda")
+            wsm = torch.empty(razer.razer_workspace_bytes(binding.OP_LINEAR_W4A4, 11008, 4096, mm), dtype=torch.uint8, device="cuda")
+            wsf = torch.empty(max(256, razer.razer_workspace_bytes(binding.OP_LINEAR, 11008, 4096, mm)), dtype=torch.uint8, device="cuda")
+            gates = [cp[4] for cp in copies]
+            ms_s = time_region(lambda i: razer.razer_linear(gates[i % n_copies], aqm, out=ym, workspace=wsm), 50, 10)
+            ms_f = time_region(lambda i: razer.razer_linear(gates[i % n_copies], aqm, out=ym, workspace=wsf), 20, 5)
+            legs["w4a4_linear_m%d_11008x4096" % mm] = {"us": ms_s * 1e3, "fused_kernel_us": ms_f * 1e3,
+                                                        "note": "unprepared binding calls (host cost included)"}
+            del wsm, wsf
 
     # ---- Llama-70B-shaped layer (configs[3]): 481 MB of packed weights, far beyond the LLC ----
     if args.legs == "all":
