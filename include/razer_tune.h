@@ -11,10 +11,11 @@
  * take a heuristic.  Results never depend on the shape beyond fp32 summation order.
  *
  * Families and their parameters p[0..3] (unused ones 0):
- *   RAZER_TUNE_GEMV         m = 1 (and 2 .. 4 with blocks other than 16 or the FP16-scale format): p[0] = groups
- *                           of 2 rows per set of waves (2, 4 or 8), p[1] = sets of waves per workgroup (1 or 2;
- *                           2 only with p[0] = 2)
- *   RAZER_TUNE_GEMV_QUAD    m = 2 .. 4, blocks of 16: p[0] = groups of 4 rows per workgroup (4 or 8)
+ *   RAZER_TUNE_GEMV         m = 1 (and 2 .. 4 with rows longer than 32768 elements): p[0] = groups of 2 rows
+ *                           per set of waves (2, 4 or 8), p[1] = sets of waves per workgroup (1 or 2; 2 only
+ *                           with p[0] = 2)
+ *   RAZER_TUNE_GEMV_QUAD    m = 2 .. 4, every block size and weight format: p[0] = groups of 4 rows per
+ *                           workgroup (4 or 8)
  *   RAZER_TUNE_SMALL_BATCH  5 <= m <= 32: p[0] = 0: K cut into slices over workgroups, summed by a second
  *                           launch from the workspace; p[1] = 128-element steps per slice (4 or 8), p[2] =
  *                           64-row blocks per workgroup (1, 2, 4).  p[0] = 1 (m <= 16 only): K inside the

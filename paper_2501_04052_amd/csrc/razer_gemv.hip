@@ -14,8 +14,8 @@
 // streaming kernel (groups of 2 rows, next group in flight while one is decoded);
 // longer rows take the multi-pass kernel (4 rows per workgroup).
 //
-// Two to four activation rows (16-element blocks) take a variant of the streaming kernel that multiplies
-// on the 4x4x4 matrix instruction (gemv_quad_kernel, further down): with v_dot2 every activation row
+// Two to four activation rows (every block size and weight format) take a variant of the streaming kernel
+// that multiplies on the 4x4x4 matrix instruction (gemv_quad_kernel, further down): with v_dot2 every activation row
 // costs another half operation per weight and the kernel turns VALU-bound.
 //
 // Decode.  The 8 codes of a dword are sign-flipped with one xor, converted to
@@ -423,12 +423,15 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_stream_grouped_kernel(
 // one sum per row of 16 lanes: the cross-row step of the wave reduction is part of the final sum).
 // Idle lanes (K tail) are silenced through their scale bits; activation rows past M are never masked,
 // their results are simply not stored.
-template <int C, int G, int D, int P, int MS, int PS = 1, bool IL = false>
+// FMT: 0 = scale bytes, blocks of 16 (two per run of 32); 1 = scale bytes, blocks of 2^lb >= 32 (one per run);
+// 2 = FP16-scale format (one 16-bit word per block of 128, decoded without the table).
+template <int C, int G, int D, int P, int MS, int PS = 1, bool IL = false, int FMT = 0>
 __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                                const float* __restrict__ w_ts, float sv0, float sv1, int64_t n,
                                                int64_t k, const uint16_t* __restrict__ a, int64_t m,
-                                               uint16_t* __restrict__ y, int64_t ld_y, int64_t row0)
+                                               uint16_t* __restrict__ y, int64_t ld_y, int64_t row0, int lb = 4)
 {
+    static_assert(!(IL && FMT != 0), "the interleaved layout holds 16-element blocks");
     constexpr int R = 4;
     static_assert(D == 2, "two register buffers");
     __shared__ uint2 lut[256];
@@ -442,7 +445,8 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
     const uint32_t b = lane >> 2, q = lane & 3u;
     // uniform 64-bit bases (first row of the workgroup) + 32-bit offsets of the lane's row, as in the
     // streaming kernel; rows past N re-read the last row
-    const uint32_t code_ld = (uint32_t)(IL ? il_row_bytes(k) : (k >> 1)), scale_ld = IL ? code_ld : (uint32_t)(k >> 4);
+    const uint32_t code_ld = (uint32_t)(IL ? il_row_bytes(k) : (k >> 1));
+    const uint32_t scale_ld = IL ? code_ld : FMT == 2 ? (uint32_t)(k >> 7) * 2u : (uint32_t)(k >> (FMT == 1 ? lb : 4));
     const uint32_t last_row = (uint32_t)((n - 1 - row0 < P * R * G - 1) ? n - 1 - row0 : P * R * G - 1);
     const uint8_t* cbase = codes + row0 * (int64_t)code_ld;
     const uint8_t* sbase = (IL ? codes : scales) + row0 * (int64_t)scale_ld;
@@ -486,11 +490,17 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
 #pragma unroll
             for (int c = 0; c < C; ++c) {
                 g.cw[c] = *reinterpret_cast<const uint4*>(cbase + (crow + (IL ? il_code_off(koff[c]) : (koff[c] >> 1))));
-                g.sw[c] = *reinterpret_cast<const uint16_t*>(sbase + (srow + (IL ? il_scale_off(koff[c]) : (koff[c] >> 4)))) & smask[c];
+                if (FMT == 2) {
+                    g.sw[c] = *reinterpret_cast<const uint16_t*>(sbase + (srow + ((koff[c] >> 7) << 1))) & smask[c];
+                } else if (FMT == 1) {
+                    g.sw[c] = sbase[srow + (koff[c] >> lb)] & smask[c];
+                } else {
+                    g.sw[c] = *reinterpret_cast<const uint16_t*>(sbase + (srow + (IL ? il_scale_off(koff[c]) : (koff[c] >> 4)))) & smask[c];
+                }
             }
         };
         load(buf[0], 0);
-        if (ps == 0) {                                                    // the first loads are in flight meanwhile
+        if (FMT != 2 && ps == 0) {                                        // the first loads are in flight meanwhile
             fill_weight_lut(lut, sv0, sv1);
             __syncthreads();                                              // LUT ready
         }
@@ -501,7 +511,18 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
 #pragma unroll
             for (int c = 0; c < C; ++c) {
                 const uint32_t xw[4] = {cur.cw[c].x, cur.cw[c].y, cur.cw[c].z, cur.cw[c].w};
-                const uint2 le0 = lut[cur.sw[c] & 255u], le1 = lut[(cur.sw[c] >> 8) & 255u];
+                uint2 le0, le1;                       // { -block scale, negated special value as a bf16 pair } of the two halves
+                if constexpr (FMT == 2) {
+                    float bs, sv;
+                    decode_scale_word(cur.sw[c], sv0, sv1, bs, sv);      // (past K: word 0, scale 0)
+                    const uint32_t nsv = (uint32_t)f32_to_bf16_rne(-sv);
+                    le0 = le1 = make_uint2(f2u(-bs), nsv | (nsv << 16));
+                } else if constexpr (FMT == 1) {
+                    le0 = le1 = lut[cur.sw[c] & 255u];
+                } else {
+                    le0 = lut[cur.sw[c] & 255u];
+                    le1 = lut[(cur.sw[c] >> 8) & 255u];
+                }
                 // bare FP4 values of the lane's 32 codes: dwords 0, 1 belong to the first block, 2, 3 to the second
                 v4bf wa[4], wb[4];
 #pragma unroll
@@ -565,18 +586,18 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
     }
 }
 
-template <int C, int G, int D, int P, int MS, int PS = 1, bool IL = false>
+template <int C, int G, int D, int P, int MS, int PS = 1, bool IL = false, int FMT = 0>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_kernel(const uint8_t* __restrict__ codes,
                                                                    const uint8_t* __restrict__ scales,
                                                                    const float* __restrict__ w_ts, float sv0, float sv1,
                                                                    int64_t n, int64_t k, const uint16_t* __restrict__ a,
-                                                                   int64_t m, uint16_t* __restrict__ y, int64_t ld_y)
+                                                                   int64_t m, uint16_t* __restrict__ y, int64_t ld_y, int lb)
 {
-    gemv_quad_body<C, G, D, P, MS, PS, IL>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y,
-                                           (int64_t)blockIdx.x * (P * 4 * G));
+    gemv_quad_body<C, G, D, P, MS, PS, IL, FMT>(codes, scales, w_ts, sv0, sv1, n, k, a, m, y, ld_y,
+                                                (int64_t)blockIdx.x * (P * 4 * G), lb);
 }
 
-template <int C, int G, int D, int P, int MS, int PS = 1, bool IL = false>
+template <int C, int G, int D, int P, int MS, int PS = 1, bool IL = false, int FMT = 0>
 __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_grouped_kernel(
     const uint8_t* c0, const uint8_t* c1, const uint8_t* c2, const uint8_t* c3,
     const uint8_t* s0, const uint8_t* s1, const uint8_t* s2, const uint8_t* s3,
@@ -585,7 +606,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_grouped_kernel(
     int64_t n0, int64_t n1, int64_t n2, int64_t n3,
     int64_t l0, int64_t l1, int64_t l2, int64_t l3,
     unsigned g1, unsigned g2, unsigned g3,
-    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int64_t m)
+    float sv0, float sv1, int64_t k, const uint16_t* __restrict__ a, int64_t m, int lb)
 {
     const unsigned b = blockIdx.x;
     const uint8_t* codes = c0; const uint8_t* scales = s0; const float* ts = t0; uint16_t* y = y0;
@@ -594,7 +615,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_grouped_kernel(
     if (b >= g1) { codes = c1; scales = s1; ts = t1; y = y1; n = n1; ld = l1; first = g1; }
     if (b >= g2) { codes = c2; scales = s2; ts = t2; y = y2; n = n2; ld = l2; first = g2; }
     if (b >= g3) { codes = c3; scales = s3; ts = t3; y = y3; n = n3; ld = l3; first = g3; }
-    gemv_quad_body<C, G, D, P, MS, PS, IL>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, (int64_t)(b - first) * (P * 4 * G));
+    gemv_quad_body<C, G, D, P, MS, PS, IL, FMT>(codes, scales, ts, sv0, sv1, n, k, a, m, y, ld, (int64_t)(b - first) * (P * 4 * G), lb);
 }
 
 // The matrix-instruction kernel serves 2 to 4 activation rows (one row: the dot-product kernel is faster):
@@ -606,7 +627,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void gemv_quad_grouped_kernel(
 // the launch has at least 16384 rows.
 static inline bool quad_fits(const SvConfig& cfg, int64_t k, int64_t m)
 {
-    return (m >= 2 && m <= 4) && cfg.lb == 4 && !cfg.f16 && k <= 32768;
+    return (m >= 2 && m <= 4) && k <= 32768;
 }
 static inline int quad_runs(int64_t k) { return (k + 511) / 512 <= kMaxWaves ? 1 : 2; }
 static inline int quad_passes(int64_t k) { return k <= 16384 ? 1 : 2; }
@@ -625,15 +646,19 @@ static hipError_t launch_gemv_quad(SvConfig cfg, const uint8_t* codes, const uin
     const int groups = passes == 2 ? 4 : quad_groups(n, k, m);   // two passes keep G running sums: 8 groups would spill
     const int nwaves = (int)((k + 512 * runs * passes - 1) / (512 * runs * passes));
     const unsigned grid = (unsigned)((n + 4 * groups - 1) / (4 * groups));
-#define RAZER_QUAD(C, G, PS)                                                                                                          \
-    do {                                                                                                                              \
-        if (cfg.il) launch(gemv_quad_kernel<C, G, 2, 1, 1, PS, true>, grid, 64 * nwaves, 0, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y); \
-        else launch(gemv_quad_kernel<C, G, 2, 1, 1, PS>, grid, 64 * nwaves, 0, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y);              \
+#define RAZER_QUAD_ARGS grid, 64 * nwaves, 0, st, codes, scales, ts, cfg.sv0, cfg.sv1, n, k, a, m, y, ld_y, cfg.lb
+#define RAZER_QUAD(C, G, PS)                                                                              \
+    do {                                                                                                  \
+        if (cfg.il) launch(gemv_quad_kernel<C, G, 2, 1, 1, PS, true, 0>, RAZER_QUAD_ARGS);                \
+        else if (cfg.f16) launch(gemv_quad_kernel<C, G, 2, 1, 1, PS, false, 2>, RAZER_QUAD_ARGS);         \
+        else if (cfg.lb != 4) launch(gemv_quad_kernel<C, G, 2, 1, 1, PS, false, 1>, RAZER_QUAD_ARGS);     \
+        else launch(gemv_quad_kernel<C, G, 2, 1, 1, PS, false, 0>, RAZER_QUAD_ARGS);                      \
     } while (0)
     if (passes == 2)    { RAZER_QUAD(2, 4, 2); }
     else if (runs == 1) { if (groups == 8) RAZER_QUAD(1, 8, 1); else RAZER_QUAD(1, 4, 1); }
     else                { if (groups == 8) RAZER_QUAD(2, 8, 1); else RAZER_QUAD(2, 4, 1); }
 #undef RAZER_QUAD
+#undef RAZER_QUAD_ARGS
     return hipGetLastError();
 }
 
@@ -655,11 +680,13 @@ static hipError_t launch_gemv_quad_grouped(SvConfig cfg, int count, const GemvPr
 #define RAZER_QUADG_ARGS                                                                                             \
     q[0].codes, q[1].codes, q[2].codes, q[3].codes, q[0].scales, q[1].scales, q[2].scales, q[3].scales, q[0].ts,     \
         q[1].ts, q[2].ts, q[3].ts, q[0].y, q[1].y, q[2].y, q[3].y, q[0].n, q[1].n, q[2].n, q[3].n, q[0].ld_y,        \
-        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m
-#define RAZER_QUADG(C, G, PS)                                                                                                   \
-    do {                                                                                                                        \
-        if (cfg.il) launch(gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS, true>, g[4], 64 * nwaves, 0, st, RAZER_QUADG_ARGS);      \
-        else launch(gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS>, g[4], 64 * nwaves, 0, st, RAZER_QUADG_ARGS);                   \
+        q[1].ld_y, q[2].ld_y, q[3].ld_y, g[1], g[2], g[3], cfg.sv0, cfg.sv1, k, a, m, cfg.lb
+#define RAZER_QUADG(C, G, PS)                                                                                                         \
+    do {                                                                                                                              \
+        if (cfg.il) launch(gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS, true, 0>, g[4], 64 * nwaves, 0, st, RAZER_QUADG_ARGS);         \
+        else if (cfg.f16) launch(gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS, false, 2>, g[4], 64 * nwaves, 0, st, RAZER_QUADG_ARGS);  \
+        else if (cfg.lb != 4) launch(gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS, false, 1>, g[4], 64 * nwaves, 0, st, RAZER_QUADG_ARGS); \
+        else launch(gemv_quad_grouped_kernel<C, G, 2, 1, 1, PS, false, 0>, g[4], 64 * nwaves, 0, st, RAZER_QUADG_ARGS);               \
     } while (0)
     if (passes == 2)    { RAZER_QUADG(2, 4, 2); }
     else if (runs == 1) { if (groups == 8) RAZER_QUADG(1, 8, 1); else RAZER_QUADG(1, 4, 1); }

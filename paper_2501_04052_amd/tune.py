@@ -41,7 +41,7 @@ def candidates(family, m, k):
 
 
 def family_of(m, k, block=16):
-    if m <= 1 or (m <= 4 and (block != 16 or k > 32768)):
+    if m <= 1 or (m <= 4 and k > 32768):
         return 0 if k <= 32768 else None
     if m <= 4:
         return 1

@@ -61,16 +61,18 @@ def test_small_batch_in_workgroup_shape_is_ignored_above_16_rows(oracle):
 
 
 @pytest.mark.parametrize("shape", [(2, 1), (2, 2), (4, 1), (8, 1)])
-@pytest.mark.parametrize("m,ns,k,block", [(1, (333,), 4096 + 32, 16), (2, (100, 57, 8), 11008, 16), (1, (41,), 28672, 16),
-                                          (4, (50,), 4096, 64)])
+@pytest.mark.parametrize("m,ns,k,block", [(1, (333,), 4096 + 32, 16), (1, (100, 57, 8), 11008, 16), (1, (41,), 28672, 16),
+                                          (1, (50,), 4096, 64), (3, (20,), 32768 + 2048, 16)])
 def test_gemv_shapes(oracle, shape, m, ns, k, block):
     _check(oracle, binding.TUNE_GEMV, shape, m, ns, k, block)
 
 
 @pytest.mark.parametrize("shape", [(4,), (8,)])
-@pytest.mark.parametrize("m,ns,k", [(2, (97, 40), 4096), (3, (333,), 4096 + 32), (4, (100, 57), 11008), (4, (70,), 16384)])
-def test_gemv_quad_shapes(oracle, shape, m, ns, k):
-    _check(oracle, binding.TUNE_GEMV_QUAD, shape, m, ns, k)
+@pytest.mark.parametrize("m,ns,k,block", [(2, (97, 40), 4096, 16), (3, (333,), 4096 + 32, 16), (4, (100, 57), 11008, 16),
+                                          (4, (70,), 16384, 16), (3, (120, 36), 4096 + 128, 64), (4, (50,), 11008 + 64, 32),
+                                          (2, (33,), 8192, 128)])
+def test_gemv_quad_shapes(oracle, shape, m, ns, k, block):
+    _check(oracle, binding.TUNE_GEMV_QUAD, shape, m, ns, k, block)
 
 
 @pytest.mark.parametrize("shape", [(1,), (3,), (16,)])
