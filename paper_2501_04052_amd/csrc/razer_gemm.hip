@@ -14,9 +14,10 @@
 // consecutive n of one output row; two lanes swap halves and store 16 bytes.
 //
 // Kernels, chosen by gemm_plan() from M and the number of output tiles:
-//   gemm_kernel      both operands decoded into LDS, all waves alike (M <= 128 for W4A4 and for
-//                    blocks of 32..128)
-//   gemm_pp_kernel   256-row tiles, two wave groups half a step out of phase (decode | MFMA)
+//   gemm_kernel      both operands decoded into LDS, all waves alike (M <= 128: the fused W4A4 kernel and
+//                    the FP16-scale format)
+//   gemm_pp_kernel   256-row tiles, two wave groups half a step out of phase (decode | MFMA): few-tile
+//                    problems above 128 rows, the fused W4A4 kernel, the FP16-scale format
 //   gemm_rb_kernel   W4A16, 16-element blocks: weights decoded in registers by the wave that uses them,
 //                    global -> LDS copies by the load unit; 256-row activation tiles when there are
 //                    many output tiles, 64- / 128-row tiles for 33..128 activation rows; KG = 2 halves
@@ -1360,10 +1361,11 @@ hipError_t launch_gemm_grouped(SvConfig cfg, int count, const GemvProblem* p, in
                        : launch_gemm_grouped_t<true>(cfg, count, p, k, a, m, workspace, st);
 }
 
-// The FP16-scale weight format from 5 activation rows up (bf16 activations): the single-group kernel with
-// bare FP4 operands and per-block folds; 32-, 64-, 128- or 256-row activation tiles.  With a workspace, K is cut
-// into slices of whole blocks while the tiles are fewer than the compute units (the rule of gemm_plan, whose
-// tiles are never smaller than these, so gemm_workspace_bytes covers it).
+// The FP16-scale weight format on the tiled kernels (bf16 activations; the host sends up to 64 activation rows
+// to the small-batch kernel): bare FP4 operands and per-block folds on the single-group kernel (32-, 64-, 128-row
+// tiles) and, above 128 rows, on the two-group kernel (256 x 128 tiles).  With a workspace, K is cut into slices
+// of whole blocks while the tiles are fewer than the compute units (the rule of gemm_plan, whose tiles are never
+// smaller than these, so gemm_workspace_bytes covers it).
 static int f16_split(int64_t m, int64_t n, int64_t k)
 {
     const int64_t tiles = m <= 64 ? (n + 255) / 256 : m <= 128 ? (n + 127) / 128 : ((m + 255) / 256) * ((n + 127) / 128);
