@@ -28,7 +28,8 @@ extern "C" {
 void razer_probe_dispatch_events(void *start_event, void *stop_event);
 
 /* Reads `bytes` (a multiple of 16) from buf (16-byte aligned) with `workgroups` workgroups of 256
- * threads, grid-stride, four 16-byte loads in flight per lane; sink: 64 dwords of device scratch. */
+ * threads, grid-stride, four non-temporal 16-byte loads in flight per lane; sink: 64 dwords of device
+ * scratch. */
 int razer_probe_stream_read(const void *buf, size_t bytes, int workgroups, void *sink, void *hip_stream);
 
 /* iters x 8 independent v_mfma_f32_32x32x16_bf16 per wavefront on `workgroups` workgroups of four

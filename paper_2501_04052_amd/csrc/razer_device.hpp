@@ -49,6 +49,16 @@ __device__ __forceinline__ uint32_t load_scale_pair(const uint8_t* __restrict__ 
     return b | (b << 8);
 }
 
+// 16 bytes of packed weight codes that the launch reads exactly once: a non-temporal load (`nt`), which tells
+// the caches not to keep the line.  Measured on MI355X with a load-only kernel over rotated buffers: 264 MB in
+// 42.3 us instead of 46.5 us (6.24 against 5.68 TB/s); the GEMV launches gain 3-5 %.  Activations, which every
+// workgroup re-reads, keep the default policy.
+__device__ __forceinline__ uint4 load_once16(const void* p)
+{
+    const v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 __device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
 

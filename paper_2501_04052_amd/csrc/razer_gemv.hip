@@ -84,7 +84,7 @@ __device__ __forceinline__ void load_group(RowGroup<R>& g, const uint8_t* __rest
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int64_t row = (row0 + r < n) ? row0 + r : n - 1;           // clamp: tail rows re-read the last row
-        g.cw[r] = *reinterpret_cast<const uint4*>(codes + row * (k / 2) + c * 16);
+        g.cw[r] = load_once16(codes + row * (k / 2) + c * 16);
         g.sw[r] = load_scale_bits<GB, SF>(scales, row, k, c * 32, lb);
     }
 }
@@ -280,7 +280,7 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
             // (24-bit multiply-add: one 32-bit instruction.  The generic 32-bit form compiles to a 64-bit
             // multiply-add whose unused high input half the register allocator overlaps with a load in
             // flight, and the wave then waits for that load before it requests its weights.)
-            g.cw[r] = *reinterpret_cast<const uint4*>(cbase + (__umul24(row, code_ld) + c_lane));
+            g.cw[r] = load_once16(cbase + (__umul24(row, code_ld) + c_lane));
             const uint8_t* sp = sbase + (__umul24(row, scale_ld) + s_lane);
             if (GB && SF == 0) g.sw[r] = *sp & smask;                     // blocks of 32 and more: one scale byte
             else g.sw[r] = *reinterpret_cast<const uint16_t*>(sp) & smask;
@@ -489,7 +489,7 @@ __device__ __forceinline__ void gemv_quad_body(const uint8_t* __restrict__ codes
             const uint32_t crow = __umul24(row, code_ld), srow = __umul24(row, scale_ld);
 #pragma unroll
             for (int c = 0; c < C; ++c) {
-                g.cw[c] = *reinterpret_cast<const uint4*>(cbase + (crow + (IL ? il_code_off(koff[c]) : (koff[c] >> 1))));
+                g.cw[c] = load_once16(cbase + (crow + (IL ? il_code_off(koff[c]) : (koff[c] >> 1))));
                 if (FMT == 2) {
                     g.sw[c] = *reinterpret_cast<const uint16_t*>(sbase + (srow + ((koff[c] >> 7) << 1))) & smask[c];
                 } else if (FMT == 1) {
