@@ -37,6 +37,16 @@ def profiled_traffic_bytes():
         return None
 
 
+def profiled_trace_avg_us():
+    """`gate_up_trace_avg_us = T` from the committed kernel-trace summary (a profiled run of this command), or None."""
+    import re
+    try:
+        m = re.search(r"gate_up_trace_avg_us\s*=\s*([0-9.]+)", open(os.path.join(ROOT, "profiles", "gemv_m1_llama7b_kernel_stats.txt")).read())
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
@@ -577,6 +587,7 @@ def main():
                "single_thread": {"value": sample_bytes / dt_one / 1e9, "unit": "GB/s", "cores": 1,
                                  "sample": "the same sample on one thread, %d repeats in ~8 s" % reps_one}}
 
+    trace_us = profiled_trace_avg_us()
     out = {
         "metric": "RaZeR W4A16 GEMV HBM GB/s at M=1 (Llama-7B-shaped layer set)",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -601,6 +612,12 @@ def main():
                      "frac_of_measured_ceiling": ceil["50.8MB"]["per_dispatch_us"] / (dom_ms * 1e3),
                      "step_frac": gbs / HBM_PEAK_GBS,
                      "step_frac_of_measured_ceiling": step_ceiling_us / (ms1 * 1e3),
+                     "profiled_trace_avg_us": trace_us,
+                     "frac_at_profiled_trace_avg": (dom_bytes / trace_us / 1e3 / HBM_PEAK_GBS) if trace_us else None,
+                     "profiled_trace_note": "average duration of this kernel in profiles/gemv_m1_llama7b_kernel_stats.txt (rocprofv3 "
+                                            "--kernel-trace of this command, parsed from that file, not measured in this run): under "
+                                            "the tracer every dispatch starts on an idle GPU and takes 5-8 % longer than in the "
+                                            "unprofiled stream that avg_launch_us times",
                      "traffic_source": "profiles/gemv_m1_llama7b_hbm_traffic.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
                                        "command, scaled by a plain copy; parsed from that file, not measured in this run"},
         "cpu_baseline": cpu,
