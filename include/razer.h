@@ -7,7 +7,7 @@
  *   element   FP4-E2M1 code S|EE|M (Sec. 4.1, FP4 equation): +-{0,.5,1,1.5,2,3,4,6};
  *             code 0x8 (negative zero) is the remapped one (Sec. 4.2).
  *   block     16 consecutive elements along the last (contraction) axis share one
- *             scale byte (Sec. 3; Sec. 5.1 "block size of 16 with 8-bit block scale");
+ *             scale byte (Sec. 3; the evaluated configuration of Sec. 5.1: 16 elements, 8-bit scale);
  *             32, 64 and 128 are accepted too (block-size study of Sec. 5.4):
  *               weights      bit7 = special-value sign, bit6 = special-value selector,
  *                            bits5:0 = E3M3 scale EEE|MMM, value 2^(E-3)(1+M/8), E=0: M/32

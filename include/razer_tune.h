@@ -1,8 +1,8 @@
 /*
  * razer_tune.h -- launch-shape tuning hooks of the gfx950 RaZeR library.
  *
- * The paper's weight-only kernel "performs offline profiling for each matrix size and, at inference
- * time, selects the optimal number of SMs to launch for each batch size" (Sec. 4.3; App. E, Tab. 13:
+ * The paper's weight-only kernel is tuned offline: every matrix size is profiled ahead of time and the
+ * number of SMs to launch is then picked per batch size when the kernel runs (Sec. 4.3; App. E, Tab. 13:
  * fewer, larger partitions cut the reduction stages of small problems).  The counterpart here: for a
  * problem (kernel family, activation rows m, weight rows, cols) the dispatch of razer_linear /
  * razer_linear_grouped takes its launch shape -- rows per workgroup, waves per K range, K-slices, which
@@ -20,7 +20,7 @@
  *                           launch from the workspace; p[1] = 128-element steps per slice (4 or 8), p[2] =
  *                           64-row blocks per workgroup (1, 2, 4).  p[0] = 1 (m <= 16 only): K inside the
  *                           workgroup, no workspace; p[1] = steps per wave and pass (1, 2), p[2] = groups of
- *                           16 rows per workgroup (2, 4, 8; 8 only with p[1] = 2)
+ *                           16 rows per workgroup (1, 2, 3, 4, 8; 8 only with p[1] = 2)
  *   RAZER_TUNE_GEMM_SLICES  33 <= m <= 128: p[0] = K-slices of the register-decode kernel (1 .. 16)
  * For razer_linear_grouped `rows` is the sum over the group.  A shape the kernels are not built for is
  * ignored (the heuristic applies).

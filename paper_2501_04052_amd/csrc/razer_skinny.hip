@@ -566,7 +566,7 @@ __global__ __launch_bounds__(64 * MAXW) void mv_grouped_kernel(
 struct MvShape {
     int s, g, maxw;
 };
-constexpr MvShape kMvShapes[] = {{1, 2, 16}, {1, 4, 16}, {2, 2, 16}, {2, 4, 16}, {2, 8, 8}};
+constexpr MvShape kMvShapes[] = {{1, 1, 16}, {1, 2, 16}, {1, 3, 16}, {1, 4, 16}, {2, 1, 16}, {2, 2, 16}, {2, 3, 16}, {2, 4, 16}, {2, 8, 8}};
 static bool mv_shape_ok(int s, int g)
 {
     for (const MvShape& sh : kMvShapes)
@@ -599,7 +599,30 @@ struct SkinnyPlan {
     int steps, nrb;         // K-sliced kernel
     int s, g;               // K-in-workgroup kernel
 };
-static SkinnyPlan skinny_plan(int64_t rows, int64_t k, int64_t m, bool f16 = false)
+// Up to 16 activation rows, no table entry: the K-in-workgroup kernel when some G <= 4 puts the whole launch into
+// ONE round of workgroups (a workgroup of 16 waves fills a compute unit, so a second round would run on a nearly
+// idle GPU) that still covers half of the 256 compute units; 2 steps per wave from 3 groups up.  Long rows with
+// more than 8 activation rows keep the K-sliced kernel.  This rule reproduces what the sweep picked on the
+// projection shapes of 7B- and 70B-class layers (4096^2: G = 1; 8192^2: 2; 11008 x 4096 and 10240 x 8192: 3;
+// {q,k,v} 3 x 4096 x 4096: 4 -- with G = 3 its 3 x 86 workgroups would be two more than the chip has units).
+constexpr int64_t kComputeUnits = 256;
+static bool mv_one_round(int64_t rows, int count, int64_t k, int64_t m, int& s, int& g)
+{
+    if (m > 16 || k > 16384 || (k > 8192 && m > 8)) return false;
+    const int64_t groups = (rows + 15) / 16;
+    for (int gg = 1; gg <= 4; ++gg) {
+        const int64_t wgs = (groups + gg - 1) / gg + (count - 1);       // (each matrix of a group rounds up on its own)
+        if (wgs <= kComputeUnits) {
+            if (wgs < kComputeUnits / 2) return false;
+            g = gg;
+            s = gg >= 3 ? 2 : 1;
+            return true;
+        }
+    }
+    return false;
+}
+
+static SkinnyPlan skinny_plan(int64_t rows, int64_t k, int64_t m, bool f16 = false, int count = 1)
 {
     SkinnyPlan p{false, (m <= 16 && k > 8192) ? 8 : 4, 1, 0, 0};
     const int64_t row_blocks = (rows + kSkRows - 1) / kSkRows;
@@ -625,6 +648,10 @@ static SkinnyPlan skinny_plan(int64_t rows, int64_t k, int64_t m, bool f16 = fal
         p.nrb = t.p[2];
         return p;
     }
+    if (mv_one_round(rows, count, k, m, p.s, p.g)) {
+        p.in_workgroup = true;
+        return p;
+    }
     const int64_t nslices = (k + 128 * p.steps - 1) / (128 * p.steps);
     const int64_t target = m <= 16 ? 2048 : 1024;
     while (p.nrb < 4 && (row_blocks / (2 * p.nrb)) * nslices >= target) p.nrb *= 2;
@@ -646,7 +673,7 @@ size_t skinny_grouped_workspace_bytes(int count, const GemvProblem* p, int64_t k
     if (m <= kGemvDirectMaxM || m > kSkinnyMaxM || k == 0 || k > kSkinnyMaxK) return 0;
     int64_t rows = 0;
     for (int i = 0; i < count; ++i) rows += p[i].n;
-    const SkinnyPlan pl = skinny_plan(rows, k, m);
+    const SkinnyPlan pl = skinny_plan(rows, k, m, false, count);
     if (pl.in_workgroup) return 0;
     const int64_t kc = 128 * pl.steps;
     const int64_t nslices = (k + kc - 1) / kc;
@@ -655,9 +682,13 @@ size_t skinny_grouped_workspace_bytes(int count, const GemvProblem* p, int64_t k
 
 #define RAZER_MV_SHAPES(LAUNCH)                       \
     do {                                              \
-        if (pl.s == 1 && pl.g == 2) LAUNCH(1, 2, 16); \
+        if (pl.s == 1 && pl.g == 1) LAUNCH(1, 1, 16); \
+        else if (pl.s == 1 && pl.g == 2) LAUNCH(1, 2, 16); \
+        else if (pl.s == 1 && pl.g == 3) LAUNCH(1, 3, 16); \
         else if (pl.s == 1) LAUNCH(1, 4, 16);         \
+        else if (pl.g == 1) LAUNCH(2, 1, 16);         \
         else if (pl.g == 2) LAUNCH(2, 2, 16);         \
+        else if (pl.g == 3) LAUNCH(2, 3, 16);         \
         else if (pl.g == 4) LAUNCH(2, 4, 16);         \
         else LAUNCH(2, 8, 8);                         \
     } while (0)
@@ -729,7 +760,7 @@ hipError_t launch_skinny_grouped(SvConfig cfg, int count, const GemvProblem* p, 
         return hipErrorInvalidValue;
     int64_t rows = 0;
     for (int i = 0; i < count; ++i) rows += p[i].n;
-    const SkinnyPlan pl = skinny_plan(rows, k, m, cfg.f16 != 0);
+    const SkinnyPlan pl = skinny_plan(rows, k, m, cfg.f16 != 0, count);
     GemvProblem q[4];
     unsigned g[5] = {0, 0, 0, 0, 0};
     for (int i = 0; i < 4; ++i) {

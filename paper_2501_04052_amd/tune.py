@@ -34,7 +34,7 @@ def candidates(family, m, k):
         return [(4,), (8,)] if k <= 16384 else [(4,)]
     if family == 2:
         sliced = [(0, 4, 1), (0, 4, 2), (0, 4, 4)] + ([(0, 8, 1), (0, 8, 2)] if m <= 16 else [])
-        inside = [(1, 1, 2), (1, 1, 4), (1, 2, 2), (1, 2, 4), (1, 2, 8)] if m <= 16 else []
+        inside = [(1, 1, 1), (1, 1, 2), (1, 1, 3), (1, 1, 4), (1, 2, 1), (1, 2, 2), (1, 2, 3), (1, 2, 4), (1, 2, 8)] if m <= 16 else []
         return sliced + inside
     kt = -(-k // 64)
     return [(s,) for s in (1, 2, 3, 4, 6, 8, 12, 16) if s <= kt]

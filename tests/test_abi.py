@@ -47,20 +47,24 @@ def test_tuning_hooks_force_lookup_and_workspace(razer):
     shape the kernels are not built for falls back to the heuristic."""
     from paper_2501_04052_amd import binding as b
     fam = b.TUNE_SMALL_BATCH
-    base = razer.razer_workspace_bytes(2, 4100, 4096, 16)
-    src0, shape0 = razer.razer_tune_lookup(fam, 16, 4100, 4096)
-    assert src0 == 0 and shape0 is None and base == 8 * 16 * 4100 * 4      # no table entry for this odd shape
+    # 30000 rows: no table entry, and too many 16-row groups for one round of workgroups -> K-sliced by default
+    base = razer.razer_workspace_bytes(2, 30000, 4096, 16)
+    src0, shape0 = razer.razer_tune_lookup(fam, 16, 30000, 4096)
+    assert src0 == 0 and shape0 is None and base == 8 * 16 * 30000 * 4
     razer.razer_tune_force(fam, (1, 1, 2))
-    assert razer.razer_tune_lookup(fam, 16, 4100, 4096) == (1, (1, 1, 2, 0))
-    assert razer.razer_workspace_bytes(2, 4100, 4096, 16) == 0
-    assert razer.razer_workspace_bytes(2, 4100, 4096, 20) == 8 * 20 * 4100 * 4   # more than 16 rows: K-sliced kernel
+    assert razer.razer_tune_lookup(fam, 16, 30000, 4096) == (1, (1, 1, 2, 0))
+    assert razer.razer_workspace_bytes(2, 30000, 4096, 16) == 0
+    assert razer.razer_workspace_bytes(2, 30000, 4096, 20) == 8 * 20 * 30000 * 4   # more than 16 rows: K-sliced kernel
     razer.razer_tune_force(fam, (0, 8, 1))
+    assert razer.razer_workspace_bytes(2, 30000, 4096, 16) == 4 * 16 * 30000 * 4
     assert razer.razer_workspace_bytes(2, 4100, 4096, 16) == 4 * 16 * 4100 * 4
     razer.razer_tune_force(fam, (1, 3, 5))                                        # not a built shape
-    assert razer.razer_workspace_bytes(2, 4100, 4096, 16) == base
+    assert razer.razer_workspace_bytes(2, 30000, 4096, 16) == base
     razer.razer_tune_force(fam, None)
-    assert razer.razer_tune_lookup(fam, 16, 4100, 4096)[0] == 0
-    assert razer.razer_workspace_bytes(2, 4100, 4096, 16) == base
+    assert razer.razer_tune_lookup(fam, 16, 30000, 4096)[0] == 0
+    assert razer.razer_workspace_bytes(2, 30000, 4096, 16) == base
+    # 4100 rows = 257 groups of 16: two groups per workgroup make one round -> K inside the workgroup, no workspace
+    assert razer.razer_tune_lookup(fam, 16, 4100, 4096)[0] == 0 and razer.razer_workspace_bytes(2, 4100, 4096, 16) == 0
     razer.razer_tune_force(-1, None)
     with pytest.raises(razer.RazerError):
         razer.razer_tune_force(9, (1, 2))
@@ -79,11 +83,12 @@ def test_workspace_sizes(razer):
     # linear: only the 5..32-row kernel meets its K-slices in a workspace
     assert razer.razer_workspace_bytes(2, 4096, 4096, 1) == 0
     assert razer.razer_workspace_bytes(2, 4096, 4096, 2048) == 0
-    assert razer.razer_workspace_bytes(2, 4100, 4096, 16) == 8 * 16 * 4100 * 4     # (a shape the tuned table does not list)
+    assert razer.razer_workspace_bytes(2, 30000, 4096, 16) == 8 * 16 * 30000 * 4   # (a shape the tuned table does not list)
+    assert razer.razer_workspace_bytes(2, 4100, 4096, 20) == 8 * 20 * 4100 * 4
     assert razer.razer_workspace_bytes(2, 4096, 512, 16) == 0
     # W4A4 query: room for the activations decoded to bf16 (rounded up to 256 bytes), one 256-byte cell for the
     # combined tensor scale, plus what the weight-only path needs for the same sizes
-    for n, k, m in ((11008, 4096, 4096), (4096, 4096, 2048), (4096, 4096, 64), (4100, 4096, 16), (512, 4096, 1024), (4096, 4096, 1),
+    for n, k, m in ((11008, 4096, 4096), (4096, 4096, 2048), (4096, 4096, 64), (4100, 4096, 16), (30000, 4096, 16), (512, 4096, 1024), (4096, 4096, 1),
                     (40, 96, 3)):
         a_bytes = (m * k * 2 + 255) // 256 * 256
         assert razer.razer_workspace_bytes(3, n, k, m) == a_bytes + 256 + razer.razer_workspace_bytes(2, n, k, m)
@@ -97,7 +102,7 @@ def test_grouped_workspace_query_covers_single_launch_and_fallback(razer):
     one = lambda n, k, m: razer.razer_workspace_bytes(2, n, k, m)
     assert q([4096, 4096, 4096], 4096, 1) == 0 and q([], 4096, 16) == 0 and q([4096] * 5, 4096, 16) == 0
     # small batch: K-slices of the matrices side by side (shapes the tuned table does not list)
-    assert q([11000, 11000], 4096, 16) == 2 * one(11000, 4096, 16) > 0
+    assert q([11000, 11000], 4096, 20) == 2 * one(11000, 4096, 20) > 0 and q([11000, 11000], 4096, 16) > 0
     for rows, k, m in (([4096, 4096, 4096], 4096, 64), ([11008, 11008], 4096, 128), ([1024, 23040], 4096, 256),
                        ([4096, 4096, 4096], 4096, 2048)):
         assert q(rows, k, m) >= max(one(n, k, m) for n in rows)

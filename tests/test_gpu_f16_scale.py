@@ -134,7 +134,7 @@ def test_linear_two_group_kernel_many_tiles(oracle, m, n, k):
     assert max_rel_err(got, y64) <= TOL
 
 
-MV_SHAPES = [None, (1, 1, 2), (1, 1, 4), (1, 2, 2), (1, 2, 4), (1, 2, 8)]
+MV_SHAPES = [None, (1, 1, 1), (1, 1, 2), (1, 1, 3), (1, 1, 4), (1, 2, 1), (1, 2, 2), (1, 2, 3), (1, 2, 4), (1, 2, 8)]
 
 
 @pytest.mark.parametrize("shape", MV_SHAPES)

@@ -374,14 +374,22 @@ def test_linear_grouped_small_batch_one_launch(oracle, m, k, ns):
     wqs = [_rand_tensor(rng, W, n, k) for n in ns]
     wts = [razer.RazerTensor.from_host(*wq, W, (5.0, 8.0)) for wq in wqs]
     bufs = [torch.full((m, n + 4), 2.0, dtype=torch.bfloat16, device="cuda") for n in ns]
-    razer.razer_linear_grouped(wts, a_dev, outs=[b[:, :n] for b, n in zip(bufs, ns)])
-    torch.cuda.synchronize()
-    for wt, wq, b, n in zip(wts, wqs, bufs, ns):
-        y64, _ = oracle.linear(wq, a_bf16=a)
-        assert max_rel_err(dev_to_bf16_bits(b[:, :n]), y64) <= TOL
-        assert torch.all(b[:, n:] == 2.0)
-        # the same kernels, one matrix per call: identical bits (same slices, same order)
-        assert torch.equal(b[:, :n], razer.razer_linear(wt, a_dev))
+    # the large case: the K-sliced kernel with two 64-row blocks per workgroup, for the group and for the single
+    # calls alike (left to itself the dispatch picks a launch shape per problem size, and with it a summation order)
+    from paper_2501_04052_amd import binding
+    if max(ns) > 1000:
+        razer.razer_tune_force(binding.TUNE_SMALL_BATCH, (0, 4, 2))
+    try:
+        razer.razer_linear_grouped(wts, a_dev, outs=[b[:, :n] for b, n in zip(bufs, ns)])
+        torch.cuda.synchronize()
+        for wt, wq, b, n in zip(wts, wqs, bufs, ns):
+            y64, _ = oracle.linear(wq, a_bf16=a)
+            assert max_rel_err(dev_to_bf16_bits(b[:, :n]), y64) <= TOL
+            assert torch.all(b[:, n:] == 2.0)
+            # the same kernels, one matrix per call: identical bits (same slices, same order)
+            assert torch.equal(b[:, :n], razer.razer_linear(wt, a_dev))
+    finally:
+        razer.razer_tune_force(binding.TUNE_SMALL_BATCH, None)
 
 
 @pytest.mark.parametrize("m,ns,k", [(2000, [2760, 2688, 2944], 160), (2000, [8200, 8192, 8192, 8448], 64),

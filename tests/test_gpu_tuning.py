@@ -44,7 +44,8 @@ def _check(oracle, family, shape, m, ns, k, block=16, seed=0):
         assert err <= TOL, (family, shape, err)
 
 
-SMALL_BATCH_SHAPES = [(1, 1, 2), (1, 1, 4), (1, 2, 2), (1, 2, 4), (1, 2, 8), (0, 4, 1), (0, 4, 2), (0, 4, 4), (0, 8, 1)]
+SMALL_BATCH_SHAPES = [(1, 1, 1), (1, 1, 2), (1, 1, 3), (1, 1, 4), (1, 2, 1), (1, 2, 2), (1, 2, 3), (1, 2, 4), (1, 2, 8),
+                      (0, 4, 1), (0, 4, 2), (0, 4, 4), (0, 8, 1)]
 
 
 @pytest.mark.parametrize("shape", SMALL_BATCH_SHAPES)
@@ -79,3 +80,27 @@ def test_gemv_quad_shapes(oracle, shape, m, ns, k, block):
 @pytest.mark.parametrize("m,ns,k", [(40, (300,), 2048 + 32), (100, (256, 132), 4096), (128, (200,), 1024)])
 def test_gemm_slice_counts(oracle, shape, m, ns, k):
     _check(oracle, binding.TUNE_GEMM_SLICES, shape, m, ns, k)
+
+
+@pytest.mark.parametrize("m,ns,k,block", [(8, (2100,), 1056, 16), (16, (4000,), 4096 + 64, 16), (12, (1400, 1400, 1396), 2048, 16),
+                                          (5, (4100,), 11008, 16), (16, (8200,), 8192, 64)])
+def test_untabled_small_batch_one_round_of_workgroups(oracle, m, ns, k, block):
+    """Up to 16 activation rows, no table entry, and a number of 16-row groups that some G <= 4 turns into one
+    round of workgroups: the heuristic takes the K-in-workgroup kernel (no workspace), results as the oracle's."""
+    print("one-round heuristic m", m, "ns", ns, "k", k, "block", block, flush=True)
+    assert razer.razer_tune_lookup(binding.TUNE_SMALL_BATCH, m, sum(ns), k)[0] == 0       # the heuristic applies
+    if len(ns) == 1:
+        assert razer.razer_workspace_bytes(binding.OP_LINEAR, ns[0], k, m) == 0
+    else:                                       # (the grouped query also covers the fallback to one call per matrix)
+        assert razer.razer_workspace_bytes_grouped(list(ns), k, m) == max(razer.razer_workspace_bytes(binding.OP_LINEAR, n, k, m) for n in ns)
+    a = synth.activation(m, k, seed=9900 + m + k)
+    a_dev = bf16_bits_to_dev(a)
+    ws = [_rand_weights(n, k, 9950 + i + n, block) for i, n in enumerate(ns)]
+    if len(ns) == 1:
+        ys = [razer.razer_linear(ws[0][1], a_dev)]
+    else:
+        ys = razer.razer_linear_grouped([w[1] for w in ws], a_dev)
+    torch.cuda.synchronize()
+    for (wq, _), y in zip(ws, ys):
+        y64, _ = oracle.linear(wq, a_bf16=a)
+        assert max_rel_err(dev_to_bf16_bits(y), y64) <= TOL
