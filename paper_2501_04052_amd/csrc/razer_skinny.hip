@@ -606,9 +606,8 @@ struct SkinnyPlan {
 // projection shapes of 7B- and 70B-class layers (4096^2: G = 1; 8192^2: 2; 11008 x 4096 and 10240 x 8192: 3;
 // {q,k,v} 3 x 4096 x 4096: 4 -- with G = 3 its 3 x 86 workgroups would be two more than the chip has units).
 constexpr int64_t kComputeUnits = 256;
-static bool mv_one_round(int64_t rows, int count, int64_t k, int64_t m, int& s, int& g)
+static bool mv_one_round_shape(int64_t rows, int count, int& s, int& g)
 {
-    if (m > 16 || k > 16384 || (k > 8192 && m > 8)) return false;
     const int64_t groups = (rows + 15) / 16;
     for (int gg = 1; gg <= 4; ++gg) {
         const int64_t wgs = (groups + gg - 1) / gg + (count - 1);       // (each matrix of a group rounds up on its own)
@@ -620,6 +619,11 @@ static bool mv_one_round(int64_t rows, int count, int64_t k, int64_t m, int& s, 
         }
     }
     return false;
+}
+static bool mv_one_round(int64_t rows, int count, int64_t k, int64_t m, int& s, int& g)
+{
+    if (m > 16 || k > 16384 || (k > 8192 && m > 8)) return false;
+    return mv_one_round_shape(rows, count, s, g);
 }
 
 static SkinnyPlan skinny_plan(int64_t rows, int64_t k, int64_t m, bool f16 = false, int count = 1)
@@ -635,6 +639,7 @@ static SkinnyPlan skinny_plan(int64_t rows, int64_t k, int64_t m, bool f16 = fal
         p.s = 1;
         p.g = 2;
         if (t.source == 1 && t.p[0] == 1 && mv_shape_ok(t.p[1], t.p[2])) { p.s = t.p[1]; p.g = t.p[2]; }
+        else if (m <= 16) mv_one_round_shape(rows, count, p.s, p.g);   // one round of workgroups where that is possible
         return p;
     }
     if (t.source && t.p[0] == 1 && m <= 16 && mv_shape_ok(t.p[1], t.p[2])) {
