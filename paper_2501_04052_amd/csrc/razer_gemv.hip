@@ -237,10 +237,11 @@ __device__ __forceinline__ void gemv_stream_body(const uint8_t* __restrict__ cod
     const float ts = *w_ts;
     // P sets of waves work side by side on P consecutive blocks of G * R rows (fewer, larger workgroups).
     // With one set and two groups the wave index is read as a scalar as well (measured 3-7 % faster on the
-    // long launches of a 70B-shaped layer, slower with two sets or eight groups).
+    // long launches of a 70B-shaped layer, slower with eight groups); with two sets at M = 1 it keeps the
+    // row offsets on the scalar unit too (67 -> 60 vector registers, i.e. eight waves per SIMD; 0-1 % faster).
     static_assert(P == 1 || P == 2, "one or two sets of waves");
     const uint32_t lane = threadIdx.x & 63u, nwaves = (blockDim.x >> 6) / P;
-    const uint32_t wid = (P == 1 && G == 2) ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) : (threadIdx.x >> 6);
+    const uint32_t wid = ((P == 1 && G == 2) || (P == 2 && M == 1)) ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) : (threadIdx.x >> 6);
     const uint32_t par = (P == 2 && wid >= nwaves) ? 1u : 0u;             // (no division: a reciprocal sits ahead of the first load)
     const uint32_t wave = wid - par * nwaves;
     const uint32_t chunks = (uint32_t)(k >> 5);                           // 16-byte code chunks per row
