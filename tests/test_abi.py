@@ -202,3 +202,23 @@ def test_bad_arguments_return_status_codes_without_gpu(razer):
     assert L.razer_linear_grouped(arr_b, 2, fake, 8, ys, lds, fake, 16, None) == 5
     # empty problems are fine and launch nothing
     assert L.razer_linear(ctypes.byref(t), fake, None, 0, None, 8, None, 0, None) == 0
+
+
+def test_every_table_entry_names_a_launch_shape_the_tuner_can_pick(razer):
+    """csrc/razer_tuned.inc is written by the tuner: every entry must be one of the candidate shapes of its
+    family for that (m, k) -- a stale or hand-edited table would silently fall back to the heuristic -- and the
+    library must report exactly that entry through the lookup."""
+    import re
+    from paper_2501_04052_amd import tune
+    text = open(tune.TABLE_PATH).read()
+    entries = re.findall(r"\{(\d+), (\d+), (\d+), (\d+), \{(-?\d+), (-?\d+), (-?\d+), (-?\d+)\}\}", text)
+    assert len(entries) == razer.razer_tune_table_size()
+    seen = set()
+    for fam, m, rows, k, *p in [tuple(map(int, e)) for e in entries]:
+        assert (fam, m, rows, k) not in seen                        # one entry per key
+        seen.add((fam, m, rows, k))
+        assert tune.family_of(m, k) == fam
+        cands = tune.candidates(fam, m, k)
+        assert tuple(p[:len(cands[0])]) in cands, (fam, m, rows, k, p)
+        assert all(v == 0 for v in p[len(cands[0]):])
+        assert razer.razer_tune_lookup(fam, m, rows, k) == (2, tuple(p))
